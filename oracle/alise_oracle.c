@@ -1,0 +1,304 @@
+/*
+ * CPU oracle for the quantized, paged KV-cache decode step.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what the
+ * GPU library must compute.  Nothing in the product path may call it; it shares
+ * no code, header, table or helper with the HIP sources.
+ *
+ * What it follows (ALISE, arXiv 2410.23537):
+ *   - Sec. 3.2 "KV Compression": x_q = round(x / lambda + z), x = lambda (x_q - z),
+ *     lambda = (max - min) / (2^b - 1), b-bit codes, INT8 by default.
+ *   - Sec. 2, Eq. 1-2: per-head Attn = softmax(Q K^T / sqrt(d/h)) V, heads concatenated.
+ *   - Sec. 2 "LLM Inference": each decode step appends the new token's K/V to the
+ *     cache and attends over everything cached.
+ *   - Sec. 3.3: the cache is block-level (paged), inherited from PagedAttention.
+ *
+ * Readings where the paper is silent or garbled (all listed in the design notes):
+ *   R1  the printed zero-point does not depend on min; taken as z = nint(-min / lambda).
+ *   R2  codes and z are clamped to [0, 2^b - 1].
+ *   R3  "round" is round-to-nearest, ties to even.
+ *   R4  z is inside the rounding, and x * (1/lambda) + z is ONE fused multiply-add.
+ *   R5  min/max run over the G values of a group and are widened to include 0.
+ *   R6  the scale is floored at 2^-14 (smallest normal fp16).
+ *   R7  the scale is stored as fp16, rounded UP, and quantization uses the stored value.
+ *   R8  1/lambda is one correctly rounded fp32 division per group.
+ *   R9  attention consumes the exact fp32 product lambda * (x_q - z); the page
+ *       dequantizer returns its fp16 round-to-nearest-even.
+ *   R10 a group is G contiguous channels of one token's one head vector; K and V alike.
+ *   R12 the new token is written first and attended to from its quantized form.
+ *   R13 the softmax scale is passed in (1/sqrt(head_dim) for Eq. 1).
+ *   R14 INT4: channel 2i in the low nibble, 2i+1 in the high nibble of byte i.
+ *   R15 query head h reads KV head h / (H / Hkv).
+ *   R16 no mask beyond t < L_i; L_i = 0 gives a zero row.
+ *
+ * Every fp32 step of the quantizer is a single IEEE-754 binary32 operation; build
+ * with -ffp-contract=off so the compiler fuses nothing on its own.
+ * Attention is evaluated in fp64 with a plain two-pass softmax.
+ *
+ * Parity pins: see tests/test_oracle_*.py (worked examples under tests/golden/,
+ * half-step error bound, structural invariants, dense-attention cross-checks).
+ * Layout strides, the INT4 nibble order (R14) and the GQA head mapping (R15) are
+ * this build's conventions, not the paper's: parity unpinned by the paper for those.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ---------------------------------------------------------------- fp16 <-> fp32 */
+
+/* Exact widening of an IEEE binary16 bit pattern. */
+float oracle_h2f(uint16_t h)
+{
+    uint32_t sign = (uint32_t)(h >> 15) & 1u;
+    int32_t exp = (h >> 10) & 0x1f;
+    uint32_t man = h & 0x3ffu;
+    double v;
+    if (exp == 0x1f) {
+        v = man ? NAN : INFINITY;
+    } else if (exp == 0) {
+        v = ldexp((double)man, -24);
+    } else {
+        v = ldexp((double)(man | 0x400u), exp - 25);
+    }
+    return (float)(sign ? -v : v);
+}
+
+/* binary32 -> binary16, round to nearest, ties to even. */
+uint16_t oracle_f2h_rne(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    uint16_t sign = (uint16_t)((u >> 16) & 0x8000u);
+    if (isnan(f)) return (uint16_t)(sign | 0x7e00u);
+    double a = fabs((double)f);
+    if (a >= 65520.0) return (uint16_t)(sign | 0x7c00u);   /* rounds to infinity */
+    if (a == 0.0) return sign;
+    int e;
+    (void)frexp(a, &e);            /* a = m * 2^e, m in [0.5, 1) */
+    int ulp_exp = e - 11;          /* 11 significant bits */
+    if (ulp_exp < -24) ulp_exp = -24;   /* subnormal spacing */
+    double scaled = ldexp(a, -ulp_exp); /* exact */
+    double r = nearbyint(scaled);       /* ties to even under the default mode */
+    double val = ldexp(r, ulp_exp);     /* a representable binary16 value */
+    /* encode */
+    if (val == 0.0) return sign;
+    int e2;
+    double m2 = frexp(val, &e2);        /* val = m2 * 2^e2 */
+    if (e2 - 1 < -14) {
+        uint32_t man = (uint32_t)ldexp(val, 24);
+        return (uint16_t)(sign | man);
+    }
+    uint32_t man = (uint32_t)ldexp(m2, 11) - 0x400u;
+    uint32_t ex = (uint32_t)(e2 - 1 + 15);
+    return (uint16_t)(sign | (ex << 10) | man);
+}
+
+/* ---------------------------------------------------------------- quantizer */
+
+/*
+ * Quantize one group of G fp16 values to b-bit codes (Sec. 3.2, readings R1-R8).
+ * codes: one byte per element (unpacked).  scale_h, zero_h: fp16 bit patterns.
+ */
+void oracle_quant_group(const uint16_t *x, int G, int bits,
+                        uint8_t *codes, uint16_t *scale_h, uint16_t *zero_h)
+{
+    const float qmax = (float)((1 << bits) - 1);
+    float mn = 0.0f, mx = 0.0f;                       /* R5: range includes 0 */
+    for (int i = 0; i < G; ++i) {
+        float v = oracle_h2f(x[i]);
+        if (v < mn) mn = v;
+        if (v > mx) mx = v;
+    }
+    float r = mx - mn;
+    float l32 = r / qmax;                             /* lambda = (max-min)/(2^b-1) */
+    uint16_t h = oracle_f2h_rne(l32);
+    if (oracle_h2f(h) < l32) h = (uint16_t)(h + 1);   /* R7: next fp16 above */
+    if (h < 0x0400u) h = 0x0400u;                     /* R6: floor 2^-14 */
+    float lam = oracle_h2f(h);
+    float inv = 1.0f / lam;                           /* R8 */
+    float zf = nearbyintf((-mn) * inv);               /* R1, R3 */
+    if (zf < 0.0f) zf = 0.0f;
+    if (zf > qmax) zf = qmax;                         /* R2 */
+    zf = (float)(int)zf;                              /* an integer; -0 becomes +0 */
+    for (int i = 0; i < G; ++i) {
+        float u = fmaf(oracle_h2f(x[i]), inv, zf);    /* R4: one rounding */
+        float q = nearbyintf(u);                      /* R3 */
+        if (q < 0.0f) q = 0.0f;
+        if (q > qmax) q = qmax;                       /* R2 */
+        codes[i] = (uint8_t)q;
+    }
+    *scale_h = h;
+    *zero_h = oracle_f2h_rne(zf);                     /* integers <= 255 are exact */
+}
+
+/* Exact fp32 dequantized value lambda * (x_q - z) (R9). */
+static float dequant_f32(uint8_t code, uint16_t scale_h, uint16_t zero_h)
+{
+    float lam = oracle_h2f(scale_h);
+    int z = (int)oracle_h2f(zero_h);
+    return lam * (float)((int)code - z);
+}
+
+/* ---------------------------------------------------------------- cache layout
+ * codes: uint8 [num_pages][Hkv][P][D*bits/8]
+ * meta : fp16  [num_pages][Hkv][P][D/G][2] = (scale, zero)
+ */
+typedef struct {
+    uint8_t *k_codes, *v_codes;
+    uint16_t *k_meta, *v_meta;
+    int32_t num_pages, page_size, num_kv_heads, head_dim, bits, group_size;
+} oracle_cache;
+
+static size_t row_index(const oracle_cache *c, int64_t page, int head, int off)
+{
+    return ((size_t)page * c->num_kv_heads + head) * c->page_size + off;
+}
+
+static uint8_t get_code(const oracle_cache *c, const uint8_t *codes, size_t row, int d)
+{
+    size_t rb = (size_t)c->head_dim * c->bits / 8;
+    if (c->bits == 8) return codes[row * rb + d];
+    uint8_t byte = codes[row * rb + d / 2];           /* R14 */
+    return (d & 1) ? (uint8_t)(byte >> 4) : (uint8_t)(byte & 0xf);
+}
+
+static void put_code(const oracle_cache *c, uint8_t *codes, size_t row, int d, uint8_t q)
+{
+    size_t rb = (size_t)c->head_dim * c->bits / 8;
+    if (c->bits == 8) { codes[row * rb + d] = q; return; }
+    uint8_t *p = &codes[row * rb + d / 2];
+    if (d & 1) *p = (uint8_t)((*p & 0x0f) | (q << 4));
+    else       *p = (uint8_t)((*p & 0xf0) | (q & 0xf));
+}
+
+/* Step 1: quantize-and-write T tokens (k, v: fp16 [T][Hkv][D]) at slot_mapping[t]. */
+int oracle_kv_quant_write(const oracle_cache *c, const uint16_t *k, const uint16_t *v,
+                          const int64_t *slot_mapping, int32_t T)
+{
+    const int D = c->head_dim, G = c->group_size, ng = D / G;
+    uint8_t *tmp = (uint8_t *)malloc((size_t)G);
+    if (!tmp) return 1;
+    for (int32_t t = 0; t < T; ++t) {
+        int64_t s = slot_mapping[t];
+        if (s < 0) continue;
+        int64_t page = s / c->page_size;
+        int off = (int)(s % c->page_size);
+        for (int h = 0; h < c->num_kv_heads; ++h) {
+            size_t row = row_index(c, page, h, off);
+            for (int which = 0; which < 2; ++which) {
+                const uint16_t *src = (which ? v : k) + ((size_t)t * c->num_kv_heads + h) * D;
+                uint8_t *codes = which ? c->v_codes : c->k_codes;
+                uint16_t *meta = which ? c->v_meta : c->k_meta;
+                for (int g = 0; g < ng; ++g) {
+                    uint16_t sh, zh;
+                    oracle_quant_group(src + g * G, G, c->bits, tmp, &sh, &zh);
+                    for (int i = 0; i < G; ++i) put_code(c, codes, row, g * G + i, tmp[i]);
+                    meta[(row * ng + g) * 2 + 0] = sh;
+                    meta[(row * ng + g) * 2 + 1] = zh;
+                }
+            }
+        }
+    }
+    free(tmp);
+    return 0;
+}
+
+/*
+ * Step 2: single-query attention per request and query head over the cached,
+ * quantized tokens (Eq. 1-2; R9, R12, R13, R15, R16).  out: fp64 [B][H][D].
+ * (request, head) pairs are independent; num_threads only splits that loop.
+ */
+int oracle_paged_decode_attn(const oracle_cache *c, const uint16_t *q, double *out,
+                             const int32_t *block_tables, int32_t max_blocks_per_seq,
+                             const int32_t *context_lens, int32_t B, int32_t H,
+                             double softmax_scale, int32_t num_threads)
+{
+    const int D = c->head_dim, G = c->group_size, ng = D / G, P = c->page_size;
+    const int qper = H / c->num_kv_heads;
+    int fail = 0;
+    if (num_threads < 1) num_threads = 1;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(num_threads)
+    for (int64_t ih = 0; ih < (int64_t)B * H; ++ih) {
+        int i = (int)(ih / H), h = (int)(ih % H);
+        int hk = h / qper;                                        /* R15 */
+        int L = context_lens[i];
+        double *o = out + (size_t)ih * D;
+        for (int d = 0; d < D; ++d) o[d] = 0.0;
+        if (L <= 0) continue;                                     /* R16 */
+        double *s = (double *)malloc(sizeof(double) * (size_t)L);
+        if (!s) { fail = 1; continue; }
+        const uint16_t *qv = q + (size_t)ih * D;
+        double m = -INFINITY;
+        for (int t = 0; t < L; ++t) {
+            int64_t page = block_tables[(size_t)i * max_blocks_per_seq + t / P];
+            size_t row = row_index(c, page, hk, t % P);
+            double acc = 0.0;
+            for (int d = 0; d < D; ++d) {
+                int g = d / G;
+                float kd = dequant_f32(get_code(c, c->k_codes, row, d),
+                                       c->k_meta[(row * ng + g) * 2], c->k_meta[(row * ng + g) * 2 + 1]);
+                acc += (double)oracle_h2f(qv[d]) * (double)kd;
+            }
+            s[t] = acc * softmax_scale;
+            if (s[t] > m) m = s[t];
+        }
+        double denom = 0.0;
+        for (int t = 0; t < L; ++t) { s[t] = exp(s[t] - m); denom += s[t]; }
+        for (int t = 0; t < L; ++t) {
+            int64_t page = block_tables[(size_t)i * max_blocks_per_seq + t / P];
+            size_t row = row_index(c, page, hk, t % P);
+            double p = s[t] / denom;
+            for (int d = 0; d < D; ++d) {
+                int g = d / G;
+                float vd = dequant_f32(get_code(c, c->v_codes, row, d),
+                                       c->v_meta[(row * ng + g) * 2], c->v_meta[(row * ng + g) * 2 + 1]);
+                o[d] += p * (double)vd;
+            }
+        }
+        free(s);
+    }
+    return fail;
+}
+
+/* Step 3: one page back to fp16 K and V [P][Hkv][D], every slot (R9). */
+int oracle_kv_dequant_page(const oracle_cache *c, int32_t page, uint16_t *k_out, uint16_t *v_out)
+{
+    const int D = c->head_dim, G = c->group_size, ng = D / G;
+    for (int off = 0; off < c->page_size; ++off)
+        for (int h = 0; h < c->num_kv_heads; ++h) {
+            size_t row = row_index(c, page, h, off);
+            for (int d = 0; d < D; ++d) {
+                int g = d / G;
+                size_t o = ((size_t)off * c->num_kv_heads + h) * D + d;
+                k_out[o] = oracle_f2h_rne(dequant_f32(get_code(c, c->k_codes, row, d),
+                              c->k_meta[(row * ng + g) * 2], c->k_meta[(row * ng + g) * 2 + 1]));
+                v_out[o] = oracle_f2h_rne(dequant_f32(get_code(c, c->v_codes, row, d),
+                              c->v_meta[(row * ng + g) * 2], c->v_meta[(row * ng + g) * 2 + 1]));
+            }
+        }
+    return 0;
+}
+
+/*
+ * Unquantized single-query attention on dense fp64 K, V [L][D] for one head
+ * (Eq. 1): the plain definition, used to measure what quantization costs.
+ */
+void oracle_dense_attn(const double *q, const double *K, const double *V, int L, int D,
+                       double softmax_scale, double *out)
+{
+    for (int d = 0; d < D; ++d) out[d] = 0.0;
+    if (L <= 0) return;
+    double *s = (double *)malloc(sizeof(double) * (size_t)L);
+    double m = -INFINITY, denom = 0.0;
+    for (int t = 0; t < L; ++t) {
+        double acc = 0.0;
+        for (int d = 0; d < D; ++d) acc += q[d] * K[(size_t)t * D + d];
+        s[t] = acc * softmax_scale;
+        if (s[t] > m) m = s[t];
+    }
+    for (int t = 0; t < L; ++t) { s[t] = exp(s[t] - m); denom += s[t]; }
+    for (int t = 0; t < L; ++t)
+        for (int d = 0; d < D; ++d) out[d] += s[t] / denom * V[(size_t)t * D + d];
+    free(s);
+}
