@@ -1,0 +1,147 @@
+/*
+ * alise_kv.h -- C ABI of the MI355X (gfx950) quantized, paged KV-cache decode path.
+ *
+ * The three operations are the decode step of an LLM server that keeps its KV
+ * cache compressed (ALISE, arXiv 2410.23537):
+ *   - the cache stores b-bit integer codes with one (scale, zero-point) pair per
+ *     group: x_q = round(x / lambda + z), x = lambda (x_q - z),
+ *     lambda = (max - min) / (2^b - 1)                       [Sec. 3.2, "KV Compression"]
+ *   - each decode iteration appends the new token's K/V to the cache and attends
+ *     over all cached tokens                                  [Sec. 2, "LLM Inference"]
+ *   - per head, Attn = softmax(q K^T / sqrt(d/h)) V; heads are concatenated
+ *                                                             [Sec. 2, Eq. 1 and Eq. 2]
+ *   - the cache is block-level (paged), as in PagedAttention  [Sec. 3.3]
+ *
+ * General rules
+ *   - Every pointer named "device" is a HIP device pointer valid on the current
+ *     device; every other pointer is a host pointer.  Nothing is retained after a
+ *     call returns; the caller owns all buffers, including the workspace.
+ *   - All calls enqueue work on `hip_stream` (a hipStream_t cast to void*, NULL =
+ *     the default stream) and return without synchronising.
+ *   - Return value: ALISE_OK or an error code below.  Arguments that can be
+ *     checked on the host are checked before any HIP call, so the error paths
+ *     need no GPU.  Contents of device arrays (slot or page indices out of range,
+ *     duplicate slots in one call, context_lens[i] > max_context_len) are not
+ *     checked: out-of-range indices are undefined behaviour; lengths above
+ *     max_context_len are clamped to it.
+ *
+ * Exact arithmetic of the quantizer (so that codes and meta are reproducible bit
+ * for bit).  With x_0..x_{G-1} one group widened to fp32, qmax = 2^bits - 1 and
+ * every operation a single correctly rounded binary32 operation:
+ *     mn = min(min_i x_i, 0)   mx = max(max_i x_i, 0)
+ *     l32 = (mx - mn) / qmax
+ *     scale = smallest fp16 >= l32, but at least 2^-14          (stored)
+ *     inv = 1 / (float)scale
+ *     zero = clamp(rint((-mn) * inv), 0, qmax)                   (stored as fp16, +0 if 0)
+ *     code_i = clamp(rint(fma(x_i, inv, zero)), 0, qmax)         (rint: ties to even)
+ * Dequantized value: (float)scale * (code - zero), exact in fp32.
+ */
+#ifndef ALISE_KV_H
+#define ALISE_KV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    ALISE_OK = 0,
+    ALISE_INVALID_ARGUMENT = 1,     /* null pointer, negative or inconsistent size            */
+    ALISE_UNSUPPORTED = 2,          /* a shape outside the supported set listed below          */
+    ALISE_WORKSPACE_TOO_SMALL = 3,
+    ALISE_MISALIGNED = 4,           /* a pointer that must be 16-byte aligned is not           */
+    ALISE_HIP_ERROR = 5             /* a HIP call or kernel launch failed                      */
+};
+
+/*
+ * The compressed cache.  Caller-filled, passed by pointer, never retained.
+ *
+ * Layout (all device memory, row-major, 16-byte aligned bases):
+ *   k_codes, v_codes : uint8 [num_pages][num_kv_heads][page_size][head_dim*bits/8]
+ *                      bits = 4 packs channel 2i in the low nibble and channel
+ *                      2i+1 in the high nibble of byte i.
+ *   k_meta,  v_meta  : fp16  [num_pages][num_kv_heads][page_size][head_dim/group_size][2]
+ *                      = (scale, zero-point) of each group of `group_size`
+ *                      contiguous channels of one token's one head vector.
+ * Slot s of the cache is page s / page_size, offset s % page_size.
+ *
+ * Supported: bits in {4, 8}; head_dim in {64, 128}; group_size a divisor of
+ * head_dim and a multiple of 128/bits (16 for INT8, 32 for INT4);
+ * page_size a power of two in [8, 256]; num_pages * page_size < 2^31.
+ */
+typedef struct alise_kv_cache {
+    void *k_codes;
+    void *v_codes;
+    void *k_meta;
+    void *v_meta;
+    int32_t num_pages;
+    int32_t page_size;
+    int32_t num_kv_heads;
+    int32_t head_dim;
+    int32_t bits;
+    int32_t group_size;
+} alise_kv_cache;
+
+/* Bytes of one codes array / one meta array of `c` (0 if `c` is unsupported). */
+size_t alise_kv_codes_bytes(const alise_kv_cache *c);
+size_t alise_kv_meta_bytes(const alise_kv_cache *c);
+
+/*
+ * Quantize T new tokens and store them in the cache              [Sec. 3.2; Sec. 2]
+ *   k, v          device, fp16 [T][num_kv_heads][head_dim], 16-byte aligned.
+ *   slot_mapping  device, int64 [T]; token t goes to slot slot_mapping[t];
+ *                 a negative slot skips the token.  Slots must be distinct.
+ * Writes codes and meta of the addressed slots only.  T = 0 is a no-op.
+ */
+int alise_kv_quant_write(const alise_kv_cache *c, const void *k, const void *v,
+                         const int64_t *slot_mapping, int32_t T, void *hip_stream);
+
+/*
+ * Workspace the attention call needs for these sizes (0 on invalid arguments).
+ */
+size_t alise_paged_decode_attn_workspace_bytes(const alise_kv_cache *c, int32_t B,
+                                               int32_t num_q_heads, int32_t max_context_len);
+
+/*
+ * Single-query attention of B requests over their cached tokens   [Eq. 1, Eq. 2; Sec. 3.2]
+ *   q, out        device, fp16 [B][num_q_heads][head_dim], 16-byte aligned.
+ *   block_tables  device, int32 [B][max_blocks_per_seq]; entry j of request i is the
+ *                 page holding its tokens j*page_size .. ; entries at index
+ *                 >= ceil(L_i / page_size) are never read.
+ *   context_lens  device, int32 [B]; L_i counts the token written in this step.
+ *                 L_i <= 0 gives a zero output row.  Slots at positions >= L_i of
+ *                 the last page are never interpreted.
+ *   num_q_heads   a multiple of num_kv_heads; query head h reads KV head
+ *                 h / (num_q_heads / num_kv_heads).
+ *   softmax_scale 1/sqrt(head_dim) for Eq. 1.
+ *   workspace     device, 256-byte aligned, at least
+ *                 alise_paged_decode_attn_workspace_bytes(...) bytes; contents on
+ *                 entry are irrelevant, contents on exit are unspecified.  Calls
+ *                 that may overlap in time must use distinct workspaces.
+ * out[i][h] = sum_t softmax_t(softmax_scale * q[i][h] . k^_t) v^_t over t < L_i, with
+ * k^, v^ the dequantized rows; accumulated in fp32, rounded once to fp16.
+ */
+int alise_paged_decode_attn(const alise_kv_cache *c, const void *q, void *out,
+                            const int32_t *block_tables, int32_t max_blocks_per_seq,
+                            const int32_t *context_lens, int32_t B, int32_t num_q_heads,
+                            int32_t max_context_len, float softmax_scale,
+                            void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Dequantize one page back to fp16                                 [Sec. 3.2]
+ *   k_out, v_out  device, fp16 [page_size][num_kv_heads][head_dim], 16-byte aligned.
+ * Every slot of the page is converted, written or not:
+ * out = fp16_round_nearest_even(scale * (code - zero)).
+ */
+int alise_kv_dequant_page(const alise_kv_cache *c, int32_t page, void *k_out, void *v_out,
+                          void *hip_stream);
+
+/* Static, human-readable name of a status code. */
+const char *alise_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ALISE_KV_H */

@@ -1,0 +1,171 @@
+"""Thin ctypes binding of ``libalise_kv.so`` -- argument marshalling only.
+
+Every function here has the name and the arguments of the C entry point it calls
+(``include/alise_kv.h``); tensors are torch device tensors used purely as device
+memory, the stream is torch's current HIP stream.  There is no fallback: if the
+library has not been built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libalise_kv.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()' "
+        "or python paper_2410_23537_amd/build.py); there is no CPU fallback")
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+ALISE_OK = 0
+ALISE_INVALID_ARGUMENT = 1
+ALISE_UNSUPPORTED = 2
+ALISE_WORKSPACE_TOO_SMALL = 3
+ALISE_MISALIGNED = 4
+ALISE_HIP_ERROR = 5
+
+EXPORTS = ("alise_kv_codes_bytes", "alise_kv_meta_bytes", "alise_kv_quant_write",
+           "alise_paged_decode_attn_workspace_bytes", "alise_paged_decode_attn",
+           "alise_kv_dequant_page", "alise_status_string")
+
+
+class alise_kv_cache(ctypes.Structure):
+    _fields_ = [("k_codes", ctypes.c_void_p), ("v_codes", ctypes.c_void_p),
+                ("k_meta", ctypes.c_void_p), ("v_meta", ctypes.c_void_p),
+                ("num_pages", ctypes.c_int32), ("page_size", ctypes.c_int32),
+                ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("bits", ctypes.c_int32), ("group_size", ctypes.c_int32)]
+
+
+_P = ctypes.POINTER(alise_kv_cache)
+_lib.alise_kv_codes_bytes.restype = ctypes.c_size_t
+_lib.alise_kv_codes_bytes.argtypes = [_P]
+_lib.alise_kv_meta_bytes.restype = ctypes.c_size_t
+_lib.alise_kv_meta_bytes.argtypes = [_P]
+_lib.alise_kv_quant_write.restype = ctypes.c_int
+_lib.alise_kv_quant_write.argtypes = [_P, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                      ctypes.c_int32, ctypes.c_void_p]
+_lib.alise_paged_decode_attn_workspace_bytes.restype = ctypes.c_size_t
+_lib.alise_paged_decode_attn_workspace_bytes.argtypes = [_P, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
+_lib.alise_paged_decode_attn.restype = ctypes.c_int
+_lib.alise_paged_decode_attn.argtypes = [_P, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                         ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
+                                         ctypes.c_int32, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t,
+                                         ctypes.c_void_p]
+_lib.alise_kv_dequant_page.restype = ctypes.c_int
+_lib.alise_kv_dequant_page.argtypes = [_P, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+_lib.alise_status_string.restype = ctypes.c_char_p
+_lib.alise_status_string.argtypes = [ctypes.c_int]
+
+
+class AliseError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {alise_status_string(status)}")
+
+
+def alise_status_string(status: int) -> str:
+    return _lib.alise_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != ALISE_OK:
+        raise AliseError(status, where)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dp(t) -> int:
+    return 0 if t is None else t.data_ptr()
+
+
+@dataclass
+class KVCache:
+    """Device buffers of the compressed cache plus its geometry (see alise_kv_cache in the header)."""
+    k_codes: torch.Tensor   # uint8 [num_pages, Hkv, P, D*bits/8]
+    v_codes: torch.Tensor
+    k_meta: torch.Tensor    # fp16  [num_pages, Hkv, P, D/G, 2]
+    v_meta: torch.Tensor
+    num_pages: int
+    page_size: int
+    num_kv_heads: int
+    head_dim: int
+    bits: int
+    group_size: int
+
+    @staticmethod
+    def allocate(num_pages, page_size, num_kv_heads, head_dim, bits, group_size, device="cuda", fill=None):
+        cshape = (num_pages, num_kv_heads, page_size, head_dim * bits // 8)
+        mshape = (num_pages, num_kv_heads, page_size, head_dim // group_size, 2)
+        mk = (lambda s, dt: torch.empty(s, dtype=dt, device=device)) if fill is None else \
+             (lambda s, dt: torch.full(s, fill, dtype=dt, device=device))
+        return KVCache(mk(cshape, torch.uint8), mk(cshape, torch.uint8), mk(mshape, torch.float16),
+                       mk(mshape, torch.float16), num_pages, page_size, num_kv_heads, head_dim, bits, group_size)
+
+    def c_struct(self) -> alise_kv_cache:
+        return alise_kv_cache(_dp(self.k_codes), _dp(self.v_codes), _dp(self.k_meta), _dp(self.v_meta),
+                              self.num_pages, self.page_size, self.num_kv_heads, self.head_dim,
+                              self.bits, self.group_size)
+
+
+def alise_kv_codes_bytes(cache: KVCache) -> int:
+    return _lib.alise_kv_codes_bytes(ctypes.byref(cache.c_struct()))
+
+
+def alise_kv_meta_bytes(cache: KVCache) -> int:
+    return _lib.alise_kv_meta_bytes(ctypes.byref(cache.c_struct()))
+
+
+def alise_kv_quant_write(cache: KVCache, k: torch.Tensor, v: torch.Tensor, slot_mapping: torch.Tensor) -> None:
+    """k, v: fp16 [T, Hkv, D] device; slot_mapping: int64 [T] device."""
+    T = int(slot_mapping.numel())
+    assert k.dtype == torch.float16 and v.dtype == torch.float16 and slot_mapping.dtype == torch.int64
+    assert k.is_contiguous() and v.is_contiguous() and slot_mapping.is_contiguous()
+    assert tuple(k.shape) == (T, cache.num_kv_heads, cache.head_dim) == tuple(v.shape)
+    st = _lib.alise_kv_quant_write(ctypes.byref(cache.c_struct()), _dp(k), _dp(v), _dp(slot_mapping), T, _stream())
+    _check(st, "alise_kv_quant_write")
+
+
+def alise_paged_decode_attn_workspace_bytes(cache: KVCache, B: int, num_q_heads: int, max_context_len: int) -> int:
+    return _lib.alise_paged_decode_attn_workspace_bytes(ctypes.byref(cache.c_struct()), B, num_q_heads,
+                                                        max_context_len)
+
+
+def alise_paged_decode_attn(cache: KVCache, q: torch.Tensor, out: torch.Tensor, block_tables: torch.Tensor,
+                            context_lens: torch.Tensor, max_context_len: int, softmax_scale: float,
+                            workspace: torch.Tensor) -> None:
+    """q, out: fp16 [B, H, D]; block_tables: int32 [B, max_blocks]; context_lens: int32 [B];
+    workspace: uint8 device tensor of at least alise_paged_decode_attn_workspace_bytes(...) bytes."""
+    B, H, D = q.shape
+    assert q.dtype == torch.float16 and out.dtype == torch.float16 and tuple(out.shape) == (B, H, D)
+    assert block_tables.dtype == torch.int32 and context_lens.dtype == torch.int32
+    assert q.is_contiguous() and out.is_contiguous() and block_tables.is_contiguous() and context_lens.is_contiguous()
+    assert block_tables.shape[0] == B and context_lens.numel() == B
+    st = _lib.alise_paged_decode_attn(ctypes.byref(cache.c_struct()), _dp(q), _dp(out), _dp(block_tables),
+                                      int(block_tables.shape[1]), _dp(context_lens), B, H, int(max_context_len),
+                                      float(softmax_scale), _dp(workspace),
+                                      int(workspace.numel() * workspace.element_size()), _stream())
+    _check(st, "alise_paged_decode_attn")
+
+
+def alise_kv_dequant_page(cache: KVCache, page: int, k_out: torch.Tensor, v_out: torch.Tensor) -> None:
+    """k_out, v_out: fp16 [P, Hkv, D] device."""
+    shape = (cache.page_size, cache.num_kv_heads, cache.head_dim)
+    assert tuple(k_out.shape) == shape == tuple(v_out.shape)
+    assert k_out.dtype == torch.float16 and v_out.dtype == torch.float16
+    assert k_out.is_contiguous() and v_out.is_contiguous()
+    st = _lib.alise_kv_dequant_page(ctypes.byref(cache.c_struct()), int(page), _dp(k_out), _dp(v_out), _stream())
+    _check(st, "alise_kv_dequant_page")
+
+
+def raw():
+    """The ctypes library handle, for tests of the error paths."""
+    return _lib

@@ -1,0 +1,228 @@
+// C-ABI layer: argument validation (host only, before any HIP call), workspace
+// carving and kernel launches.  See include/alise_kv.h for the contract.
+#include "../../include/alise_kv.h"
+#include "alise_kernels.h"
+
+#include <cstdlib>
+
+namespace {
+
+using alise::AttnWorkspace;
+using alise::CacheView;
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline int ilog2_exact(int32_t v)
+{
+    if (v <= 0 || (v & (v - 1))) return -1;
+    int l = 0;
+    while ((1 << l) < v) ++l;
+    return l;
+}
+
+// Shape checks shared by every entry point.
+int check_cache(const alise_kv_cache *c, CacheView *out)
+{
+    if (!c) return ALISE_INVALID_ARGUMENT;
+    if (c->num_pages <= 0 || c->page_size <= 0 || c->num_kv_heads <= 0 || c->head_dim <= 0 ||
+        c->group_size <= 0)
+        return ALISE_INVALID_ARGUMENT;
+    if (c->bits != 4 && c->bits != 8) return ALISE_UNSUPPORTED;
+    if (c->head_dim != 64 && c->head_dim != 128) return ALISE_UNSUPPORTED;
+    if (c->head_dim % c->group_size != 0) return ALISE_UNSUPPORTED;
+    if (c->group_size % (128 / c->bits) != 0) return ALISE_UNSUPPORTED;
+    const int logP = ilog2_exact(c->page_size);
+    if (logP < 3 || logP > 8) return ALISE_UNSUPPORTED;
+    if ((int64_t)c->num_pages * c->page_size >= (int64_t)1 << 31) return ALISE_UNSUPPORTED;
+    if (out) {
+        out->k_codes = static_cast<uint8_t *>(c->k_codes);
+        out->v_codes = static_cast<uint8_t *>(c->v_codes);
+        out->k_meta = static_cast<uint32_t *>(c->k_meta);
+        out->v_meta = static_cast<uint32_t *>(c->v_meta);
+        out->num_pages = c->num_pages;
+        out->P = c->page_size;
+        out->logP = logP;
+        out->Hkv = c->num_kv_heads;
+        out->D = c->head_dim;
+        out->bits = c->bits;
+        out->G = c->group_size;
+        out->NG = c->head_dim / c->group_size;
+        out->row_code_bytes = c->head_dim * c->bits / 8;
+    }
+    return ALISE_OK;
+}
+
+int check_cache_pointers(const alise_kv_cache *c)
+{
+    if (!c->k_codes || !c->v_codes || !c->k_meta || !c->v_meta) return ALISE_INVALID_ARGUMENT;
+    if (!aligned16(c->k_codes) || !aligned16(c->v_codes) || !aligned16(c->k_meta) || !aligned16(c->v_meta))
+        return ALISE_MISALIGNED;
+    return ALISE_OK;
+}
+
+// Tokens per split.  Long requests are cut into splits of this many tokens so that
+// one long and many short requests fill the chip alike; ALISE_SPLIT_TOKENS overrides
+// the default (a multiple of 64) for tuning.
+int32_t split_tokens()
+{
+    static const int32_t cached = [] {
+        const char *e = std::getenv("ALISE_SPLIT_TOKENS");
+        long v = e ? std::strtol(e, nullptr, 10) : 0;
+        if (v < 64 || v > (1 << 20) || (v % 64) != 0) v = 512;
+        return (int32_t)v;
+    }();
+    return cached;
+}
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Workspace layout: [counter, n_items | tile_base[B+1] | tile_req[max_tiles] | part].
+size_t carve_workspace(const CacheView &c, int32_t B, int32_t H, int32_t max_len, void *base,
+                       AttnWorkspace *ws)
+{
+    const int32_t C = split_tokens();
+    const int64_t splits = ((int64_t)max_len + C - 1) / C;
+    const int64_t max_tiles = (int64_t)B * (splits > 0 ? splits : 1);
+    size_t off = 256;
+    const size_t off_base = off;
+    off = align_up(off + sizeof(int32_t) * ((size_t)B + 1), 256);
+    const size_t off_req = off;
+    off = align_up(off + sizeof(int32_t) * (size_t)max_tiles, 256);
+    const size_t off_part = off;
+    off = align_up(off + sizeof(float) * (size_t)max_tiles * H * (c.D + 2), 256);
+    if (ws) {
+        char *b = static_cast<char *>(base);
+        ws->counter = reinterpret_cast<uint32_t *>(b);
+        ws->n_items = reinterpret_cast<int32_t *>(b + 4);
+        ws->tile_base = reinterpret_cast<int32_t *>(b + off_base);
+        ws->tile_req = reinterpret_cast<int32_t *>(b + off_req);
+        ws->part = reinterpret_cast<float *>(b + off_part);
+        ws->max_tiles = (int32_t)max_tiles;
+        ws->chunk_tokens = C;
+    }
+    return off;
+}
+
+int check_attn_sizes(const CacheView &c, int32_t B, int32_t H, int32_t max_len)
+{
+    if (B < 0 || H <= 0 || max_len < 0) return ALISE_INVALID_ARGUMENT;
+    if (H % c.Hkv != 0) return ALISE_UNSUPPORTED;
+    const int64_t splits = ((int64_t)max_len + split_tokens() - 1) / split_tokens();
+    if ((int64_t)B * (splits > 0 ? splits : 1) * H >= (int64_t)1 << 31) return ALISE_UNSUPPORTED;
+    return ALISE_OK;
+}
+
+int num_compute_units()
+{
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t alise_kv_codes_bytes(const alise_kv_cache *c)
+{
+    if (check_cache(c, nullptr) != ALISE_OK) return 0;
+    return (size_t)c->num_pages * c->num_kv_heads * c->page_size * (c->head_dim * c->bits / 8);
+}
+
+size_t alise_kv_meta_bytes(const alise_kv_cache *c)
+{
+    if (check_cache(c, nullptr) != ALISE_OK) return 0;
+    return (size_t)c->num_pages * c->num_kv_heads * c->page_size * (c->head_dim / c->group_size) * 4;
+}
+
+int alise_kv_quant_write(const alise_kv_cache *c, const void *k, const void *v,
+                         const int64_t *slot_mapping, int32_t T, void *hip_stream)
+{
+    CacheView cv;
+    int st = check_cache(c, &cv);
+    if (st != ALISE_OK) return st;
+    if (T < 0) return ALISE_INVALID_ARGUMENT;
+    if (T == 0) return ALISE_OK;
+    if (!k || !v || !slot_mapping) return ALISE_INVALID_ARGUMENT;
+    st = check_cache_pointers(c);
+    if (st != ALISE_OK) return st;
+    if (!aligned16(k) || !aligned16(v)) return ALISE_MISALIGNED;
+    if ((reinterpret_cast<uintptr_t>(slot_mapping) & 7u) != 0) return ALISE_MISALIGNED;
+    hipError_t e = alise::launch_quant_write(cv, k, v, slot_mapping, T, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? ALISE_OK : ALISE_HIP_ERROR;
+}
+
+size_t alise_paged_decode_attn_workspace_bytes(const alise_kv_cache *c, int32_t B, int32_t num_q_heads,
+                                               int32_t max_context_len)
+{
+    CacheView cv;
+    if (check_cache(c, &cv) != ALISE_OK) return 0;
+    if (check_attn_sizes(cv, B, num_q_heads, max_context_len) != ALISE_OK) return 0;
+    return carve_workspace(cv, B, num_q_heads, max_context_len, nullptr, nullptr);
+}
+
+int alise_paged_decode_attn(const alise_kv_cache *c, const void *q, void *out,
+                            const int32_t *block_tables, int32_t max_blocks_per_seq,
+                            const int32_t *context_lens, int32_t B, int32_t num_q_heads,
+                            int32_t max_context_len, float softmax_scale,
+                            void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    CacheView cv;
+    int st = check_cache(c, &cv);
+    if (st != ALISE_OK) return st;
+    st = check_attn_sizes(cv, B, num_q_heads, max_context_len);
+    if (st != ALISE_OK) return st;
+    if (B == 0) return ALISE_OK;
+    if (max_blocks_per_seq <= 0) return ALISE_INVALID_ARGUMENT;
+    if ((int64_t)max_blocks_per_seq * cv.P < max_context_len) return ALISE_INVALID_ARGUMENT;
+    if (!(softmax_scale == softmax_scale) || softmax_scale <= 0.0f) return ALISE_INVALID_ARGUMENT;
+    if (!q || !out || !block_tables || !context_lens || !workspace) return ALISE_INVALID_ARGUMENT;
+    st = check_cache_pointers(c);
+    if (st != ALISE_OK) return st;
+    if (!aligned16(q) || !aligned16(out)) return ALISE_MISALIGNED;
+    if ((reinterpret_cast<uintptr_t>(block_tables) & 3u) || (reinterpret_cast<uintptr_t>(context_lens) & 3u))
+        return ALISE_MISALIGNED;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return ALISE_MISALIGNED;
+    AttnWorkspace ws;
+    const size_t need = carve_workspace(cv, B, num_q_heads, max_context_len, workspace, &ws);
+    if (workspace_bytes < need) return ALISE_WORKSPACE_TOO_SMALL;
+    hipError_t e = alise::launch_decode_attn(cv, q, out, block_tables, max_blocks_per_seq, context_lens, B,
+                                             num_q_heads, max_context_len, softmax_scale, ws,
+                                             num_compute_units(), static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? ALISE_OK : ALISE_HIP_ERROR;
+}
+
+int alise_kv_dequant_page(const alise_kv_cache *c, int32_t page, void *k_out, void *v_out, void *hip_stream)
+{
+    CacheView cv;
+    int st = check_cache(c, &cv);
+    if (st != ALISE_OK) return st;
+    if (page < 0 || page >= c->num_pages) return ALISE_INVALID_ARGUMENT;
+    if (!k_out || !v_out) return ALISE_INVALID_ARGUMENT;
+    st = check_cache_pointers(c);
+    if (st != ALISE_OK) return st;
+    if (!aligned16(k_out) || !aligned16(v_out)) return ALISE_MISALIGNED;
+    hipError_t e = alise::launch_dequant_page(cv, page, k_out, v_out, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? ALISE_OK : ALISE_HIP_ERROR;
+}
+
+const char *alise_status_string(int status)
+{
+    switch (status) {
+    case ALISE_OK: return "ALISE_OK";
+    case ALISE_INVALID_ARGUMENT: return "ALISE_INVALID_ARGUMENT";
+    case ALISE_UNSUPPORTED: return "ALISE_UNSUPPORTED";
+    case ALISE_WORKSPACE_TOO_SMALL: return "ALISE_WORKSPACE_TOO_SMALL";
+    case ALISE_MISALIGNED: return "ALISE_MISALIGNED";
+    case ALISE_HIP_ERROR: return "ALISE_HIP_ERROR";
+    default: return "ALISE_UNKNOWN_STATUS";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,39 @@
+// Internal launch interface between the C-ABI layer and the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace alise {
+
+// Geometry of the compressed cache, validated by the ABI layer.
+struct CacheView {
+    uint8_t *k_codes, *v_codes;
+    uint32_t *k_meta, *v_meta;      // one dword per group: fp16 scale (low half), fp16 zero (high half)
+    int32_t num_pages, P, logP, Hkv, D, bits, G, NG;
+    int32_t row_code_bytes;         // D * bits / 8
+};
+
+// Workspace carved up by the ABI layer for one attention call.
+struct AttnWorkspace {
+    uint32_t *counter;      // [1]  next work item, reset by the plan kernel
+    int32_t *n_items;       // [1]  tiles * H, written by the plan kernel
+    int32_t *tile_base;     // [B+1] first tile of each request (exclusive scan of chunk counts)
+    int32_t *tile_req;      // [max_tiles] request of each tile
+    float *part;            // [max_tiles * H][D + 2] = (m, l, o[D]) of every split
+    int32_t max_tiles;
+    int32_t chunk_tokens;   // tokens per split
+};
+
+hipError_t launch_quant_write(const CacheView &c, const void *k, const void *v,
+                              const int64_t *slot_mapping, int32_t T, hipStream_t s);
+
+hipError_t launch_dequant_page(const CacheView &c, int32_t page, void *k_out, void *v_out,
+                               hipStream_t s);
+
+hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
+                              const int32_t *block_tables, int32_t max_blocks,
+                              const int32_t *context_lens, int32_t B, int32_t H,
+                              int32_t max_context_len, float softmax_scale,
+                              const AttnWorkspace &ws, int32_t num_cus, hipStream_t s);
+
+}  // namespace alise

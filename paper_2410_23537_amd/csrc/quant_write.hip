@@ -1,0 +1,192 @@
+// Quantize-and-write and page dequantize kernels for gfx950.
+//
+// Quantizer: ALISE Sec. 3.2 ("KV Compression"): x_q = round(x/lambda + z),
+// x = lambda (x_q - z), lambda = (max - min)/(2^b - 1).  The exact sequence of
+// single-rounding fp32 operations is the one stated in include/alise_kv.h; it
+// must be followed to the letter because codes and meta are compared bit for bit.
+//
+// Mapping: one lane owns 8 consecutive channels of one (token, kv-head, K|V) row
+// (one 16-byte load).  A row is D/8 lanes, a group G/8 lanes; min/max travel over
+// the lanes of a group with xor-shuffles.  Both kernels are pure streaming:
+// 16-byte loads, 8- or 4-byte code stores (16-byte stores for dequantize).
+#include "alise_kernels.h"
+
+#include <hip/hip_fp16.h>
+
+namespace alise {
+namespace {
+
+typedef _Float16 h8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 h2_t __attribute__((ext_vector_type(2)));
+
+struct QuantParams {
+    CacheView c;
+    const _Float16 *k, *v;
+    const int64_t *slots;
+    int32_t T;
+    int32_t lanes_per_row;      // D / 8
+    int32_t lanes_per_group;    // G / 8
+    int64_t total_lanes;        // T * Hkv * 2 * lanes_per_row
+};
+
+__device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
+
+__global__ __launch_bounds__(256) void quant_write_kernel(QuantParams p)
+{
+    const int64_t gl = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    // Rows are ordered (token, K|V, head): the lanes of a wave stay inside one
+    // tensor's contiguous [Hkv][D] slab of one token as long as possible.
+    const int lpr = p.lanes_per_row;
+    const bool live = gl < p.total_lanes;
+    const int64_t g = live ? gl : p.total_lanes - 1;
+    const int lane_in_row = (int)(g % lpr);
+    const int64_t row = g / lpr;
+    const int head = (int)(row % p.c.Hkv);
+    const int64_t tw = row / p.c.Hkv;
+    const int which = (int)(tw & 1);
+    const int64_t t = tw >> 1;
+
+    const _Float16 *src = (which ? p.v : p.k) + (t * p.c.Hkv + head) * p.c.D + lane_in_row * 8;
+    const h8_t x = *reinterpret_cast<const h8_t *>(src);
+    const int64_t slot = p.slots[t];
+
+    float xf[8];
+    float mn = 0.0f, mx = 0.0f;          // the range always includes 0
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        xf[i] = (float)x[i];
+        mn = fminf(mn, xf[i]);
+        mx = fmaxf(mx, xf[i]);
+    }
+    for (int d = 1; d < p.lanes_per_group; d <<= 1) {
+        mn = fminf(mn, __shfl_xor(mn, d));
+        mx = fmaxf(mx, __shfl_xor(mx, d));
+    }
+    const float qmax = (float)((1 << p.c.bits) - 1);
+    const float r = mx - mn;
+    const float l32 = r / qmax;
+    _Float16 h = (_Float16)l32;                       // round to nearest even
+    uint16_t hb = __builtin_bit_cast(uint16_t, h);
+    if ((float)h < l32) hb = (uint16_t)(hb + 1);      // scale is rounded up
+    if (hb < 0x0400u) hb = 0x0400u;                   // floor at 2^-14
+    const float lam = (float)__builtin_bit_cast(_Float16, hb);
+    const float inv = 1.0f / lam;
+    float zf = __builtin_rintf((-mn) * inv);
+    zf = fminf(fmaxf(zf, 0.0f), qmax);
+    const int zi = (int)zf;
+    zf = (float)zi;
+    uint32_t code[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        float u = __builtin_fmaf(xf[i], inv, zf);     // one rounding
+        float qv = __builtin_rintf(u);
+        qv = fminf(fmaxf(qv, 0.0f), qmax);
+        code[i] = (uint32_t)(int)qv;
+    }
+    if (!live || slot < 0) return;
+
+    const int64_t page = slot >> p.c.logP;
+    const int off = (int)(slot & (p.c.P - 1));
+    const int64_t crow = (page * p.c.Hkv + head) * p.c.P + off;
+    uint8_t *codes = which ? p.c.v_codes : p.c.k_codes;
+    uint32_t *meta = which ? p.c.v_meta : p.c.k_meta;
+    if (p.c.bits == 8) {
+        uint2 w;
+        w.x = code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24);
+        w.y = code[4] | (code[5] << 8) | (code[6] << 16) | (code[7] << 24);
+        *reinterpret_cast<uint2 *>(codes + crow * p.c.row_code_bytes + lane_in_row * 8) = w;
+    } else {
+        uint32_t w = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) w |= code[i] << (4 * i);   // channel 2i low nibble, 2i+1 high
+        *reinterpret_cast<uint32_t *>(codes + crow * p.c.row_code_bytes + lane_in_row * 4) = w;
+    }
+    if ((lane_in_row % p.lanes_per_group) == 0) {
+        const int grp = lane_in_row / p.lanes_per_group;
+        const uint16_t zb = __builtin_bit_cast(uint16_t, (_Float16)zf);
+        meta[crow * p.c.NG + grp] = (uint32_t)hb | ((uint32_t)zb << 16);
+    }
+}
+
+struct DequantParams {
+    CacheView c;
+    int32_t page;
+    _Float16 *k_out, *v_out;
+    int32_t lanes_per_row;      // D / 8
+    int32_t total_lanes;        // P * Hkv * 2 * lanes_per_row
+};
+
+__global__ __launch_bounds__(256) void dequant_page_kernel(DequantParams p)
+{
+    const int gl = blockIdx.x * 256 + threadIdx.x;
+    if (gl >= p.total_lanes) return;
+    const int lpr = p.lanes_per_row;
+    const int lane_in_row = gl % lpr;
+    int row = gl / lpr;                     // (which, head, off): follows the cache's own order
+    const int off = row % p.c.P;
+    row /= p.c.P;
+    const int head = row % p.c.Hkv;
+    const int which = row / p.c.Hkv;
+
+    const int64_t crow = ((int64_t)p.page * p.c.Hkv + head) * p.c.P + off;
+    const uint8_t *codes = which ? p.c.v_codes : p.c.k_codes;
+    const uint32_t *meta = which ? p.c.v_meta : p.c.k_meta;
+    const int grp = (lane_in_row * 8) / p.c.G;
+    const uint32_t m = meta[crow * p.c.NG + grp];
+    const float lam = (float)__builtin_bit_cast(_Float16, (uint16_t)(m & 0xffffu));
+    const float z = (float)__builtin_bit_cast(_Float16, (uint16_t)(m >> 16));
+    uint32_t code[8];
+    if (p.c.bits == 8) {
+        const uint2 w = *reinterpret_cast<const uint2 *>(codes + crow * p.c.row_code_bytes + lane_in_row * 8);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            code[i] = (w.x >> (8 * i)) & 0xffu;
+            code[4 + i] = (w.y >> (8 * i)) & 0xffu;
+        }
+    } else {
+        const uint32_t w = *reinterpret_cast<const uint32_t *>(codes + crow * p.c.row_code_bytes + lane_in_row * 4);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) code[i] = (w >> (4 * i)) & 0xfu;
+    }
+    h8_t o;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = (_Float16)(lam * ((float)code[i] - z));   // product is exact in fp32
+    _Float16 *dst = (which ? p.v_out : p.k_out) + ((int64_t)off * p.c.Hkv + head) * p.c.D + lane_in_row * 8;
+    *reinterpret_cast<h8_t *>(dst) = o;
+}
+
+}  // namespace
+
+hipError_t launch_quant_write(const CacheView &c, const void *k, const void *v,
+                              const int64_t *slot_mapping, int32_t T, hipStream_t s)
+{
+    if (T == 0) return hipSuccess;
+    QuantParams p;
+    p.c = c;
+    p.k = static_cast<const _Float16 *>(k);
+    p.v = static_cast<const _Float16 *>(v);
+    p.slots = slot_mapping;
+    p.T = T;
+    p.lanes_per_row = c.D / 8;
+    p.lanes_per_group = c.G / 8;
+    p.total_lanes = (int64_t)T * c.Hkv * 2 * p.lanes_per_row;
+    const int64_t blocks = (p.total_lanes + 255) / 256;
+    hipLaunchKernelGGL(quant_write_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_dequant_page(const CacheView &c, int32_t page, void *k_out, void *v_out, hipStream_t s)
+{
+    DequantParams p;
+    p.c = c;
+    p.page = page;
+    p.k_out = static_cast<_Float16 *>(k_out);
+    p.v_out = static_cast<_Float16 *>(v_out);
+    p.lanes_per_row = c.D / 8;
+    p.total_lanes = c.P * c.Hkv * 2 * p.lanes_per_row;
+    const int blocks = (p.total_lanes + 255) / 256;
+    hipLaunchKernelGGL(dequant_page_kernel, dim3(blocks), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
+}  // namespace alise

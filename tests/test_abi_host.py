@@ -1,0 +1,131 @@
+"""Host-side checks of the C-ABI library: it loads, exports every symbol the header
+declares, and rejects bad arguments before touching a GPU (no compute calls here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "alise_kv.h")
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2410_23537_amd import binding
+    return binding
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(alise_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_exports_match_header(B):
+    names = _declared_functions()
+    assert set(names) == set(B.EXPORTS)
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings(B):
+    for code, name in [(0, "ALISE_OK"), (1, "ALISE_INVALID_ARGUMENT"), (2, "ALISE_UNSUPPORTED"),
+                       (3, "ALISE_WORKSPACE_TOO_SMALL"), (4, "ALISE_MISALIGNED"), (5, "ALISE_HIP_ERROR")]:
+        assert B.alise_status_string(code) == name
+    assert B.alise_status_string(99) == "ALISE_UNKNOWN_STATUS"
+
+
+def _cache(B, **kw):
+    base = dict(k_codes=0x1000, v_codes=0x2000, k_meta=0x3000, v_meta=0x4000, num_pages=10, page_size=16,
+                num_kv_heads=8, head_dim=128, bits=8, group_size=64)
+    base.update(kw)
+    return B.alise_kv_cache(**base)
+
+
+def test_layout_helpers(B):
+    lib = B.raw()
+    c = _cache(B)
+    assert lib.alise_kv_codes_bytes(ctypes.byref(c)) == 10 * 8 * 16 * 128
+    assert lib.alise_kv_meta_bytes(ctypes.byref(c)) == 10 * 8 * 16 * 2 * 4
+    c4 = _cache(B, bits=4, group_size=32)
+    assert lib.alise_kv_codes_bytes(ctypes.byref(c4)) == 10 * 8 * 16 * 64
+    assert lib.alise_kv_meta_bytes(ctypes.byref(c4)) == 10 * 8 * 16 * 4 * 4
+    assert lib.alise_kv_codes_bytes(ctypes.byref(_cache(B, bits=5))) == 0
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(bits=3), 2), (dict(bits=16), 2), (dict(head_dim=96), 2), (dict(group_size=48), 2),
+    (dict(group_size=8), 2), (dict(bits=4, group_size=16), 2), (dict(page_size=12), 2),
+    (dict(page_size=4), 2), (dict(page_size=512), 2), (dict(num_pages=0), 1), (dict(num_kv_heads=-1), 1),
+    (dict(num_pages=1 << 28, page_size=16), 2),
+    (dict(k_codes=0), 1), (dict(v_meta=0), 1), (dict(k_codes=0x1008), 4),
+])
+def test_bad_cache_is_rejected_by_every_entry_point(B, kw, want):
+    lib = B.raw()
+    c = _cache(B, **kw)
+    assert lib.alise_kv_quant_write(ctypes.byref(c), 0x10000, 0x20000, 0x30000, 4, None) == want
+    assert lib.alise_kv_dequant_page(ctypes.byref(c), 0, 0x10000, 0x20000, None) == want
+    assert lib.alise_paged_decode_attn(ctypes.byref(c), 0x10000, 0x20000, 0x30000, 16, 0x40000, 2, 8, 256,
+                                       0.1, 0x50000, 1 << 30, None) == want
+
+
+def test_quant_write_arguments(B):
+    lib = B.raw()
+    c = _cache(B)
+    assert lib.alise_kv_quant_write(None, 0x10000, 0x20000, 0x30000, 4, None) == 1
+    assert lib.alise_kv_quant_write(ctypes.byref(c), 0x10000, 0x20000, 0x30000, -1, None) == 1
+    assert lib.alise_kv_quant_write(ctypes.byref(c), 0, 0, 0, 0, None) == 0          # T = 0: no-op
+    assert lib.alise_kv_quant_write(ctypes.byref(c), 0, 0x20000, 0x30000, 4, None) == 1
+    assert lib.alise_kv_quant_write(ctypes.byref(c), 0x10000, 0x20000, 0, 4, None) == 1
+    assert lib.alise_kv_quant_write(ctypes.byref(c), 0x10004, 0x20000, 0x30000, 4, None) == 4
+    assert lib.alise_kv_quant_write(ctypes.byref(c), 0x10000, 0x20000, 0x30004, 4, None) == 4
+
+
+def test_dequant_page_arguments(B):
+    lib = B.raw()
+    c = _cache(B)
+    assert lib.alise_kv_dequant_page(ctypes.byref(c), -1, 0x10000, 0x20000, None) == 1
+    assert lib.alise_kv_dequant_page(ctypes.byref(c), 10, 0x10000, 0x20000, None) == 1
+    assert lib.alise_kv_dequant_page(ctypes.byref(c), 0, 0, 0x20000, None) == 1
+    assert lib.alise_kv_dequant_page(ctypes.byref(c), 0, 0x10002, 0x20000, None) == 4
+
+
+def test_attention_arguments(B):
+    lib = B.raw()
+    c = _cache(B)
+    f = lib.alise_paged_decode_attn
+    ok = [ctypes.byref(c), 0x10000, 0x20000, 0x30000, 16, 0x40000, 2, 8, 256, 0.1, 0x50000, 1 << 30, None]
+
+    def call(**kw):
+        names = ["c", "q", "out", "bt", "mb", "lens", "B", "H", "maxlen", "scale", "ws", "wsb", "stream"]
+        a = list(ok)
+        for k, v in kw.items():
+            a[names.index(k)] = v
+        return f(*a)
+
+    assert call(B=0) == 0                      # empty batch: nothing to do, nothing launched
+    assert call(B=-1) == 1
+    assert call(H=0) == 1
+    assert call(H=12) == 2                     # not a multiple of the 8 KV heads
+    assert call(maxlen=-5) == 1
+    assert call(mb=0) == 1
+    assert call(mb=15) == 1                    # 15 pages of 16 cannot hold 256 tokens
+    assert call(scale=0.0) == 1
+    assert call(scale=float("nan")) == 1
+    assert call(q=0) == 1
+    assert call(out=0) == 1
+    assert call(bt=0) == 1
+    assert call(lens=0) == 1
+    assert call(ws=0) == 1
+    assert call(q=0x10008) == 4
+    assert call(bt=0x30002) == 4
+    assert call(ws=0x50010) == 4
+    need = lib.alise_paged_decode_attn_workspace_bytes(ctypes.byref(c), 2, 8, 256)
+    assert need > 0 and need % 256 == 0
+    assert call(wsb=need - 1) == 3
+    assert lib.alise_paged_decode_attn_workspace_bytes(ctypes.byref(c), 2, 12, 256) == 0
+    # the workspace grows with the batch and with the longest context
+    assert lib.alise_paged_decode_attn_workspace_bytes(ctypes.byref(c), 64, 8, 256) > need
+    assert lib.alise_paged_decode_attn_workspace_bytes(ctypes.byref(c), 2, 8, 1 << 16) > need

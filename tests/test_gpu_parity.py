@@ -1,0 +1,232 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle on the same
+seeded inputs.  Codes and meta bit for bit; attention within 2e-3 max-abs of the
+fp64 oracle (fp16 output); page dequantizer bit for bit."""
+import numpy as np
+import pytest
+
+from paper_2410_23537_amd import workloads as wl
+from tests import harness
+
+pytestmark = pytest.mark.gpu
+
+ATTN_TOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2410_23537_amd import binding
+    import oracle
+    oracle.build()
+    return binding, torch, oracle
+
+
+def _problem(w, lens=None):
+    pg = wl.paging(w, lens)
+    pool = wl.value_pool(w, n_min=int(max(1, pg.lens.max(initial=1))) * w.Hkv * w.D)
+    offs = wl.request_offsets(w)
+    gain = wl.k_channel_gain(w)
+    return pg, pool, offs, gain
+
+
+def _compare_caches(w, pg, dev, orc):
+    mask = harness.written_mask(w, pg)
+    for name in ("k_codes", "v_codes", "k_meta", "v_meta"):
+        d = getattr(dev, name).cpu().numpy()
+        o = getattr(orc, name)
+        if name.endswith("meta"):
+            d, o = d.view(np.uint16), o.view(np.uint16)
+        d = np.moveaxis(d, 1, 2)      # [page, off, head, ...]
+        o = np.moveaxis(o, 1, 2)
+        assert np.array_equal(d[mask], o[mask]), f"{name}: written slots differ"
+        assert np.array_equal(d[~mask], o[~mask]), f"{name}: untouched slots were modified"
+
+
+SMALL = [
+    wl.CONFIGS["tiny"],
+    wl.scaled(wl.CONFIGS["opt13b"], B=9, max_len=700),
+    wl.scaled(wl.CONFIGS["llama7b"], B=10, max_len=1300),
+    wl.replace(wl.scaled(wl.CONFIGS["gqa70b"], B=4, max_len=900), length_law="uniform:100,900"),
+    wl.scaled(wl.CONFIGS["int4"], B=24, max_len=1700),
+    wl.replace(wl.scaled(wl.CONFIGS["int4"], B=6, max_len=600, name="int4_d64"), D=64, G=32, P=32),
+    wl.replace(wl.scaled(wl.CONFIGS["opt13b"], B=5, max_len=300, name="int8_g16_p8"), G=16, P=8, Hkv=3, H=3),
+    wl.replace(wl.scaled(wl.CONFIGS["int4"], B=5, max_len=400, name="int4_g128_gqa"), G=128, Hkv=2, H=6, P=64),
+]
+
+
+@pytest.mark.parametrize("w", SMALL, ids=lambda w: w.name)
+def test_write_attend_dequant(env, w):
+    B, torch, oracle = env
+    print(f"case {w.name}: B={w.B} H={w.H} Hkv={w.Hkv} D={w.D} P={w.P} bits={w.bits} G={w.G}", flush=True)
+    pg, pool, offs, gain = _problem(w)
+    orc = harness.fill_oracle_cache(oracle, w, pg, pool, offs, gain)
+    dev = harness.fill_device_cache(B, torch, w, pg, pool, offs, gain, max_tokens_per_call=777)
+    _compare_caches(w, pg, dev, orc)
+
+    q = wl.queries(w)
+    want = oracle.paged_decode_attn(orc, q, pg.block_tables, pg.lens, 1.0 / np.sqrt(w.D), num_threads=8)
+    got = harness.run_device_attn(B, torch, w, dev, q, pg).astype(np.float64)
+    assert np.isfinite(got).all()
+    err = np.abs(got - want).max()
+    print(f"  max-abs attention error {err:.3e}", flush=True)
+    assert err <= ATTN_TOL
+
+    # page dequantizer on a fully written page, a partly written one and the untouched one
+    last = int(np.argmax(pg.lens % w.P != 0)) if np.any(pg.lens % w.P != 0) else 0
+    pages = {int(pg.block_tables[0, 0]), int(pg.block_tables[last, (int(pg.lens[last]) - 1) // w.P])}
+    k_out = torch.empty((w.P, w.Hkv, w.D), dtype=torch.float16, device="cuda")
+    v_out = torch.empty_like(k_out)
+    written = harness.written_mask(w, pg)
+    for page in pages:
+        B.alise_kv_dequant_page(dev, page, k_out, v_out)
+        torch.cuda.synchronize()
+        ko, vo = oracle.kv_dequant_page(orc, page)
+        rows = written[page]
+        assert np.array_equal(k_out.cpu().numpy().view(np.uint16)[rows], ko.view(np.uint16)[rows])
+        assert np.array_equal(v_out.cpu().numpy().view(np.uint16)[rows], vo.view(np.uint16)[rows])
+
+
+@pytest.mark.parametrize("bits,G", [(8, 64), (4, 32)])
+def test_edge_lengths_and_splits(env, bits, G):
+    """Empty and one-token requests, lengths around page and split boundaries, several splits."""
+    B, torch, oracle = env
+    lens = np.array([0, 1, 15, 16, 17, 63, 64, 65, 511, 512, 513, 1024, 1025, 2, 2100, 0, 3], np.int32)
+    w = wl.Workload("edges", B=len(lens), H=4, Hkv=4, D=128, P=16, bits=bits, G=G,
+                    length_law="fixed:1", seed=77 + bits, max_len=int(lens.max()))
+    print(f"case edges bits={bits} G={G}", flush=True)
+    pg, pool, offs, gain = _problem(w, lens)
+    orc = harness.fill_oracle_cache(oracle, w, pg, pool, offs, gain)
+    dev = harness.fill_device_cache(B, torch, w, pg, pool, offs, gain)
+    _compare_caches(w, pg, dev, orc)
+    q = wl.queries(w)
+    want = oracle.paged_decode_attn(orc, q, pg.block_tables, pg.lens, 1.0 / np.sqrt(w.D), num_threads=8)
+    got = harness.run_device_attn(B, torch, w, dev, q, pg).astype(np.float64)
+    assert np.isfinite(got).all()
+    assert not got[lens == 0].any()
+    assert np.abs(got - want).max() <= ATTN_TOL
+    # a larger max_context_len than any request changes the plan, not the result
+    wide = np.full((w.B, pg.max_blocks + 70), pg.poison_page, np.int32)
+    wide[:, :pg.max_blocks] = pg.block_tables
+    pg_wide = wl.Paging(pg.lens, wide, pg.num_pages, pg.poison_page, wide.shape[1])
+    got2 = harness.run_device_attn(B, torch, w, dev, q, pg_wide, max_len=int(lens.max()) + 1000).astype(np.float64)
+    assert np.array_equal(got, got2)
+
+
+def test_dominant_and_large_values(env):
+    """Scores with a wide spread (running maximum moves a lot) and |v| large enough that
+    a single V row carries almost all the weight."""
+    B, torch, oracle = env
+    print("case dominant", flush=True)
+    rng = np.random.default_rng(5)
+    Hkv, D, P, L = 2, 128, 16, 700
+    w = wl.Workload("dom", B=2, H=2, Hkv=Hkv, D=D, P=P, bits=8, G=32, length_law="fixed:700", seed=5, max_len=L)
+    pg = wl.paging(w, np.array([L, L], np.int32))
+    q = rng.standard_normal((2, Hkv, D)).astype(np.float16)
+    k = (rng.standard_normal((2, L, Hkv, D)) * 0.2).astype(np.float16)
+    v = (rng.standard_normal((2, L, Hkv, D)) * 0.8).astype(np.float16)
+    # keys that grow towards the end: every block brings a new maximum
+    ramp = np.linspace(0.0, 6.0, L, dtype=np.float32)[None, :, None, None]
+    k = (k.astype(np.float32) + ramp * q[:, None].astype(np.float32) / np.sqrt(D)).astype(np.float16)
+    k[1, 123] = (q[1].astype(np.float32) * 3).astype(np.float16)      # one dominant key
+    orc = oracle.Cache.empty(pg.num_pages, P, Hkv, D, 8, 32)
+    dev = B.KVCache.allocate(pg.num_pages, P, Hkv, D, 8, 32, fill=0)
+    for i in range(2):
+        slots = wl.slots_of(w, pg, i, 0, L)
+        oracle.kv_quant_write(orc, k[i], v[i], slots)
+        B.alise_kv_quant_write(dev, torch.from_numpy(k[i]).cuda(), torch.from_numpy(v[i]).cuda(),
+                               torch.from_numpy(slots).cuda())
+    torch.cuda.synchronize()
+    _compare_caches(w, pg, dev, orc)
+    want = oracle.paged_decode_attn(orc, q, pg.block_tables, pg.lens, 1.0 / np.sqrt(D))
+    got = harness.run_device_attn(B, torch, w, dev, q, pg).astype(np.float64)
+    assert np.abs(got - want).max() <= ATTN_TOL
+
+
+def test_skipped_slots_and_empty_write(env):
+    B, torch, oracle = env
+    print("case skipped slots", flush=True)
+    rng = np.random.default_rng(8)
+    P, Hkv, D, T = 16, 5, 64, 33
+    dev = B.KVCache.allocate(4, P, Hkv, D, 4, 32, fill=0x5A)
+    orc = oracle.Cache.empty(4, P, Hkv, D, 4, 32, fill=0x5A)
+    dev.k_meta.fill_(0.0)
+    dev.v_meta.fill_(0.0)
+    k = rng.standard_normal((T, Hkv, D)).astype(np.float16)
+    v = rng.standard_normal((T, Hkv, D)).astype(np.float16)
+    slots = rng.permutation(4 * P)[:T].astype(np.int64)
+    slots[[0, 7, 32]] = -1
+    oracle.kv_quant_write(orc, k, v, slots)
+    B.alise_kv_quant_write(dev, torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda(), torch.from_numpy(slots).cuda())
+    B.alise_kv_quant_write(dev, torch.empty((0, Hkv, D), dtype=torch.float16, device="cuda"),
+                           torch.empty((0, Hkv, D), dtype=torch.float16, device="cuda"),
+                           torch.empty(0, dtype=torch.int64, device="cuda"))
+    torch.cuda.synchronize()
+    for name in ("k_codes", "v_codes", "k_meta", "v_meta"):
+        d = getattr(dev, name).cpu().numpy()
+        o = getattr(orc, name)
+        if name.endswith("meta"):
+            d, o = d.view(np.uint16), o.view(np.uint16)
+        assert np.array_equal(d, o), name
+
+
+def test_quantizer_corner_values(env):
+    """Groups built to sit on rounding ties, the scale floor, subnormals and the fp16 maximum."""
+    B, torch, oracle = env
+    print("case quantizer corners", flush=True)
+    rng = np.random.default_rng(13)
+    P, Hkv, D = 16, 2, 128
+    for bits, G in ((8, 16), (8, 128), (4, 32)):
+        T = 64
+        x = rng.standard_normal((2, T, Hkv, D)).astype(np.float16)
+        x[:, 0] = 0
+        x[:, 1] = np.float16(6e-8)
+        x[:, 2] = np.float16(-6e-8)
+        x[:, 3] = np.float16(65504.0)
+        x[:, 4, :, ::2] = np.float16(-65504.0)
+        x[:, 5] = np.float16(0.3)
+        x[:, 6] = (np.arange(D) % 16 * (1 / 64)).astype(np.float16)          # exact multiples of a power-of-two scale
+        x[:, 7] = ((np.arange(D) % 32) * 0.5 / 64 + 0.25 / 64).astype(np.float16)   # half-way values
+        x[:, 8] = (rng.integers(-255, 256, (Hkv, D)) * 2.0 ** -10).astype(np.float16)
+        x[:, 9] = np.abs(x[:, 9])
+        x[:, 10] = -np.abs(x[:, 10])
+        x[:, 11] = (rng.standard_normal((Hkv, D)) * 1e-4).astype(np.float16)
+        x[:, 12] = (rng.standard_normal((Hkv, D)) * 3e3).astype(np.float16)
+        dev = B.KVCache.allocate(T // P, P, Hkv, D, bits, G, fill=0)
+        orc = oracle.Cache.empty(T // P, P, Hkv, D, bits, G)
+        slots = np.arange(T, dtype=np.int64)
+        oracle.kv_quant_write(orc, x[0], x[1], slots)
+        B.alise_kv_quant_write(dev, torch.from_numpy(x[0]).cuda(), torch.from_numpy(x[1]).cuda(),
+                               torch.from_numpy(slots).cuda())
+        torch.cuda.synchronize()
+        for name in ("k_codes", "v_codes", "k_meta", "v_meta"):
+            d = getattr(dev, name).cpu().numpy()
+            o = getattr(orc, name)
+            if name.endswith("meta"):
+                d, o = d.view(np.uint16), o.view(np.uint16)
+            assert np.array_equal(d, o), (bits, G, name)
+
+
+def test_invariances_on_device(env):
+    """Page permutation and batch order leave the device result unchanged (bit for bit:
+    the arithmetic per request does not depend on where its pages live)."""
+    B, torch, oracle = env
+    print("case invariances", flush=True)
+    w = wl.scaled(wl.CONFIGS["llama7b"], B=7, max_len=900)
+    pg, pool, offs, gain = _problem(w)
+    dev = harness.fill_device_cache(B, torch, w, pg, pool, offs, gain)
+    q = wl.queries(w)
+    base = harness.run_device_attn(B, torch, w, dev, q, pg)
+    rng = np.random.default_rng(3)
+    perm = rng.permutation(pg.num_pages)
+    dev2 = B.KVCache.allocate(pg.num_pages, w.P, w.Hkv, w.D, w.bits, w.G)
+    idx = torch.from_numpy(perm).cuda()
+    for name in ("k_codes", "v_codes", "k_meta", "v_meta"):
+        getattr(dev2, name)[idx] = getattr(dev, name)
+    pg2 = wl.Paging(pg.lens, perm[pg.block_tables].astype(np.int32), pg.num_pages, int(perm[pg.poison_page]), pg.max_blocks)
+    out2 = harness.run_device_attn(B, torch, w, dev2, q, pg2)
+    assert np.array_equal(base.view(np.uint16), out2.view(np.uint16))
+    order = rng.permutation(w.B)
+    pg3 = wl.Paging(pg.lens[order], pg.block_tables[order], pg.num_pages, pg.poison_page, pg.max_blocks)
+    out3 = harness.run_device_attn(B, torch, w, dev, q[order], pg3)
+    assert np.array_equal(base[order].view(np.uint16), out3.view(np.uint16))
