@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized, paged KV decode step on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic serving batch that is
+already resident in HBM: alise_kv_quant_write of the step's new tokens, then
+alise_paged_decode_attn over every request's cached context, then
+alise_kv_dequant_page of one page.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload int4|llama7b|gqa70b|opt13b|tiny]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published peak HBM3E bandwidth
+
+# HBM bytes per attention launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a
+# copy kernel of known size; see profiles/.  None where not measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="int4")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def cpu_baseline(w, step, target_seconds):
+    """The CPU oracle timed on a bounded sample of the same workload: whole requests taken in
+    batch order until a token budget is reached.  Reported, never a target."""
+    import numpy as np
+    import oracle
+    from paper_2410_23537_amd import workloads as wl
+
+    oracle.build()
+    threads = max(1, min(16, os.cpu_count() or 1))
+    lens = step.lens
+    # calibrate the oracle's two rates on one short request
+    cal = wl.replace(w, B=1, name="cal")
+    probe_len = int(min(256, lens.max()))
+    pg1 = wl.paging(cal, np.array([probe_len], np.int32))
+    c1 = oracle.Cache.empty(pg1.num_pages, w.P, w.Hkv, w.D, w.bits, w.G)
+    k, v = wl.request_kv(w, step.pool_host, step.offs, 0, 0, probe_len, step.gain)
+    t0 = time.perf_counter()
+    oracle.kv_quant_write(c1, k, v, wl.slots_of(cal, pg1, 0, 0, probe_len))
+    fill_per_token = (time.perf_counter() - t0) / probe_len / threads      # filled by `threads` workers
+    qrep = np.repeat(step.q_host[:1], threads, axis=0)
+    t0 = time.perf_counter()
+    oracle.paged_decode_attn(c1, qrep, np.repeat(pg1.block_tables, threads, axis=0),
+                             np.repeat(pg1.lens, threads), step.scale, num_threads=threads)
+    attn_per_token = (time.perf_counter() - t0) / (probe_len * threads)
+    # token budget: timed work near the target, untimed cache filling at most ~3x that
+    budget = int(min(target_seconds / max(attn_per_token, 1e-9), 3 * target_seconds / max(fill_per_token, 1e-9)))
+    budget = max(budget, int(lens.min()))
+    # sample: every n-th request in batch order so the length mix is kept, within the budget
+    stride = max(1, int(math.ceil(lens.astype(np.int64).sum() / budget)))
+    chosen, tot = [], 0
+    for i in range(0, w.B, stride):
+        if tot + int(lens[i]) > budget and chosen:
+            continue
+        chosen.append(int(i))
+        tot += int(lens[i])
+    sub_lens = lens[chosen]
+    ws = wl.replace(w, B=len(chosen), name="sample")
+    pgs = wl.paging(ws, sub_lens)
+    cache = oracle.Cache.empty(pgs.num_pages, w.P, w.Hkv, w.D, w.bits, w.G)
+    from concurrent.futures import ThreadPoolExecutor
+
+    def fill(j):
+        # untimed set-up: the context of one sampled request (requests own disjoint pages)
+        i = chosen[j]
+        L = int(lens[i])
+        k, v = wl.request_kv(w, step.pool_host, step.offs, i, 0, L, step.gain)
+        slots = wl.slots_of(ws, pgs, j, 0, L)
+        for a in range(0, L - 1, 512):
+            b = min(L - 1, a + 512)
+            oracle.kv_quant_write(cache, k[a:b], v[a:b], slots[a:b])
+        return k[-1:].copy(), v[-1:].copy(), slots[-1:]
+
+    with ThreadPoolExecutor(threads) as ex:
+        parts = list(ex.map(fill, range(len(chosen))))
+    step_k = np.concatenate([p[0] for p in parts])
+    step_v = np.concatenate([p[1] for p in parts])
+    step_slots = [p[2] for p in parts]
+    step_slots = np.concatenate(step_slots)
+    q = step.q_host[chosen]
+    t0 = time.perf_counter()
+    oracle.kv_quant_write(cache, step_k, step_v, step_slots)
+    oracle.paged_decode_attn(cache, q, pgs.block_tables, pgs.lens, step.scale, num_threads=threads)
+    oracle.kv_dequant_page(cache, int(pgs.block_tables[0, 0]))
+    dt = time.perf_counter() - t0
+    nbytes = (wl.algorithmic_bytes_attn(ws, sub_lens) + wl.algorithmic_bytes_write(ws, len(chosen))
+              + wl.algorithmic_bytes_dequant(ws, 1))
+    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": f"{len(chosen)} of {w.B} requests (every {stride}-th in batch order, {tot} of "
+                      f"{int(lens.astype(np.int64).sum())} KV tokens), one decode token each, "
+                      f"attention split over {threads} threads",
+            "seconds": dt, "kv_tokens_per_s": tot / dt}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
+              "(the path shards by request or by KV head without any exchange, see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2410_23537_amd import workloads as wl
+    from paper_2410_23537_amd.decode_step import DecodeStep
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+    w = wl.CONFIGS[args.workload]
+    probe = wl.context_lens(w)
+    working_set = int(probe.astype(np.int64).sum()) * w.Hkv * w.row_bytes
+    copies = 1 if working_set >= (1 << 30) else int(math.ceil((1 << 30) / max(working_set, 1))) + 1
+    copies = min(copies, 64)
+    t_setup = time.perf_counter()
+    step = DecodeStep(w, n_cache_copies=copies)
+    step.populate()
+    torch.cuda.synchronize()
+    print(f"[bench] workload {w.name}: B={w.B} H={w.H} Hkv={w.Hkv} D={w.D} P={w.P} bits={w.bits} G={w.G} "
+          f"sum(L)={step.kv_tokens()} step tokens={int(step.step_slots.numel())} cache copies={copies} "
+          f"setup {time.perf_counter() - t_setup:.1f}s", file=sys.stderr, flush=True)
+
+    for s in range(args.warmup):
+        step.step(s % copies)
+    torch.cuda.synchronize()
+
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    evw = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        c = s % copies
+        evw[s][0].record()
+        step.quant_write(c)
+        evw[s][1].record()
+        ev[s][0].record()
+        step.attend(c)
+        ev[s][1].record()
+        step.dequant_page(c)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    ms_per_step = elapsed / args.steps * 1e3
+    attn_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    write_ms = float(np.mean([a.elapsed_time(b) for a, b in evw]))
+    b_attn, b_write, b_dq = step.bytes_attn(), step.bytes_write(), step.bytes_dequant()
+    total_bytes = b_attn + b_write + b_dq
+    value = total_bytes / (ms_per_step * 1e-3) / 1e9
+    achieved = b_attn / (attn_ms * 1e-3) / 1e9
+    result = {
+        "metric": "quantized-KV decode attention HBM GB/s (% of peak) + KV-tokens/s attended",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={w.B} H={w.H} Hkv={w.Hkv} D={w.D} page={w.P} INT{w.bits} G={w.G} "
+                               f"lengths={w.length_law} sum(L)={step.kv_tokens()}",
+                   "step": "quant_write(step tokens) + paged_decode_attn + dequant_page(1)",
+                   "step_tokens_written": int(step.step_slots.numel()), "cache_copies_rotated": copies},
+        "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
+        "kv_tokens_per_s": step.kv_tokens() / (ms_per_step * 1e-3),
+        "bytes_per_step": {"attn": b_attn, "quant_write": b_write, "dequant_page": b_dq},
+        "kernel_ms": {"paged_decode_attn": attn_ms, "quant_write": write_ms},
+        "roofline": {"bound": "hbm", "kernel": "decode_attn_kernel (alise_paged_decode_attn)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(w.name)},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, step, args.cpu_seconds)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

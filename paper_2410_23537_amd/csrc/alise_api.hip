@@ -65,13 +65,20 @@ int check_cache_pointers(const alise_kv_cache *c)
 // the default (a multiple of 64) for tuning.
 int32_t split_tokens()
 {
-    static const int32_t cached = [] {
-        const char *e = std::getenv("ALISE_SPLIT_TOKENS");
-        long v = e ? std::strtol(e, nullptr, 10) : 0;
-        if (v < 64 || v > (1 << 20) || (v % 64) != 0) v = 512;
-        return (int32_t)v;
-    }();
-    return cached;
+    const char *e = std::getenv("ALISE_SPLIT_TOKENS");
+    long v = e ? std::strtol(e, nullptr, 10) : 0;
+    if (v < 64 || v > (1 << 20) || (v % 64) != 0) v = 1024;
+    return (int32_t)v;
+}
+
+// Resident waves per compute unit of the persistent attention grid (ALISE_WAVES_PER_CU
+// overrides the default for tuning; a multiple of 4, at most 32).
+int32_t waves_per_cu()
+{
+    const char *e = std::getenv("ALISE_WAVES_PER_CU");
+    long v = e ? std::strtol(e, nullptr, 10) : 0;
+    if (v < 4 || v > 32 || (v % 4) != 0) v = 16;
+    return (int32_t)v;
 }
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -194,7 +201,7 @@ int alise_paged_decode_attn(const alise_kv_cache *c, const void *q, void *out,
     if (workspace_bytes < need) return ALISE_WORKSPACE_TOO_SMALL;
     hipError_t e = alise::launch_decode_attn(cv, q, out, block_tables, max_blocks_per_seq, context_lens, B,
                                              num_q_heads, max_context_len, softmax_scale, ws,
-                                             num_compute_units(), static_cast<hipStream_t>(hip_stream));
+                                             num_compute_units() * waves_per_cu(), static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? ALISE_OK : ALISE_HIP_ERROR;
 }
 

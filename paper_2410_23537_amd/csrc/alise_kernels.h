@@ -34,6 +34,6 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
                               const int32_t *block_tables, int32_t max_blocks,
                               const int32_t *context_lens, int32_t B, int32_t H,
                               int32_t max_context_len, float softmax_scale,
-                              const AttnWorkspace &ws, int32_t num_cus, hipStream_t s);
+                              const AttnWorkspace &ws, int32_t resident_waves, hipStream_t s);
 
 }  // namespace alise

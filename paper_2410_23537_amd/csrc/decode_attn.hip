@@ -419,10 +419,9 @@ __global__ __launch_bounds__(256) void merge_kernel(AttnParams p)
 }
 
 template <int BITS, int D>
-hipError_t launch_t(const AttnParams &p, int32_t num_cus, hipStream_t s)
+hipError_t launch_t(const AttnParams &p, int32_t resident_waves, hipStream_t s)
 {
-    const int waves_wanted = num_cus * 8;           // two waves per SIMD
-    int blocks = waves_wanted / 4;
+    int blocks = resident_waves / 4;
     const int64_t max_items = (int64_t)p.ws.max_tiles * p.H;
     if ((int64_t)blocks * 4 > max_items) blocks = (int)((max_items + 3) / 4);
     if (blocks < 1) blocks = 1;
@@ -440,7 +439,7 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
                               const int32_t *block_tables, int32_t max_blocks,
                               const int32_t *context_lens, int32_t B, int32_t H,
                               int32_t max_context_len, float softmax_scale,
-                              const AttnWorkspace &ws, int32_t num_cus, hipStream_t s)
+                              const AttnWorkspace &ws, int32_t resident_waves, hipStream_t s)
 {
     if (B == 0) return hipSuccess;
     AttnParams p;
@@ -459,10 +458,10 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, s, context_lens, B, H, max_context_len, ws);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (c.bits == 8 && c.D == 128) return launch_t<8, 128>(p, num_cus, s);
-    if (c.bits == 8 && c.D == 64) return launch_t<8, 64>(p, num_cus, s);
-    if (c.bits == 4 && c.D == 128) return launch_t<4, 128>(p, num_cus, s);
-    if (c.bits == 4 && c.D == 64) return launch_t<4, 64>(p, num_cus, s);
+    if (c.bits == 8 && c.D == 128) return launch_t<8, 128>(p, resident_waves, s);
+    if (c.bits == 8 && c.D == 64) return launch_t<8, 64>(p, resident_waves, s);
+    if (c.bits == 4 && c.D == 128) return launch_t<4, 128>(p, resident_waves, s);
+    if (c.bits == 4 && c.D == 64) return launch_t<4, 64>(p, resident_waves, s);
     return hipErrorInvalidValue;
 }
 

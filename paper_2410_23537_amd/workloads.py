@@ -176,10 +176,11 @@ def value_pool(w: Workload, n_min: int | None = None) -> np.ndarray:
 
 
 def request_offsets(w: Workload) -> Tuple[np.ndarray, np.ndarray]:
-    """Pool offsets (K, V) of every request."""
+    """Pool offsets (K, V) of every request, in elements; multiples of 8 so that a
+    slice of the pool is a 16-byte aligned fp16 tensor."""
     rng = np.random.default_rng([w.seed, 4])
-    return (rng.integers(0, _POOL_SPAN, w.B, dtype=np.int64),
-            rng.integers(0, _POOL_SPAN, w.B, dtype=np.int64))
+    return (rng.integers(0, _POOL_SPAN // 8, w.B, dtype=np.int64) * 8,
+            rng.integers(0, _POOL_SPAN // 8, w.B, dtype=np.int64) * 8)
 
 
 def k_channel_gain(w: Workload) -> np.ndarray:
