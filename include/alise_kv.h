@@ -67,9 +67,20 @@ enum {
  *                      contiguous channels of one token's one head vector.
  * Slot s of the cache is page s / page_size, offset s % page_size.
  *
+ * A (page, head) block is the [page_size][...] slab of one array.  The distance in bytes
+ * between consecutive blocks is codes_block_stride for k_codes and v_codes and
+ * meta_block_stride for k_meta and v_meta; 0 means dense (the shapes above, four separate
+ * arrays).  Larger strides describe one allocation in which the four slabs of a (page, head)
+ * pair sit next to each other -- block b at base + b * stride holds
+ * [K codes | V codes | K meta | V meta], the four pointers name the four slabs of block 0 and
+ * both strides equal the block size -- which is what the attention kernel streams best,
+ * since a wave then reads one contiguous region per page.  Strides are multiples of 16 and at
+ * least the dense slab size.
+ *
  * Supported: bits in {4, 8}; head_dim in {64, 128}; group_size a divisor of
  * head_dim and a multiple of 128/bits (16 for INT8, 32 for INT4);
- * page_size a power of two in [8, 256]; num_pages * page_size < 2^31.
+ * page_size a power of two in [8, 256]; num_pages * page_size < 2^31;
+ * num_pages * num_kv_heads < 2^31; strides below 2^31.
  */
 typedef struct alise_kv_cache {
     void *k_codes;
@@ -82,9 +93,12 @@ typedef struct alise_kv_cache {
     int32_t head_dim;
     int32_t bits;
     int32_t group_size;
+    int64_t codes_block_stride;     /* bytes; 0 = dense = page_size * head_dim * bits / 8      */
+    int64_t meta_block_stride;      /* bytes; 0 = dense = page_size * (head_dim/group_size) * 4 */
 } alise_kv_cache;
 
-/* Bytes of one codes array / one meta array of `c` (0 if `c` is unsupported). */
+/* Bytes spanned by one codes array / one meta array of `c`, from its base pointer to the end
+ * of its last block (0 if `c` is unsupported). */
 size_t alise_kv_codes_bytes(const alise_kv_cache *c);
 size_t alise_kv_meta_bytes(const alise_kv_cache *c);
 

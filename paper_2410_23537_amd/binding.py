@@ -14,7 +14,7 @@ from dataclasses import dataclass
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libalise_kv.so")
+LIB_PATH = os.environ.get("ALISE_KV_LIB") or os.path.join(_HERE, "libalise_kv.so")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -40,7 +40,8 @@ class alise_kv_cache(ctypes.Structure):
                 ("k_meta", ctypes.c_void_p), ("v_meta", ctypes.c_void_p),
                 ("num_pages", ctypes.c_int32), ("page_size", ctypes.c_int32),
                 ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
-                ("bits", ctypes.c_int32), ("group_size", ctypes.c_int32)]
+                ("bits", ctypes.c_int32), ("group_size", ctypes.c_int32),
+                ("codes_block_stride", ctypes.c_int64), ("meta_block_stride", ctypes.c_int64)]
 
 
 _P = ctypes.POINTER(alise_kv_cache)
@@ -100,20 +101,47 @@ class KVCache:
     head_dim: int
     bits: int
     group_size: int
+    codes_block_stride: int = 0     # bytes between (page, head) blocks; 0 = dense
+    meta_block_stride: int = 0
+    storage: torch.Tensor | None = None   # the single allocation of an interleaved cache
 
     @staticmethod
-    def allocate(num_pages, page_size, num_kv_heads, head_dim, bits, group_size, device="cuda", fill=None):
-        cshape = (num_pages, num_kv_heads, page_size, head_dim * bits // 8)
-        mshape = (num_pages, num_kv_heads, page_size, head_dim // group_size, 2)
-        mk = (lambda s, dt: torch.empty(s, dtype=dt, device=device)) if fill is None else \
-             (lambda s, dt: torch.full(s, fill, dtype=dt, device=device))
-        return KVCache(mk(cshape, torch.uint8), mk(cshape, torch.uint8), mk(mshape, torch.float16),
-                       mk(mshape, torch.float16), num_pages, page_size, num_kv_heads, head_dim, bits, group_size)
+    def allocate(num_pages, page_size, num_kv_heads, head_dim, bits, group_size, device="cuda", fill=None,
+                 layout="interleaved"):
+        """``layout="dense"``: four separate arrays in the canonical shapes.
+        ``layout="interleaved"``: one allocation whose (page, head) blocks hold
+        [K codes | V codes | K meta | V meta]; the four tensors are strided views of it with
+        the same logical shapes."""
+        rowb = head_dim * bits // 8
+        ng = head_dim // group_size
+        cshape = (num_pages, num_kv_heads, page_size, rowb)
+        mshape = (num_pages, num_kv_heads, page_size, ng, 2)
+        if layout == "dense":
+            mk = (lambda s, dt: torch.empty(s, dtype=dt, device=device)) if fill is None else \
+                 (lambda s, dt: torch.full(s, fill, dtype=dt, device=device))
+            return KVCache(mk(cshape, torch.uint8), mk(cshape, torch.uint8), mk(mshape, torch.float16),
+                           mk(mshape, torch.float16), num_pages, page_size, num_kv_heads, head_dim, bits,
+                           group_size)
+        assert layout == "interleaved"
+        cb, mb = page_size * rowb, page_size * ng * 4
+        blk = 2 * cb + 2 * mb
+        store = torch.empty((num_pages, num_kv_heads, blk), dtype=torch.uint8, device=device)
+        if fill is not None:
+            store.fill_(fill)
+        kc = store[:, :, 0:cb].unflatten(-1, (page_size, rowb))
+        vc = store[:, :, cb:2 * cb].unflatten(-1, (page_size, rowb))
+        km = store[:, :, 2 * cb:2 * cb + mb].view(torch.float16).unflatten(-1, (page_size, ng, 2))
+        vm = store[:, :, 2 * cb + mb:blk].view(torch.float16).unflatten(-1, (page_size, ng, 2))
+        if fill is not None:
+            km.fill_(fill)
+            vm.fill_(fill)
+        return KVCache(kc, vc, km, vm, num_pages, page_size, num_kv_heads, head_dim, bits, group_size,
+                       blk, blk, store)
 
     def c_struct(self) -> alise_kv_cache:
         return alise_kv_cache(_dp(self.k_codes), _dp(self.v_codes), _dp(self.k_meta), _dp(self.v_meta),
                               self.num_pages, self.page_size, self.num_kv_heads, self.head_dim,
-                              self.bits, self.group_size)
+                              self.bits, self.group_size, self.codes_block_stride, self.meta_block_stride)
 
 
 def alise_kv_codes_bytes(cache: KVCache) -> int:

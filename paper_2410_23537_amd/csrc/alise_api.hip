@@ -34,6 +34,13 @@ int check_cache(const alise_kv_cache *c, CacheView *out)
     const int logP = ilog2_exact(c->page_size);
     if (logP < 3 || logP > 8) return ALISE_UNSUPPORTED;
     if ((int64_t)c->num_pages * c->page_size >= (int64_t)1 << 31) return ALISE_UNSUPPORTED;
+    if ((int64_t)c->num_pages * c->num_kv_heads >= (int64_t)1 << 31) return ALISE_UNSUPPORTED;
+    const int64_t dense_c = (int64_t)c->page_size * (c->head_dim * c->bits / 8);
+    const int64_t dense_m = (int64_t)c->page_size * (c->head_dim / c->group_size) * 4;
+    const int64_t cs = c->codes_block_stride ? c->codes_block_stride : dense_c;
+    const int64_t ms = c->meta_block_stride ? c->meta_block_stride : dense_m;
+    if (cs < dense_c || ms < dense_m || (cs & 15) || (ms & 15)) return ALISE_INVALID_ARGUMENT;
+    if (cs >= (int64_t)1 << 31 || ms >= (int64_t)1 << 31) return ALISE_UNSUPPORTED;
     if (out) {
         out->k_codes = static_cast<uint8_t *>(c->k_codes);
         out->v_codes = static_cast<uint8_t *>(c->v_codes);
@@ -48,6 +55,8 @@ int check_cache(const alise_kv_cache *c, CacheView *out)
         out->G = c->group_size;
         out->NG = c->head_dim / c->group_size;
         out->row_code_bytes = c->head_dim * c->bits / 8;
+        out->cstride = (int32_t)cs;
+        out->mstride = (int32_t)ms;
     }
     return ALISE_OK;
 }
@@ -63,11 +72,14 @@ int check_cache_pointers(const alise_kv_cache *c)
 // Tokens per split.  Long requests are cut into splits of this many tokens so that
 // one long and many short requests fill the chip alike; ALISE_SPLIT_TOKENS overrides
 // the default (a multiple of 64) for tuning.
-int32_t split_tokens()
+// A split never spans more than 64 pages: the attention kernel keeps a split's
+// block-table entries in one register, one entry per lane.
+int32_t split_tokens(int32_t page_size)
 {
     const char *e = std::getenv("ALISE_SPLIT_TOKENS");
     long v = e ? std::strtol(e, nullptr, 10) : 0;
     if (v < 64 || v > (1 << 20) || (v % 64) != 0) v = 1024;
+    if (v > 64L * page_size) v = 64L * page_size;
     return (int32_t)v;
 }
 
@@ -81,28 +93,44 @@ int32_t waves_per_cu()
     return (int32_t)v;
 }
 
+// Wave-loads per block of the attention kernel (ALISE_LOADS_PER_BLOCK overrides: 2, 3 or 4).
+int32_t loads_per_block()
+{
+    const char *e = std::getenv("ALISE_LOADS_PER_BLOCK");
+    long v = e ? std::strtol(e, nullptr, 10) : 0;
+    if (v < 2 || v > 4) v = 4;
+    return (int32_t)v;
+}
+
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-// Workspace layout: [counter, n_items | tile_base[B+1] | tile_req[max_tiles] | part].
+// Workspace layout: [queue counters, n_items | tile_base[B+1] | req_full_base[B] | req_rem_base[B] |
+// order[max_tiles] | part].
 size_t carve_workspace(const CacheView &c, int32_t B, int32_t H, int32_t max_len, void *base,
                        AttnWorkspace *ws)
 {
-    const int32_t C = split_tokens();
+    const int32_t C = split_tokens(c.P);
     const int64_t splits = ((int64_t)max_len + C - 1) / C;
     const int64_t max_tiles = (int64_t)B * (splits > 0 ? splits : 1);
-    size_t off = 256;
+    size_t off = 2304;      // eight queue counters, 256 bytes apart, then n_items
     const size_t off_base = off;
     off = align_up(off + sizeof(int32_t) * ((size_t)B + 1), 256);
-    const size_t off_req = off;
-    off = align_up(off + sizeof(int32_t) * (size_t)max_tiles, 256);
+    const size_t off_fb = off;
+    off = align_up(off + sizeof(int32_t) * (size_t)B, 256);
+    const size_t off_rb = off;
+    off = align_up(off + sizeof(int32_t) * (size_t)B, 256);
+    const size_t off_order = off;
+    off = align_up(off + 16 * (size_t)max_tiles, 256);
     const size_t off_part = off;
     off = align_up(off + sizeof(float) * (size_t)max_tiles * H * (c.D + 2), 256);
     if (ws) {
         char *b = static_cast<char *>(base);
         ws->counter = reinterpret_cast<uint32_t *>(b);
-        ws->n_items = reinterpret_cast<int32_t *>(b + 4);
+        ws->n_items = reinterpret_cast<int32_t *>(b + 2048);
         ws->tile_base = reinterpret_cast<int32_t *>(b + off_base);
-        ws->tile_req = reinterpret_cast<int32_t *>(b + off_req);
+        ws->req_full_base = reinterpret_cast<int32_t *>(b + off_fb);
+        ws->req_rem_base = reinterpret_cast<int32_t *>(b + off_rb);
+        ws->order = reinterpret_cast<int4 *>(b + off_order);
         ws->part = reinterpret_cast<float *>(b + off_part);
         ws->max_tiles = (int32_t)max_tiles;
         ws->chunk_tokens = C;
@@ -114,7 +142,7 @@ int check_attn_sizes(const CacheView &c, int32_t B, int32_t H, int32_t max_len)
 {
     if (B < 0 || H <= 0 || max_len < 0) return ALISE_INVALID_ARGUMENT;
     if (H % c.Hkv != 0) return ALISE_UNSUPPORTED;
-    const int64_t splits = ((int64_t)max_len + split_tokens() - 1) / split_tokens();
+    const int64_t splits = ((int64_t)max_len + split_tokens(c.P) - 1) / split_tokens(c.P);
     if ((int64_t)B * (splits > 0 ? splits : 1) * H >= (int64_t)1 << 31) return ALISE_UNSUPPORTED;
     return ALISE_OK;
 }
@@ -138,14 +166,18 @@ extern "C" {
 
 size_t alise_kv_codes_bytes(const alise_kv_cache *c)
 {
-    if (check_cache(c, nullptr) != ALISE_OK) return 0;
-    return (size_t)c->num_pages * c->num_kv_heads * c->page_size * (c->head_dim * c->bits / 8);
+    CacheView cv;
+    if (check_cache(c, &cv) != ALISE_OK) return 0;
+    const size_t blocks = (size_t)c->num_pages * c->num_kv_heads;
+    return (blocks - 1) * (size_t)cv.cstride + (size_t)c->page_size * cv.row_code_bytes;
 }
 
 size_t alise_kv_meta_bytes(const alise_kv_cache *c)
 {
-    if (check_cache(c, nullptr) != ALISE_OK) return 0;
-    return (size_t)c->num_pages * c->num_kv_heads * c->page_size * (c->head_dim / c->group_size) * 4;
+    CacheView cv;
+    if (check_cache(c, &cv) != ALISE_OK) return 0;
+    const size_t blocks = (size_t)c->num_pages * c->num_kv_heads;
+    return (blocks - 1) * (size_t)cv.mstride + (size_t)c->page_size * cv.NG * 4;
 }
 
 int alise_kv_quant_write(const alise_kv_cache *c, const void *k, const void *v,
@@ -201,7 +233,8 @@ int alise_paged_decode_attn(const alise_kv_cache *c, const void *q, void *out,
     if (workspace_bytes < need) return ALISE_WORKSPACE_TOO_SMALL;
     hipError_t e = alise::launch_decode_attn(cv, q, out, block_tables, max_blocks_per_seq, context_lens, B,
                                              num_q_heads, max_context_len, softmax_scale, ws,
-                                             num_compute_units() * waves_per_cu(), static_cast<hipStream_t>(hip_stream));
+                                             num_compute_units() * waves_per_cu(), loads_per_block(),
+                                             static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? ALISE_OK : ALISE_HIP_ERROR;
 }
 

@@ -11,14 +11,17 @@ struct CacheView {
     uint32_t *k_meta, *v_meta;      // one dword per group: fp16 scale (low half), fp16 zero (high half)
     int32_t num_pages, P, logP, Hkv, D, bits, G, NG;
     int32_t row_code_bytes;         // D * bits / 8
+    int32_t cstride, mstride;       // bytes between consecutive (page, head) blocks of the codes / meta arrays
 };
 
 // Workspace carved up by the ABI layer for one attention call.
 struct AttnWorkspace {
-    uint32_t *counter;      // [1]  next work item, reset by the plan kernel
+    uint32_t *counter;      // [8 x 64] next item of each work queue (one 256-byte line each), reset by the plan kernel
     int32_t *n_items;       // [1]  tiles * H, written by the plan kernel
-    int32_t *tile_base;     // [B+1] first tile of each request (exclusive scan of chunk counts)
-    int32_t *tile_req;      // [max_tiles] request of each tile
+    int32_t *tile_base;     // [B+1] first tile of each request (exclusive scan of tile counts)
+    int32_t *req_full_base; // [B] scratch of the plan kernel: first full tile of each request in the work order
+    int32_t *req_rem_base;  // [B] scratch of the plan kernel: rank of each request's remainder tile
+    int4 *order;            // [max_tiles] work order: (request, first token, end token, split buffer index or -1)
     float *part;            // [max_tiles * H][D + 2] = (m, l, o[D]) of every split
     int32_t max_tiles;
     int32_t chunk_tokens;   // tokens per split
@@ -34,6 +37,7 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
                               const int32_t *block_tables, int32_t max_blocks,
                               const int32_t *context_lens, int32_t B, int32_t H,
                               int32_t max_context_len, float softmax_scale,
-                              const AttnWorkspace &ws, int32_t resident_waves, hipStream_t s);
+                              const AttnWorkspace &ws, int32_t resident_waves, int32_t loads_per_block,
+                              hipStream_t s);
 
 }  // namespace alise

@@ -5,26 +5,34 @@
 // with k^ = lambda_k (code - z_k), v^ = lambda_v (code - z_v) dequantized in registers.
 //
 // Work decomposition (this build's, not the paper's):
-//   plan kernel   : context_lens -> list of tiles (request, split of C tokens)
+//   plan kernel   : context_lens -> tile descriptors (request, token range of at most C
+//                   tokens), full tiles first, the shorter remainders last
 //   attn kernel   : persistent waves pull (tile, head) items from an atomic counter;
-//                   one wave = one item, no workgroup barrier anywhere
+//                   one wave = one item, no workgroup barrier anywhere; the counter
+//                   and the descriptor of the following item are fetched one item ahead
 //   merge kernel  : log-sum-exp combination of the splits of long requests
 //
 // Inside a wave every load instruction reads 1 KiB of contiguous codes: a token's
 // row of D*bits/8 bytes is split over LPT lanes of 16 bytes, so a wave-load covers
-// TPW = 64/LPT consecutive tokens ("slots").  A lane keeps its 16 bytes' worth of
-// channels for both K and V, so the scalar product needs a reduction over the LPT
-// lanes of a slot (DPP) and the weighted sum needs one reduction over the TPW slots
-// at the end of the tile (through LDS).
+// TPW = 64/LPT consecutive tokens ("slots").  When a wave-load never straddles a page
+// (TPW <= page size) its base address is wave-uniform and lives in scalar registers.
+// Loads are double buffered: the codes of block n+1 are in flight while block n is
+// being consumed.  A lane keeps its 16 bytes' worth of channels for both K and V, so
+// the scalar product needs a reduction over the LPT lanes of a slot (DPP) and the
+// weighted sum needs one reduction over the TPW slots at the end of the tile (LDS).
 //
-// Dequantization never materialises k^: with the group's (lambda, z),
-//   q . k^ = lambda * (sum_c q_c code_c - z * sum_c q_c)
-// and the codes are turned into fp16 by bit tricks (1024 + code has the bit pattern
-// 0x6400 | code), two at a time, and fed to the packed fp16 dot product with fp32
-// accumulation.  The offset 1024 * sum q is subtracted with the zero-point.
+// Dequantization never materialises k^ or v^:
+//   q . k^      = lambda_k (sum_c q_c code_c - z_k sum_c q_c)
+//   sum_t p_t v^ = sum_t (p_t lambda_v) code  -  sum_t (p_t lambda_v) z_v
+// Codes become fp16 by bit tricks, two at a time: for K, 0x6400 | code is 1024 + code
+// and feeds the packed fp16 dot product (fp32 accumulate; the 1024 sum(q) offset leaves
+// with the zero-point); for V the bare code bits are the fp16 subnormal code * 2^-24,
+// which the mixed-precision FMA multiplies by the fp32 weight exactly.
 #include "alise_kernels.h"
 
 #include <hip/hip_fp16.h>
+
+#include <type_traits>
 
 namespace alise {
 namespace {
@@ -33,6 +41,9 @@ typedef _Float16 h2_t __attribute__((ext_vector_type(2)));
 
 constexpr float kNegInf = -__builtin_inff();
 constexpr float kLazy = 8.0f;   // the running maximum is raised only past this slack (log2 units)
+constexpr int kQueues = 8;          // work queues of the attention kernel, one per XCD
+constexpr int kQueueStride = 64;    // uint32 between queue counters: one 256-byte line each
+constexpr float kFloor = -1.0e30f;   // finite stand-in for "no token seen yet": -inf - kFloor stays -inf
 
 struct AttnParams {
     CacheView c;
@@ -49,6 +60,14 @@ __device__ __forceinline__ h2_t as_h2(uint32_t u) { return __builtin_bit_cast(h2
 __device__ __forceinline__ uint32_t as_u32(h2_t h) { return __builtin_bit_cast(uint32_t, h); }
 __device__ __forceinline__ float half_lo(uint32_t u) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(u & 0xffffu)); }
 __device__ __forceinline__ float half_hi(uint32_t u) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(u >> 16)); }
+
+// (x & mask) | bits in one instruction; the mask sits in a scalar register.
+__device__ __forceinline__ uint32_t and_or(uint32_t x, uint32_t mask, uint32_t bits)
+{
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "s"(mask), "v"(bits));
+    return r;
+}
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_f(float v)
@@ -75,49 +94,79 @@ __device__ __forceinline__ void wave_lds_sync()
 
 // ------------------------------------------------------------------ plan
 
-// One workgroup: chunk counts, their exclusive scan, the tile -> request table.
+// Inclusive scan of one int per thread over a 1024-thread workgroup.
+__device__ __forceinline__ int block_scan_1024(int v, int32_t *buf)
+{
+    const int tid = threadIdx.x;
+    buf[tid] = v;
+    __syncthreads();
+    for (int d = 1; d < 1024; d <<= 1) {
+        const int add = tid >= d ? buf[tid - d] : 0;
+        __syncthreads();
+        buf[tid] += add;
+        __syncthreads();
+    }
+    const int r = buf[tid];
+    __syncthreads();
+    return r;
+}
+
+// One workgroup.  Per request: number of full tiles (C tokens) and whether a shorter
+// remainder tile exists.  Tiles of a request are numbered consecutively (tile_base) for
+// the split buffers; the work order lists all full tiles first and the remainders last,
+// so that the waves that finish late finish on short items.
 __global__ __launch_bounds__(1024) void plan_kernel(const int32_t *context_lens, int32_t B, int32_t H,
                                                     int32_t max_len, AttnWorkspace ws)
 {
-    __shared__ int32_t s_scan[1024];
-    __shared__ int32_t s_carry;
+    __shared__ int32_t s_buf[1024];
+    __shared__ int32_t s_tot[3];
     const int tid = threadIdx.x;
-    if (tid == 0) s_carry = 0;
-    __syncthreads();
     const int C = ws.chunk_tokens;
+    if (tid < 3) s_tot[tid] = 0;
+    __syncthreads();
     for (int base = 0; base < B; base += 1024) {
         const int i = base + tid;
-        int n = 0;
+        int L = 0;
         if (i < B) {
-            int L = context_lens[i];
+            L = context_lens[i];
             L = L < 0 ? 0 : (L > max_len ? max_len : L);
-            n = (L + C - 1) / C;
         }
-        s_scan[tid] = n;
-        __syncthreads();
-        for (int d = 1; d < 1024; d <<= 1) {
-            int add = tid >= d ? s_scan[tid - d] : 0;
-            __syncthreads();
-            s_scan[tid] += add;
-            __syncthreads();
-        }
-        const int carry = s_carry;
-        const int first = carry + s_scan[tid] - n;
+        const int nfull = L / C;
+        const int nrem = (L % C) != 0;
+        const int s_all = block_scan_1024(nfull + nrem, s_buf);
+        const int s_full = block_scan_1024(nfull, s_buf);
+        const int s_rem = block_scan_1024(nrem, s_buf);
+        const int c_all = s_tot[0], c_full = s_tot[1], c_rem = s_tot[2];
         if (i < B) {
-            ws.tile_base[i] = first;
-            for (int c = 0; c < n; ++c)
-                if (first + c < ws.max_tiles) ws.tile_req[first + c] = i;
+            ws.tile_base[i] = c_all + s_all - (nfull + nrem);
+            ws.req_full_base[i] = c_full + s_full - nfull;
+            ws.req_rem_base[i] = c_rem + s_rem - nrem;
         }
         __syncthreads();
-        if (tid == 1023) s_carry = carry + s_scan[1023];
+        if (tid == 1023) {
+            s_tot[0] = c_all + s_all;
+            s_tot[1] = c_full + s_full;
+            s_tot[2] = c_rem + s_rem;
+        }
         __syncthreads();
     }
+    const int total = s_tot[0], total_full = s_tot[1];
+    for (int i = tid; i < B; i += 1024) {
+        int L = context_lens[i];
+        L = L < 0 ? 0 : (L > max_len ? max_len : L);
+        const int nfull = L / C;
+        const int nrem = (L % C) != 0;
+        const int tb = ws.tile_base[i];
+        const bool split = nfull + nrem > 1;
+        const int fb = ws.req_full_base[i];
+        for (int s = 0; s < nfull; ++s)
+            ws.order[fb + s] = make_int4(i, s * C, (s + 1) * C, split ? tb + s : -1);
+        if (nrem) ws.order[total_full + ws.req_rem_base[i]] = make_int4(i, nfull * C, L, split ? tb + nfull : -1);
+    }
     if (tid == 0) {
-        int total = s_carry;
-        if (total > ws.max_tiles) total = ws.max_tiles;
         ws.tile_base[B] = total;
         *ws.n_items = total * H;
-        *ws.counter = 0u;
+        for (int q = 0; q < kQueues; ++q) ws.counter[q * kQueueStride] = 0u;
     }
 }
 
@@ -129,15 +178,170 @@ struct Geo {
     static constexpr int LPT = ROWB / 16;       // lanes per token
     static constexpr int TPW = 64 / LPT;        // tokens per wave-load
     static constexpr int SL = 128 / BITS;       // channels per lane
-    static constexpr int NB = 4;                // wave-loads in flight per block
     static constexpr int LDS_ROW = D + 4;       // floats per slot row in the end-of-tile reduction
 };
 
+// The codes and meta of N wave-loads, as they arrive.
+template <int N>
+struct Buf {
+    uint4 kc[N], vc[N];
+    uint32_t km[N], vm[N];
+};
+
+// Running softmax state of one lane: its slot's reference maximum and denominator, the
+// weighted code sums of its SL channels, and the weighted zero-point sum.
+template <int SL>
+struct Acc {
+    float m_ref, l, wz;
+    float a[SL];
+};
+
+// This lane's slice of q, paired the way the code pairs come out of a dword.
+template <int BITS>
+struct QSlice {
+    uint32_t qp[64 / BITS];   // SL / 2 packed fp16 pairs
+    float qsum;               // sum of q over the slice
+    float koff;               // what the 1024 offsets add to the packed dot product
+};
+
 template <int BITS, int D>
+__device__ __forceinline__ void load_q(QSlice<BITS> &qs, const _Float16 *qrow)
+{
+    constexpr int SL = Geo<BITS, D>::SL;
+    const uint32_t *qsrc = reinterpret_cast<const uint32_t *>(qrow);
+    uint32_t raw[SL / 2];
+#pragma unroll
+    for (int k = 0; k < SL / 2; k += 4) {
+        const uint4 v4 = *reinterpret_cast<const uint4 *>(qsrc + k);
+        raw[k] = v4.x; raw[k + 1] = v4.y; raw[k + 2] = v4.z; raw[k + 3] = v4.w;
+    }
+    if constexpr (BITS == 8) {
+        float s = 0.0f;
+#pragma unroll
+        for (int k = 0; k < SL / 2; ++k) {
+            qs.qp[k] = raw[k];
+            s += half_lo(raw[k]) + half_hi(raw[k]);
+        }
+        qs.qsum = s;
+        qs.koff = 1024.0f * s;
+    } else {
+        // a code dword holds channels 8w..8w+7 in nibbles 0..7; the pairs taken from it are
+        // (n0,n4) (n1,n5)*16 (n2,n6) (n3,n7)*16, so q is paired the same way and the
+        // partners of the *16 pairs are pre-divided by 16 (exact in fp16 above the subnormals).
+        float sa = 0.0f, sb = 0.0f;
+#pragma unroll
+        for (int w = 0; w < SL / 8; ++w) {
+            _Float16 qc[8];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                qc[2 * k] = __builtin_bit_cast(_Float16, (uint16_t)(raw[4 * w + k] & 0xffffu));
+                qc[2 * k + 1] = __builtin_bit_cast(_Float16, (uint16_t)(raw[4 * w + k] >> 16));
+            }
+            const _Float16 sc = (_Float16)0.0625f;
+            const h2_t a0 = {qc[0], qc[4]}, b0 = {qc[1] * sc, qc[5] * sc};
+            const h2_t a1 = {qc[2], qc[6]}, b1 = {qc[3] * sc, qc[7] * sc};
+            qs.qp[4 * w + 0] = as_u32(a0); qs.qp[4 * w + 1] = as_u32(b0);
+            qs.qp[4 * w + 2] = as_u32(a1); qs.qp[4 * w + 3] = as_u32(b1);
+            sa += (float)a0.x + (float)a0.y + (float)a1.x + (float)a1.y;
+            sb += (float)b0.x + (float)b0.y + (float)b1.x + (float)b1.y;   // already /16
+        }
+        qs.qsum = sa + 16.0f * sb;
+        qs.koff = 1024.0f * (sa + sb);
+    }
+}
+
+// One wave-load: score of this lane's token, lazy maximum, weight, weighted code sums.
+// `valid` is false for a token at or beyond the end of the tile (its slot may hold
+// anything, NaN meta included: selected away, never multiplied by zero).
+template <int BITS, int D>
+__device__ __forceinline__ void consume_one(const uint4 kc, const uint4 vc, const uint32_t km, uint32_t vm,
+                                            Acc<Geo<BITS, D>::SL> &st, const QSlice<BITS> &qs,
+                                            float scale_log2e, bool valid)
+{
+    using G = Geo<BITS, D>;
+    constexpr int LPT = G::LPT, SL = G::SL;
+    const uint32_t kw[4] = {kc.x, kc.y, kc.z, kc.w};
+    float dot = 0.0f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        if constexpr (BITS == 8) {
+            const uint32_t lo = __builtin_amdgcn_perm(0x64646464u, kw[w], 0x04010400u);
+            const uint32_t hi = __builtin_amdgcn_perm(0x64646464u, kw[w], 0x04030402u);
+            dot = __builtin_amdgcn_fdot2(as_h2(lo), as_h2(qs.qp[2 * w]), dot, false);
+            dot = __builtin_amdgcn_fdot2(as_h2(hi), as_h2(qs.qp[2 * w + 1]), dot, false);
+        } else {
+            const uint32_t x = kw[w], y = kw[w] >> 8;
+            const uint32_t a0 = and_or(x, 0x000F000Fu, 0x64006400u);
+            const uint32_t b0 = and_or(x, 0x00F000F0u, 0x64006400u);
+            const uint32_t a1 = and_or(y, 0x000F000Fu, 0x64006400u);
+            const uint32_t b1 = and_or(y, 0x00F000F0u, 0x64006400u);
+            dot = __builtin_amdgcn_fdot2(as_h2(a0), as_h2(qs.qp[4 * w + 0]), dot, false);
+            dot = __builtin_amdgcn_fdot2(as_h2(b0), as_h2(qs.qp[4 * w + 1]), dot, false);
+            dot = __builtin_amdgcn_fdot2(as_h2(a1), as_h2(qs.qp[4 * w + 2]), dot, false);
+            dot = __builtin_amdgcn_fdot2(as_h2(b1), as_h2(qs.qp[4 * w + 3]), dot, false);
+        }
+    }
+    const float lam = half_lo(km) * scale_log2e;
+    const float z = half_hi(km);
+    float part = lam * ((dot - qs.koff) - z * qs.qsum);
+    part = slot_sum<LPT>(part);
+    const float s = valid ? part : kNegInf;
+    vm = valid ? vm : 0u;                 // scale 0, zero-point 0: the token adds nothing
+
+    // running maximum, raised lazily (wave-uniform branch, rarely taken after the first tokens)
+    if (__builtin_amdgcn_ballot_w64(s > st.m_ref + kLazy) != 0) {
+        const float m_new = (s > st.m_ref + kLazy) ? s : st.m_ref;
+        const float f = __builtin_amdgcn_exp2f(st.m_ref - m_new);     // 1 where unchanged
+        st.l *= f;
+        st.wz *= f;
+#pragma unroll
+        for (int k = 0; k < SL; ++k) st.a[k] *= f;
+        st.m_ref = m_new;
+    }
+
+    const float pj = __builtin_amdgcn_exp2f(s - st.m_ref);            // 0 for a masked token
+    st.l += pj;
+    const float w = pj * half_lo(vm);
+    st.wz = __builtin_fmaf(w, half_hi(vm), st.wz);
+    const uint32_t vw[4] = {vc.x, vc.y, vc.z, vc.w};
+    if constexpr (BITS == 8) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            // bytes -> fp16 subnormals code * 2^-24 (high byte zero)
+            const h2_t lo = as_h2(__builtin_amdgcn_perm(0u, vw[d], 0x0c010c00u));
+            const h2_t hi = as_h2(__builtin_amdgcn_perm(0u, vw[d], 0x0c030c02u));
+            st.a[4 * d + 0] = __builtin_fmaf((float)lo.x, w, st.a[4 * d + 0]);
+            st.a[4 * d + 1] = __builtin_fmaf((float)lo.y, w, st.a[4 * d + 1]);
+            st.a[4 * d + 2] = __builtin_fmaf((float)hi.x, w, st.a[4 * d + 2]);
+            st.a[4 * d + 3] = __builtin_fmaf((float)hi.y, w, st.a[4 * d + 3]);
+        }
+    } else {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const uint32_t x = vw[d], y = vw[d] >> 8;
+            const h2_t a0 = as_h2(x & 0x000F000Fu);      // (n0, n4)      * 2^-24
+            const h2_t b0 = as_h2(x & 0x00F000F0u);      // (n1, n5) * 16 * 2^-24
+            const h2_t a1 = as_h2(y & 0x000F000Fu);      // (n2, n6)
+            const h2_t b1 = as_h2(y & 0x00F000F0u);      // (n3, n7) * 16
+            st.a[8 * d + 0] = __builtin_fmaf((float)a0.x, w, st.a[8 * d + 0]);
+            st.a[8 * d + 1] = __builtin_fmaf((float)a0.y, w, st.a[8 * d + 1]);
+            st.a[8 * d + 2] = __builtin_fmaf((float)b0.x, w, st.a[8 * d + 2]);
+            st.a[8 * d + 3] = __builtin_fmaf((float)b0.y, w, st.a[8 * d + 3]);
+            st.a[8 * d + 4] = __builtin_fmaf((float)a1.x, w, st.a[8 * d + 4]);
+            st.a[8 * d + 5] = __builtin_fmaf((float)a1.y, w, st.a[8 * d + 5]);
+            st.a[8 * d + 6] = __builtin_fmaf((float)b1.x, w, st.a[8 * d + 6]);
+            st.a[8 * d + 7] = __builtin_fmaf((float)b1.y, w, st.a[8 * d + 7]);
+        }
+    }
+}
+
+// NB = wave-loads per block; two blocks are in flight per wave.
+template <int BITS, int D, bool UNI, int NB>
 __global__ __launch_bounds__(256) void decode_attn_kernel(AttnParams p)
 {
     using G = Geo<BITS, D>;
-    constexpr int LPT = G::LPT, TPW = G::TPW, SL = G::SL, NB = G::NB, ROWB = G::ROWB;
+    constexpr int LPT = G::LPT, TPW = G::TPW, SL = G::SL, ROWB = G::ROWB;
+    constexpr int BT = NB * TPW;      // tokens per block
     __shared__ float s_red[4][TPW * G::LDS_ROW];
 
     const int lane = threadIdx.x & 63;
@@ -146,212 +350,139 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(AttnParams p)
     const int slot = lane / LPT;        // which token of a wave-load
     const int ch0 = sub * SL;           // first channel of this lane
     const int grp = ch0 / p.c.G;        // the lane's channels lie in one group
+    const int NG = p.c.NG, logP = p.c.logP, P = p.c.P, Hkv = p.c.Hkv;
+    // per-lane addresses of the first (page, head) block; == slot * ROWB + sub * 16 == lane * 16
+    const uint8_t *lane_k = p.c.k_codes + lane * 16;
+    const uint8_t *lane_v = p.c.v_codes + lane * 16;
+    const uint8_t *lane_km = reinterpret_cast<const uint8_t *>(p.c.k_meta) + (slot * NG + grp) * 4;
+    const uint8_t *lane_vm = reinterpret_cast<const uint8_t *>(p.c.v_meta) + (slot * NG + grp) * 4;
     float *red = s_red[wave];
     const int n_items = *p.ws.n_items;
-    const int C = p.ws.chunk_tokens;
+    const int4 *order = p.ws.order;
 
-    for (;;) {
-        int it = 0;
-        if (lane == 0) it = (int)atomicAdd(p.ws.counter, 1u);
-        it = __builtin_amdgcn_readfirstlane(it);
-        if (it >= n_items) break;
-        const int tile = it / p.H;
-        const int h = it - tile * p.H;
-        const int i = p.ws.tile_req[tile];
-        const int tb_first = p.ws.tile_base[i];
-        const int n_split = p.ws.tile_base[i + 1] - tb_first;
-        const int split = tile - tb_first;
-        int L = p.context_lens[i];
-        L = L > p.max_len ? p.max_len : L;
-        const int t0 = split * C;
-        const int t1 = min(L, t0 + C);
+    // Work queues.  Item q + nq * n is the n-th item of queue q; a workgroup serves queue
+    // blockIdx % nq.  Workgroups are dealt to the eight XCDs round-robin, so the waves that
+    // bump one counter sit on one XCD and its cache line stays in that XCD's L2 instead of
+    // bouncing between dies; any other placement is still correct, only slower.
+    const int nq = gridDim.x >= kQueues ? kQueues : 1;
+    const int q = blockIdx.x % nq;
+    uint32_t *counter = p.ws.counter + q * kQueueStride;
+    // item pipeline: the counter is fetched two items ahead, the descriptor one item ahead
+    int it_cur = 0;
+    if (lane == 0) it_cur = (int)atomicAdd(counter, 1u);
+    it_cur = q + nq * __builtin_amdgcn_readfirstlane(it_cur);
+    int nx = 0;
+    if (lane == 0) nx = (int)atomicAdd(counter, 1u);
+    int4 dc = order[(it_cur < n_items ? it_cur : 0) / p.H];
+
+    while (it_cur < n_items) {
+        const int it_next = q + nq * __builtin_amdgcn_readfirstlane(nx);
+        const int4 dn = order[(it_next < n_items ? it_next : 0) / p.H];
+        if (lane == 0) nx = (int)atomicAdd(counter, 1u);
+
+        const int h = it_cur % p.H;
+        const int i = __builtin_amdgcn_readfirstlane(dc.x);
+        const int t0 = __builtin_amdgcn_readfirstlane(dc.y);
+        const int t1 = __builtin_amdgcn_readfirstlane(dc.z);
+        const int part_idx = __builtin_amdgcn_readfirstlane(dc.w);
         const int hk = h / p.qper;
         const int32_t *bt = p.block_tables + (int64_t)i * p.max_blocks;
+        const int last_blk = (t1 - 1) >> logP;
 
-        // ---- this lane's slice of q, arranged to meet the code pairs
-        uint32_t qp[SL / 2];
-        float qsum = 0.0f;      // sum of q over the slice
-        float koff = 0.0f;      // what the 1024 offsets add to the packed dot product
-        {
-            const uint32_t *qsrc = reinterpret_cast<const uint32_t *>(p.q + ((int64_t)i * p.H + h) * D + ch0);
-            uint32_t raw[SL / 2];
-#pragma unroll
-            for (int k = 0; k < SL / 2; k += 4) {
-                const uint4 v4 = *reinterpret_cast<const uint4 *>(qsrc + k);
-                raw[k] = v4.x; raw[k + 1] = v4.y; raw[k + 2] = v4.z; raw[k + 3] = v4.w;
-            }
-            if constexpr (BITS == 8) {
-#pragma unroll
-                for (int k = 0; k < SL / 2; ++k) {
-                    qp[k] = raw[k];
-                    qsum += half_lo(raw[k]) + half_hi(raw[k]);
-                }
-                koff = 1024.0f * qsum;
-            } else {
-                // a code dword holds channels 8w..8w+7 in nibbles 0..7; the pairs taken from it are
-                // (n0,n4) (n1,n5)*16 (n2,n6) (n3,n7)*16, so q is paired the same way and the
-                // partners of the *16 pairs are pre-divided by 16.
-                float sa = 0.0f, sb = 0.0f;
-#pragma unroll
-                for (int w = 0; w < SL / 8; ++w) {
-                    _Float16 qc[8];
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        qc[2 * k] = __builtin_bit_cast(_Float16, (uint16_t)(raw[4 * w + k] & 0xffffu));
-                        qc[2 * k + 1] = __builtin_bit_cast(_Float16, (uint16_t)(raw[4 * w + k] >> 16));
-                    }
-                    const _Float16 sc = (_Float16)0.0625f;
-                    h2_t a0 = {qc[0], qc[4]}, b0 = {qc[1] * sc, qc[5] * sc};
-                    h2_t a1 = {qc[2], qc[6]}, b1 = {qc[3] * sc, qc[7] * sc};
-                    qp[4 * w + 0] = as_u32(a0); qp[4 * w + 1] = as_u32(b0);
-                    qp[4 * w + 2] = as_u32(a1); qp[4 * w + 3] = as_u32(b1);
-                    sa += (float)a0.x + (float)a0.y + (float)a1.x + (float)a1.y;
-                    sb += (float)b0.x + (float)b0.y + (float)b1.x + (float)b1.y;   // already /16
-                }
-                qsum = sa + 16.0f * sb;
-                koff = 1024.0f * (sa + sb);
-            }
-        }
+        // the tile's block-table entries, one per lane (a tile spans at most 64 pages)
+        const int win_first = t0 >> logP;
+        const int pgreg = bt[min(win_first + lane, last_blk)];
 
-        float m_ref = kNegInf, l = 0.0f, wz = 0.0f;
-        float acc[SL];
-#pragma unroll
-        for (int k = 0; k < SL; ++k) acc[k] = 0.0f;
+        QSlice<BITS> qs;
+        load_q<BITS, D>(qs, p.q + ((int64_t)i * p.H + h) * D + ch0);
 
-        for (int tb = t0; tb < t1; tb += NB * TPW) {
-            uint4 kc[NB], vc[NB];
-            uint32_t km[NB], vm[NB];
-            bool valid[NB];
+        Acc<SL> st;
+        st.m_ref = kFloor; st.l = 0.0f; st.wz = 0.0f;
+#pragma unroll
+        for (int k = 0; k < SL; ++k) st.a[k] = 0.0f;
+
+        const int nw = (t1 - t0 + TPW - 1) / TPW;     // wave-loads in the tile
+        const int nblk = (nw + NB - 1) / NB;          // blocks of NB wave-loads
+
+        // Issue the NB wave-loads of block k.  Straight-line code on purpose: a branch around
+        // a load would make the compiler wait for every outstanding load at the join, which
+        // serialises the two buffers.  Wave-loads past the end of the tile re-read its last
+        // wave-load; their tokens are masked when consumed.
+        auto issue = [&](Buf<NB> &buf, int k) {
 #pragma unroll
             for (int j = 0; j < NB; ++j) {
-                const int tok = tb + j * TPW + slot;
-                valid[j] = tok < t1;
-                const int tc = valid[j] ? tok : t1 - 1;        // stay on a real token
-                const int64_t page = bt[tc >> p.c.logP];
-                const int64_t row = (page * p.c.Hkv + hk) * p.c.P + (tc & (p.c.P - 1));
-                const int64_t coff = row * ROWB + sub * 16;
-                kc[j] = *reinterpret_cast<const uint4 *>(p.c.k_codes + coff);
-                vc[j] = *reinterpret_cast<const uint4 *>(p.c.v_codes + coff);
-                km[j] = p.c.k_meta[row * p.c.NG + grp];
-                vm[j] = p.c.v_meta[row * p.c.NG + grp];
-            }
-
-            // ---- scores (log2 domain)
-            float s[NB];
-            float mx = kNegInf;
-#pragma unroll
-            for (int j = 0; j < NB; ++j) {
-                const uint32_t kw[4] = {kc[j].x, kc[j].y, kc[j].z, kc[j].w};
-                float dot = 0.0f;
-#pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    if constexpr (BITS == 8) {
-                        const uint32_t lo = __builtin_amdgcn_perm(0x64646464u, kw[w], 0x04010400u);
-                        const uint32_t hi = __builtin_amdgcn_perm(0x64646464u, kw[w], 0x04030402u);
-                        dot = __builtin_amdgcn_fdot2(as_h2(lo), as_h2(qp[2 * w]), dot, false);
-                        dot = __builtin_amdgcn_fdot2(as_h2(hi), as_h2(qp[2 * w + 1]), dot, false);
-                    } else {
-                        const uint32_t x = kw[w], y = kw[w] >> 8;
-                        const uint32_t a0 = (x & 0x000F000Fu) | 0x64006400u;
-                        const uint32_t b0 = (x & 0x00F000F0u) | 0x64006400u;
-                        const uint32_t a1 = (y & 0x000F000Fu) | 0x64006400u;
-                        const uint32_t b1 = (y & 0x00F000F0u) | 0x64006400u;
-                        dot = __builtin_amdgcn_fdot2(as_h2(a0), as_h2(qp[4 * w + 0]), dot, false);
-                        dot = __builtin_amdgcn_fdot2(as_h2(b0), as_h2(qp[4 * w + 1]), dot, false);
-                        dot = __builtin_amdgcn_fdot2(as_h2(a1), as_h2(qp[4 * w + 2]), dot, false);
-                        dot = __builtin_amdgcn_fdot2(as_h2(b1), as_h2(qp[4 * w + 3]), dot, false);
-                    }
-                }
-                const float lam = half_lo(km[j]) * p.scale_log2e;
-                const float z = half_hi(km[j]);
-                float part = lam * ((dot - koff) - z * qsum);
-                part = slot_sum<LPT>(part);
-                s[j] = valid[j] ? part : kNegInf;
-                mx = fmaxf(mx, s[j]);
-            }
-
-            // ---- running maximum, raised lazily (wave-uniform branch, rarely taken)
-            if (__builtin_amdgcn_ballot_w64(mx > m_ref + kLazy) != 0) {
-                const float m_new = (mx > m_ref + kLazy) ? mx : m_ref;
-                const float f = (m_new == m_ref) ? 1.0f : __builtin_amdgcn_exp2f(m_ref - m_new);
-                l *= f;
-                wz *= f;
-#pragma unroll
-                for (int k = 0; k < SL; ++k) acc[k] *= f;
-                m_ref = m_new;
-            }
-
-            // ---- weights and weighted sum of V codes
-#pragma unroll
-            for (int j = 0; j < NB; ++j) {
-                const float pj = valid[j] ? __builtin_amdgcn_exp2f(s[j] - m_ref) : 0.0f;
-                l += pj;
-                const float w = pj * half_lo(vm[j]);
-                const uint32_t vw[4] = {vc[j].x, vc[j].y, vc[j].z, vc[j].w};
-                if constexpr (BITS == 8) {
-                    wz = __builtin_fmaf(w, 1024.0f + half_hi(vm[j]), wz);
-#pragma unroll
-                    for (int d = 0; d < 4; ++d) {
-                        const h2_t lo = as_h2(__builtin_amdgcn_perm(0x64646464u, vw[d], 0x04010400u));
-                        const h2_t hi = as_h2(__builtin_amdgcn_perm(0x64646464u, vw[d], 0x04030402u));
-                        acc[4 * d + 0] = __builtin_fmaf((float)lo.x, w, acc[4 * d + 0]);
-                        acc[4 * d + 1] = __builtin_fmaf((float)lo.y, w, acc[4 * d + 1]);
-                        acc[4 * d + 2] = __builtin_fmaf((float)hi.x, w, acc[4 * d + 2]);
-                        acc[4 * d + 3] = __builtin_fmaf((float)hi.y, w, acc[4 * d + 3]);
-                    }
+                const int w = min(k * NB + j, nw - 1);
+                const int tw = t0 + w * TPW;
+                if constexpr (UNI) {
+                    const int page = __builtin_amdgcn_readlane(pgreg, (tw >> logP) - win_first);
+                    const int blk = page * Hkv + hk;                    // < 2^31, checked on the host
+                    const int off = tw & (P - 1);
+                    const int64_t co = (int64_t)blk * p.c.cstride + off * ROWB;
+                    const int64_t mo = (int64_t)blk * p.c.mstride + off * NG * 4;
+                    buf.kc[j] = *reinterpret_cast<const uint4 *>(lane_k + co);
+                    buf.vc[j] = *reinterpret_cast<const uint4 *>(lane_v + co);
+                    buf.km[j] = *reinterpret_cast<const uint32_t *>(lane_km + mo);
+                    buf.vm[j] = *reinterpret_cast<const uint32_t *>(lane_vm + mo);
                 } else {
-                    // exact integer (code - z) in fp16, so nothing is left to cancel later
-                    const uint32_t zb = vm[j] >> 16;                       // fp16 bits of z
-                    const h2_t zz = as_h2(zb | (zb << 16));
-                    const h2_t k1 = {(_Float16)-1024.0f, (_Float16)-1024.0f};
-                    const h2_t k16 = {(_Float16)-16.0f, (_Float16)-16.0f};
-                    const h2_t offa = k1 - zz;                             // -(1024 + z)
-                    const h2_t offb = zz * k16 + k1;                       // -(1024 + 16 z)
-#pragma unroll
-                    for (int d = 0; d < 4; ++d) {
-                        const uint32_t x = vw[d], y = vw[d] >> 8;
-                        const h2_t a0 = as_h2((x & 0x000F000Fu) | 0x64006400u) + offa;
-                        const h2_t b0 = as_h2((x & 0x00F000F0u) | 0x64006400u) + offb;
-                        const h2_t a1 = as_h2((y & 0x000F000Fu) | 0x64006400u) + offa;
-                        const h2_t b1 = as_h2((y & 0x00F000F0u) | 0x64006400u) + offb;
-                        // acc order inside a dword: channels 0,4,1,5,2,6,3,7 (odd ones carry *16)
-                        acc[8 * d + 0] = __builtin_fmaf((float)a0.x, w, acc[8 * d + 0]);
-                        acc[8 * d + 1] = __builtin_fmaf((float)a0.y, w, acc[8 * d + 1]);
-                        acc[8 * d + 2] = __builtin_fmaf((float)b0.x, w, acc[8 * d + 2]);
-                        acc[8 * d + 3] = __builtin_fmaf((float)b0.y, w, acc[8 * d + 3]);
-                        acc[8 * d + 4] = __builtin_fmaf((float)a1.x, w, acc[8 * d + 4]);
-                        acc[8 * d + 5] = __builtin_fmaf((float)a1.y, w, acc[8 * d + 5]);
-                        acc[8 * d + 6] = __builtin_fmaf((float)b1.x, w, acc[8 * d + 6]);
-                        acc[8 * d + 7] = __builtin_fmaf((float)b1.y, w, acc[8 * d + 7]);
-                    }
+                    const int tok = tw + slot;
+                    const int tc = tok < t1 ? tok : t1 - 1;        // stay on a real token
+                    const int page = __shfl(pgreg, (tc >> logP) - win_first);
+                    const int blk = page * Hkv + hk;
+                    const int off = tc & (P - 1);
+                    const int64_t co = (int64_t)blk * p.c.cstride + off * ROWB + sub * 16;
+                    const int64_t mo = (int64_t)blk * p.c.mstride + (off * NG + grp) * 4;
+                    buf.kc[j] = *reinterpret_cast<const uint4 *>(p.c.k_codes + co);
+                    buf.vc[j] = *reinterpret_cast<const uint4 *>(p.c.v_codes + co);
+                    buf.km[j] = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const uint8_t *>(p.c.k_meta) + mo);
+                    buf.vm[j] = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const uint8_t *>(p.c.v_meta) + mo);
                 }
+            }
+        };
+        auto eat = [&](const Buf<NB> &buf, int k) {
+#pragma unroll
+            for (int j = 0; j < NB; ++j) {
+                const bool valid = t0 + k * BT + j * TPW + slot < t1;
+                consume_one<BITS, D>(buf.kc[j], buf.vc[j], buf.km[j], buf.vm[j], st, qs, p.scale_log2e, valid);
+            }
+        };
+
+        {
+            Buf<NB> bufA, bufB;
+            issue(bufA, 0);
+            for (int k = 0; k < nblk; k += 2) {
+                issue(bufB, min(k + 1, nblk - 1));
+                eat(bufA, k);
+                issue(bufA, min(k + 2, nblk - 1));
+                if (k + 1 < nblk) eat(bufB, k + 1);
             }
         }
 
         // ---- bring the TPW slots to one maximum, then add them up through LDS
-        float m_fin = m_ref;
+        float m_fin = st.m_ref;
 #pragma unroll
         for (int d = LPT; d < 64; d <<= 1) m_fin = fmaxf(m_fin, __shfl_xor(m_fin, d));
-        const float f = (m_ref == kNegInf) ? 0.0f : __builtin_amdgcn_exp2f(m_ref - m_fin);
-        l *= f;
+        const float f = __builtin_amdgcn_exp2f(st.m_ref - m_fin);     // 0 for a slot that saw no token
+        float l = st.l * f;
 #pragma unroll
         for (int d = LPT; d < 64; d <<= 1) l += __shfl_xor(l, d);
         float *myrow = red + slot * G::LDS_ROW + ch0;
+        const float fz = st.wz * f;
+        const float f24 = f * 16777216.0f;      // undo the 2^-24 of the subnormal codes
         if constexpr (BITS == 8) {
 #pragma unroll
-            for (int k = 0; k < SL; ++k) myrow[k] = (acc[k] - wz) * f;
+            for (int k = 0; k < SL; ++k) myrow[k] = __builtin_fmaf(st.a[k], f24, -fz);
         } else {
-            const float f16 = f * 0.0625f;
+            const float f20 = f * 1048576.0f;   // ... and the extra *16 of the odd nibbles
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
-                myrow[8 * d + 0] = acc[8 * d + 0] * f;
-                myrow[8 * d + 4] = acc[8 * d + 1] * f;
-                myrow[8 * d + 1] = acc[8 * d + 2] * f16;
-                myrow[8 * d + 5] = acc[8 * d + 3] * f16;
-                myrow[8 * d + 2] = acc[8 * d + 4] * f;
-                myrow[8 * d + 6] = acc[8 * d + 5] * f;
-                myrow[8 * d + 3] = acc[8 * d + 6] * f16;
-                myrow[8 * d + 7] = acc[8 * d + 7] * f16;
+                myrow[8 * d + 0] = __builtin_fmaf(st.a[8 * d + 0], f24, -fz);
+                myrow[8 * d + 4] = __builtin_fmaf(st.a[8 * d + 1], f24, -fz);
+                myrow[8 * d + 1] = __builtin_fmaf(st.a[8 * d + 2], f20, -fz);
+                myrow[8 * d + 5] = __builtin_fmaf(st.a[8 * d + 3], f20, -fz);
+                myrow[8 * d + 2] = __builtin_fmaf(st.a[8 * d + 4], f24, -fz);
+                myrow[8 * d + 6] = __builtin_fmaf(st.a[8 * d + 5], f24, -fz);
+                myrow[8 * d + 3] = __builtin_fmaf(st.a[8 * d + 6], f20, -fz);
+                myrow[8 * d + 7] = __builtin_fmaf(st.a[8 * d + 7], f20, -fz);
             }
         }
         wave_lds_sync();
@@ -365,17 +496,20 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(AttnParams p)
         }
         wave_lds_sync();   // the next item overwrites `red`
 
-        if (n_split == 1) {
+        if (part_idx < 0) {
             const float inv_l = 1.0f / l;
             _Float16 *dst = p.out + ((int64_t)i * p.H + h) * D;
 #pragma unroll
             for (int r = 0; r < D / 64; ++r) dst[r * 64 + lane] = (_Float16)(o[r] * inv_l);
         } else {
-            float *dst = p.ws.part + ((int64_t)tile * p.H + h) * (D + 2);
+            float *dst = p.ws.part + ((int64_t)part_idx * p.H + h) * (D + 2);
             if (lane == 0) { dst[0] = m_fin; dst[1] = l; }
 #pragma unroll
             for (int r = 0; r < D / 64; ++r) dst[2 + r * 64 + lane] = o[r];
         }
+
+        it_cur = it_next;
+        dc = dn;
     }
 }
 
@@ -418,14 +552,19 @@ __global__ __launch_bounds__(256) void merge_kernel(AttnParams p)
     for (int r = 0; r < D / 64; ++r) dst[r * 64 + lane] = (_Float16)(o[r] * inv_l);
 }
 
-template <int BITS, int D>
+template <int BITS, int D, int NB>
 hipError_t launch_t(const AttnParams &p, int32_t resident_waves, hipStream_t s)
 {
     int blocks = resident_waves / 4;
     const int64_t max_items = (int64_t)p.ws.max_tiles * p.H;
     if ((int64_t)blocks * 4 > max_items) blocks = (int)((max_items + 3) / 4);
     if (blocks < 1) blocks = 1;
-    hipLaunchKernelGGL((decode_attn_kernel<BITS, D>), dim3(blocks), dim3(256), 0, s, p);
+    // a wave-load covers TPW consecutive tokens; it has one page if pages are at least that long
+    const bool uniform_page = p.c.P >= Geo<BITS, D>::TPW;
+    if (uniform_page)
+        hipLaunchKernelGGL((decode_attn_kernel<BITS, D, true, NB>), dim3(blocks), dim3(256), 0, s, p);
+    else
+        hipLaunchKernelGGL((decode_attn_kernel<BITS, D, false, NB>), dim3(blocks), dim3(256), 0, s, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int mblocks = (p.B * p.H + 3) / 4;
@@ -439,7 +578,8 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
                               const int32_t *block_tables, int32_t max_blocks,
                               const int32_t *context_lens, int32_t B, int32_t H,
                               int32_t max_context_len, float softmax_scale,
-                              const AttnWorkspace &ws, int32_t resident_waves, hipStream_t s)
+                              const AttnWorkspace &ws, int32_t resident_waves, int32_t loads_per_block,
+                              hipStream_t s)
 {
     if (B == 0) return hipSuccess;
     AttnParams p;
@@ -458,10 +598,17 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, s, context_lens, B, H, max_context_len, ws);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (c.bits == 8 && c.D == 128) return launch_t<8, 128>(p, resident_waves, s);
-    if (c.bits == 8 && c.D == 64) return launch_t<8, 64>(p, resident_waves, s);
-    if (c.bits == 4 && c.D == 128) return launch_t<4, 128>(p, resident_waves, s);
-    if (c.bits == 4 && c.D == 64) return launch_t<4, 64>(p, resident_waves, s);
+#define ALISE_DISPATCH(NBV)                                                              \
+    do {                                                                                 \
+        if (c.bits == 8 && c.D == 128) return launch_t<8, 128, NBV>(p, resident_waves, s); \
+        if (c.bits == 8 && c.D == 64) return launch_t<8, 64, NBV>(p, resident_waves, s);   \
+        if (c.bits == 4 && c.D == 128) return launch_t<4, 128, NBV>(p, resident_waves, s); \
+        if (c.bits == 4 && c.D == 64) return launch_t<4, 64, NBV>(p, resident_waves, s);   \
+    } while (0)
+    if (loads_per_block == 2) ALISE_DISPATCH(2);
+    if (loads_per_block == 3) ALISE_DISPATCH(3);
+    if (loads_per_block == 4) ALISE_DISPATCH(4);
+#undef ALISE_DISPATCH
     return hipErrorInvalidValue;
 }
 

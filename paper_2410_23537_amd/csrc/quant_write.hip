@@ -87,24 +87,25 @@ __global__ __launch_bounds__(256) void quant_write_kernel(QuantParams p)
 
     const int64_t page = slot >> p.c.logP;
     const int off = (int)(slot & (p.c.P - 1));
-    const int64_t crow = (page * p.c.Hkv + head) * p.c.P + off;
-    uint8_t *codes = which ? p.c.v_codes : p.c.k_codes;
-    uint32_t *meta = which ? p.c.v_meta : p.c.k_meta;
+    const int64_t blk = page * p.c.Hkv + head;
+    uint8_t *codes = (which ? p.c.v_codes : p.c.k_codes) + blk * p.c.cstride + (int64_t)off * p.c.row_code_bytes;
+    uint32_t *meta = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(which ? p.c.v_meta : p.c.k_meta) +
+                                                  blk * p.c.mstride) + off * p.c.NG;
     if (p.c.bits == 8) {
         uint2 w;
         w.x = code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24);
         w.y = code[4] | (code[5] << 8) | (code[6] << 16) | (code[7] << 24);
-        *reinterpret_cast<uint2 *>(codes + crow * p.c.row_code_bytes + lane_in_row * 8) = w;
+        *reinterpret_cast<uint2 *>(codes + lane_in_row * 8) = w;
     } else {
         uint32_t w = 0;
 #pragma unroll
         for (int i = 0; i < 8; ++i) w |= code[i] << (4 * i);   // channel 2i low nibble, 2i+1 high
-        *reinterpret_cast<uint32_t *>(codes + crow * p.c.row_code_bytes + lane_in_row * 4) = w;
+        *reinterpret_cast<uint32_t *>(codes + lane_in_row * 4) = w;
     }
     if ((lane_in_row % p.lanes_per_group) == 0) {
         const int grp = lane_in_row / p.lanes_per_group;
         const uint16_t zb = __builtin_bit_cast(uint16_t, (_Float16)zf);
-        meta[crow * p.c.NG + grp] = (uint32_t)hb | ((uint32_t)zb << 16);
+        meta[grp] = (uint32_t)hb | ((uint32_t)zb << 16);
     }
 }
 
@@ -128,23 +129,25 @@ __global__ __launch_bounds__(256) void dequant_page_kernel(DequantParams p)
     const int head = row % p.c.Hkv;
     const int which = row / p.c.Hkv;
 
-    const int64_t crow = ((int64_t)p.page * p.c.Hkv + head) * p.c.P + off;
-    const uint8_t *codes = which ? p.c.v_codes : p.c.k_codes;
-    const uint32_t *meta = which ? p.c.v_meta : p.c.k_meta;
+    const int64_t blk = (int64_t)p.page * p.c.Hkv + head;
+    const uint8_t *codes = (which ? p.c.v_codes : p.c.k_codes) + blk * p.c.cstride + (int64_t)off * p.c.row_code_bytes;
+    const uint32_t *meta = reinterpret_cast<const uint32_t *>(
+                               reinterpret_cast<const uint8_t *>(which ? p.c.v_meta : p.c.k_meta) + blk * p.c.mstride) +
+                           off * p.c.NG;
     const int grp = (lane_in_row * 8) / p.c.G;
-    const uint32_t m = meta[crow * p.c.NG + grp];
+    const uint32_t m = meta[grp];
     const float lam = (float)__builtin_bit_cast(_Float16, (uint16_t)(m & 0xffffu));
     const float z = (float)__builtin_bit_cast(_Float16, (uint16_t)(m >> 16));
     uint32_t code[8];
     if (p.c.bits == 8) {
-        const uint2 w = *reinterpret_cast<const uint2 *>(codes + crow * p.c.row_code_bytes + lane_in_row * 8);
+        const uint2 w = *reinterpret_cast<const uint2 *>(codes + lane_in_row * 8);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             code[i] = (w.x >> (8 * i)) & 0xffu;
             code[4 + i] = (w.y >> (8 * i)) & 0xffu;
         }
     } else {
-        const uint32_t w = *reinterpret_cast<const uint32_t *>(codes + crow * p.c.row_code_bytes + lane_in_row * 4);
+        const uint32_t w = *reinterpret_cast<const uint32_t *>(codes + lane_in_row * 4);
 #pragma unroll
         for (int i = 0; i < 8; ++i) code[i] = (w >> (4 * i)) & 0xfu;
     }

@@ -18,7 +18,7 @@ from . import workloads as wl
 
 
 class DecodeStep:
-    def __init__(self, w: wl.Workload, n_cache_copies: int = 1, device: str = "cuda"):
+    def __init__(self, w: wl.Workload, n_cache_copies: int = 1, device: str = "cuda", layout: str = "interleaved"):
         self.w = w
         self.device = device
         self.pg = wl.paging(w)
@@ -35,7 +35,7 @@ class DecodeStep:
         self.context_lens = torch.from_numpy(self.lens.astype(np.int32)).to(device)
         self.max_len = int(self.lens.max())
         self.scale = 1.0 / float(np.sqrt(w.D))
-        self.caches = [B.KVCache.allocate(self.pg.num_pages, w.P, w.Hkv, w.D, w.bits, w.G, device=device)
+        self.caches = [B.KVCache.allocate(self.pg.num_pages, w.P, w.Hkv, w.D, w.bits, w.G, device=device, layout=layout)
                        for _ in range(n_cache_copies)]
         nbytes = B.alise_paged_decode_attn_workspace_bytes(self.caches[0], w.B, w.H, self.max_len)
         if nbytes == 0:

@@ -19,9 +19,9 @@ def fill_oracle_cache(oracle_mod, w, pg, pool, offs, gain):
     return cache
 
 
-def fill_device_cache(B, torch, w, pg, pool, offs, gain, max_tokens_per_call=1 << 16):
+def fill_device_cache(B, torch, w, pg, pool, offs, gain, max_tokens_per_call=1 << 16, layout="interleaved"):
     """Poisoned device cache (0xFF codes, NaN meta) filled through alise_kv_quant_write."""
-    cache = B.KVCache.allocate(pg.num_pages, w.P, w.Hkv, w.D, w.bits, w.G, fill=0xFF)
+    cache = B.KVCache.allocate(pg.num_pages, w.P, w.Hkv, w.D, w.bits, w.G, fill=0xFF, layout=layout)
     cache.k_meta.view(torch.int16).fill_(0x7E00)  # NaN, same bit pattern as on the host
     cache.v_meta.view(torch.int16).fill_(0x7E00)
     ks, vs, ss, n = [], [], [], 0

@@ -53,6 +53,11 @@ def test_layout_helpers(B):
     assert lib.alise_kv_codes_bytes(ctypes.byref(c4)) == 10 * 8 * 16 * 64
     assert lib.alise_kv_meta_bytes(ctypes.byref(c4)) == 10 * 8 * 16 * 4 * 4
     assert lib.alise_kv_codes_bytes(ctypes.byref(_cache(B, bits=5))) == 0
+    # interleaved blocks [K codes | V codes | K meta | V meta]: span from the base to the end of the last slab
+    blk = 2 * 16 * 128 + 2 * 16 * 2 * 4
+    ci = _cache(B, codes_block_stride=blk, meta_block_stride=blk)
+    assert lib.alise_kv_codes_bytes(ctypes.byref(ci)) == (10 * 8 - 1) * blk + 16 * 128
+    assert lib.alise_kv_meta_bytes(ctypes.byref(ci)) == (10 * 8 - 1) * blk + 16 * 2 * 4
 
 
 @pytest.mark.parametrize("kw,want", [
@@ -61,6 +66,9 @@ def test_layout_helpers(B):
     (dict(page_size=4), 2), (dict(page_size=512), 2), (dict(num_pages=0), 1), (dict(num_kv_heads=-1), 1),
     (dict(num_pages=1 << 28, page_size=16), 2),
     (dict(k_codes=0), 1), (dict(v_meta=0), 1), (dict(k_codes=0x1008), 4),
+    (dict(codes_block_stride=16 * 128 - 16), 1), (dict(codes_block_stride=16 * 128 + 8), 1),
+    (dict(meta_block_stride=64), 1), (dict(codes_block_stride=1 << 31), 2),
+    (dict(num_pages=1 << 24, num_kv_heads=128, page_size=8), 2),
 ])
 def test_bad_cache_is_rejected_by_every_entry_point(B, kw, want):
     lib = B.raw()

@@ -55,13 +55,14 @@ SMALL = [
 ]
 
 
+@pytest.mark.parametrize("layout", ["interleaved", "dense"])
 @pytest.mark.parametrize("w", SMALL, ids=lambda w: w.name)
-def test_write_attend_dequant(env, w):
+def test_write_attend_dequant(env, w, layout):
     B, torch, oracle = env
-    print(f"case {w.name}: B={w.B} H={w.H} Hkv={w.Hkv} D={w.D} P={w.P} bits={w.bits} G={w.G}", flush=True)
+    print(f"case {w.name} ({layout}): B={w.B} H={w.H} Hkv={w.Hkv} D={w.D} P={w.P} bits={w.bits} G={w.G}", flush=True)
     pg, pool, offs, gain = _problem(w)
     orc = harness.fill_oracle_cache(oracle, w, pg, pool, offs, gain)
-    dev = harness.fill_device_cache(B, torch, w, pg, pool, offs, gain, max_tokens_per_call=777)
+    dev = harness.fill_device_cache(B, torch, w, pg, pool, offs, gain, max_tokens_per_call=777, layout=layout)
     _compare_caches(w, pg, dev, orc)
 
     q = wl.queries(w)
@@ -148,7 +149,7 @@ def test_skipped_slots_and_empty_write(env):
     print("case skipped slots", flush=True)
     rng = np.random.default_rng(8)
     P, Hkv, D, T = 16, 5, 64, 33
-    dev = B.KVCache.allocate(4, P, Hkv, D, 4, 32, fill=0x5A)
+    dev = B.KVCache.allocate(4, P, Hkv, D, 4, 32, fill=0x5A, layout="dense")
     orc = oracle.Cache.empty(4, P, Hkv, D, 4, 32, fill=0x5A)
     dev.k_meta.fill_(0.0)
     dev.v_meta.fill_(0.0)
