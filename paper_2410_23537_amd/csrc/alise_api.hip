@@ -83,13 +83,13 @@ int32_t split_tokens(int32_t page_size)
     return (int32_t)v;
 }
 
-// Resident waves per compute unit of the persistent attention grid (ALISE_WAVES_PER_CU
-// overrides the default for tuning; a multiple of 4, at most 32).
+// Waves per compute unit of the persistent attention grid: 0 = as many as fit (the
+// default); ALISE_WAVES_PER_CU fixes it for tuning (a multiple of 4, at most 32).
 int32_t waves_per_cu()
 {
     const char *e = std::getenv("ALISE_WAVES_PER_CU");
     long v = e ? std::strtol(e, nullptr, 10) : 0;
-    if (v < 4 || v > 32 || (v % 4) != 0) v = 16;
+    if (v < 4 || v > 32 || (v % 4) != 0) v = 0;
     return (int32_t)v;
 }
 
@@ -98,13 +98,13 @@ int32_t loads_per_block()
 {
     const char *e = std::getenv("ALISE_LOADS_PER_BLOCK");
     long v = e ? std::strtol(e, nullptr, 10) : 0;
-    if (v < 2 || v > 4) v = 4;
+    if (v < 2 || v > 4) v = 2;
     return (int32_t)v;
 }
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-// Workspace layout: [queue counters, n_items | tile_base[B+1] | req_full_base[B] | req_rem_base[B] |
+// Workspace layout: [queue counters, n_items, n_merge | tile_base[B+1] | req_full_base[B] | merge_req[B] |
 // order[max_tiles] | part].
 size_t carve_workspace(const CacheView &c, int32_t B, int32_t H, int32_t max_len, void *base,
                        AttnWorkspace *ws)
@@ -129,7 +129,8 @@ size_t carve_workspace(const CacheView &c, int32_t B, int32_t H, int32_t max_len
         ws->n_items = reinterpret_cast<int32_t *>(b + 2048);
         ws->tile_base = reinterpret_cast<int32_t *>(b + off_base);
         ws->req_full_base = reinterpret_cast<int32_t *>(b + off_fb);
-        ws->req_rem_base = reinterpret_cast<int32_t *>(b + off_rb);
+        ws->merge_req = reinterpret_cast<int32_t *>(b + off_rb);
+        ws->n_merge = reinterpret_cast<int32_t *>(b + 2052);
         ws->order = reinterpret_cast<int4 *>(b + off_order);
         ws->part = reinterpret_cast<float *>(b + off_part);
         ws->max_tiles = (int32_t)max_tiles;
@@ -233,7 +234,7 @@ int alise_paged_decode_attn(const alise_kv_cache *c, const void *q, void *out,
     if (workspace_bytes < need) return ALISE_WORKSPACE_TOO_SMALL;
     hipError_t e = alise::launch_decode_attn(cv, q, out, block_tables, max_blocks_per_seq, context_lens, B,
                                              num_q_heads, max_context_len, softmax_scale, ws,
-                                             num_compute_units() * waves_per_cu(), loads_per_block(),
+                                             num_compute_units(), waves_per_cu(), loads_per_block(),
                                              static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? ALISE_OK : ALISE_HIP_ERROR;
 }

@@ -20,7 +20,8 @@ struct AttnWorkspace {
     int32_t *n_items;       // [1]  tiles * H, written by the plan kernel
     int32_t *tile_base;     // [B+1] first tile of each request (exclusive scan of tile counts)
     int32_t *req_full_base; // [B] scratch of the plan kernel: first full tile of each request in the work order
-    int32_t *req_rem_base;  // [B] scratch of the plan kernel: rank of each request's remainder tile
+    int32_t *merge_req;     // [B] requests with more than one split, in no particular order
+    int32_t *n_merge;       // [1] how many of them
     int4 *order;            // [max_tiles] work order: (request, first token, end token, split buffer index or -1)
     float *part;            // [max_tiles * H][D + 2] = (m, l, o[D]) of every split
     int32_t max_tiles;
@@ -37,7 +38,7 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
                               const int32_t *block_tables, int32_t max_blocks,
                               const int32_t *context_lens, int32_t B, int32_t H,
                               int32_t max_context_len, float softmax_scale,
-                              const AttnWorkspace &ws, int32_t resident_waves, int32_t loads_per_block,
-                              hipStream_t s);
+                              const AttnWorkspace &ws, int32_t num_cus, int32_t waves_per_cu,
+                              int32_t loads_per_block, hipStream_t s);
 
 }  // namespace alise

@@ -111,18 +111,32 @@ __device__ __forceinline__ int block_scan_1024(int v, int32_t *buf)
     return r;
 }
 
+constexpr int kRemBuckets = 1024;   // remainder tiles are ordered by length through this many buckets
+
+// Bucket of a remainder of r tokens (0 < r < C): longer remainders get lower buckets.
+__device__ __forceinline__ int rem_bucket(int r, int C)
+{
+    return (int)(((int64_t)(C - r) * kRemBuckets) / C);      // in [0, kRemBuckets)
+}
+
 // One workgroup.  Per request: number of full tiles (C tokens) and whether a shorter
 // remainder tile exists.  Tiles of a request are numbered consecutively (tile_base) for
-// the split buffers; the work order lists all full tiles first and the remainders last,
-// so that the waves that finish late finish on short items.
+// the split buffers.  The work order is longest-first: all full tiles, then the remainder
+// tiles by decreasing length (a counting sort over length buckets; the order inside a
+// bucket is arbitrary), so that the waves that finish last finish on the shortest items.
+// Also lists the requests whose splits need merging and zeroes the rows of empty requests.
 __global__ __launch_bounds__(1024) void plan_kernel(const int32_t *context_lens, int32_t B, int32_t H,
-                                                    int32_t max_len, AttnWorkspace ws)
+                                                    int32_t max_len, AttnWorkspace ws, _Float16 *out, int32_t D)
 {
     __shared__ int32_t s_buf[1024];
-    __shared__ int32_t s_tot[3];
+    __shared__ int32_t s_hist[kRemBuckets];
+    __shared__ int32_t s_tot[2];
+    __shared__ int32_t s_merge;
     const int tid = threadIdx.x;
     const int C = ws.chunk_tokens;
-    if (tid < 3) s_tot[tid] = 0;
+    s_hist[tid] = 0;            // kRemBuckets == blockDim.x
+    if (tid < 2) s_tot[tid] = 0;
+    if (tid == 0) s_merge = 0;
     __syncthreads();
     for (int base = 0; base < B; base += 1024) {
         const int i = base + tid;
@@ -132,40 +146,51 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t *context_lens,
             L = L < 0 ? 0 : (L > max_len ? max_len : L);
         }
         const int nfull = L / C;
-        const int nrem = (L % C) != 0;
+        const int r = L % C;
+        const int nrem = r != 0;
         const int s_all = block_scan_1024(nfull + nrem, s_buf);
         const int s_full = block_scan_1024(nfull, s_buf);
-        const int s_rem = block_scan_1024(nrem, s_buf);
-        const int c_all = s_tot[0], c_full = s_tot[1], c_rem = s_tot[2];
+        const int c_all = s_tot[0], c_full = s_tot[1];
         if (i < B) {
             ws.tile_base[i] = c_all + s_all - (nfull + nrem);
             ws.req_full_base[i] = c_full + s_full - nfull;
-            ws.req_rem_base[i] = c_rem + s_rem - nrem;
+            if (nrem) atomicAdd(&s_hist[rem_bucket(r, C)], 1);
+            if (nfull + nrem > 1) ws.merge_req[atomicAdd(&s_merge, 1)] = i;
+            if (L == 0)
+                for (int e = 0; e < H * D; ++e) out[(int64_t)i * H * D + e] = (_Float16)0.0f;
         }
         __syncthreads();
         if (tid == 1023) {
             s_tot[0] = c_all + s_all;
             s_tot[1] = c_full + s_full;
-            s_tot[2] = c_rem + s_rem;
         }
         __syncthreads();
     }
     const int total = s_tot[0], total_full = s_tot[1];
+    // exclusive scan of the bucket counts -> first position of each bucket among the remainders
+    const int my_count = s_hist[tid];
+    const int incl = block_scan_1024(my_count, s_buf);
+    s_hist[tid] = incl - my_count;
+    __syncthreads();
     for (int i = tid; i < B; i += 1024) {
         int L = context_lens[i];
         L = L < 0 ? 0 : (L > max_len ? max_len : L);
         const int nfull = L / C;
-        const int nrem = (L % C) != 0;
+        const int r = L % C;
         const int tb = ws.tile_base[i];
-        const bool split = nfull + nrem > 1;
+        const bool split = nfull + (r != 0) > 1;
         const int fb = ws.req_full_base[i];
         for (int s = 0; s < nfull; ++s)
             ws.order[fb + s] = make_int4(i, s * C, (s + 1) * C, split ? tb + s : -1);
-        if (nrem) ws.order[total_full + ws.req_rem_base[i]] = make_int4(i, nfull * C, L, split ? tb + nfull : -1);
+        if (r) {
+            const int pos = atomicAdd(&s_hist[rem_bucket(r, C)], 1);
+            ws.order[total_full + pos] = make_int4(i, nfull * C, L, split ? tb + nfull : -1);
+        }
     }
     if (tid == 0) {
         ws.tile_base[B] = total;
         *ws.n_items = total * H;
+        *ws.n_merge = s_merge;
         for (int q = 0; q < kQueues; ++q) ws.counter[q * kQueueStride] = 0u;
     }
 }
@@ -205,16 +230,9 @@ struct QSlice {
 };
 
 template <int BITS, int D>
-__device__ __forceinline__ void load_q(QSlice<BITS> &qs, const _Float16 *qrow)
+__device__ __forceinline__ void make_q(QSlice<BITS> &qs, const uint32_t (&raw)[Geo<BITS, D>::SL / 2])
 {
     constexpr int SL = Geo<BITS, D>::SL;
-    const uint32_t *qsrc = reinterpret_cast<const uint32_t *>(qrow);
-    uint32_t raw[SL / 2];
-#pragma unroll
-    for (int k = 0; k < SL / 2; k += 4) {
-        const uint4 v4 = *reinterpret_cast<const uint4 *>(qsrc + k);
-        raw[k] = v4.x; raw[k + 1] = v4.y; raw[k + 2] = v4.z; raw[k + 3] = v4.w;
-    }
     if constexpr (BITS == 8) {
         float s = 0.0f;
 #pragma unroll
@@ -335,7 +353,25 @@ __device__ __forceinline__ void consume_one(const uint4 kc, const uint4 vc, cons
     }
 }
 
+// One work item: a tile (request, token range) for one query head.  Everything is
+// wave-uniform except `pg`, which holds the tile's block-table entries, one per lane.
+struct TileCtx {
+    int valid;          // item index below n_items
+    int i, h, hk;       // request, query head, KV head
+    int t0, t1;         // token range
+    int part;           // split buffer index, or -1: the tile is the whole request
+    int nw, nblk;       // wave-loads, blocks
+    int win_first;      // first page index of the tile
+};
+
 // NB = wave-loads per block; two blocks are in flight per wave.
+//
+// The kernel is one continuous stream of blocks: the last load slot of a tile already
+// fetches the first block of the wave's next tile, the next tile's q is fetched before
+// the epilogue of the current one, and the bookkeeping runs ahead of the data:
+//   queue counter   three items ahead
+//   tile descriptor two items ahead
+//   block-table entries (pg) one item ahead
 template <int BITS, int D, bool UNI, int NB>
 __global__ __launch_bounds__(256) void decode_attn_kernel(AttnParams p)
 {
@@ -363,99 +399,129 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(AttnParams p)
     // Work queues.  Item q + nq * n is the n-th item of queue q; a workgroup serves queue
     // blockIdx % nq.  Workgroups are dealt to the eight XCDs round-robin, so the waves that
     // bump one counter sit on one XCD and its cache line stays in that XCD's L2 instead of
-    // bouncing between dies; any other placement is still correct, only slower.
+    // bouncing between dies; any other placement is still correct, only slower.  (Giving a
+    // queue whole tiles, all heads together, was measured and is slower: coarser balance.)
     const int nq = gridDim.x >= kQueues ? kQueues : 1;
     const int q = blockIdx.x % nq;
     uint32_t *counter = p.ws.counter + q * kQueueStride;
-    // item pipeline: the counter is fetched two items ahead, the descriptor one item ahead
-    int it_cur = 0;
-    if (lane == 0) it_cur = (int)atomicAdd(counter, 1u);
-    it_cur = q + nq * __builtin_amdgcn_readfirstlane(it_cur);
-    int nx = 0;
-    if (lane == 0) nx = (int)atomicAdd(counter, 1u);
-    int4 dc = order[(it_cur < n_items ? it_cur : 0) / p.H];
+    auto next_ticket = [&]() {
+        int n = 0;
+        if (lane == 0) n = (int)atomicAdd(counter, 1u);
+        return n;       // valid in lane 0
+    };
+    auto item_of = [&](int ticket_v) { return q + nq * __builtin_amdgcn_readfirstlane(ticket_v); };
+    auto desc_of = [&](int it) { return order[(it < n_items ? it : 0) / p.H]; };
+    auto make_ctx = [&](int it, const int4 d) {
+        TileCtx c;
+        c.valid = it < n_items;
+        c.h = (it < n_items ? it : 0) % p.H;
+        c.hk = c.h / p.qper;
+        c.i = __builtin_amdgcn_readfirstlane(d.x);
+        c.t0 = __builtin_amdgcn_readfirstlane(d.y);
+        c.t1 = __builtin_amdgcn_readfirstlane(d.z);
+        c.part = __builtin_amdgcn_readfirstlane(d.w);
+        c.nw = (c.t1 - c.t0 + TPW - 1) / TPW;
+        c.nblk = (c.nw + NB - 1) / NB;
+        c.win_first = c.t0 >> logP;
+        return c;
+    };
+    // a tile spans at most 64 pages, so one entry per lane covers it
+    auto load_pg = [&](const TileCtx &c) {
+        const int32_t *bt = p.block_tables + (int64_t)c.i * p.max_blocks;
+        return bt[min(c.win_first + lane, (c.t1 - 1) >> logP)];
+    };
+    auto load_q_raw = [&](const TileCtx &c, uint32_t (&raw)[SL / 2]) {
+        const uint32_t *qsrc = reinterpret_cast<const uint32_t *>(p.q + ((int64_t)c.i * p.H + c.h) * D + ch0);
+#pragma unroll
+        for (int k = 0; k < SL / 2; k += 4) {
+            const uint4 v4 = *reinterpret_cast<const uint4 *>(qsrc + k);
+            raw[k] = v4.x; raw[k + 1] = v4.y; raw[k + 2] = v4.z; raw[k + 3] = v4.w;
+        }
+    };
 
-    while (it_cur < n_items) {
-        const int it_next = q + nq * __builtin_amdgcn_readfirstlane(nx);
-        const int4 dn = order[(it_next < n_items ? it_next : 0) / p.H];
-        if (lane == 0) nx = (int)atomicAdd(counter, 1u);
+    // Issue the NB wave-loads of block k of tile c.  Straight-line code on purpose: a branch
+    // around a load would make the compiler wait for every outstanding load at the join,
+    // which serialises the two buffers.  Wave-loads past the end of the tile re-read its
+    // last wave-load; their tokens are masked when consumed.
+    auto issue = [&](Buf<NB> &buf, const TileCtx &c, int pg, int k) {
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            const int w = min(k * NB + j, c.nw - 1);
+            const int tw = c.t0 + w * TPW;
+            if constexpr (UNI) {
+                const int page = __builtin_amdgcn_readlane(pg, (tw >> logP) - c.win_first);
+                const int blk = page * Hkv + c.hk;                    // < 2^31, checked on the host
+                const int off = tw & (P - 1);
+                const int64_t co = (int64_t)blk * p.c.cstride + off * ROWB;
+                const int64_t mo = (int64_t)blk * p.c.mstride + off * NG * 4;
+                buf.kc[j] = *reinterpret_cast<const uint4 *>(lane_k + co);
+                buf.vc[j] = *reinterpret_cast<const uint4 *>(lane_v + co);
+                buf.km[j] = *reinterpret_cast<const uint32_t *>(lane_km + mo);
+                buf.vm[j] = *reinterpret_cast<const uint32_t *>(lane_vm + mo);
+            } else {
+                const int tok = tw + slot;
+                const int tc = tok < c.t1 ? tok : c.t1 - 1;        // stay on a real token
+                const int page = __shfl(pg, (tc >> logP) - c.win_first);
+                const int blk = page * Hkv + c.hk;
+                const int off = tc & (P - 1);
+                const int64_t co = (int64_t)blk * p.c.cstride + off * ROWB + sub * 16;
+                const int64_t mo = (int64_t)blk * p.c.mstride + (off * NG + grp) * 4;
+                buf.kc[j] = *reinterpret_cast<const uint4 *>(p.c.k_codes + co);
+                buf.vc[j] = *reinterpret_cast<const uint4 *>(p.c.v_codes + co);
+                buf.km[j] = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const uint8_t *>(p.c.k_meta) + mo);
+                buf.vm[j] = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const uint8_t *>(p.c.v_meta) + mo);
+            }
+        }
+    };
 
-        const int h = it_cur % p.H;
-        const int i = __builtin_amdgcn_readfirstlane(dc.x);
-        const int t0 = __builtin_amdgcn_readfirstlane(dc.y);
-        const int t1 = __builtin_amdgcn_readfirstlane(dc.z);
-        const int part_idx = __builtin_amdgcn_readfirstlane(dc.w);
-        const int hk = h / p.qper;
-        const int32_t *bt = p.block_tables + (int64_t)i * p.max_blocks;
-        const int last_blk = (t1 - 1) >> logP;
+    // ---- fill the pipeline
+    const int tk0 = next_ticket(), tk1 = next_ticket(), tk2 = next_ticket();
+    int tk3 = next_ticket();
+    const int it0 = item_of(tk0), it1 = item_of(tk1);
+    int it2 = item_of(tk2);
+    TileCtx cur = make_ctx(it0, desc_of(it0));
+    if (!cur.valid) return;                     // wave-uniform
+    TileCtx nxt = make_ctx(it1, desc_of(it1));
+    int4 d2 = desc_of(it2);
+    int pg_cur = load_pg(cur);
+    int pg_nxt = load_pg(nxt);
+    uint32_t qraw[SL / 2];
+    load_q_raw(cur, qraw);
+    Buf<NB> bufA, bufB;
+    issue(bufA, cur, pg_cur, 0);
 
-        // the tile's block-table entries, one per lane (a tile spans at most 64 pages)
-        const int win_first = t0 >> logP;
-        const int pgreg = bt[min(win_first + lane, last_blk)];
-
+    for (;;) {
         QSlice<BITS> qs;
-        load_q<BITS, D>(qs, p.q + ((int64_t)i * p.H + h) * D + ch0);
+        make_q<BITS, D>(qs, qraw);
 
         Acc<SL> st;
         st.m_ref = kFloor; st.l = 0.0f; st.wz = 0.0f;
 #pragma unroll
         for (int k = 0; k < SL; ++k) st.a[k] = 0.0f;
 
-        const int nw = (t1 - t0 + TPW - 1) / TPW;     // wave-loads in the tile
-        const int nblk = (nw + NB - 1) / NB;          // blocks of NB wave-loads
-
-        // Issue the NB wave-loads of block k.  Straight-line code on purpose: a branch around
-        // a load would make the compiler wait for every outstanding load at the join, which
-        // serialises the two buffers.  Wave-loads past the end of the tile re-read its last
-        // wave-load; their tokens are masked when consumed.
-        auto issue = [&](Buf<NB> &buf, int k) {
-#pragma unroll
-            for (int j = 0; j < NB; ++j) {
-                const int w = min(k * NB + j, nw - 1);
-                const int tw = t0 + w * TPW;
-                if constexpr (UNI) {
-                    const int page = __builtin_amdgcn_readlane(pgreg, (tw >> logP) - win_first);
-                    const int blk = page * Hkv + hk;                    // < 2^31, checked on the host
-                    const int off = tw & (P - 1);
-                    const int64_t co = (int64_t)blk * p.c.cstride + off * ROWB;
-                    const int64_t mo = (int64_t)blk * p.c.mstride + off * NG * 4;
-                    buf.kc[j] = *reinterpret_cast<const uint4 *>(lane_k + co);
-                    buf.vc[j] = *reinterpret_cast<const uint4 *>(lane_v + co);
-                    buf.km[j] = *reinterpret_cast<const uint32_t *>(lane_km + mo);
-                    buf.vm[j] = *reinterpret_cast<const uint32_t *>(lane_vm + mo);
-                } else {
-                    const int tok = tw + slot;
-                    const int tc = tok < t1 ? tok : t1 - 1;        // stay on a real token
-                    const int page = __shfl(pgreg, (tc >> logP) - win_first);
-                    const int blk = page * Hkv + hk;
-                    const int off = tc & (P - 1);
-                    const int64_t co = (int64_t)blk * p.c.cstride + off * ROWB + sub * 16;
-                    const int64_t mo = (int64_t)blk * p.c.mstride + (off * NG + grp) * 4;
-                    buf.kc[j] = *reinterpret_cast<const uint4 *>(p.c.k_codes + co);
-                    buf.vc[j] = *reinterpret_cast<const uint4 *>(p.c.v_codes + co);
-                    buf.km[j] = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const uint8_t *>(p.c.k_meta) + mo);
-                    buf.vm[j] = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const uint8_t *>(p.c.v_meta) + mo);
-                }
-            }
-        };
         auto eat = [&](const Buf<NB> &buf, int k) {
 #pragma unroll
             for (int j = 0; j < NB; ++j) {
-                const bool valid = t0 + k * BT + j * TPW + slot < t1;
+                const bool valid = cur.t0 + k * BT + j * TPW + slot < cur.t1;
                 consume_one<BITS, D>(buf.kc[j], buf.vc[j], buf.km[j], buf.vm[j], st, qs, p.scale_log2e, valid);
             }
         };
 
-        {
-            Buf<NB> bufA, bufB;
-            issue(bufA, 0);
-            for (int k = 0; k < nblk; k += 2) {
-                issue(bufB, min(k + 1, nblk - 1));
-                eat(bufA, k);
-                issue(bufA, min(k + 2, nblk - 1));
-                if (k + 1 < nblk) eat(bufB, k + 1);
-            }
+        // bufA holds block 0 of the tile (in flight).  The slot after the tile's last block
+        // fetches block 0 of the next tile, so bufA is ready for it when this tile is done.
+        const int nblk = cur.nblk;
+        for (int k = 0; k < nblk; k += 2) {
+            issue(bufB, cur, pg_cur, min(k + 1, nblk - 1));
+            eat(bufA, k);
+            const bool hop = (k + 2 >= nblk) && nxt.valid;      // wave-uniform
+            TileCtx src = cur;
+            if (hop) src = nxt;
+            issue(bufA, src, hop ? pg_nxt : pg_cur, hop ? 0 : min(k + 2, nblk - 1));
+            if (k + 1 < nblk) eat(bufB, k + 1);
         }
+
+        // the next tile's q, in flight during the epilogue
+        load_q_raw(nxt.valid ? nxt : cur, qraw);
 
         // ---- bring the TPW slots to one maximum, then add them up through LDS
         float m_fin = st.m_ref;
@@ -496,78 +562,111 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(AttnParams p)
         }
         wave_lds_sync();   // the next item overwrites `red`
 
-        if (part_idx < 0) {
+        if (cur.part < 0) {
             const float inv_l = 1.0f / l;
-            _Float16 *dst = p.out + ((int64_t)i * p.H + h) * D;
+            _Float16 *dst = p.out + ((int64_t)cur.i * p.H + cur.h) * D;
 #pragma unroll
             for (int r = 0; r < D / 64; ++r) dst[r * 64 + lane] = (_Float16)(o[r] * inv_l);
         } else {
-            float *dst = p.ws.part + ((int64_t)part_idx * p.H + h) * (D + 2);
+            float *dst = p.ws.part + ((int64_t)cur.part * p.H + cur.h) * (D + 2);
             if (lane == 0) { dst[0] = m_fin; dst[1] = l; }
 #pragma unroll
             for (int r = 0; r < D / 64; ++r) dst[2 + r * 64 + lane] = o[r];
         }
 
-        it_cur = it_next;
-        dc = dn;
+        // ---- advance the pipeline (loads below are unconditional; indices are clamped)
+        if (!nxt.valid) break;                  // wave-uniform; nothing is in flight that matters
+        cur = nxt;
+        pg_cur = pg_nxt;
+        nxt = make_ctx(it2, d2);
+        pg_nxt = load_pg(nxt);
+        it2 = item_of(tk3);
+        d2 = desc_of(it2);
+        tk3 = next_ticket();
     }
 }
 
 // ------------------------------------------------------------------ merge
 
-// One wave per (request, head): zero rows for empty requests, log-sum-exp combination
-// of the splits of requests longer than one split; single-split rows were already written.
+// Log-sum-exp combination of the splits of every request that has more than one; a
+// fixed grid of waves strides over (listed request, head) pairs.  Lane c reads the (m, l)
+// header of split c, so the maximum and the denominator are two wave reductions, and the
+// weighted rows are then fetched with independent loads.
 template <int D>
 __global__ __launch_bounds__(256) void merge_kernel(AttnParams p)
 {
     const int lane = threadIdx.x & 63;
-    const int ih = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (ih >= p.B * p.H) return;
-    const int i = ih / p.H, h = ih - i * p.H;
-    const int first = p.ws.tile_base[i];
-    const int n = p.ws.tile_base[i + 1] - first;
-    if (n == 1) return;
-    _Float16 *dst = p.out + (int64_t)ih * D;
-    if (n == 0) {
+    const int n_waves = gridDim.x * 4;
+    const int n_pairs = *p.ws.n_merge * p.H;
+    for (int pair = blockIdx.x * 4 + (threadIdx.x >> 6); pair < n_pairs; pair += n_waves) {
+        const int i = p.ws.merge_req[pair / p.H], h = pair % p.H;
+        const int first = p.ws.tile_base[i];
+        const int n = p.ws.tile_base[i + 1] - first;
+        const float *part = p.ws.part + ((int64_t)first * p.H + h) * (D + 2);
+        const int64_t stride = (int64_t)p.H * (D + 2);
+        float m = kNegInf, l = 0.0f, o[D / 64];
 #pragma unroll
-        for (int r = 0; r < D / 64; ++r) dst[r * 64 + lane] = (_Float16)0.0f;
-        return;
+        for (int r = 0; r < D / 64; ++r) o[r] = 0.0f;
+        for (int c0 = 0; c0 < n; c0 += 64) {            // 64 splits at a time
+            const int nc = min(64, n - c0);
+            const float *pc = part + (c0 + min(lane, nc - 1)) * stride;
+            const float mc = lane < nc ? pc[0] : kNegInf;
+            const float lc = lane < nc ? pc[1] : 0.0f;
+            float m_new = mc;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) m_new = fmaxf(m_new, __shfl_xor(m_new, d));
+            m_new = fmaxf(m_new, m);
+            const float fc = __builtin_amdgcn_exp2f(mc - m_new);        // weight of split c0 + lane
+            const float fo = __builtin_amdgcn_exp2f(m - m_new);         // rescale what was merged before
+            float lsum = lc * fc;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) lsum += __shfl_xor(lsum, d);
+            l = l * fo + lsum;
+#pragma unroll
+            for (int r = 0; r < D / 64; ++r) o[r] *= fo;
+            for (int c = 0; c < nc; ++c) {
+                const float f = __shfl(fc, c);
+                const float *row = part + (c0 + c) * stride + 2;
+#pragma unroll
+                for (int r = 0; r < D / 64; ++r) o[r] = __builtin_fmaf(row[r * 64 + lane], f, o[r]);
+            }
+            m = m_new;
+        }
+        const float inv_l = 1.0f / l;
+        _Float16 *dst = p.out + ((int64_t)i * p.H + h) * D;
+#pragma unroll
+        for (int r = 0; r < D / 64; ++r) dst[r * 64 + lane] = (_Float16)(o[r] * inv_l);
     }
-    const float *part = p.ws.part + ((int64_t)first * p.H + h) * (D + 2);
-    const int64_t stride = (int64_t)p.H * (D + 2);
-    float m = kNegInf;
-    for (int c = 0; c < n; ++c) m = fmaxf(m, part[c * stride]);
-    float l = 0.0f, o[D / 64];
-#pragma unroll
-    for (int r = 0; r < D / 64; ++r) o[r] = 0.0f;
-    for (int c = 0; c < n; ++c) {
-        const float *pc = part + c * stride;
-        const float f = __builtin_amdgcn_exp2f(pc[0] - m);
-        l = __builtin_fmaf(pc[1], f, l);
-#pragma unroll
-        for (int r = 0; r < D / 64; ++r) o[r] = __builtin_fmaf(pc[2 + r * 64 + lane], f, o[r]);
-    }
-    const float inv_l = 1.0f / l;
-#pragma unroll
-    for (int r = 0; r < D / 64; ++r) dst[r * 64 + lane] = (_Float16)(o[r] * inv_l);
 }
 
 template <int BITS, int D, int NB>
-hipError_t launch_t(const AttnParams &p, int32_t resident_waves, hipStream_t s)
+hipError_t launch_t(const AttnParams &p, int32_t num_cus, int32_t waves_per_cu, hipStream_t s)
 {
-    int blocks = resident_waves / 4;
+    // a wave-load covers TPW consecutive tokens; it has one page if pages are at least that long
+    const bool uniform_page = p.c.P >= Geo<BITS, D>::TPW;
+    // The grid is persistent: as many workgroups as the kernel's registers and LDS let the
+    // chip hold at once (asked once per kernel variant), unless the caller fixes the number.
+    static int resident_wgs_per_cu[2] = {0, 0};
+    int &occ = resident_wgs_per_cu[uniform_page ? 1 : 0];
+    if (occ == 0) {
+        int n = 0;
+        hipError_t oe = uniform_page
+            ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, decode_attn_kernel<BITS, D, true, NB>, 256, 0)
+            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, decode_attn_kernel<BITS, D, false, NB>, 256, 0);
+        occ = (oe == hipSuccess && n > 0) ? n : 2;
+    }
+    int blocks = num_cus * (waves_per_cu > 0 ? waves_per_cu / 4 : occ);
     const int64_t max_items = (int64_t)p.ws.max_tiles * p.H;
     if ((int64_t)blocks * 4 > max_items) blocks = (int)((max_items + 3) / 4);
     if (blocks < 1) blocks = 1;
-    // a wave-load covers TPW consecutive tokens; it has one page if pages are at least that long
-    const bool uniform_page = p.c.P >= Geo<BITS, D>::TPW;
     if (uniform_page)
         hipLaunchKernelGGL((decode_attn_kernel<BITS, D, true, NB>), dim3(blocks), dim3(256), 0, s, p);
     else
         hipLaunchKernelGGL((decode_attn_kernel<BITS, D, false, NB>), dim3(blocks), dim3(256), 0, s, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int mblocks = (p.B * p.H + 3) / 4;
+    int mblocks = (p.B * p.H + 3) / 4;
+    if (mblocks > 1024) mblocks = 1024;
     hipLaunchKernelGGL((merge_kernel<D>), dim3(mblocks), dim3(256), 0, s, p);
     return hipGetLastError();
 }
@@ -578,8 +677,8 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
                               const int32_t *block_tables, int32_t max_blocks,
                               const int32_t *context_lens, int32_t B, int32_t H,
                               int32_t max_context_len, float softmax_scale,
-                              const AttnWorkspace &ws, int32_t resident_waves, int32_t loads_per_block,
-                              hipStream_t s)
+                              const AttnWorkspace &ws, int32_t num_cus, int32_t waves_per_cu,
+                              int32_t loads_per_block, hipStream_t s)
 {
     if (B == 0) return hipSuccess;
     AttnParams p;
@@ -595,15 +694,15 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
     p.max_len = max_context_len;
     p.scale_log2e = softmax_scale * 1.44269504088896340736f;
     p.ws = ws;
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, s, context_lens, B, H, max_context_len, ws);
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, s, context_lens, B, H, max_context_len, ws, p.out, c.D);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 #define ALISE_DISPATCH(NBV)                                                              \
     do {                                                                                 \
-        if (c.bits == 8 && c.D == 128) return launch_t<8, 128, NBV>(p, resident_waves, s); \
-        if (c.bits == 8 && c.D == 64) return launch_t<8, 64, NBV>(p, resident_waves, s);   \
-        if (c.bits == 4 && c.D == 128) return launch_t<4, 128, NBV>(p, resident_waves, s); \
-        if (c.bits == 4 && c.D == 64) return launch_t<4, 64, NBV>(p, resident_waves, s);   \
+        if (c.bits == 8 && c.D == 128) return launch_t<8, 128, NBV>(p, num_cus, waves_per_cu, s); \
+        if (c.bits == 8 && c.D == 64) return launch_t<8, 64, NBV>(p, num_cus, waves_per_cu, s);   \
+        if (c.bits == 4 && c.D == 128) return launch_t<4, 128, NBV>(p, num_cus, waves_per_cu, s); \
+        if (c.bits == 4 && c.D == 64) return launch_t<4, 64, NBV>(p, num_cus, waves_per_cu, s);   \
     } while (0)
     if (loads_per_block == 2) ALISE_DISPATCH(2);
     if (loads_per_block == 3) ALISE_DISPATCH(3);
