@@ -74,11 +74,13 @@ int check_cache_pointers(const alise_kv_cache *c)
 // the default (a multiple of 64) for tuning.
 // A split never spans more than 64 pages: the attention kernel keeps a split's
 // block-table entries in one register, one entry per lane.
-int32_t split_tokens(int32_t page_size)
+// The matrix-core path hands a whole group of query heads to one wave, so it has fewer
+// items per tile and takes shorter tiles (ALISE_SPLIT_TOKENS_GQA overrides).
+int32_t split_tokens(int32_t page_size, bool gqa)
 {
-    const char *e = std::getenv("ALISE_SPLIT_TOKENS");
+    const char *e = std::getenv(gqa ? "ALISE_SPLIT_TOKENS_GQA" : "ALISE_SPLIT_TOKENS");
     long v = e ? std::strtol(e, nullptr, 10) : 0;
-    if (v < 64 || v > (1 << 20) || (v % 64) != 0) v = 1024;
+    if (v < 64 || v > (1 << 20) || (v % 64) != 0) v = gqa ? 256 : 1024;
     if (v > 64L * page_size) v = 64L * page_size;
     return (int32_t)v;
 }
@@ -109,7 +111,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 size_t carve_workspace(const CacheView &c, int32_t B, int32_t H, int32_t max_len, void *base,
                        AttnWorkspace *ws)
 {
-    const int32_t C = split_tokens(c.P);
+    const int32_t C = split_tokens(c.P, alise::gqa_mfma_applies(c, H));
     const int64_t splits = ((int64_t)max_len + C - 1) / C;
     const int64_t max_tiles = (int64_t)B * (splits > 0 ? splits : 1);
     size_t off = 2304;      // eight queue counters, 256 bytes apart, then n_items
@@ -143,7 +145,8 @@ int check_attn_sizes(const CacheView &c, int32_t B, int32_t H, int32_t max_len)
 {
     if (B < 0 || H <= 0 || max_len < 0) return ALISE_INVALID_ARGUMENT;
     if (H % c.Hkv != 0) return ALISE_UNSUPPORTED;
-    const int64_t splits = ((int64_t)max_len + split_tokens(c.P) - 1) / split_tokens(c.P);
+    const int32_t C = split_tokens(c.P, alise::gqa_mfma_applies(c, H));
+    const int64_t splits = ((int64_t)max_len + C - 1) / C;
     if ((int64_t)B * (splits > 0 ? splits : 1) * H >= (int64_t)1 << 31) return ALISE_UNSUPPORTED;
     return ALISE_OK;
 }

@@ -28,6 +28,10 @@ struct AttnWorkspace {
     int32_t chunk_tokens;   // tokens per split
 };
 
+// True when the attention call takes the matrix-core path for grouped-query layouts
+// (its tiles are shorter, so the workspace is carved differently).
+bool gqa_mfma_applies(const CacheView &c, int32_t H);
+
 hipError_t launch_quant_write(const CacheView &c, const void *k, const void *v,
                               const int64_t *slot_mapping, int32_t T, hipStream_t s);
 

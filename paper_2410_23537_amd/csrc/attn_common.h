@@ -1,0 +1,39 @@
+// Definitions shared by the attention kernels (vector path and GQA matrix-core path).
+#pragma once
+#include "alise_kernels.h"
+
+#include <hip/hip_fp16.h>
+
+#include <type_traits>
+
+namespace alise {
+
+typedef _Float16 h2_t __attribute__((ext_vector_type(2)));
+
+constexpr float kNegInf = -__builtin_inff();
+constexpr float kLazy = 8.0f;   // the running maximum is raised only past this slack (log2 units)
+constexpr int kQueues = 8;          // work queues of the attention kernels, one per XCD
+constexpr int kQueueStride = 64;    // uint32 between queue counters: one 256-byte line each
+constexpr float kFloor = -1.0e30f;   // finite stand-in for "no token seen yet": -inf - kFloor stays -inf
+
+struct AttnParams {
+    CacheView c;
+    const _Float16 *q;
+    _Float16 *out;
+    const int32_t *block_tables;
+    const int32_t *context_lens;
+    int32_t max_blocks, B, H, qper, max_len;
+    float scale_log2e;
+    AttnWorkspace ws;
+};
+
+__device__ __forceinline__ h2_t as_h2(uint32_t u) { return __builtin_bit_cast(h2_t, u); }
+__device__ __forceinline__ uint32_t as_u32(h2_t h) { return __builtin_bit_cast(uint32_t, h); }
+__device__ __forceinline__ float half_lo(uint32_t u) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(u & 0xffffu)); }
+__device__ __forceinline__ float half_hi(uint32_t u) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(u >> 16)); }
+
+// The matrix-core kernel for grouped-query attention: one wave serves all query heads of a
+// KV head, so a tile's items are its KV heads.  Defined in decode_attn_gqa.hip.
+hipError_t launch_gqa_mfma(const AttnParams &p, int32_t num_cus, hipStream_t s);
+
+}  // namespace alise

@@ -28,38 +28,10 @@
 // and feeds the packed fp16 dot product (fp32 accumulate; the 1024 sum(q) offset leaves
 // with the zero-point); for V the bare code bits are the fp16 subnormal code * 2^-24,
 // which the mixed-precision FMA multiplies by the fp32 weight exactly.
-#include "alise_kernels.h"
-
-#include <hip/hip_fp16.h>
-
-#include <type_traits>
+#include "attn_common.h"
 
 namespace alise {
 namespace {
-
-typedef _Float16 h2_t __attribute__((ext_vector_type(2)));
-
-constexpr float kNegInf = -__builtin_inff();
-constexpr float kLazy = 8.0f;   // the running maximum is raised only past this slack (log2 units)
-constexpr int kQueues = 8;          // work queues of the attention kernel, one per XCD
-constexpr int kQueueStride = 64;    // uint32 between queue counters: one 256-byte line each
-constexpr float kFloor = -1.0e30f;   // finite stand-in for "no token seen yet": -inf - kFloor stays -inf
-
-struct AttnParams {
-    CacheView c;
-    const _Float16 *q;
-    _Float16 *out;
-    const int32_t *block_tables;
-    const int32_t *context_lens;
-    int32_t max_blocks, B, H, qper, max_len;
-    float scale_log2e;
-    AttnWorkspace ws;
-};
-
-__device__ __forceinline__ h2_t as_h2(uint32_t u) { return __builtin_bit_cast(h2_t, u); }
-__device__ __forceinline__ uint32_t as_u32(h2_t h) { return __builtin_bit_cast(uint32_t, h); }
-__device__ __forceinline__ float half_lo(uint32_t u) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(u & 0xffffu)); }
-__device__ __forceinline__ float half_hi(uint32_t u) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(u >> 16)); }
 
 // (x & mask) | bits in one instruction; the mask sits in a scalar register.
 __device__ __forceinline__ uint32_t and_or(uint32_t x, uint32_t mask, uint32_t bits)
@@ -126,7 +98,8 @@ __device__ __forceinline__ int rem_bucket(int r, int C)
 // bucket is arbitrary), so that the waves that finish last finish on the shortest items.
 // Also lists the requests whose splits need merging and zeroes the rows of empty requests.
 __global__ __launch_bounds__(1024) void plan_kernel(const int32_t *context_lens, int32_t B, int32_t H,
-                                                    int32_t max_len, AttnWorkspace ws, _Float16 *out, int32_t D)
+                                                    int32_t items_per_tile, int32_t max_len, AttnWorkspace ws,
+                                                    _Float16 *out, int32_t D)
 {
     __shared__ int32_t s_buf[1024];
     __shared__ int32_t s_hist[kRemBuckets];
@@ -189,7 +162,7 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t *context_lens,
     }
     if (tid == 0) {
         ws.tile_base[B] = total;
-        *ws.n_items = total * H;
+        *ws.n_items = total * items_per_tile;
         *ws.n_merge = s_merge;
         for (int q = 0; q < kQueues; ++q) ws.counter[q * kQueueStride] = 0u;
     }
@@ -663,11 +636,17 @@ hipError_t launch_t(const AttnParams &p, int32_t num_cus, int32_t waves_per_cu, 
         hipLaunchKernelGGL((decode_attn_kernel<BITS, D, true, NB>), dim3(blocks), dim3(256), 0, s, p);
     else
         hipLaunchKernelGGL((decode_attn_kernel<BITS, D, false, NB>), dim3(blocks), dim3(256), 0, s, p);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    return hipGetLastError();
+}
+
+hipError_t launch_merge(const AttnParams &p, hipStream_t s)
+{
     int mblocks = (p.B * p.H + 3) / 4;
     if (mblocks > 1024) mblocks = 1024;
-    hipLaunchKernelGGL((merge_kernel<D>), dim3(mblocks), dim3(256), 0, s, p);
+    if (p.c.D == 128)
+        hipLaunchKernelGGL((merge_kernel<128>), dim3(mblocks), dim3(256), 0, s, p);
+    else
+        hipLaunchKernelGGL((merge_kernel<64>), dim3(mblocks), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 
@@ -694,21 +673,29 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
     p.max_len = max_context_len;
     p.scale_log2e = softmax_scale * 1.44269504088896340736f;
     p.ws = ws;
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, s, context_lens, B, H, max_context_len, ws, p.out, c.D);
+    const bool gqa = gqa_mfma_applies(c, H);
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, s, context_lens, B, H, gqa ? c.Hkv : H, max_context_len, ws,
+                       p.out, c.D);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-#define ALISE_DISPATCH(NBV)                                                              \
-    do {                                                                                 \
-        if (c.bits == 8 && c.D == 128) return launch_t<8, 128, NBV>(p, num_cus, waves_per_cu, s); \
-        if (c.bits == 8 && c.D == 64) return launch_t<8, 64, NBV>(p, num_cus, waves_per_cu, s);   \
-        if (c.bits == 4 && c.D == 128) return launch_t<4, 128, NBV>(p, num_cus, waves_per_cu, s); \
-        if (c.bits == 4 && c.D == 64) return launch_t<4, 64, NBV>(p, num_cus, waves_per_cu, s);   \
+    e = hipErrorInvalidValue;
+    if (gqa) {
+        e = launch_gqa_mfma(p, num_cus, s);
+    } else {
+#define ALISE_DISPATCH(NBV)                                                                          \
+    do {                                                                                             \
+        if (c.bits == 8 && c.D == 128) e = launch_t<8, 128, NBV>(p, num_cus, waves_per_cu, s);        \
+        else if (c.bits == 8 && c.D == 64) e = launch_t<8, 64, NBV>(p, num_cus, waves_per_cu, s);     \
+        else if (c.bits == 4 && c.D == 128) e = launch_t<4, 128, NBV>(p, num_cus, waves_per_cu, s);   \
+        else if (c.bits == 4 && c.D == 64) e = launch_t<4, 64, NBV>(p, num_cus, waves_per_cu, s);     \
     } while (0)
-    if (loads_per_block == 2) ALISE_DISPATCH(2);
-    if (loads_per_block == 3) ALISE_DISPATCH(3);
-    if (loads_per_block == 4) ALISE_DISPATCH(4);
+        if (loads_per_block == 2) ALISE_DISPATCH(2);
+        else if (loads_per_block == 3) ALISE_DISPATCH(3);
+        else if (loads_per_block == 4) ALISE_DISPATCH(4);
 #undef ALISE_DISPATCH
-    return hipErrorInvalidValue;
+    }
+    if (e != hipSuccess) return e;
+    return launch_merge(p, s);
 }
 
 }  // namespace alise

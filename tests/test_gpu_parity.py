@@ -52,6 +52,13 @@ SMALL = [
     wl.replace(wl.scaled(wl.CONFIGS["int4"], B=6, max_len=600, name="int4_d64"), D=64, G=32, P=32),
     wl.replace(wl.scaled(wl.CONFIGS["opt13b"], B=5, max_len=300, name="int8_g16_p8"), G=16, P=8, Hkv=3, H=3),
     wl.replace(wl.scaled(wl.CONFIGS["int4"], B=5, max_len=400, name="int4_g128_gqa"), G=128, Hkv=2, H=6, P=64),
+    # grouped-query layouts on the matrix-core path: two groups per row, 16 and 3 query heads per KV head
+    wl.replace(wl.scaled(wl.CONFIGS["gqa70b"], B=5, max_len=700, name="gqa_g64_p16"), G=64, P=16, Hkv=2, H=8,
+               length_law="uniform:1,700"),
+    wl.replace(wl.scaled(wl.CONFIGS["gqa70b"], B=4, max_len=600, name="gqa_q16_p64"), G=128, P=64, Hkv=1, H=16,
+               length_law="uniform:30,600"),
+    wl.replace(wl.scaled(wl.CONFIGS["gqa70b"], B=6, max_len=300, name="gqa_q3"), G=128, P=32, Hkv=2, H=6,
+               length_law="uniform:1,300"),
 ]
 
 
@@ -88,14 +95,16 @@ def test_write_attend_dequant(env, w, layout):
         assert np.array_equal(v_out.cpu().numpy().view(np.uint16)[rows], vo.view(np.uint16)[rows])
 
 
-@pytest.mark.parametrize("bits,G", [(8, 64), (4, 32)])
-def test_edge_lengths_and_splits(env, bits, G):
-    """Empty and one-token requests, lengths around page and split boundaries, several splits."""
+@pytest.mark.parametrize("bits,G,H", [(8, 64, 4), (4, 32, 4), (8, 128, 16)])
+def test_edge_lengths_and_splits(env, bits, G, H):
+    """Empty and one-token requests, lengths around page and split boundaries, several splits;
+    H = 16 over 4 KV heads takes the grouped-query path (splits of 256 tokens)."""
     B, torch, oracle = env
-    lens = np.array([0, 1, 15, 16, 17, 63, 64, 65, 511, 512, 513, 1024, 1025, 2, 2100, 0, 3], np.int32)
-    w = wl.Workload("edges", B=len(lens), H=4, Hkv=4, D=128, P=16, bits=bits, G=G,
+    lens = np.array([0, 1, 15, 16, 17, 31, 32, 33, 63, 64, 65, 255, 256, 257, 511, 512, 513, 1024, 1025, 2, 2100, 0, 3],
+                    np.int32)
+    w = wl.Workload("edges", B=len(lens), H=H, Hkv=4, D=128, P=16, bits=bits, G=G,
                     length_law="fixed:1", seed=77 + bits, max_len=int(lens.max()))
-    print(f"case edges bits={bits} G={G}", flush=True)
+    print(f"case edges bits={bits} G={G} H={H}", flush=True)
     pg, pool, offs, gain = _problem(w, lens)
     orc = harness.fill_oracle_cache(oracle, w, pg, pool, offs, gain)
     dev = harness.fill_device_cache(B, torch, w, pg, pool, offs, gain)
