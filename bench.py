@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published peak HBM3E bandwidth
 
 # HBM bytes per attention launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a
 # copy kernel of known size; see profiles/.  None where not measured.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {"int4": 7184247468, "gqa70b": 1162731943, "llama7b": 1967319825}
 
 
 def parse():
@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--workload", default="int4")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-calibration", action="store_true",
+                    help="also launch an elementwise kernel that reads and writes exactly 1 GiB, so that a "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run of this command can be scaled")
     return ap.parse_args()
 
 
@@ -158,6 +161,13 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
+    if args.traffic_calibration:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(2):
+            torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+
     ms_per_step = elapsed / args.steps * 1e3
     attn_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
     write_ms = float(np.mean([a.elapsed_time(b) for a, b in evw]))
@@ -178,7 +188,9 @@ def main():
         "kv_tokens_per_s": step.kv_tokens() / (ms_per_step * 1e-3),
         "bytes_per_step": {"attn": b_attn, "quant_write": b_write, "dequant_page": b_dq},
         "kernel_ms": {"paged_decode_attn": attn_ms, "quant_write": write_ms},
-        "roofline": {"bound": "hbm", "kernel": "decode_attn_kernel (alise_paged_decode_attn)",
+        "roofline": {"bound": "hbm",
+                     "kernel": "alise_paged_decode_attn = plan_kernel + decode_attn(_gqa)_kernel + merge_kernel, "
+                               "timed as one call; the attention kernel is >97 % of it",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(w.name)},
     }
