@@ -76,12 +76,19 @@ int check_cache_pointers(const alise_kv_cache *c)
 // block-table entries in one register, one entry per lane.
 // The matrix-core path hands a whole group of query heads to one wave, so it has fewer
 // items per tile and takes shorter tiles (ALISE_SPLIT_TOKENS_GQA overrides).
-int32_t split_tokens(int32_t page_size, bool gqa)
+// Returns the largest split; *min_split is the smallest the plan kernel may fall back to
+// when a batch is too small to give every wave several items (equal to the largest when
+// the environment fixes the split).
+int32_t split_tokens(int32_t page_size, bool gqa, int32_t *min_split)
 {
     const char *e = std::getenv(gqa ? "ALISE_SPLIT_TOKENS_GQA" : "ALISE_SPLIT_TOKENS");
     long v = e ? std::strtol(e, nullptr, 10) : 0;
-    if (v < 64 || v > (1 << 20) || (v % 64) != 0) v = gqa ? 256 : 1024;
+    const bool fixed = !(v < 64 || v > (1 << 20) || (v % 64) != 0);
+    if (!fixed) v = 1024;
     if (v > 64L * page_size) v = 64L * page_size;
+    long lo = fixed ? v : 256;
+    if (lo > v) lo = v;
+    if (min_split) *min_split = (int32_t)lo;
     return (int32_t)v;
 }
 
@@ -100,7 +107,17 @@ int32_t loads_per_block()
 {
     const char *e = std::getenv("ALISE_LOADS_PER_BLOCK");
     long v = e ? std::strtol(e, nullptr, 10) : 0;
-    if (v < 2 || v > 4) v = 2;
+    if (v < 2 || v > 4) v = 0;      // 0: the kernel's default for the cache's bit width
+    return (int32_t)v;
+}
+
+// Items per wave below which the plan kernel shortens the splits (ALISE_MIN_ITEMS_PER_WAVE
+// overrides; 0 = the kernels' own defaults).
+int32_t min_items_per_wave()
+{
+    const char *e = std::getenv("ALISE_MIN_ITEMS_PER_WAVE");
+    long v = e ? std::strtol(e, nullptr, 10) : 0;
+    if (v < 0 || v > 1024) v = 0;
     return (int32_t)v;
 }
 
@@ -111,8 +128,9 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 size_t carve_workspace(const CacheView &c, int32_t B, int32_t H, int32_t max_len, void *base,
                        AttnWorkspace *ws)
 {
-    const int32_t C = split_tokens(c.P, alise::gqa_mfma_applies(c, H));
-    const int64_t splits = ((int64_t)max_len + C - 1) / C;
+    int32_t C_min = 0;
+    const int32_t C = split_tokens(c.P, alise::gqa_mfma_applies(c, H), &C_min);
+    const int64_t splits = ((int64_t)max_len + C_min - 1) / C_min;
     const int64_t max_tiles = (int64_t)B * (splits > 0 ? splits : 1);
     size_t off = 2304;      // eight queue counters, 256 bytes apart, then n_items
     const size_t off_base = off;
@@ -137,6 +155,8 @@ size_t carve_workspace(const CacheView &c, int32_t B, int32_t H, int32_t max_len
         ws->part = reinterpret_cast<float *>(b + off_part);
         ws->max_tiles = (int32_t)max_tiles;
         ws->chunk_tokens = C;
+        ws->min_chunk_tokens = C_min;
+        ws->min_items = 0;      // set by the caller once the grid is known
     }
     return off;
 }
@@ -145,8 +165,9 @@ int check_attn_sizes(const CacheView &c, int32_t B, int32_t H, int32_t max_len)
 {
     if (B < 0 || H <= 0 || max_len < 0) return ALISE_INVALID_ARGUMENT;
     if (H % c.Hkv != 0) return ALISE_UNSUPPORTED;
-    const int32_t C = split_tokens(c.P, alise::gqa_mfma_applies(c, H));
-    const int64_t splits = ((int64_t)max_len + C - 1) / C;
+    int32_t C_min = 0;
+    (void)split_tokens(c.P, alise::gqa_mfma_applies(c, H), &C_min);
+    const int64_t splits = ((int64_t)max_len + C_min - 1) / C_min;
     if ((int64_t)B * (splits > 0 ? splits : 1) * H >= (int64_t)1 << 31) return ALISE_UNSUPPORTED;
     return ALISE_OK;
 }
@@ -237,7 +258,7 @@ int alise_paged_decode_attn(const alise_kv_cache *c, const void *q, void *out,
     if (workspace_bytes < need) return ALISE_WORKSPACE_TOO_SMALL;
     hipError_t e = alise::launch_decode_attn(cv, q, out, block_tables, max_blocks_per_seq, context_lens, B,
                                              num_q_heads, max_context_len, softmax_scale, ws,
-                                             num_compute_units(), waves_per_cu(), loads_per_block(),
+                                             num_compute_units(), waves_per_cu(), loads_per_block(), min_items_per_wave(),
                                              static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? ALISE_OK : ALISE_HIP_ERROR;
 }

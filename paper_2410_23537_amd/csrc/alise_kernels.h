@@ -25,7 +25,9 @@ struct AttnWorkspace {
     int4 *order;            // [max_tiles] work order: (request, first token, end token, split buffer index or -1)
     float *part;            // [max_tiles * H][D + 2] = (m, l, o[D]) of every split
     int32_t max_tiles;
-    int32_t chunk_tokens;   // tokens per split
+    int32_t chunk_tokens;   // largest tokens per split; the plan kernel halves it (down to min_chunk_tokens)
+    int32_t min_chunk_tokens;   // while the batch would give fewer than min_items work items
+    int32_t min_items;
 };
 
 // True when the attention call takes the matrix-core path for grouped-query layouts
@@ -43,6 +45,6 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
                               const int32_t *context_lens, int32_t B, int32_t H,
                               int32_t max_context_len, float softmax_scale,
                               const AttnWorkspace &ws, int32_t num_cus, int32_t waves_per_cu,
-                              int32_t loads_per_block, hipStream_t s);
+                              int32_t loads_per_block, int32_t min_items_per_wave, hipStream_t s);
 
 }  // namespace alise

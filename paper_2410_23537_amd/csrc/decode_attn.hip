@@ -106,11 +106,31 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t *context_lens,
     __shared__ int32_t s_tot[2];
     __shared__ int32_t s_merge;
     const int tid = threadIdx.x;
-    const int C = ws.chunk_tokens;
     s_hist[tid] = 0;            // kRemBuckets == blockDim.x
     if (tid < 2) s_tot[tid] = 0;
     if (tid == 0) s_merge = 0;
     __syncthreads();
+    // Split length: the largest allowed, halved while the batch would leave the persistent
+    // grid with too few items to balance (small batches, or few items per tile).
+    int C = ws.chunk_tokens;
+    {
+        int64_t sum = 0;
+        int nonempty = 0;
+        for (int i = tid; i < B; i += 1024) {
+            int L = context_lens[i];
+            L = L < 0 ? 0 : (L > max_len ? max_len : L);
+            sum += L;
+            nonempty += L > 0;
+        }
+        // the token total is scanned in units of 64 tokens so that it fits the int scan
+        const int total64 = block_scan_1024((int)((sum + 63) >> 6), s_buf);
+        const int total_req = block_scan_1024(nonempty, s_buf);
+        __shared__ int32_t s_pick[2];
+        if (tid == 1023) { s_pick[0] = total64; s_pick[1] = total_req; }
+        __syncthreads();
+        const int64_t tokens = (int64_t)s_pick[0] << 6;
+        while (C > ws.min_chunk_tokens && (tokens / C + s_pick[1]) * items_per_tile < ws.min_items) C >>= 1;
+    }
     for (int base = 0; base < B; base += 1024) {
         const int i = base + tid;
         int L = 0;
@@ -657,7 +677,7 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
                               const int32_t *context_lens, int32_t B, int32_t H,
                               int32_t max_context_len, float softmax_scale,
                               const AttnWorkspace &ws, int32_t num_cus, int32_t waves_per_cu,
-                              int32_t loads_per_block, hipStream_t s)
+                              int32_t loads_per_block, int32_t min_items_per_wave, hipStream_t s)
 {
     if (B == 0) return hipSuccess;
     AttnParams p;
@@ -674,7 +694,11 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
     p.scale_log2e = softmax_scale * 1.44269504088896340736f;
     p.ws = ws;
     const bool gqa = gqa_mfma_applies(c, H);
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, s, context_lens, B, H, gqa ? c.Hkv : H, max_context_len, ws,
+    // the plan kernel shortens the splits until every wave of a full grid (about eight waves
+    // per compute unit) would get this many items; the matrix-core kernel, whose items are
+    // heavier to start, asks for fewer
+    p.ws.min_items = num_cus * 8 * (min_items_per_wave > 0 ? min_items_per_wave : (gqa ? 2 : 8));
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, s, context_lens, B, H, gqa ? c.Hkv : H, max_context_len, p.ws,
                        p.out, c.D);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -689,6 +713,7 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
         else if (c.bits == 4 && c.D == 128) e = launch_t<4, 128, NBV>(p, num_cus, waves_per_cu, s);   \
         else if (c.bits == 4 && c.D == 64) e = launch_t<4, 64, NBV>(p, num_cus, waves_per_cu, s);     \
     } while (0)
+        if (loads_per_block == 0) loads_per_block = c.bits == 4 ? 3 : 4;
         if (loads_per_block == 2) ALISE_DISPATCH(2);
         else if (loads_per_block == 3) ALISE_DISPATCH(3);
         else if (loads_per_block == 4) ALISE_DISPATCH(4);
