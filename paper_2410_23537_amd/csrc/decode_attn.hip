@@ -447,10 +447,10 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(AttnParams p)
                 const int off = tw & (P - 1);
                 const int64_t co = (int64_t)blk * p.c.cstride + off * ROWB;
                 const int64_t mo = (int64_t)blk * p.c.mstride + off * NG * 4;
-                buf.kc[j] = *reinterpret_cast<const uint4 *>(lane_k + co);
-                buf.vc[j] = *reinterpret_cast<const uint4 *>(lane_v + co);
-                buf.km[j] = *reinterpret_cast<const uint32_t *>(lane_km + mo);
-                buf.vm[j] = *reinterpret_cast<const uint32_t *>(lane_vm + mo);
+                buf.kc[j] = stream_load16(lane_k + co);
+                buf.vc[j] = stream_load16(lane_v + co);
+                buf.km[j] = stream_load4(lane_km + mo);
+                buf.vm[j] = stream_load4(lane_vm + mo);
             } else {
                 const int tok = tw + slot;
                 const int tc = tok < c.t1 ? tok : c.t1 - 1;        // stay on a real token
@@ -459,10 +459,10 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(AttnParams p)
                 const int off = tc & (P - 1);
                 const int64_t co = (int64_t)blk * p.c.cstride + off * ROWB + sub * 16;
                 const int64_t mo = (int64_t)blk * p.c.mstride + (off * NG + grp) * 4;
-                buf.kc[j] = *reinterpret_cast<const uint4 *>(p.c.k_codes + co);
-                buf.vc[j] = *reinterpret_cast<const uint4 *>(p.c.v_codes + co);
-                buf.km[j] = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const uint8_t *>(p.c.k_meta) + mo);
-                buf.vm[j] = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const uint8_t *>(p.c.v_meta) + mo);
+                buf.kc[j] = stream_load16(p.c.k_codes + co);
+                buf.vc[j] = stream_load16(p.c.v_codes + co);
+                buf.km[j] = stream_load4(reinterpret_cast<const uint8_t *>(p.c.k_meta) + mo);
+                buf.vm[j] = stream_load4(reinterpret_cast<const uint8_t *>(p.c.v_meta) + mo);
             }
         }
     };

@@ -143,20 +143,20 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(AttnParams p)
                 const int64_t co = (int64_t)blk * p.c.cstride + (int64_t)off * ROWB;
                 const int64_t mo = (int64_t)blk * p.c.mstride + (int64_t)(off + g * 4) * NGRP * 4;
                 const uint8_t *kb = p.c.k_codes + co + n * ROWB + g * 16;
-                b.k[x][0] = *reinterpret_cast<const uint4 *>(kb);
-                b.k[x][1] = *reinterpret_cast<const uint4 *>(kb + 64);
+                b.k[x][0] = stream_load16(kb);
+                b.k[x][1] = stream_load16(kb + 64);
                 const uint8_t *kmb = reinterpret_cast<const uint8_t *>(p.c.k_meta) + mo;
                 const uint8_t *vmb = reinterpret_cast<const uint8_t *>(p.c.v_meta) + mo;
 #pragma unroll
                 for (int u = 0; u < NGRP; ++u) {
-                    b.km[x][u] = *reinterpret_cast<const uint4 *>(kmb + u * 16);
-                    b.vm[x][u] = *reinterpret_cast<const uint4 *>(vmb + u * 16);
+                    b.km[x][u] = stream_load16(kmb + u * 16);
+                    b.vm[x][u] = stream_load16(vmb + u * 16);
                 }
                 const uint8_t *vb = p.c.v_codes + co + (g * 4) * ROWB + n * 4;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    b.v[x][r][0] = *reinterpret_cast<const uint32_t *>(vb + r * ROWB);
-                    b.v[x][r][1] = *reinterpret_cast<const uint32_t *>(vb + r * ROWB + 64);
+                    b.v[x][r][0] = stream_load4(vb + r * ROWB);
+                    b.v[x][r][1] = stream_load4(vb + r * ROWB + 64);
                 }
             }
         };
