@@ -47,6 +47,6 @@ __device__ __forceinline__ uint32_t stream_load4(const void *p) {
 
 // The matrix-core kernel for grouped-query attention: one wave serves all query heads of a
 // KV head, so a tile's items are its KV heads.  Defined in decode_attn_gqa.hip.
-hipError_t launch_gqa_mfma(const AttnParams &p, int32_t num_cus, hipStream_t s);
+hipError_t launch_gqa_mfma(const AttnParams &p, int32_t num_cus, int32_t waves_per_cu, int32_t stages, hipStream_t s);
 
 }  // namespace alise

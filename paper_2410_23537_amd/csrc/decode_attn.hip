@@ -66,21 +66,29 @@ __device__ __forceinline__ void wave_lds_sync()
 
 // ------------------------------------------------------------------ plan
 
-// Inclusive scan of one int per thread over a 1024-thread workgroup.
-__device__ __forceinline__ int block_scan_1024(int v, int32_t *buf)
+// Inclusive scans of two ints per thread over a 1024-thread workgroup, and their totals:
+// a shuffle scan inside each wave, then the 16 wave totals through LDS (two barriers).
+__device__ __forceinline__ void block_scan2_1024(int a, int b, int32_t (*wave_tot)[16], int &scan_a, int &scan_b,
+                                                 int &total_a, int &total_b)
 {
-    const int tid = threadIdx.x;
-    buf[tid] = v;
-    __syncthreads();
-    for (int d = 1; d < 1024; d <<= 1) {
-        const int add = tid >= d ? buf[tid - d] : 0;
-        __syncthreads();
-        buf[tid] += add;
-        __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int ua = __shfl_up(a, d), ub = __shfl_up(b, d);
+        if (lane >= d) { a += ua; b += ub; }
     }
-    const int r = buf[tid];
+    if (lane == 63) { wave_tot[0][wave] = a; wave_tot[1][wave] = b; }
     __syncthreads();
-    return r;
+    int pa = 0, pb = 0, ta = 0, tb = 0;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        const int va = wave_tot[0][k], vb = wave_tot[1][k];
+        if (k < wave) { pa += va; pb += vb; }
+        ta += va; tb += vb;
+    }
+    __syncthreads();        // wave_tot may be rewritten by the next call
+    scan_a = a + pa; scan_b = b + pb;
+    total_a = ta; total_b = tb;
 }
 
 constexpr int kRemBuckets = 1024;   // remainder tiles are ordered by length through this many buckets
@@ -101,13 +109,11 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t *context_lens,
                                                     int32_t items_per_tile, int32_t max_len, AttnWorkspace ws,
                                                     _Float16 *out, int32_t D)
 {
-    __shared__ int32_t s_buf[1024];
+    __shared__ int32_t s_wave[2][16];
     __shared__ int32_t s_hist[kRemBuckets];
-    __shared__ int32_t s_tot[2];
     __shared__ int32_t s_merge;
     const int tid = threadIdx.x;
     s_hist[tid] = 0;            // kRemBuckets == blockDim.x
-    if (tid < 2) s_tot[tid] = 0;
     if (tid == 0) s_merge = 0;
     __syncthreads();
     // Split length: the largest allowed, halved while the batch would leave the persistent
@@ -122,15 +128,13 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t *context_lens,
             sum += L;
             nonempty += L > 0;
         }
-        // the token total is scanned in units of 64 tokens so that it fits the int scan
-        const int total64 = block_scan_1024((int)((sum + 63) >> 6), s_buf);
-        const int total_req = block_scan_1024(nonempty, s_buf);
-        __shared__ int32_t s_pick[2];
-        if (tid == 1023) { s_pick[0] = total64; s_pick[1] = total_req; }
-        __syncthreads();
-        const int64_t tokens = (int64_t)s_pick[0] << 6;
-        while (C > ws.min_chunk_tokens && (tokens / C + s_pick[1]) * items_per_tile < ws.min_items) C >>= 1;
+        // the token total is counted in units of 64 tokens so that it fits an int
+        int sa, sb, total64, total_req;
+        block_scan2_1024((int)((sum + 63) >> 6), nonempty, s_wave, sa, sb, total64, total_req);
+        const int64_t tokens = (int64_t)total64 << 6;
+        while (C > ws.min_chunk_tokens && (tokens / C + total_req) * items_per_tile < ws.min_items) C >>= 1;
     }
+    int total = 0, total_full = 0;
     for (int base = 0; base < B; base += 1024) {
         const int i = base + tid;
         int L = 0;
@@ -141,30 +145,28 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t *context_lens,
         const int nfull = L / C;
         const int r = L % C;
         const int nrem = r != 0;
-        const int s_all = block_scan_1024(nfull + nrem, s_buf);
-        const int s_full = block_scan_1024(nfull, s_buf);
-        const int c_all = s_tot[0], c_full = s_tot[1];
+        int s_all, s_full, t_all, t_full;
+        block_scan2_1024(nfull + nrem, nfull, s_wave, s_all, s_full, t_all, t_full);
         if (i < B) {
-            ws.tile_base[i] = c_all + s_all - (nfull + nrem);
-            ws.req_full_base[i] = c_full + s_full - nfull;
+            ws.tile_base[i] = total + s_all - (nfull + nrem);
+            ws.req_full_base[i] = total_full + s_full - nfull;
             if (nrem) atomicAdd(&s_hist[rem_bucket(r, C)], 1);
             if (nfull + nrem > 1) ws.merge_req[atomicAdd(&s_merge, 1)] = i;
             if (L == 0)
                 for (int e = 0; e < H * D; ++e) out[(int64_t)i * H * D + e] = (_Float16)0.0f;
         }
-        __syncthreads();
-        if (tid == 1023) {
-            s_tot[0] = c_all + s_all;
-            s_tot[1] = c_full + s_full;
-        }
+        total += t_all;
+        total_full += t_full;
+    }
+    __syncthreads();            // the histogram is complete
+    // exclusive scan of the bucket counts -> first position of each bucket among the remainders
+    {
+        const int my_count = s_hist[tid];
+        int incl, unused, t0, t1;
+        block_scan2_1024(my_count, 0, s_wave, incl, unused, t0, t1);
+        s_hist[tid] = incl - my_count;
         __syncthreads();
     }
-    const int total = s_tot[0], total_full = s_tot[1];
-    // exclusive scan of the bucket counts -> first position of each bucket among the remainders
-    const int my_count = s_hist[tid];
-    const int incl = block_scan_1024(my_count, s_buf);
-    s_hist[tid] = incl - my_count;
-    __syncthreads();
     for (int i = tid; i < B; i += 1024) {
         int L = context_lens[i];
         L = L < 0 ? 0 : (L > max_len ? max_len : L);
@@ -704,7 +706,7 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
     if (e != hipSuccess) return e;
     e = hipErrorInvalidValue;
     if (gqa) {
-        e = launch_gqa_mfma(p, num_cus, s);
+        e = launch_gqa_mfma(p, num_cus, waves_per_cu, loads_per_block, s);
     } else {
 #define ALISE_DISPATCH(NBV)                                                                          \
     do {                                                                                             \

@@ -12,13 +12,27 @@
 //   O  += P V     A = p * lambda_v as fp16 (split into high and low parts so that no
 //                 weight loses precision), B = V codes (32 tokens x 16 channels).
 //
-// Operands are built in registers, never through LDS:
-//   K: a lane loads 2 x 16 bytes of one token's row; 0x6400 | code is the fp16 1024 + code;
+// The cache reaches the wave through LDS, by direct global -> LDS loads of 1 KiB (8 token
+// rows) per instruction: fully coalesced, no vector registers in between, so the depth of
+// the prefetch costs LDS space only.  (Fetching the operands in their matrix layouts
+// straight from memory -- a 16-byte piece of 16 different rows per quarter wave -- kept the
+// address unit busy over 70 % of the time and capped the kernel near 4.2 TB/s.)  The 16-byte
+// pieces of a row are stored XOR-swizzled by the row number, which is free on the way in
+// (a lane chooses which piece it fetches) and makes the operand reads conflict-free:
+//   K: a lane reads 2 x 16 bytes of one token's row; 0x6400 | code is the fp16 1024 + code;
 //      the 1024 * sum(q) offset leaves with the zero-point, per group of the row.
-//   V: the product contracts over tokens, but a row holds channels.  A lane loads one dword
+//   V: the product contracts over tokens, but a row holds channels.  A lane reads one dword
 //      (4 channels) from each of its 8 tokens and a byte permute picks the same channel out
 //      of two dwords, leaving the fp16 subnormals code * 2^-24 of two tokens side by side --
 //      which is the operand layout.  The matrix cores multiply subnormals exactly.
+//
+// A wave owns a fixed list of items (dealt out by rank in the longest-first order, odd
+// rounds in reverse wave order) and treats it as one stream of steps: the producer side of
+// the loop runs S - 1 steps ahead of the consumer side, across item boundaries.  What an
+// item needs besides the cache (descriptor, block-table entries, query rows) also arrives
+// by direct loads, ahead of time, into small rings beside the stages.  No load in the loop
+// returns into a register, so the compiler places no wait of its own; every wait is placed
+// here from a running count of issued loads.
 //
 // Softmax state (running maximum, denominator, weighted zero-points) lives in the lanes of
 // the S^T layout and is brought to the rows of O only at the end of a tile.
@@ -32,14 +46,69 @@ typedef float f4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kStep = 32;       // tokens per step: two 16-token tiles
 
-// Loaded data of one step.  NGRP = groups per token row (1 or 2).
-template <int NGRP>
-struct StepBuf {
-    uint4 k[2][2];          // [tile][piece]: 16 code bytes of this lane's token, channels g*16.. and 64+g*16..
-    uint4 km[2][NGRP];      // [tile]: (scale, zero) of this lane's 4 tokens, NGRP dwords per token
-    uint4 vm[2][NGRP];
-    uint32_t v[2][4][2];    // [tile][token r][set]: 4 code bytes, channels 64*set + 4n ..
-};
+typedef const void __attribute__((address_space(1))) *gptr_t;
+typedef uint8_t __attribute__((address_space(3))) *lptr_t;
+typedef void __attribute__((address_space(3))) *lvoid_t;
+
+// Direct global -> LDS loads: lane l's bytes land at the LDS base + l * size, wherever the
+// lane's global address points.  The cache is streamed (non-temporal); the bookkeeping is not.
+__device__ __forceinline__ void dma16_stream(const void *g, lptr_t l) { __builtin_amdgcn_global_load_lds((gptr_t)g, (lvoid_t)l, 16, 0, 2); }
+__device__ __forceinline__ void dma4_stream(const void *g, lptr_t l) { __builtin_amdgcn_global_load_lds((gptr_t)g, (lvoid_t)l, 4, 0, 2); }
+__device__ __forceinline__ void dma16(const void *g, lptr_t l) { __builtin_amdgcn_global_load_lds((gptr_t)g, (lvoid_t)l, 16, 0, 0); }
+__device__ __forceinline__ void dma4(const void *g, lptr_t l) { __builtin_amdgcn_global_load_lds((gptr_t)g, (lvoid_t)l, 4, 0, 0); }
+
+#define ALISE_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xf) | (((n) >> 4) << 14) | (0x7 << 4) | (0xf << 8))
+
+// Wait until the load that has `newer` loads issued after it has landed.  Loads complete in
+// the order they were issued, so it is enough that at most `newer` stay in flight; the count
+// is rounded down to a multiple of four (the menu of immediates), which only waits longer.
+// Stores are never counted: they may complete out of order with the loads.
+__device__ __forceinline__ void wait_newer(int newer)       // wave-uniform
+{
+    const int k = newer >> 2;
+    if (k >= 12) ALISE_VMCNT(48);
+    else if (k >= 9) ALISE_VMCNT(36);
+    else if (k >= 6) ALISE_VMCNT(24);
+    else if (k >= 4) ALISE_VMCNT(16);
+    else if (k == 3) ALISE_VMCNT(12);
+    else if (k == 2) ALISE_VMCNT(8);
+    else if (k == 1) ALISE_VMCNT(4);
+    else ALISE_VMCNT(0);
+}
+
+// LDS reads of data that arrived by direct loads are written in assembly: the compiler does
+// not see them, so it never orders them against the loads in flight -- the waits above do.
+__device__ __forceinline__ uint4 lds_read16(uint32_t addr)
+{
+    uint4 r;
+    asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(r) : "v"(addr) : "memory");
+    return r;
+}
+__device__ __forceinline__ uint32_t lds_read4(uint32_t addr)
+{
+    uint32_t r;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(r) : "v"(addr) : "memory");
+    return r;
+}
+// four 16-byte reads, one wait
+__device__ __forceinline__ void lds_read16x4(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3,
+                                             uint4 &r0, uint4 &r1, uint4 &r2, uint4 &r3)
+{
+    asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %5\n\tds_read_b128 %2, %6\n\tds_read_b128 %3, %7\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(r0), "=&v"(r1), "=&v"(r2), "=&v"(r3) : "v"(a0), "v"(a1), "v"(a2), "v"(a3) : "memory");
+}
+// eight dword reads at eight addresses, one wait
+__device__ __forceinline__ void lds_read4x8(const uint32_t (&a)[8], uint32_t off, uint32_t (&r)[8])
+{
+    asm volatile("ds_read_b32 %0, %8\n\tds_read_b32 %1, %9\n\tds_read_b32 %2, %10\n\tds_read_b32 %3, %11\n\t"
+                 "ds_read_b32 %4, %12\n\tds_read_b32 %5, %13\n\tds_read_b32 %6, %14\n\tds_read_b32 %7, %15\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3]), "=&v"(r[4]), "=&v"(r[5]), "=&v"(r[6]), "=&v"(r[7])
+                 : "v"(a[0] + off), "v"(a[1] + off), "v"(a[2] + off), "v"(a[3] + off),
+                   "v"(a[4] + off), "v"(a[5] + off), "v"(a[6] + off), "v"(a[7] + off)
+                 : "memory");
+}
 
 template <int NGRP>
 __device__ __forceinline__ uint32_t meta_of(const uint4 (&m)[NGRP], int r, int grp)
@@ -57,55 +126,211 @@ __device__ __forceinline__ h8_t pack8(uint32_t a, uint32_t b, uint32_t c, uint32
     return __builtin_bit_cast(h8_t, u);
 }
 
-template <int NGRP>
-__global__ __launch_bounds__(256) void decode_attn_gqa_kernel(AttnParams p)
+// NGRP = groups per token row (1 or 2); QROWS = query rows kept per item (8 or 16, >= qper);
+// S = stages of one step each.
+template <int NGRP, int QROWS, int S>
+__global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
 {
     constexpr int D = 128, ROWB = 128;
-    const int lane = threadIdx.x & 63;
+    constexpr int TILEB = 4352;                 // one 16-token tile in LDS: K 2 KiB | V 2 KiB | K meta 128 B | V meta 128 B
+    constexpr int T_V = 2048, T_KM = 4096, T_VM = 4224;
+    constexpr int STEPB = 2 * TILEB;
+    constexpr int RD = 4, RG = 2, RQ = 1;       // rings: descriptors, page windows, query rows
+    constexpr int QSLOT = QROWS * 256;
+    constexpr int OFF_DESC = S * STEPB, OFF_PG = OFF_DESC + RD * 16, OFF_Q = OFF_PG + RG * 256;
+    static_assert(S >= 2 && S <= 4, "stage marks occupy four lanes");
+    __shared__ __attribute__((aligned(16))) uint8_t lds[OFF_Q + RQ * QSLOT];
+
+    const int lane = threadIdx.x;
     const int n = lane & 15;        // column of the matrix layouts: token (K), query head (S^T), channel (V, O)
     const int g = lane >> 4;        // quarter of the wave: 8 consecutive k-slots, 4 consecutive rows
-    const int logP = p.c.logP, P = p.c.P, Hkv = p.c.Hkv, qper = p.qper;
+    const int logP = p.c.logP, P = p.c.P, Hkv = p.c.Hkv, qper = p.qper, H = p.H;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)lds;
+    lptr_t const ldsp = (lptr_t)lds;
     const int n_items = *p.ws.n_items;
-    const int4 *order = p.ws.order;
-    const int C = p.ws.chunk_tokens;
-    (void)C;
+    const uint32_t *order_words = reinterpret_cast<const uint32_t *>(p.ws.order);
 
-    // work queues: see the vector kernel; an item is (tile, KV head)
-    const int nq = gridDim.x >= kQueues ? kQueues : 1;
-    const int qid = blockIdx.x % nq;
-    uint32_t *counter = p.ws.counter + qid * kQueueStride;
+    // ---- per-lane constants of the LDS layout.  A 1 KiB load covers 8 token rows; row r keeps
+    // its 16-byte piece c at position c ^ r.
+    const int src_lane = (lane >> 3) * ROWB + (((lane & 7) ^ (lane >> 3)) * 16);     // what this lane fetches of the 1 KiB
+    // K operand: row n, pieces g and 4 + g
+    const uint32_t k_rd0 = (n >> 3) * 1024 + ((n & 7) * 8 + (g ^ (n & 7))) * 16;
+    const uint32_t k_rd1 = (n >> 3) * 1024 + ((n & 7) * 8 + ((4 + g) ^ (n & 7))) * 16;
+    // V operand: rows 4g + r, channels 64 * set + 4n .. (a dword)
+    uint32_t v_rd[8];               // [set * 4 + r]
+#pragma unroll
+    for (int set = 0; set < 2; ++set)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = 4 * g + r;
+            const int piece = 4 * set + (n >> 2);
+            v_rd[set * 4 + r] = T_V + (row >> 3) * 1024 + ((row & 7) * 8 + (piece ^ (row & 7))) * 16 + (n & 3) * 4;
+        }
+    const uint32_t m_rd = g * 16 * NGRP;        // meta of this lane's 4 tokens
 
-    int ticket = 0;
-    if (lane == 0) ticket = (int)atomicAdd(counter, 1u);
-    int it = qid + nq * __builtin_amdgcn_readfirstlane(ticket);
+    // ---- this wave's list of items (an item is a tile for one KV head)
+    const int W = gridDim.x, w = blockIdx.x;
+    auto item_at = [&](int r) {
+        const int it = r * W + ((r & 1) ? W - 1 - w : w);
+        return it < n_items ? it : -1;              // once -1, -1 for every later round
+    };
+    if (item_at(0) < 0) return;
 
-    while (it < n_items) {
-        // the next ticket travels while this item is processed
-        if (lane == 0) ticket = (int)atomicAdd(counter, 1u);
+    // ---- issue counts.  `marks` is a lane-indexed table of the value of `issued` when a
+    // thing was issued: lanes 0..3 descriptors, 16..17 page windows, 20 query rows, 32.. stages.
+    int issued = 0;
+    int marks = 0;
+    auto set_mark = [&](int idx) { marks = lane == idx ? issued : marks; };
+    auto newer_than = [&](int idx) { return issued - __builtin_amdgcn_readlane(marks, idx); };
 
-        const int4 d = order[it / Hkv];
+    auto issue_desc = [&](int r) {
+        const int it = item_at(r);
+        if (it < 0) return;
+        if (lane < 4) dma4(order_words + (it / Hkv) * 4 + lane, ldsp + OFF_DESC + (r % RD) * 16);
+        issued += 1;
+        set_mark(r % RD);
+    };
+    auto read_desc = [&](int r) {
+        const uint4 d = lds_read16(lds0 + OFF_DESC + (r % RD) * 16);
+        // Clamped to what the plan kernel can write, so that every address derived from a
+        // descriptor stays inside the caller's buffers whatever the bytes in LDS are.
+        int4 c;
+        c.x = min(max(__builtin_amdgcn_readfirstlane((int)d.x), 0), p.B - 1);
+        c.y = min(max(__builtin_amdgcn_readfirstlane((int)d.y), 0), p.max_len - 1) & ~15;     // tiles start on a multiple of the split
+        c.z = min(max(__builtin_amdgcn_readfirstlane((int)d.z), c.y + 1), min(c.y + p.ws.chunk_tokens, p.max_len));
+        c.w = min(max(__builtin_amdgcn_readfirstlane((int)d.w), -1), p.ws.max_tiles - 1);
+        return c;
+    };
+    // block-table entries of the item's tile (at most 64 pages)
+    auto issue_pg = [&](int r) {
+        if (item_at(r) < 0) return;
+        const int4 d = read_desc(r);
+        const int32_t *bt = p.block_tables + (int64_t)d.x * p.max_blocks;
+        dma4(bt + min((d.y >> logP) + lane, (d.z - 1) >> logP), ldsp + OFF_PG + (r % RG) * 256);
+        issued += 1;
+        set_mark(16 + r % RG);
+    };
+    // the query rows of the item's KV head: row j = 256 bytes, QROWS of them (rows past qper repeat the first)
+    auto issue_q = [&](int r, int i, int hk) {
+#pragma unroll
+        for (int c = 0; c < QROWS / 4; ++c) {
+            const int row = c * 4 + g;
+            const _Float16 *src = p.q + ((int64_t)i * H + hk * qper + (row < qper ? row : 0)) * D + n * 8;
+            dma16(src, ldsp + OFF_Q + (r % RQ) * QSLOT + c * 1024);
+        }
+        issued += QROWS / 4;
+        set_mark(20 + r % RQ);
+    };
+
+    // ---- producer state: the item being fetched
+    int pr = -1, p_valid = 1, p_next = 0, p_hk = 0, p_t0 = 0, p_t1 = 0, p_ns = 1, p_s = 0, p_win = 0, p_pg = 0;
+    int steps_issued = 0, steps_consumed = 0, c_entered = 0;
+    // Entering item r overwrites the query rows of item r - RQ, which the consumer must have
+    // taken into registers already.
+    auto producer_may_enter = [&](int r) { return r - RQ < c_entered; };
+    auto producer_enter = [&](int r) {
+        pr = r;
+        const int it = item_at(r);
+        p_valid = it >= 0;
+        p_next = 0;
+        issue_desc(r + 2);
+        if (item_at(r + 1) >= 0) {
+            wait_newer(newer_than((r + 1) % RD));
+            issue_pg(r + 1);
+        }
+        if (!p_valid) return;
+        wait_newer(newer_than(16 + r % RG));        // covers the descriptor too: it was issued earlier
+        const int4 d = read_desc(r);
+        p_hk = it % Hkv;
+        p_t0 = d.y;
+        p_t1 = d.z;
+        p_ns = (d.z - d.y + kStep - 1) / kStep;
+        p_win = d.y >> logP;
+        p_s = 0;
+        p_pg = (int)lds_read4(lds0 + OFF_PG + (r % RG) * 256 + lane * 4);
+        issue_q(r, d.x, p_hk);
+    };
+    // one step of the producer's item into the next stage
+    auto produce = [&]() {
+        const int st = steps_issued % S;
+#pragma unroll
+        for (int x = 0; x < 2; ++x) {
+            int tx = p_t0 + p_s * kStep + x * 16;
+            if (tx >= p_t1) tx -= 16;                       // second tile starts past the end: repeat the first
+            const int page = min(max(__builtin_amdgcn_readlane(p_pg, (tx >> logP) - p_win), 0), p.c.num_pages - 1);
+            const int blk = page * Hkv + p_hk;
+            const int off = tx & (P - 1);
+            const int64_t co = (int64_t)blk * p.c.cstride + (int64_t)off * ROWB;
+            const int64_t mo = (int64_t)blk * p.c.mstride + (int64_t)off * NGRP * 4;
+            lptr_t dst = ldsp + st * STEPB + x * TILEB;
+            const uint8_t *kb = p.c.k_codes + co + src_lane;
+            const uint8_t *vb = p.c.v_codes + co + src_lane;
+            dma16_stream(kb, dst);
+            dma16_stream(kb + 1024, dst + 1024);
+            dma16_stream(vb, dst + T_V);
+            dma16_stream(vb + 1024, dst + T_V + 1024);
+            if (lane < 16 * NGRP) {
+                dma4_stream(reinterpret_cast<const uint8_t *>(p.c.k_meta) + mo + lane * 4, dst + T_KM);
+                dma4_stream(reinterpret_cast<const uint8_t *>(p.c.v_meta) + mo + lane * 4, dst + T_VM);
+            }
+        }
+        issued += 12;
+        set_mark(32 + st);
+        ++steps_issued;
+        if (++p_s == p_ns) p_next = 1;                      // the item is fetched; the next one is entered when allowed
+    };
+    // keep the stages full
+    auto fill = [&]() {
+        for (;;) {
+            if (p_next) {
+                if (!producer_may_enter(pr + 1)) break;
+                producer_enter(pr + 1);
+            }
+            if (!p_valid || steps_issued - steps_consumed >= S) break;
+            produce();
+        }
+    };
+
+    // ---- start: descriptors of the first items, the first page window
+    issue_desc(0);
+    issue_desc(1);
+    ALISE_VMCNT(0);
+    issue_pg(0);
+    producer_enter(0);
+    // the consumer of the step that is about to be eaten must not be overwritten: at most S - 1 ahead here
+    for (;;) {
+        if (p_next) {
+            if (!producer_may_enter(pr + 1)) break;
+            producer_enter(pr + 1);
+        }
+        if (!p_valid || steps_issued >= S - 1) break;
+        produce();
+    }
+
+    // ---- consumer
+    for (int cr = 0;; ++cr) {
+        const int it = item_at(cr);
+        if (it < 0) break;                          // wave-uniform
+        const int4 cd = read_desc(cr);              // landed before the producer entered the item
+        const int i = cd.x, t0 = cd.y, t1 = cd.z, part = cd.w;
         const int hk = it % Hkv;
-        const int i = __builtin_amdgcn_readfirstlane(d.x);
-        const int t0 = __builtin_amdgcn_readfirstlane(d.y);
-        const int t1 = __builtin_amdgcn_readfirstlane(d.z);
-        const int part = __builtin_amdgcn_readfirstlane(d.w);
-        const int32_t *bt = p.block_tables + (int64_t)i * p.max_blocks;
-        const int win_first = t0 >> logP;
-        const int pg = bt[min(win_first + lane, (t1 - 1) >> logP)];    // a tile spans at most 64 pages
         const int nsteps = (t1 - t0 + kStep - 1) / kStep;
 
         // ---- Q^T as the B operand of the four k-chunks: chunk j, slot g*8+e <-> channel (j/2)*64 + g*16 + (j%2)*8 + e
         h8_t qop[4];
         float qs[NGRP];             // sum of this query head's q over the channels of a group
         {
-            const int qh = hk * qper + n;
-            const _Float16 *qrow = p.q + ((int64_t)i * p.H + (n < qper ? qh : hk * qper)) * D;
+            wait_newer(newer_than(20 + cr % RQ));
+            // query row n sits at (n / 4) * 1024 + (n % 4) * 256 of the slot: row c*4+g was written by quarter g of load c
+            const uint32_t qa = lds0 + OFF_Q + (cr % RQ) * QSLOT + ((n % QROWS) >> 2) * 1024 + (n & 3) * 256;
+            uint4 raw[4];
+            lds_read16x4(qa + g * 32, qa + g * 32 + 16, qa + 128 + g * 32, qa + 128 + g * 32 + 16, raw[0], raw[1], raw[2], raw[3]);
             float part_sum[NGRP];
 #pragma unroll
             for (int gr = 0; gr < NGRP; ++gr) part_sum[gr] = 0.0f;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                h8_t v = *reinterpret_cast<const h8_t *>(qrow + (j / 2) * 64 + g * 16 + (j % 2) * 8);
+                h8_t v = pack8(raw[j].x, raw[j].y, raw[j].z, raw[j].w);
                 if (n >= qper) v = (h8_t)(_Float16)0.0f;
                 qop[j] = v;
                 float sacc = 0.0f;
@@ -121,6 +346,7 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(AttnParams p)
                 qs[gr] = v;
             }
         }
+        ++c_entered;
 
         float m_ref = kFloor, l_part = 0.0f, z_part[NGRP];
 #pragma unroll
@@ -129,43 +355,28 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(AttnParams p)
 #pragma unroll
         for (int t = 0; t < 8; ++t) o[t] = (f4_t)0.0f;
 
-        // Issue the loads of step k (clamped to the last step; tiles past the end of the tile
-        // re-read its last 16-token tile).  Straight-line code: no branch around a load.
-        auto issue = [&](StepBuf<NGRP> &b, int k) {
-            const int ks = min(k, nsteps - 1);
-#pragma unroll
-            for (int x = 0; x < 2; ++x) {
-                int tx = t0 + ks * kStep + x * 16;
-                if (tx >= t1) tx -= 16;                     // second tile starts past the end: repeat the first
-                const int page = __builtin_amdgcn_readlane(pg, (tx >> logP) - win_first);
-                const int blk = page * Hkv + hk;
-                const int off = tx & (P - 1);
-                const int64_t co = (int64_t)blk * p.c.cstride + (int64_t)off * ROWB;
-                const int64_t mo = (int64_t)blk * p.c.mstride + (int64_t)(off + g * 4) * NGRP * 4;
-                const uint8_t *kb = p.c.k_codes + co + n * ROWB + g * 16;
-                b.k[x][0] = stream_load16(kb);
-                b.k[x][1] = stream_load16(kb + 64);
-                const uint8_t *kmb = reinterpret_cast<const uint8_t *>(p.c.k_meta) + mo;
-                const uint8_t *vmb = reinterpret_cast<const uint8_t *>(p.c.v_meta) + mo;
-#pragma unroll
-                for (int u = 0; u < NGRP; ++u) {
-                    b.km[x][u] = stream_load16(kmb + u * 16);
-                    b.vm[x][u] = stream_load16(vmb + u * 16);
-                }
-                const uint8_t *vb = p.c.v_codes + co + (g * 4) * ROWB + n * 4;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    b.v[x][r][0] = stream_load4(vb + r * ROWB);
-                    b.v[x][r][1] = stream_load4(vb + r * ROWB + 64);
-                }
-            }
-        };
+        for (int k = 0; k < nsteps; ++k) {
+            fill();
+            const int sg = steps_consumed % S;
+            wait_newer(newer_than(32 + sg));
+            const uint32_t base = lds0 + sg * STEPB;
 
-        auto eat = [&](const StepBuf<NGRP> &b, int k) {
             // ---- S^T = K Q^T for the two 16-token tiles
             float s[2][4];
             float lamv[2][4][NGRP], zv[2][4][NGRP];
             float mx = kNegInf;
+            uint4 kp[2][2];
+            lds_read16x4(base + k_rd0, base + k_rd1, base + TILEB + k_rd0, base + TILEB + k_rd1, kp[0][0], kp[0][1], kp[1][0], kp[1][1]);
+            uint4 kmeta[2][NGRP], vmeta[2][NGRP];
+            if constexpr (NGRP == 1) {
+                lds_read16x4(base + T_KM + m_rd, base + T_VM + m_rd, base + TILEB + T_KM + m_rd, base + TILEB + T_VM + m_rd,
+                             kmeta[0][0], vmeta[0][0], kmeta[1][0], vmeta[1][0]);
+            } else {
+                lds_read16x4(base + T_KM + m_rd, base + T_KM + m_rd + 16, base + T_VM + m_rd, base + T_VM + m_rd + 16,
+                             kmeta[0][0], kmeta[0][1], vmeta[0][0], vmeta[0][1]);
+                lds_read16x4(base + TILEB + T_KM + m_rd, base + TILEB + T_KM + m_rd + 16, base + TILEB + T_VM + m_rd,
+                             base + TILEB + T_VM + m_rd + 16, kmeta[1][0], kmeta[1][1], vmeta[1][0], vmeta[1][1]);
+            }
 #pragma unroll
             for (int x = 0; x < 2; ++x) {
                 f4_t acc[NGRP];
@@ -173,7 +384,7 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(AttnParams p)
                 for (int gr = 0; gr < NGRP; ++gr) acc[gr] = (f4_t)0.0f;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const uint4 piece = b.k[x][j / 2];
+                    const uint4 piece = kp[x][j / 2];
                     const uint32_t w0 = (j % 2) ? piece.z : piece.x, w1 = (j % 2) ? piece.w : piece.y;
                     const h8_t a = pack8(__builtin_amdgcn_perm(0x64646464u, w0, 0x04010400u),
                                          __builtin_amdgcn_perm(0x64646464u, w0, 0x04030402u),
@@ -189,8 +400,8 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(AttnParams p)
                     float sv = 0.0f;
 #pragma unroll
                     for (int gr = 0; gr < NGRP; ++gr) {
-                        const uint32_t km = meta_of<NGRP>(b.km[x], r, gr);
-                        const uint32_t vm = valid ? meta_of<NGRP>(b.vm[x], r, gr) : 0u;
+                        const uint32_t km = meta_of<NGRP>(kmeta[x], r, gr);
+                        const uint32_t vm = valid ? meta_of<NGRP>(vmeta[x], r, gr) : 0u;
                         const float lam = half_lo(km) * p.scale_log2e;
                         sv += lam * (acc[gr][r] - (1024.0f + half_hi(km)) * qs[gr]);
                         lamv[x][r][gr] = half_lo(vm);
@@ -229,41 +440,34 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(AttnParams p)
                     l_part += pj;
 #pragma unroll
                     for (int gr = 0; gr < NGRP; ++gr) {
-                        const float w = pj * lamv[x][r][gr];
-                        z_part[gr] = __builtin_fmaf(w, zv[x][r][gr], z_part[gr]);
-                        const _Float16 hi = (_Float16)w;
-                        const _Float16 lo = (_Float16)(w - (float)hi);
+                        const float wv = pj * lamv[x][r][gr];
+                        z_part[gr] = __builtin_fmaf(wv, zv[x][r][gr], z_part[gr]);
+                        const _Float16 hi = (_Float16)wv;
+                        const _Float16 lo = (_Float16)(wv - (float)hi);
                         a_hi[gr][x * 4 + r] = hi;
                         a_lo[gr][x * 4 + r] = lo;
                     }
                 }
 
             // ---- O += P V: byte nu of the dwords of two tokens -> two fp16 subnormals
+            uint32_t vd[2][8];          // [tile][set * 4 + r]
+            lds_read4x8(v_rd, base, vd[0]);
+            lds_read4x8(v_rd, base + TILEB, vd[1]);
 #pragma unroll
             for (int set = 0; set < 2; ++set)
 #pragma unroll
                 for (int nu = 0; nu < 4; ++nu) {
                     const uint32_t sel = 0x0c000c00u | ((4u + nu) << 16) | (uint32_t)nu;
-                    const h8_t bv = pack8(__builtin_amdgcn_perm(b.v[0][1][set], b.v[0][0][set], sel),
-                                          __builtin_amdgcn_perm(b.v[0][3][set], b.v[0][2][set], sel),
-                                          __builtin_amdgcn_perm(b.v[1][1][set], b.v[1][0][set], sel),
-                                          __builtin_amdgcn_perm(b.v[1][3][set], b.v[1][2][set], sel));
+                    const h8_t bv = pack8(__builtin_amdgcn_perm(vd[0][set * 4 + 1], vd[0][set * 4 + 0], sel),
+                                          __builtin_amdgcn_perm(vd[0][set * 4 + 3], vd[0][set * 4 + 2], sel),
+                                          __builtin_amdgcn_perm(vd[1][set * 4 + 1], vd[1][set * 4 + 0], sel),
+                                          __builtin_amdgcn_perm(vd[1][set * 4 + 3], vd[1][set * 4 + 2], sel));
                     const int gr = NGRP == 2 ? set : 0;
                     f4_t &dst = o[set * 4 + nu];
                     dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_hi[gr], bv, dst, 0, 0, 0);
                     dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_lo[gr], bv, dst, 0, 0, 0);
                 }
-        };
-
-        {
-            StepBuf<NGRP> bufA, bufB;
-            issue(bufA, 0);
-            for (int k = 0; k < nsteps; k += 2) {
-                issue(bufB, k + 1);
-                eat(bufA, k);
-                issue(bufA, k + 2);
-                if (k + 1 < nsteps) eat(bufB, k + 1);
-            }
+            ++steps_consumed;
         }
 
         // ---- per query head: add the four quarters; then fetch the values of this lane's rows
@@ -288,7 +492,7 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(AttnParams p)
                 const int qh = hk * qper + row;
                 if (part < 0) {
                     const float inv_l = 1.0f / l_row;
-                    _Float16 *dst = p.out + ((int64_t)i * p.H + qh) * D + 4 * n;
+                    _Float16 *dst = p.out + ((int64_t)i * H + qh) * D + 4 * n;
 #pragma unroll
                     for (int set = 0; set < 2; ++set) {
                         const float zr = z_row[NGRP == 2 ? set : 0];
@@ -300,7 +504,7 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(AttnParams p)
                         *reinterpret_cast<h4_t *>(dst + 64 * set) = v;
                     }
                 } else {
-                    float *dst = p.ws.part + ((int64_t)part * p.H + qh) * (D + 2);
+                    float *dst = p.ws.part + ((int64_t)part * H + qh) * (D + 2);
                     if (n == 0) { dst[0] = m_row; dst[1] = l_row; }
 #pragma unroll
                     for (int set = 0; set < 2; ++set) {
@@ -317,9 +521,26 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(AttnParams p)
                 }
             }
         }
-
-        it = qid + nq * __builtin_amdgcn_readfirstlane(ticket);
     }
+    ALISE_VMCNT(0);     // nothing may still be on its way into LDS when the wave ends
+}
+
+template <int NGRP, int QROWS, int S>
+hipError_t launch_gqa_t(const AttnParams &p, int32_t num_cus, int32_t waves_per_cu, hipStream_t s)
+{
+    // one wave per workgroup; as many as the LDS lets a compute unit hold, unless the caller fixes the number
+    static int occ = 0;
+    if (occ == 0) {
+        int n = 0;
+        hipError_t oe = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, decode_attn_gqa_kernel<NGRP, QROWS, S>, 64, 0);
+        occ = (oe == hipSuccess && n > 0) ? n : 4;
+    }
+    int waves = num_cus * (waves_per_cu > 0 ? waves_per_cu : occ);
+    const int64_t max_items = (int64_t)p.ws.max_tiles * p.c.Hkv;
+    if (waves > max_items) waves = (int)max_items;
+    if (waves < 1) waves = 1;
+    hipLaunchKernelGGL((decode_attn_gqa_kernel<NGRP, QROWS, S>), dim3(waves), dim3(64), 0, s, p);
+    return hipGetLastError();
 }
 
 }  // namespace
@@ -330,27 +551,22 @@ bool gqa_mfma_applies(const CacheView &c, int32_t H)
     return c.bits == 8 && c.D == 128 && (c.G == 128 || c.G == 64) && c.P >= 16 && qper >= 2 && qper <= 16;
 }
 
-hipError_t launch_gqa_mfma(const AttnParams &p, int32_t num_cus, hipStream_t s)
+hipError_t launch_gqa_mfma(const AttnParams &p, int32_t num_cus, int32_t waves_per_cu, int32_t stages, hipStream_t s)
 {
-    static int occ[2] = {0, 0};
     const int ngrp = p.c.D / p.c.G;
-    int &o = occ[ngrp - 1];
-    if (o == 0) {
-        int n = 0;
-        hipError_t oe = ngrp == 1
-            ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, decode_attn_gqa_kernel<1>, 256, 0)
-            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, decode_attn_gqa_kernel<2>, 256, 0);
-        o = (oe == hipSuccess && n > 0) ? n : 2;
-    }
-    int blocks = num_cus * o;
-    const int64_t max_items = (int64_t)p.ws.max_tiles * p.c.Hkv;
-    if ((int64_t)blocks * 4 > max_items) blocks = (int)((max_items + 3) / 4);
-    if (blocks < 1) blocks = 1;
-    if (ngrp == 1)
-        hipLaunchKernelGGL((decode_attn_gqa_kernel<1>), dim3(blocks), dim3(256), 0, s, p);
-    else
-        hipLaunchKernelGGL((decode_attn_gqa_kernel<2>), dim3(blocks), dim3(256), 0, s, p);
-    return hipGetLastError();
+    const bool small = p.qper <= 8;
+#define ALISE_GQA_DISPATCH(SV)                                                                                        \
+    do {                                                                                                              \
+        if (ngrp == 1)                                                                                                \
+            return small ? launch_gqa_t<1, 8, SV>(p, num_cus, waves_per_cu, s) : launch_gqa_t<1, 16, SV>(p, num_cus, waves_per_cu, s); \
+        return small ? launch_gqa_t<2, 8, SV>(p, num_cus, waves_per_cu, s) : launch_gqa_t<2, 16, SV>(p, num_cus, waves_per_cu, s);     \
+    } while (0)
+    // Two stages and more resident waves beat deeper prefetch with fewer waves (measured on the
+    // 8-heads-per-KV-head workload: 209 us against 217-222 us for three and four stages).
+    if (stages == 3) ALISE_GQA_DISPATCH(3);
+    if (stages == 4) ALISE_GQA_DISPATCH(4);
+    ALISE_GQA_DISPATCH(2);
+#undef ALISE_GQA_DISPATCH
 }
 
 }  // namespace alise
