@@ -23,31 +23,39 @@ struct QuantParams {
     CacheView c;
     const _Float16 *k, *v;
     const int64_t *slots;
-    int32_t T;
-    int32_t lanes_per_row;      // D / 8
+    int32_t log_lanes_per_row;  // log2(D / 8)
     int32_t lanes_per_group;    // G / 8
-    int64_t total_lanes;        // T * Hkv * 2 * lanes_per_row
+    uint32_t total_lanes;       // T * Hkv * 2 * lanes_per_row, below 2^31
+    uint32_t hkv_magic;         // row / Hkv == mul_hi(row, hkv_magic) >> hkv_shift for row < 2^31
+    uint32_t hkv_shift;
 };
 
 __device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
 
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+
+// BITS = code width; LPG = lanes per group (G / 8): 2, 4, 8 or 16, so a group never leaves a row of 16 lanes.
+template <int BITS, int LPG>
 __global__ __launch_bounds__(256) void quant_write_kernel(QuantParams p)
 {
-    const int64_t gl = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const uint32_t gl = blockIdx.x * 256u + threadIdx.x;
     // Rows are ordered (token, K|V, head): the lanes of a wave stay inside one
     // tensor's contiguous [Hkv][D] slab of one token as long as possible.
-    const int lpr = p.lanes_per_row;
     const bool live = gl < p.total_lanes;
-    const int64_t g = live ? gl : p.total_lanes - 1;
-    const int lane_in_row = (int)(g % lpr);
-    const int64_t row = g / lpr;
-    const int head = (int)(row % p.c.Hkv);
-    const int64_t tw = row / p.c.Hkv;
-    const int which = (int)(tw & 1);
+    const uint32_t g = live ? gl : p.total_lanes - 1;
+    const int lane_in_row = (int)(g & ((1u << p.log_lanes_per_row) - 1u));
+    const uint32_t row = g >> p.log_lanes_per_row;
+    const uint32_t tw = p.c.Hkv == 1 ? row : (__umulhi(row, p.hkv_magic) >> p.hkv_shift);
+    const int head = (int)(row - tw * (uint32_t)p.c.Hkv);
+    const int which = (int)(tw & 1u);
     const int64_t t = tw >> 1;
 
     const _Float16 *src = (which ? p.v : p.k) + (t * p.c.Hkv + head) * p.c.D + lane_in_row * 8;
-    const h8_t x = *reinterpret_cast<const h8_t *>(src);
+    const h8_t x = __builtin_nontemporal_load(reinterpret_cast<const h8_t *>(src));    // read once
     const int64_t slot = p.slots[t];
 
     float xf[8];
@@ -58,11 +66,12 @@ __global__ __launch_bounds__(256) void quant_write_kernel(QuantParams p)
         mn = fminf(mn, xf[i]);
         mx = fmaxf(mx, xf[i]);
     }
-    for (int d = 1; d < p.lanes_per_group; d <<= 1) {
-        mn = fminf(mn, __shfl_xor(mn, d));
-        mx = fmaxf(mx, __shfl_xor(mx, d));
-    }
-    const float qmax = (float)((1 << p.c.bits) - 1);
+    // minimum and maximum over the lanes of the group, every lane gets both
+    mn = fminf(mn, dpp_f<0xB1>(mn));  mx = fmaxf(mx, dpp_f<0xB1>(mx));                    // quad_perm [1,0,3,2]
+    if constexpr (LPG >= 4) { mn = fminf(mn, dpp_f<0x4E>(mn)); mx = fmaxf(mx, dpp_f<0x4E>(mx)); }     // quad_perm [2,3,0,1]
+    if constexpr (LPG >= 8) { mn = fminf(mn, dpp_f<0x141>(mn)); mx = fmaxf(mx, dpp_f<0x141>(mx)); }   // row_half_mirror
+    if constexpr (LPG >= 16) { mn = fminf(mn, dpp_f<0x140>(mn)); mx = fmaxf(mx, dpp_f<0x140>(mx)); }  // row_mirror
+    const float qmax = (float)((1 << BITS) - 1);
     const float r = mx - mn;
     const float l32 = r / qmax;
     _Float16 h = (_Float16)l32;                       // round to nearest even
@@ -91,7 +100,7 @@ __global__ __launch_bounds__(256) void quant_write_kernel(QuantParams p)
     uint8_t *codes = (which ? p.c.v_codes : p.c.k_codes) + blk * p.c.cstride + (int64_t)off * p.c.row_code_bytes;
     uint32_t *meta = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(which ? p.c.v_meta : p.c.k_meta) +
                                                   blk * p.c.mstride) + off * p.c.NG;
-    if (p.c.bits == 8) {
+    if constexpr (BITS == 8) {
         uint2 w;
         w.x = code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24);
         w.y = code[4] | (code[5] << 8) | (code[6] << 16) | (code[7] << 24);
@@ -102,8 +111,8 @@ __global__ __launch_bounds__(256) void quant_write_kernel(QuantParams p)
         for (int i = 0; i < 8; ++i) w |= code[i] << (4 * i);   // channel 2i low nibble, 2i+1 high
         *reinterpret_cast<uint32_t *>(codes + lane_in_row * 4) = w;
     }
-    if ((lane_in_row % p.lanes_per_group) == 0) {
-        const int grp = lane_in_row / p.lanes_per_group;
+    if ((lane_in_row % LPG) == 0) {
+        const int grp = lane_in_row / LPG;
         const uint16_t zb = __builtin_bit_cast(uint16_t, (_Float16)zf);
         meta[grp] = (uint32_t)hb | ((uint32_t)zb << 16);
     }
@@ -166,16 +175,41 @@ hipError_t launch_quant_write(const CacheView &c, const void *k, const void *v,
     if (T == 0) return hipSuccess;
     QuantParams p;
     p.c = c;
-    p.k = static_cast<const _Float16 *>(k);
-    p.v = static_cast<const _Float16 *>(v);
-    p.slots = slot_mapping;
-    p.T = T;
-    p.lanes_per_row = c.D / 8;
+    const int lanes_per_row = c.D / 8;
+    p.log_lanes_per_row = lanes_per_row == 16 ? 4 : 3;      // D is 128 or 64
     p.lanes_per_group = c.G / 8;
-    p.total_lanes = (int64_t)T * c.Hkv * 2 * p.lanes_per_row;
-    const int64_t blocks = (p.total_lanes + 255) / 256;
-    hipLaunchKernelGGL(quant_write_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p);
-    return hipGetLastError();
+    // division by Hkv as a multiplication: with L = ceil(log2 Hkv), M = ceil(2^(31+L) / Hkv) fits
+    // 32 bits and floor(n / Hkv) == (n * M) >> (31 + L) for every n < 2^31
+    int L = 0;
+    while ((1 << L) < c.Hkv) ++L;
+    p.hkv_magic = (uint32_t)((((uint64_t)1 << (31 + L)) + (uint64_t)c.Hkv - 1) / (uint64_t)c.Hkv);
+    p.hkv_shift = (uint32_t)(L > 0 ? L - 1 : 0);
+    // a launch covers at most 2^30 lanes (16 GiB of input), so that lane indices fit 31 bits
+    const int64_t lanes_per_token = (int64_t)c.Hkv * 2 * lanes_per_row;
+    const int64_t tokens_per_launch = ((int64_t)1 << 30) / lanes_per_token;
+    for (int64_t t0 = 0; t0 < T; t0 += tokens_per_launch) {
+        const int64_t n = T - t0 < tokens_per_launch ? T - t0 : tokens_per_launch;
+        p.k = static_cast<const _Float16 *>(k) + t0 * c.Hkv * c.D;
+        p.v = static_cast<const _Float16 *>(v) + t0 * c.Hkv * c.D;
+        p.slots = slot_mapping + t0;
+        p.total_lanes = (uint32_t)(n * lanes_per_token);
+        const dim3 grid((p.total_lanes + 255u) / 256u), block(256);
+        const int lpg = p.lanes_per_group;
+#define ALISE_QW(BITSV)                                                                              \
+    do {                                                                                             \
+        if (lpg == 16) hipLaunchKernelGGL((quant_write_kernel<BITSV, 16>), grid, block, 0, s, p);    \
+        else if (lpg == 8) hipLaunchKernelGGL((quant_write_kernel<BITSV, 8>), grid, block, 0, s, p); \
+        else if (lpg == 4) hipLaunchKernelGGL((quant_write_kernel<BITSV, 4>), grid, block, 0, s, p); \
+        else if (lpg == 2) hipLaunchKernelGGL((quant_write_kernel<BITSV, 2>), grid, block, 0, s, p); \
+        else return hipErrorInvalidValue;                                                            \
+    } while (0)
+        if (c.bits == 8) ALISE_QW(8);
+        else ALISE_QW(4);
+#undef ALISE_QW
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_dequant_page(const CacheView &c, int32_t page, void *k_out, void *v_out, hipStream_t s)
