@@ -55,6 +55,12 @@ def lib():
         L.oracle_quant_group.restype = None
         L.oracle_quant_group.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int,
                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        L.oracle_kv_swap_bytes.restype = ctypes.c_size_t
+        L.oracle_kv_swap_bytes.argtypes = [ctypes.POINTER(_CCache), ctypes.c_int32]
+        L.oracle_kv_swap_out.restype = ctypes.c_int
+        L.oracle_kv_swap_out.argtypes = [ctypes.POINTER(_CCache), ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p]
+        L.oracle_kv_swap_in.restype = ctypes.c_int
+        L.oracle_kv_swap_in.argtypes = [ctypes.POINTER(_CCache), ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p]
         L.oracle_kv_quant_write.restype = ctypes.c_int
         L.oracle_kv_quant_write.argtypes = [ctypes.POINTER(_CCache), ctypes.c_void_p, ctypes.c_void_p,
                                             ctypes.c_void_p, ctypes.c_int32]
@@ -173,3 +179,30 @@ def dense_attn(q: np.ndarray, K: np.ndarray, V: np.ndarray, softmax_scale: float
     out = np.zeros(D, np.float64)
     lib().oracle_dense_attn(_ptr(q), _ptr(K), _ptr(V), L, D, float(softmax_scale), _ptr(out))
     return out
+
+
+def kv_swap_bytes(cache: Cache, num_tokens: int) -> int:
+    c = cache._c()
+    return int(lib().oracle_kv_swap_bytes(ctypes.byref(c), int(num_tokens)))
+
+
+def kv_swap_out(cache: Cache, block_table: np.ndarray, num_tokens: int) -> np.ndarray:
+    """Offloaded form (uint8 array) of the request whose pages ``block_table`` lists."""
+    bt = np.ascontiguousarray(block_table, dtype=np.int32)
+    c = cache._c()
+    packed = np.zeros(kv_swap_bytes(cache, num_tokens), np.uint8)
+    rc = lib().oracle_kv_swap_out(ctypes.byref(c), _ptr(bt), int(num_tokens), _ptr(packed))
+    if rc:
+        raise ValueError("block table entry out of range")
+    return packed
+
+
+def kv_swap_in(cache: Cache, block_table: np.ndarray, num_tokens: int, packed: np.ndarray) -> None:
+    """Upload: write the offloaded form back into the pages ``block_table`` lists now."""
+    bt = np.ascontiguousarray(block_table, dtype=np.int32)
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    assert packed.size >= kv_swap_bytes(cache, num_tokens)
+    c = cache._c()
+    rc = lib().oracle_kv_swap_in(ctypes.byref(c), _ptr(bt), int(num_tokens), _ptr(packed))
+    if rc:
+        raise ValueError("block table entry out of range")

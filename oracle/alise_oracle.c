@@ -12,6 +12,10 @@
  *   - Sec. 2 "LLM Inference": each decode step appends the new token's K/V to the
  *     cache and attends over everything cached.
  *   - Sec. 3.3: the cache is block-level (paged), inherited from PagedAttention.
+ *   - Sec. 3.2 "Dynamic Swapping", Alg. 2: a preempted job's whole KV cache is offloaded
+ *     to CPU memory and uploaded again later, at the request level.  The oracle states
+ *     the data movement (pack a request's pages into one buffer, unpack them into any
+ *     pages); which job moves when is the scheduler's business and is not here.
  *
  * Readings where the paper is silent or garbled (all listed in the design notes):
  *   R1  the printed zero-point does not depend on min; taken as z = nint(-min / lambda).
@@ -30,6 +34,9 @@
  *   R14 INT4: channel 2i in the low nibble, 2i+1 in the high nibble of byte i.
  *   R15 query head h reads KV head h / (H / Hkv).
  *   R16 no mask beyond t < L_i; L_i = 0 gives a zero row.
+ *   R17 the offloaded form of a request is its pages in logical order, whole pages
+ *       (every slot of the last page too), each as [K codes | V codes | K meta | V meta]
+ *       per KV head: compressed bytes move as they are, nothing is requantized.
  *
  * Every fp32 step of the quantizer is a single IEEE-754 binary32 operation; build
  * with -ffp-contract=off so the compiler fuses nothing on its own.
@@ -301,4 +308,69 @@ void oracle_dense_attn(const double *q, const double *K, const double *V, int L,
     for (int t = 0; t < L; ++t)
         for (int d = 0; d < D; ++d) out[d] += s[t] / denom * V[(size_t)t * D + d];
     free(s);
+}
+
+/* ---------------------------------------------------------------- dynamic swapping (data movement) */
+
+/* Bytes of one (page, head) block in the offloaded form (R17). */
+static size_t swap_block_bytes(const oracle_cache *c)
+{
+    size_t rowb = (size_t)c->head_dim * c->bits / 8, ng = (size_t)(c->head_dim / c->group_size);
+    return 2 * (size_t)c->page_size * rowb + 2 * (size_t)c->page_size * ng * 4;
+}
+
+/* Size of the offloaded form of a request of num_tokens tokens. */
+size_t oracle_kv_swap_bytes(const oracle_cache *c, int32_t num_tokens)
+{
+    size_t nblk = num_tokens > 0 ? ((size_t)num_tokens + c->page_size - 1) / c->page_size : 0;
+    return nblk * (size_t)c->num_kv_heads * swap_block_bytes(c);
+}
+
+/*
+ * Offload (Alg. 2 "offload"): copy the request's pages, found through its block table, into
+ * `packed`, byte by byte.  Upload ("upload") is the same walk in the other direction, into
+ * whatever pages the block table names at that time.  dir = 0: cache -> packed, 1: packed -> cache.
+ */
+static int swap_walk(oracle_cache *c, const int32_t *block_table, int32_t num_tokens, uint8_t *packed, int dir)
+{
+    const int P = c->page_size, H = c->num_kv_heads;
+    const size_t rowb = (size_t)c->head_dim * c->bits / 8, ng = (size_t)(c->head_dim / c->group_size);
+    const int nblk = num_tokens > 0 ? (num_tokens + P - 1) / P : 0;
+    size_t pos = 0;
+    for (int j = 0; j < nblk; ++j) {
+        int64_t page = block_table[j];
+        if (page < 0 || page >= c->num_pages) return 1;
+        for (int h = 0; h < H; ++h) {
+            for (int which = 0; which < 2; ++which) {           /* K codes, then V codes */
+                uint8_t *codes = which ? c->v_codes : c->k_codes;
+                for (int off = 0; off < P; ++off)
+                    for (size_t b = 0; b < rowb; ++b) {
+                        uint8_t *cell = &codes[row_index(c, page, h, off) * rowb + b];
+                        if (dir == 0) packed[pos] = *cell; else *cell = packed[pos];
+                        ++pos;
+                    }
+            }
+            for (int which = 0; which < 2; ++which) {           /* K meta, then V meta: (scale, zero) pairs of fp16 */
+                uint16_t *meta = which ? c->v_meta : c->k_meta;
+                for (int off = 0; off < P; ++off)
+                    for (size_t e = 0; e < ng * 2; ++e) {
+                        uint16_t *cell = &meta[row_index(c, page, h, off) * ng * 2 + e];
+                        if (dir == 0) { packed[pos] = (uint8_t)(*cell & 0xff); packed[pos + 1] = (uint8_t)(*cell >> 8); }
+                        else *cell = (uint16_t)(packed[pos] | ((uint16_t)packed[pos + 1] << 8));
+                        pos += 2;
+                    }
+            }
+        }
+    }
+    return 0;
+}
+
+int oracle_kv_swap_out(const oracle_cache *c, const int32_t *block_table, int32_t num_tokens, uint8_t *packed)
+{
+    return swap_walk((oracle_cache *)c, block_table, num_tokens, packed, 0);
+}
+
+int oracle_kv_swap_in(oracle_cache *c, const int32_t *block_table, int32_t num_tokens, const uint8_t *packed)
+{
+    return swap_walk(c, block_table, num_tokens, (uint8_t *)packed, 1);
 }
