@@ -115,6 +115,40 @@ def cpu_baseline(w, step, target_seconds):
             "seconds": dt, "kv_tokens_per_s": tot / dt}
 
 
+def swap_leg(step):
+    """Offload + upload of the longest request (Sec. 3.2 "Dynamic Swapping", the data movement),
+    outside the timed steps: into a device staging buffer (bound: HBM copy) and into pinned host
+    memory written by the kernel itself (bound: the host link)."""
+    import numpy as np
+    import torch
+    from paper_2410_23537_amd import binding as B
+    cache = step.caches[0]
+    i = int(np.argmax(step.lens))
+    L = int(step.lens[i])
+    bt = torch.from_numpy(np.ascontiguousarray(step.pg.block_tables[i])).cuda()
+    n = B.alise_kv_swap_bytes(cache, L)
+    out = {"request_tokens": L, "bytes": n}
+    for where, buf in (("device_staging", torch.empty(n, dtype=torch.uint8, device="cuda")),
+                       ("pinned_host", torch.empty(n, dtype=torch.uint8, pin_memory=True))):
+        for name, fn in (("offload", B.alise_kv_swap_out), ("upload", B.alise_kv_swap_in)):
+            reps = 10
+            for _ in range(2):
+                fn(cache, bt, L, buf)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn(cache, bt, L, buf)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            moved = 2 * n if where == "device_staging" else n      # HBM read + HBM write, or bytes over the link
+            out[f"{where}_{name}_GBs"] = moved / (ms * 1e-3) / 1e9
+    out["note"] = ("device_staging counts bytes read + written in HBM (plain copy on this box: about 5200 GB/s); "
+                   "pinned_host counts bytes over the host link (hipMemcpyAsync of the same buffer: about 56 GB/s)")
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -194,6 +228,7 @@ def main():
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(w.name)},
     }
+    result["swap"] = swap_leg(step)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, step, args.cpu_seconds)
     print(json.dumps(result), flush=True)

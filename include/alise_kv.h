@@ -1,8 +1,8 @@
 /*
  * alise_kv.h -- C ABI of the MI355X (gfx950) quantized, paged KV-cache decode path.
  *
- * The three operations are the decode step of an LLM server that keeps its KV
- * cache compressed (ALISE, arXiv 2410.23537):
+ * The operations are the decode step of an LLM server that keeps its KV cache
+ * compressed, and the movement of a preempted request's cache (ALISE, arXiv 2410.23537):
  *   - the cache stores b-bit integer codes with one (scale, zero-point) pair per
  *     group: x_q = round(x / lambda + z), x = lambda (x_q - z),
  *     lambda = (max - min) / (2^b - 1)                       [Sec. 3.2, "KV Compression"]
@@ -151,6 +151,40 @@ int alise_paged_decode_attn(const alise_kv_cache *c, const void *q, void *out,
  */
 int alise_kv_dequant_page(const alise_kv_cache *c, int32_t page, void *k_out, void *v_out,
                           void *hip_stream);
+
+/*
+ * Offload and upload of one request's cache            [Sec. 3.2 "Dynamic Swapping", Alg. 2]
+ *
+ * The paper's cache manager moves the whole KV cache of a preempted job between GPU memory
+ * and CPU memory (request level), overlapped with computation; which job moves when (the
+ * estimated wait time, the job limit M) is host-side scheduling and not part of this
+ * library.  These two calls are the data movement: they gather the request's compressed
+ * pages, found through its block table, into one contiguous buffer, and scatter such a
+ * buffer into whatever pages the block table names at upload time.  Compressed bytes move
+ * as they are; nothing is requantized.
+ *
+ *   block_table   device, int32 [ceil(num_tokens / page_size)]: the request's pages in
+ *                 logical order (one row of the attention call's block_tables).
+ *   packed        device-ACCESSIBLE memory, 16-byte aligned, at least
+ *                 alise_kv_swap_bytes(c, num_tokens) bytes: either device memory (a staging
+ *                 buffer that a copy engine then moves, hipMemcpyAsync) or pinned host
+ *                 memory from hipHostMalloc, which the kernels read and write directly
+ *                 over the host link.
+ *   layout of packed: logical block j, KV head h at offset (j * num_kv_heads + h) * BB,
+ *                 BB = 2 * page_size * head_dim*bits/8 + 2 * page_size * (head_dim/group_size) * 4,
+ *                 holding [K codes | V codes | K meta | V meta] of that (page, head), each
+ *                 in the canonical order.  Whole pages travel, the unused slots of the last
+ *                 page included, so an upload reproduces every page bit for bit.
+ * Run them on a stream of their own to overlap them with attention; a request must not be
+ * attended to or written while it is in transit.  num_tokens = 0 is legal and does nothing.
+ */
+size_t alise_kv_swap_bytes(const alise_kv_cache *c, int32_t num_tokens);
+
+int alise_kv_swap_out(const alise_kv_cache *c, const int32_t *block_table, int32_t num_tokens,
+                      void *packed, size_t packed_bytes, void *hip_stream);
+
+int alise_kv_swap_in(const alise_kv_cache *c, const int32_t *block_table, int32_t num_tokens,
+                     const void *packed, size_t packed_bytes, void *hip_stream);
 
 /* Static, human-readable name of a status code. */
 const char *alise_status_string(int status);

@@ -32,7 +32,8 @@ ALISE_HIP_ERROR = 5
 
 EXPORTS = ("alise_kv_codes_bytes", "alise_kv_meta_bytes", "alise_kv_quant_write",
            "alise_paged_decode_attn_workspace_bytes", "alise_paged_decode_attn",
-           "alise_kv_dequant_page", "alise_status_string")
+           "alise_kv_dequant_page", "alise_kv_swap_bytes", "alise_kv_swap_out", "alise_kv_swap_in",
+           "alise_status_string")
 
 
 class alise_kv_cache(ctypes.Structure):
@@ -61,6 +62,12 @@ _lib.alise_paged_decode_attn.argtypes = [_P, ctypes.c_void_p, ctypes.c_void_p, c
                                          ctypes.c_void_p]
 _lib.alise_kv_dequant_page.restype = ctypes.c_int
 _lib.alise_kv_dequant_page.argtypes = [_P, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+_lib.alise_kv_swap_bytes.restype = ctypes.c_size_t
+_lib.alise_kv_swap_bytes.argtypes = [_P, ctypes.c_int32]
+_lib.alise_kv_swap_out.restype = ctypes.c_int
+_lib.alise_kv_swap_out.argtypes = [_P, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+_lib.alise_kv_swap_in.restype = ctypes.c_int
+_lib.alise_kv_swap_in.argtypes = [_P, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
 _lib.alise_status_string.restype = ctypes.c_char_p
 _lib.alise_status_string.argtypes = [ctypes.c_int]
 
@@ -192,6 +199,27 @@ def alise_kv_dequant_page(cache: KVCache, page: int, k_out: torch.Tensor, v_out:
     assert k_out.is_contiguous() and v_out.is_contiguous()
     st = _lib.alise_kv_dequant_page(ctypes.byref(cache.c_struct()), int(page), _dp(k_out), _dp(v_out), _stream())
     _check(st, "alise_kv_dequant_page")
+
+
+def alise_kv_swap_bytes(cache: KVCache, num_tokens: int) -> int:
+    return int(_lib.alise_kv_swap_bytes(ctypes.byref(cache.c_struct()), int(num_tokens)))
+
+
+def alise_kv_swap_out(cache: KVCache, block_table: torch.Tensor, num_tokens: int, packed: torch.Tensor) -> None:
+    """block_table: int32 device [>= ceil(num_tokens / P)]; packed: uint8, device or pinned host memory."""
+    assert block_table.dtype == torch.int32 and block_table.is_cuda and block_table.is_contiguous()
+    assert packed.dtype == torch.uint8 and packed.is_contiguous() and (packed.is_cuda or packed.is_pinned())
+    st = _lib.alise_kv_swap_out(ctypes.byref(cache.c_struct()), _dp(block_table), int(num_tokens), _dp(packed),
+                                packed.numel(), _stream())
+    _check(st, "alise_kv_swap_out")
+
+
+def alise_kv_swap_in(cache: KVCache, block_table: torch.Tensor, num_tokens: int, packed: torch.Tensor) -> None:
+    assert block_table.dtype == torch.int32 and block_table.is_cuda and block_table.is_contiguous()
+    assert packed.dtype == torch.uint8 and packed.is_contiguous() and (packed.is_cuda or packed.is_pinned())
+    st = _lib.alise_kv_swap_in(ctypes.byref(cache.c_struct()), _dp(block_table), int(num_tokens), _dp(packed),
+                               packed.numel(), _stream())
+    _check(st, "alise_kv_swap_in")
 
 
 def raw():

@@ -277,6 +277,45 @@ int alise_kv_dequant_page(const alise_kv_cache *c, int32_t page, void *k_out, vo
     return e == hipSuccess ? ALISE_OK : ALISE_HIP_ERROR;
 }
 
+size_t alise_kv_swap_bytes(const alise_kv_cache *c, int32_t num_tokens)
+{
+    CacheView cv;
+    if (check_cache(c, &cv) != ALISE_OK || num_tokens <= 0) return 0;
+    const int64_t nblk = ((int64_t)num_tokens + cv.P - 1) / cv.P;
+    return (size_t)(nblk * cv.Hkv * alise::swap_block_bytes(cv));
+}
+
+static int swap_call(const alise_kv_cache *c, const int32_t *block_table, int32_t num_tokens, void *packed,
+                     size_t packed_bytes, bool upload, void *hip_stream)
+{
+    CacheView cv;
+    int st = check_cache(c, &cv);
+    if (st != ALISE_OK) return st;
+    if (num_tokens < 0) return ALISE_INVALID_ARGUMENT;
+    if ((int64_t)num_tokens > (int64_t)cv.num_pages * cv.P) return ALISE_INVALID_ARGUMENT;
+    if (num_tokens == 0) return ALISE_OK;
+    if (!block_table || !packed) return ALISE_INVALID_ARGUMENT;
+    if (packed_bytes < alise_kv_swap_bytes(c, num_tokens)) return ALISE_INVALID_ARGUMENT;
+    st = check_cache_pointers(c);
+    if (st != ALISE_OK) return st;
+    if (!aligned16(packed) || (reinterpret_cast<uintptr_t>(block_table) & 3u)) return ALISE_MISALIGNED;
+    hipError_t e = alise::launch_swap(cv, block_table, num_tokens, packed, upload, num_compute_units(),
+                                      static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? ALISE_OK : ALISE_HIP_ERROR;
+}
+
+int alise_kv_swap_out(const alise_kv_cache *c, const int32_t *block_table, int32_t num_tokens,
+                      void *packed, size_t packed_bytes, void *hip_stream)
+{
+    return swap_call(c, block_table, num_tokens, packed, packed_bytes, false, hip_stream);
+}
+
+int alise_kv_swap_in(const alise_kv_cache *c, const int32_t *block_table, int32_t num_tokens,
+                     const void *packed, size_t packed_bytes, void *hip_stream)
+{
+    return swap_call(c, block_table, num_tokens, const_cast<void *>(packed), packed_bytes, true, hip_stream);
+}
+
 const char *alise_status_string(int status)
 {
     switch (status) {

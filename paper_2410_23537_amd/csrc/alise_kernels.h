@@ -37,6 +37,14 @@ bool gqa_mfma_applies(const CacheView &c, int32_t H);
 hipError_t launch_quant_write(const CacheView &c, const void *k, const void *v,
                               const int64_t *slot_mapping, int32_t T, hipStream_t s);
 
+// Bytes of one (page, head) block in the offloaded form of a request.
+int64_t swap_block_bytes(const CacheView &c);
+
+// Gather (upload = false) or scatter (upload = true) the pages of one request; `packed` is
+// device-accessible memory.
+hipError_t launch_swap(const CacheView &c, const int32_t *block_table, int32_t num_tokens, void *packed,
+                       bool upload, int32_t num_cus, hipStream_t s);
+
 hipError_t launch_dequant_page(const CacheView &c, int32_t page, void *k_out, void *v_out,
                                hipStream_t s);
 

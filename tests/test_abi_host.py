@@ -137,3 +137,26 @@ def test_attention_arguments(B):
     # the workspace grows with the batch and with the longest context
     assert lib.alise_paged_decode_attn_workspace_bytes(ctypes.byref(c), 64, 8, 256) > need
     assert lib.alise_paged_decode_attn_workspace_bytes(ctypes.byref(c), 2, 8, 1 << 16) > need
+
+
+def test_swap_arguments(B):
+    lib = B.raw()
+    c = _cache(B)                                   # 10 pages of 16 tokens, 8 heads, INT8, D=128, G=64
+    blk = 2 * 16 * 128 + 2 * 16 * 2 * 4             # bytes of one (page, head) block
+    assert lib.alise_kv_swap_bytes(ctypes.byref(c), 0) == 0
+    assert lib.alise_kv_swap_bytes(ctypes.byref(c), 1) == 8 * blk
+    assert lib.alise_kv_swap_bytes(ctypes.byref(c), 16) == 8 * blk
+    assert lib.alise_kv_swap_bytes(ctypes.byref(c), 17) == 2 * 8 * blk
+    assert lib.alise_kv_swap_bytes(ctypes.byref(_cache(B, bits=5)), 17) == 0
+    need = 2 * 8 * blk
+    for f in (lib.alise_kv_swap_out, lib.alise_kv_swap_in):
+        assert f(None, 0x10000, 17, 0x20000, need, None) == 1
+        assert f(ctypes.byref(c), 0x10000, -1, 0x20000, need, None) == 1
+        assert f(ctypes.byref(c), 0x10000, 161, 0x20000, 1 << 30, None) == 1      # more tokens than the cache holds
+        assert f(ctypes.byref(c), 0, 0, 0, 0, None) == 0                            # no tokens: no-op
+        assert f(ctypes.byref(c), 0, 17, 0x20000, need, None) == 1
+        assert f(ctypes.byref(c), 0x10000, 17, 0, need, None) == 1
+        assert f(ctypes.byref(c), 0x10000, 17, 0x20000, need - 1, None) == 1        # buffer too small
+        assert f(ctypes.byref(c), 0x10000, 17, 0x20008, need, None) == 4
+        assert f(ctypes.byref(c), 0x10002, 17, 0x20000, need, None) == 4
+        assert f(ctypes.byref(_cache(B, head_dim=96)), 0x10000, 17, 0x20000, need, None) == 2
