@@ -7,9 +7,9 @@
 // Work decomposition (this build's, not the paper's):
 //   plan kernel   : context_lens -> tile descriptors (request, token range of at most C
 //                   tokens), full tiles first, the shorter remainders last
-//   attn kernel   : persistent waves pull (tile, head) items from an atomic counter;
-//                   one wave = one item, no workgroup barrier anywhere; the counter
-//                   and the descriptor of the following item are fetched one item ahead
+//   attn kernel   : persistent waves, each with a fixed list of (tile, head) items dealt
+//                   out from the longest-first order; one wave = one item at a time, no
+//                   workgroup barrier anywhere; the stream of loads runs on across items
 //   merge kernel  : log-sum-exp combination of the splits of long requests
 //
 // Inside a wave every load instruction reads 1 KiB of contiguous codes: a token's
@@ -192,6 +192,22 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t *context_lens,
 
 // ------------------------------------------------------------------ attention
 
+// Stores of the end of a tile, written in assembly so that the compiler does not count them.
+// A store may complete out of order with the loads, so with a store in flight the compiler's
+// next wait for a load becomes "wait for everything", which drained the double buffer once
+// per item.  Not counting a store only makes the compiler's waits for loads longer than
+// needed by at most that store, never shorter: loads still complete in issue order.
+__device__ __forceinline__ void stream_store_f32(float *p, float v)
+{
+    asm volatile("global_store_dword %0, %1, off" : : "v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void stream_store_f16(_Float16 *p, _Float16 v)
+{
+    const uint32_t u = __builtin_bit_cast(uint16_t, v);
+    asm volatile("global_store_short %0, %1, off" : : "v"(p), "v"(u) : "memory");
+}
+
+
 template <int BITS, int D>
 struct Geo {
     static constexpr int ROWB = D * BITS / 8;   // code bytes of one token's row
@@ -362,11 +378,10 @@ struct TileCtx {
 // NB = wave-loads per block; two blocks are in flight per wave.
 //
 // The kernel is one continuous stream of blocks: the last load slot of a tile already
-// fetches the first block of the wave's next tile, the next tile's q is fetched before
-// the epilogue of the current one, and the bookkeeping runs ahead of the data:
-//   queue counter   three items ahead
-//   tile descriptor two items ahead
-//   block-table entries (pg) one item ahead
+// fetches the first block of the wave's next tile, and what a tile needs besides the cache
+// is there before it starts: its q is fetched at the start of the tile before it, its
+// block-table entries (pg) at the end of the tile before it, its descriptor through the
+// scalar unit.  Nothing at a tile boundary waits for the vector loads in flight.
 template <int BITS, int D, bool UNI, int NB>
 __global__ __launch_bounds__(256) void decode_attn_kernel(AttnParams p)
 {
@@ -391,21 +406,23 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(AttnParams p)
     const int n_items = *p.ws.n_items;
     const int4 *order = p.ws.order;
 
-    // Work queues.  Item q + nq * n is the n-th item of queue q; a workgroup serves queue
-    // blockIdx % nq.  Workgroups are dealt to the eight XCDs round-robin, so the waves that
-    // bump one counter sit on one XCD and its cache line stays in that XCD's L2 instead of
-    // bouncing between dies; any other placement is still correct, only slower.  (Giving a
-    // queue whole tiles, all heads together, was measured and is slower: coarser balance.)
-    const int nq = gridDim.x >= kQueues ? kQueues : 1;
-    const int q = blockIdx.x % nq;
-    uint32_t *counter = p.ws.counter + q * kQueueStride;
-    auto next_ticket = [&]() {
-        int n = 0;
-        if (lane == 0) n = (int)atomicAdd(counter, 1u);
-        return n;       // valid in lane 0
+    // A wave owns a fixed list of items, dealt out by rank in the longest-first order: round r
+    // gives wave w item r * W + w, odd rounds in reverse wave order.  That evens out the totals
+    // to well under one per cent, and it needs no counter: a ticket fetched with an atomic
+    // returns into a register, and waiting for it drained the wave's load pipeline once per
+    // item (the whole grid must be resident, which the occupancy-sized launch guarantees).
+    const int W = gridDim.x * 4, w_id = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + wave);
+    auto item_at = [&](int r) { return r * W + ((r & 1) ? W - 1 - w_id : w_id); };
+    // The descriptor of an item comes through the scalar unit, at the moment it is needed: a
+    // scalar load is counted apart from the vector loads, so waiting for it leaves the wave's
+    // prefetched blocks in flight (a vector load here made the compiler wait for all of them).
+    auto desc_of = [&](int it) {
+        typedef int32_t i32x4_t __attribute__((ext_vector_type(4)));
+        const int4 *src = order + (it < n_items ? it : 0) / p.H;
+        i32x4_t d;
+        asm volatile("s_load_dwordx4 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(d) : "s"(src) : "memory");
+        return make_int4(d.x, d.y, d.z, d.w);
     };
-    auto item_of = [&](int ticket_v) { return q + nq * __builtin_amdgcn_readfirstlane(ticket_v); };
-    auto desc_of = [&](int it) { return order[(it < n_items ? it : 0) / p.H]; };
     auto make_ctx = [&](int it, const int4 d) {
         TileCtx c;
         c.valid = it < n_items;
@@ -470,14 +487,11 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(AttnParams p)
     };
 
     // ---- fill the pipeline
-    const int tk0 = next_ticket(), tk1 = next_ticket(), tk2 = next_ticket();
-    int tk3 = next_ticket();
-    const int it0 = item_of(tk0), it1 = item_of(tk1);
-    int it2 = item_of(tk2);
+    int round = 0;
+    const int it0 = item_at(0), it1 = item_at(1);
     TileCtx cur = make_ctx(it0, desc_of(it0));
     if (!cur.valid) return;                     // wave-uniform
     TileCtx nxt = make_ctx(it1, desc_of(it1));
-    int4 d2 = desc_of(it2);
     int pg_cur = load_pg(cur);
     int pg_nxt = load_pg(nxt);
     uint32_t qraw[SL / 2];
@@ -488,6 +502,8 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(AttnParams p)
     for (;;) {
         QSlice<BITS> qs;
         make_q<BITS, D>(qs, qraw);
+        // the next tile's q travels during this whole tile, so nothing waits for it later
+        load_q_raw(nxt.valid ? nxt : cur, qraw);
 
         Acc<SL> st;
         st.m_ref = kFloor; st.l = 0.0f; st.wz = 0.0f;
@@ -505,7 +521,12 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(AttnParams p)
         // bufA holds block 0 of the tile (in flight).  The slot after the tile's last block
         // fetches block 0 of the next tile, so bufA is ready for it when this tile is done.
         const int nblk = cur.nblk;
-        for (int k = 0; k < nblk; k += 2) {
+        // A tile has at least one block, and the loop says so (do-while): the compiler sizes
+        // its waits for the loads issued an item ago (descriptor, page ids, q) by the fewest
+        // loads that can follow them, and a loop that might not run counts as none, which
+        // turned those waits into "wait for the prefetched block as well".
+        int k = 0;
+        do {
             issue(bufB, cur, pg_cur, min(k + 1, nblk - 1));
             eat(bufA, k);
             const bool hop = (k + 2 >= nblk) && nxt.valid;      // wave-uniform
@@ -513,10 +534,8 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(AttnParams p)
             if (hop) src = nxt;
             issue(bufA, src, hop ? pg_nxt : pg_cur, hop ? 0 : min(k + 2, nblk - 1));
             if (k + 1 < nblk) eat(bufB, k + 1);
-        }
-
-        // the next tile's q, in flight during the epilogue
-        load_q_raw(nxt.valid ? nxt : cur, qraw);
+            k += 2;
+        } while (k < nblk);
 
         // ---- bring the TPW slots to one maximum, then add them up through LDS
         float m_fin = st.m_ref;
@@ -561,23 +580,22 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(AttnParams p)
             const float inv_l = 1.0f / l;
             _Float16 *dst = p.out + ((int64_t)cur.i * p.H + cur.h) * D;
 #pragma unroll
-            for (int r = 0; r < D / 64; ++r) dst[r * 64 + lane] = (_Float16)(o[r] * inv_l);
+            for (int r = 0; r < D / 64; ++r) stream_store_f16(dst + r * 64 + lane, (_Float16)(o[r] * inv_l));
         } else {
             float *dst = p.ws.part + ((int64_t)cur.part * p.H + cur.h) * (D + 2);
-            if (lane == 0) { dst[0] = m_fin; dst[1] = l; }
+            if (lane == 0) { stream_store_f32(dst, m_fin); stream_store_f32(dst + 1, l); }
 #pragma unroll
-            for (int r = 0; r < D / 64; ++r) dst[2 + r * 64 + lane] = o[r];
+            for (int r = 0; r < D / 64; ++r) stream_store_f32(dst + 2 + r * 64 + lane, o[r]);
         }
 
         // ---- advance the pipeline (loads below are unconditional; indices are clamped)
         if (!nxt.valid) break;                  // wave-uniform; nothing is in flight that matters
         cur = nxt;
         pg_cur = pg_nxt;
-        nxt = make_ctx(it2, d2);
+        ++round;
+        const int it_nxt = item_at(round + 1);
+        nxt = make_ctx(it_nxt, desc_of(it_nxt));
         pg_nxt = load_pg(nxt);
-        it2 = item_of(tk3);
-        d2 = desc_of(it2);
-        tk3 = next_ticket();
     }
 }
 
@@ -715,7 +733,7 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
         else if (c.bits == 4 && c.D == 128) e = launch_t<4, 128, NBV>(p, num_cus, waves_per_cu, s);   \
         else if (c.bits == 4 && c.D == 64) e = launch_t<4, 64, NBV>(p, num_cus, waves_per_cu, s);     \
     } while (0)
-        if (loads_per_block == 0) loads_per_block = c.bits == 4 ? 3 : 4;
+        if (loads_per_block == 0) loads_per_block = 2;      // 3 and 4 measure within 1 % of it
         if (loads_per_block == 2) ALISE_DISPATCH(2);
         else if (loads_per_block == 3) ALISE_DISPATCH(3);
         else if (loads_per_block == 4) ALISE_DISPATCH(4);
