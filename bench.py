@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published peak HBM3E bandwidth
 
 # HBM bytes per attention launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a
 # copy kernel of known size; see profiles/.  None where not measured.
-MEASURED_TRAFFIC_BYTES = {"int4": 7236786694, "gqa70b": 1112172716, "llama7b": 2021116155}
+MEASURED_TRAFFIC_BYTES = {"int4": 7200323825, "gqa70b": 1112229165, "llama7b": 1999709357}
 
 
 def parse():

@@ -123,7 +123,7 @@ int32_t min_items_per_wave()
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-// Workspace layout: [queue counters, n_items, n_merge | tile_base[B+1] | req_full_base[B] | merge_req[B] |
+// Workspace layout: [n_items, n_merge | tile_base[B+1] | req_full_base[B] | merge_req[B] |
 // order[max_tiles] | part].
 size_t carve_workspace(const CacheView &c, int32_t B, int32_t H, int32_t max_len, void *base,
                        AttnWorkspace *ws)
@@ -132,7 +132,7 @@ size_t carve_workspace(const CacheView &c, int32_t B, int32_t H, int32_t max_len
     const int32_t C = split_tokens(c.P, alise::gqa_mfma_applies(c, H), &C_min);
     const int64_t splits = ((int64_t)max_len + C_min - 1) / C_min;
     const int64_t max_tiles = (int64_t)B * (splits > 0 ? splits : 1);
-    size_t off = 2304;      // eight queue counters, 256 bytes apart, then n_items
+    size_t off = 256;       // header: n_items, n_merge
     const size_t off_base = off;
     off = align_up(off + sizeof(int32_t) * ((size_t)B + 1), 256);
     const size_t off_fb = off;
@@ -145,12 +145,11 @@ size_t carve_workspace(const CacheView &c, int32_t B, int32_t H, int32_t max_len
     off = align_up(off + sizeof(float) * (size_t)max_tiles * H * (c.D + 2), 256);
     if (ws) {
         char *b = static_cast<char *>(base);
-        ws->counter = reinterpret_cast<uint32_t *>(b);
-        ws->n_items = reinterpret_cast<int32_t *>(b + 2048);
+        ws->n_items = reinterpret_cast<int32_t *>(b);
         ws->tile_base = reinterpret_cast<int32_t *>(b + off_base);
         ws->req_full_base = reinterpret_cast<int32_t *>(b + off_fb);
         ws->merge_req = reinterpret_cast<int32_t *>(b + off_rb);
-        ws->n_merge = reinterpret_cast<int32_t *>(b + 2052);
+        ws->n_merge = reinterpret_cast<int32_t *>(b + 4);
         ws->order = reinterpret_cast<int4 *>(b + off_order);
         ws->part = reinterpret_cast<float *>(b + off_part);
         ws->max_tiles = (int32_t)max_tiles;

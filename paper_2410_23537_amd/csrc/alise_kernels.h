@@ -16,7 +16,6 @@ struct CacheView {
 
 // Workspace carved up by the ABI layer for one attention call.
 struct AttnWorkspace {
-    uint32_t *counter;      // [8 x 64] next item of each work queue (one 256-byte line each), reset by the plan kernel
     int32_t *n_items;       // [1]  tiles * H, written by the plan kernel
     int32_t *tile_base;     // [B+1] first tile of each request (exclusive scan of tile counts)
     int32_t *req_full_base; // [B] scratch of the plan kernel: first full tile of each request in the work order

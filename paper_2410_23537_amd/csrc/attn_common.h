@@ -12,8 +12,6 @@ typedef _Float16 h2_t __attribute__((ext_vector_type(2)));
 
 constexpr float kNegInf = -__builtin_inff();
 constexpr float kLazy = 8.0f;   // the running maximum is raised only past this slack (log2 units)
-constexpr int kQueues = 8;          // work queues of the attention kernels, one per XCD
-constexpr int kQueueStride = 64;    // uint32 between queue counters: one 256-byte line each
 constexpr float kFloor = -1.0e30f;   // finite stand-in for "no token seen yet": -inf - kFloor stays -inf
 
 struct AttnParams {

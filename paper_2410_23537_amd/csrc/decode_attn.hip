@@ -186,7 +186,6 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t *context_lens,
         ws.tile_base[B] = total;
         *ws.n_items = total * items_per_tile;
         *ws.n_merge = s_merge;
-        for (int q = 0; q < kQueues; ++q) ws.counter[q * kQueueStride] = 0u;
     }
 }
 
