@@ -55,6 +55,10 @@ def lib():
         L.oracle_quant_group.restype = None
         L.oracle_quant_group.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int,
                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        L.oracle_paged_prefill_attn.restype = ctypes.c_int
+        L.oracle_paged_prefill_attn.argtypes = [ctypes.POINTER(_CCache), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                                ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32,
+                                                ctypes.c_int32, ctypes.c_double, ctypes.c_int32]
         L.oracle_kv_swap_bytes.restype = ctypes.c_size_t
         L.oracle_kv_swap_bytes.argtypes = [ctypes.POINTER(_CCache), ctypes.c_int32]
         L.oracle_kv_swap_out.restype = ctypes.c_int
@@ -206,3 +210,24 @@ def kv_swap_in(cache: Cache, block_table: np.ndarray, num_tokens: int, packed: n
     rc = lib().oracle_kv_swap_in(ctypes.byref(c), _ptr(bt), int(num_tokens), _ptr(packed))
     if rc:
         raise ValueError("block table entry out of range")
+
+
+def paged_prefill_attn(cache: Cache, q: np.ndarray, q_start: np.ndarray, block_tables: np.ndarray,
+                       context_lens: np.ndarray, softmax_scale: float, num_threads: int = 0) -> np.ndarray:
+    """q: fp16 [total_q, H, D], the requests' chunks back to back; q_start: int32 [B+1].
+    Returns fp64 [total_q, H, D]: every query token attends causally over the cache."""
+    q = np.ascontiguousarray(q, dtype=np.float16)
+    qs = np.ascontiguousarray(q_start, dtype=np.int32)
+    bt = np.ascontiguousarray(block_tables, dtype=np.int32)
+    lens = np.ascontiguousarray(context_lens, dtype=np.int32)
+    B = lens.shape[0]
+    assert qs.shape == (B + 1,) and qs[0] == 0 and qs[-1] == q.shape[0]
+    out = np.zeros(q.shape, np.float64)
+    c = cache._c()
+    if num_threads <= 0:
+        num_threads = min(16, os.cpu_count() or 1)
+    rc = lib().oracle_paged_prefill_attn(ctypes.byref(c), _ptr(q), _ptr(out), _ptr(qs), _ptr(bt), bt.shape[1],
+                                         _ptr(lens), B, q.shape[1], float(softmax_scale), num_threads)
+    if rc:
+        raise ValueError("a chunk is longer than its request")
+    return out

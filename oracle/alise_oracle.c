@@ -34,6 +34,9 @@
  *   R14 INT4: channel 2i in the low nibble, 2i+1 in the high nibble of byte i.
  *   R15 query head h reads KV head h / (H / Hkv).
  *   R16 no mask beyond t < L_i; L_i = 0 gives a zero row.
+ *   R18 prefill in chunks: the chunk's own K/V are written first (quantized, R12), then
+ *       query j of an n-token chunk of a request with L cached tokens sits at position
+ *       L - n + j and attends to positions 0 .. L - n + j (causal), all from the cache.
  *   R17 the offloaded form of a request is its pages in logical order, whole pages
  *       (every slot of the last page too), each as [K codes | V codes | K meta | V meta]
  *       per KV head: compressed bytes move as they are, nothing is requantized.
@@ -308,6 +311,69 @@ void oracle_dense_attn(const double *q, const double *K, const double *V, int L,
     for (int t = 0; t < L; ++t)
         for (int d = 0; d < D; ++d) out[d] += s[t] / denom * V[(size_t)t * D + d];
     free(s);
+}
+
+/*
+ * Chunked prefill (Sec. 2 "LLM Inference": the prompt's tokens are processed in one pass;
+ * Eq. 1-2 with the causal order of an autoregressive model; R18).  q, out: [total_q][H][D],
+ * the chunks of the requests back to back; q_start[i] .. q_start[i+1] - 1 are request i's
+ * rows.  Every (query token, head) is the single-query definition over its own prefix.
+ * out: fp64.  Returns nonzero if a chunk is longer than its request or memory runs out.
+ */
+int oracle_paged_prefill_attn(const oracle_cache *c, const uint16_t *q, double *out, const int32_t *q_start,
+                              const int32_t *block_tables, int32_t max_blocks_per_seq,
+                              const int32_t *context_lens, int32_t B, int32_t H,
+                              double softmax_scale, int32_t num_threads)
+{
+    const int D = c->head_dim, G = c->group_size, ng = D / G, P = c->page_size;
+    const int qper = H / c->num_kv_heads;
+    int fail = 0;
+    if (num_threads < 1) num_threads = 1;
+    for (int i = 0; i < B; ++i)
+        if (q_start[i + 1] - q_start[i] > context_lens[i] || q_start[i + 1] < q_start[i]) return 2;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(num_threads)
+    for (int64_t row = 0; row < (int64_t)q_start[B] * H; ++row) {
+        int tq = (int)(row / H), h = (int)(row % H);
+        int i = 0;
+        while (q_start[i + 1] <= tq) ++i;                         /* the request this query token belongs to */
+        int n = q_start[i + 1] - q_start[i], j = tq - q_start[i];
+        int L = context_lens[i] - n + j + 1;                      /* the query's own position is the last one it sees */
+        int hk = h / qper;
+        double *o = out + (size_t)row * D;
+        for (int d = 0; d < D; ++d) o[d] = 0.0;
+        double *s = (double *)malloc(sizeof(double) * (size_t)L);
+        if (!s) { fail = 1; continue; }
+        const uint16_t *qv = q + (size_t)row * D;
+        double m = -INFINITY;
+        for (int t = 0; t < L; ++t) {
+            int64_t page = block_tables[(size_t)i * max_blocks_per_seq + t / P];
+            size_t r = row_index(c, page, hk, t % P);
+            double acc = 0.0;
+            for (int d = 0; d < D; ++d) {
+                int g = d / G;
+                float kd = dequant_f32(get_code(c, c->k_codes, r, d),
+                                       c->k_meta[(r * ng + g) * 2], c->k_meta[(r * ng + g) * 2 + 1]);
+                acc += (double)oracle_h2f(qv[d]) * (double)kd;
+            }
+            s[t] = acc * softmax_scale;
+            if (s[t] > m) m = s[t];
+        }
+        double denom = 0.0;
+        for (int t = 0; t < L; ++t) { s[t] = exp(s[t] - m); denom += s[t]; }
+        for (int t = 0; t < L; ++t) {
+            int64_t page = block_tables[(size_t)i * max_blocks_per_seq + t / P];
+            size_t r = row_index(c, page, hk, t % P);
+            double p = s[t] / denom;
+            for (int d = 0; d < D; ++d) {
+                int g = d / G;
+                float vd = dequant_f32(get_code(c, c->v_codes, r, d),
+                                       c->v_meta[(r * ng + g) * 2], c->v_meta[(r * ng + g) * 2 + 1]);
+                o[d] += p * (double)vd;
+            }
+        }
+        free(s);
+    }
+    return fail;
 }
 
 /* ---------------------------------------------------------------- dynamic swapping (data movement) */
