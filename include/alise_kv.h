@@ -153,6 +153,38 @@ int alise_kv_dequant_page(const alise_kv_cache *c, int32_t page, void *k_out, vo
                           void *hip_stream);
 
 /*
+ * Chunked-prefill attention over the compressed cache        [Sec. 2 "LLM Inference", Eq. 1-2]
+ *
+ * The prefilling stage processes the prompt's tokens in one pass.  Here a request brings a
+ * chunk of n_i query tokens; their K/V have already been quantized and written
+ * (alise_kv_quant_write), so the cache holds L_i tokens including the chunk, the chunk at
+ * positions L_i - n_i .. L_i - 1.  Query token j of the chunk attends, per head, to the cached
+ * tokens 0 .. L_i - n_i + j (causal order), read from their quantized form like every other
+ * token.  A chunk of one token is the decode step.
+ *
+ *   q, out        device, fp16 [total_q_tokens][num_q_heads][head_dim], 16-byte aligned: the
+ *                 chunks of the B requests back to back.
+ *   q_start       device, int32 [B + 1]: request i owns rows q_start[i] .. q_start[i+1] - 1;
+ *                 q_start[0] = 0, nondecreasing, q_start[B] = total_q_tokens.  n_i = 0 is legal.
+ *                 n_i > L_i is a caller error (the chunk is then cut to L_i rows).
+ *   block_tables, max_blocks_per_seq, context_lens, max_context_len, softmax_scale, workspace:
+ *                 as for alise_paged_decode_attn; the workspace size comes from
+ *                 alise_paged_prefill_attn_workspace_bytes.
+ * Supported shapes: bits = 8, head_dim = 128, group_size 64 or 128, page_size >= 16,
+ * num_q_heads / num_kv_heads between 1 and 16; anything else returns ALISE_UNSUPPORTED.
+ * out[t][h] = sum_u softmax_u(softmax_scale * q[t][h] . k^_u) v^_u over u <= position of t,
+ * accumulated in fp32, rounded once to fp16.
+ */
+size_t alise_paged_prefill_attn_workspace_bytes(const alise_kv_cache *c, int32_t B, int32_t total_q_tokens,
+                                                int32_t num_q_heads);
+
+int alise_paged_prefill_attn(const alise_kv_cache *c, const void *q, void *out, const int32_t *q_start,
+                             const int32_t *block_tables, int32_t max_blocks_per_seq,
+                             const int32_t *context_lens, int32_t B, int32_t total_q_tokens,
+                             int32_t num_q_heads, int32_t max_context_len, float softmax_scale,
+                             void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Offload and upload of one request's cache            [Sec. 3.2 "Dynamic Swapping", Alg. 2]
  *
  * The paper's cache manager moves the whole KV cache of a preempted job between GPU memory

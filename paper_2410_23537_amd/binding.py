@@ -33,6 +33,7 @@ ALISE_HIP_ERROR = 5
 EXPORTS = ("alise_kv_codes_bytes", "alise_kv_meta_bytes", "alise_kv_quant_write",
            "alise_paged_decode_attn_workspace_bytes", "alise_paged_decode_attn",
            "alise_kv_dequant_page", "alise_kv_swap_bytes", "alise_kv_swap_out", "alise_kv_swap_in",
+           "alise_paged_prefill_attn_workspace_bytes", "alise_paged_prefill_attn",
            "alise_status_string")
 
 
@@ -62,6 +63,13 @@ _lib.alise_paged_decode_attn.argtypes = [_P, ctypes.c_void_p, ctypes.c_void_p, c
                                          ctypes.c_void_p]
 _lib.alise_kv_dequant_page.restype = ctypes.c_int
 _lib.alise_kv_dequant_page.argtypes = [_P, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+_lib.alise_paged_prefill_attn_workspace_bytes.restype = ctypes.c_size_t
+_lib.alise_paged_prefill_attn_workspace_bytes.argtypes = [_P, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
+_lib.alise_paged_prefill_attn.restype = ctypes.c_int
+_lib.alise_paged_prefill_attn.argtypes = [_P, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                          ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
+                                          ctypes.c_int32, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p,
+                                          ctypes.c_size_t, ctypes.c_void_p]
 _lib.alise_kv_swap_bytes.restype = ctypes.c_size_t
 _lib.alise_kv_swap_bytes.argtypes = [_P, ctypes.c_int32]
 _lib.alise_kv_swap_out.restype = ctypes.c_int
@@ -199,6 +207,27 @@ def alise_kv_dequant_page(cache: KVCache, page: int, k_out: torch.Tensor, v_out:
     assert k_out.is_contiguous() and v_out.is_contiguous()
     st = _lib.alise_kv_dequant_page(ctypes.byref(cache.c_struct()), int(page), _dp(k_out), _dp(v_out), _stream())
     _check(st, "alise_kv_dequant_page")
+
+
+def alise_paged_prefill_attn_workspace_bytes(cache: KVCache, B: int, total_q_tokens: int, num_q_heads: int) -> int:
+    return int(_lib.alise_paged_prefill_attn_workspace_bytes(ctypes.byref(cache.c_struct()), int(B), int(total_q_tokens),
+                                                             int(num_q_heads)))
+
+
+def alise_paged_prefill_attn(cache: KVCache, q: torch.Tensor, out: torch.Tensor, q_start: torch.Tensor,
+                             block_tables: torch.Tensor, context_lens: torch.Tensor, max_context_len: int,
+                             softmax_scale: float, workspace: torch.Tensor) -> None:
+    """q, out: fp16 [total_q, H, D]; q_start: int32 [B+1]; block_tables: int32 [B, max_blocks]; context_lens: int32 [B]."""
+    assert q.dtype == torch.float16 and out.dtype == torch.float16 and q.shape == out.shape and q.dim() == 3
+    assert q.is_contiguous() and out.is_contiguous() and block_tables.is_contiguous()
+    assert q_start.dtype == torch.int32 and block_tables.dtype == torch.int32 and context_lens.dtype == torch.int32
+    B = context_lens.shape[0]
+    assert q_start.shape[0] == B + 1 and block_tables.shape[0] == B
+    st = _lib.alise_paged_prefill_attn(ctypes.byref(cache.c_struct()), _dp(q), _dp(out), _dp(q_start), _dp(block_tables),
+                                       block_tables.shape[1], _dp(context_lens), B, q.shape[0], q.shape[1],
+                                       int(max_context_len), float(softmax_scale), _dp(workspace), workspace.numel(),
+                                       _stream())
+    _check(st, "alise_paged_prefill_attn")
 
 
 def alise_kv_swap_bytes(cache: KVCache, num_tokens: int) -> int:

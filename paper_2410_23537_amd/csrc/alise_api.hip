@@ -276,6 +276,71 @@ int alise_kv_dequant_page(const alise_kv_cache *c, int32_t page, void *k_out, vo
     return e == hipSuccess ? ALISE_OK : ALISE_HIP_ERROR;
 }
 
+static size_t carve_prefill(const CacheView &cv, int32_t B, int32_t total_q, int32_t H, void *base,
+                            alise::PrefillWorkspace *ws)
+{
+    const int tpw = alise::prefill_tokens_per_workgroup(H / cv.Hkv);
+    const int64_t max_tiles = ((int64_t)total_q + tpw - 1) / tpw + B;
+    const size_t bytes = align_up(256 + sizeof(int32_t) * 2 * (size_t)max_tiles, 256);
+    if (ws) {
+        char *b = static_cast<char *>(base);
+        ws->n_tiles = reinterpret_cast<int32_t *>(b);
+        ws->table = reinterpret_cast<int2 *>(b + 256);
+        ws->max_tiles = (int32_t)max_tiles;
+    }
+    return bytes;
+}
+
+static int check_prefill_sizes(const CacheView &cv, int32_t B, int32_t total_q, int32_t H, int32_t max_len)
+{
+    if (B < 0 || total_q < 0 || H <= 0 || max_len < 0) return ALISE_INVALID_ARGUMENT;
+    if (H % cv.Hkv != 0) return ALISE_UNSUPPORTED;
+    if (!alise::prefill_mfma_applies(cv, H)) return ALISE_UNSUPPORTED;
+    if ((int64_t)total_q * H >= (int64_t)1 << 31) return ALISE_UNSUPPORTED;
+    return ALISE_OK;
+}
+
+size_t alise_paged_prefill_attn_workspace_bytes(const alise_kv_cache *c, int32_t B, int32_t total_q_tokens,
+                                                int32_t num_q_heads)
+{
+    CacheView cv;
+    if (check_cache(c, &cv) != ALISE_OK) return 0;
+    if (check_prefill_sizes(cv, B, total_q_tokens, num_q_heads, 0) != ALISE_OK) return 0;
+    return carve_prefill(cv, B, total_q_tokens, num_q_heads, nullptr, nullptr);
+}
+
+int alise_paged_prefill_attn(const alise_kv_cache *c, const void *q, void *out, const int32_t *q_start,
+                             const int32_t *block_tables, int32_t max_blocks_per_seq,
+                             const int32_t *context_lens, int32_t B, int32_t total_q_tokens,
+                             int32_t num_q_heads, int32_t max_context_len, float softmax_scale,
+                             void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    CacheView cv;
+    int st = check_cache(c, &cv);
+    if (st != ALISE_OK) return st;
+    st = check_prefill_sizes(cv, B, total_q_tokens, num_q_heads, max_context_len);
+    if (st != ALISE_OK) return st;
+    if (B == 0 || total_q_tokens == 0) return ALISE_OK;
+    if (max_blocks_per_seq <= 0) return ALISE_INVALID_ARGUMENT;
+    if ((int64_t)max_blocks_per_seq * cv.P < max_context_len) return ALISE_INVALID_ARGUMENT;
+    if (!(softmax_scale == softmax_scale) || softmax_scale <= 0.0f) return ALISE_INVALID_ARGUMENT;
+    if (!q || !out || !q_start || !block_tables || !context_lens || !workspace) return ALISE_INVALID_ARGUMENT;
+    st = check_cache_pointers(c);
+    if (st != ALISE_OK) return st;
+    if (!aligned16(q) || !aligned16(out)) return ALISE_MISALIGNED;
+    if ((reinterpret_cast<uintptr_t>(block_tables) & 3u) || (reinterpret_cast<uintptr_t>(context_lens) & 3u) ||
+        (reinterpret_cast<uintptr_t>(q_start) & 3u))
+        return ALISE_MISALIGNED;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return ALISE_MISALIGNED;
+    alise::PrefillWorkspace ws;
+    const size_t need = carve_prefill(cv, B, total_q_tokens, num_q_heads, workspace, &ws);
+    if (workspace_bytes < need) return ALISE_WORKSPACE_TOO_SMALL;
+    hipError_t e = alise::launch_prefill_attn(cv, q, out, q_start, block_tables, max_blocks_per_seq, context_lens, B,
+                                              num_q_heads, max_context_len, softmax_scale, ws,
+                                              static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? ALISE_OK : ALISE_HIP_ERROR;
+}
+
 size_t alise_kv_swap_bytes(const alise_kv_cache *c, int32_t num_tokens)
 {
     CacheView cv;

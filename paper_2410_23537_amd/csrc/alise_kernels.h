@@ -36,6 +36,22 @@ bool gqa_mfma_applies(const CacheView &c, int32_t H);
 hipError_t launch_quant_write(const CacheView &c, const void *k, const void *v,
                               const int64_t *slot_mapping, int32_t T, hipStream_t s);
 
+// Workspace of one chunked-prefill call.
+struct PrefillWorkspace {
+    int32_t *n_tiles;       // [1] workgroup tiles in the table, written by the plan kernel
+    int2 *table;            // [max_tiles] (request, row tile of the request's chunk)
+    int32_t max_tiles;
+};
+
+// Shapes the matrix-core prefill kernel takes (INT8, D = 128, G in {64, 128}, P >= 16, 1..16 query heads per KV head).
+bool prefill_mfma_applies(const CacheView &c, int32_t H);
+int32_t prefill_tokens_per_workgroup(int32_t qper);
+
+hipError_t launch_prefill_attn(const CacheView &c, const void *q, void *out, const int32_t *q_start,
+                               const int32_t *block_tables, int32_t max_blocks, const int32_t *context_lens,
+                               int32_t B, int32_t H, int32_t max_context_len, float softmax_scale,
+                               const PrefillWorkspace &ws, hipStream_t s);
+
 // Bytes of one (page, head) block in the offloaded form of a request.
 int64_t swap_block_bytes(const CacheView &c);
 

@@ -1,0 +1,96 @@
+// Pieces shared by the matrix-core attention kernels (decode for grouped-query layouts, chunked
+// prefill): direct global -> LDS loads, the hand-placed waits that go with them, LDS reads in
+// assembly, operand packing.
+#pragma once
+#include "attn_common.h"
+
+namespace alise {
+namespace {
+
+typedef _Float16 h8_t __attribute__((ext_vector_type(8)));
+typedef float f4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kStep = 32;       // tokens per step: two 16-token tiles
+
+typedef const void __attribute__((address_space(1))) *gptr_t;
+typedef uint8_t __attribute__((address_space(3))) *lptr_t;
+typedef void __attribute__((address_space(3))) *lvoid_t;
+
+// Direct global -> LDS loads: lane l's bytes land at the LDS base + l * size, wherever the
+// lane's global address points.  The cache is streamed (non-temporal); the bookkeeping is not.
+__device__ __forceinline__ void dma16_stream(const void *g, lptr_t l) { __builtin_amdgcn_global_load_lds((gptr_t)g, (lvoid_t)l, 16, 0, 2); }
+__device__ __forceinline__ void dma4_stream(const void *g, lptr_t l) { __builtin_amdgcn_global_load_lds((gptr_t)g, (lvoid_t)l, 4, 0, 2); }
+__device__ __forceinline__ void dma16(const void *g, lptr_t l) { __builtin_amdgcn_global_load_lds((gptr_t)g, (lvoid_t)l, 16, 0, 0); }
+__device__ __forceinline__ void dma4(const void *g, lptr_t l) { __builtin_amdgcn_global_load_lds((gptr_t)g, (lvoid_t)l, 4, 0, 0); }
+
+#define ALISE_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xf) | (((n) >> 4) << 14) | (0x7 << 4) | (0xf << 8))
+
+// Wait until the load that has `newer` loads issued after it has landed.  Loads complete in
+// the order they were issued, so it is enough that at most `newer` stay in flight; the count
+// is rounded down to a multiple of four (the menu of immediates), which only waits longer.
+// Stores are never counted: they may complete out of order with the loads.
+__device__ __forceinline__ void wait_newer(int newer)       // wave-uniform
+{
+    const int k = newer >> 2;
+    if (k >= 12) ALISE_VMCNT(48);
+    else if (k >= 9) ALISE_VMCNT(36);
+    else if (k >= 6) ALISE_VMCNT(24);
+    else if (k >= 4) ALISE_VMCNT(16);
+    else if (k == 3) ALISE_VMCNT(12);
+    else if (k == 2) ALISE_VMCNT(8);
+    else if (k == 1) ALISE_VMCNT(4);
+    else ALISE_VMCNT(0);
+}
+
+// LDS reads of data that arrived by direct loads are written in assembly: the compiler does
+// not see them, so it never orders them against the loads in flight -- the waits above do.
+__device__ __forceinline__ uint4 lds_read16(uint32_t addr)
+{
+    uint4 r;
+    asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(r) : "v"(addr) : "memory");
+    return r;
+}
+__device__ __forceinline__ uint32_t lds_read4(uint32_t addr)
+{
+    uint32_t r;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(r) : "v"(addr) : "memory");
+    return r;
+}
+// four 16-byte reads, one wait
+__device__ __forceinline__ void lds_read16x4(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3,
+                                             uint4 &r0, uint4 &r1, uint4 &r2, uint4 &r3)
+{
+    asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %5\n\tds_read_b128 %2, %6\n\tds_read_b128 %3, %7\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(r0), "=&v"(r1), "=&v"(r2), "=&v"(r3) : "v"(a0), "v"(a1), "v"(a2), "v"(a3) : "memory");
+}
+// eight dword reads at eight addresses, one wait
+__device__ __forceinline__ void lds_read4x8(const uint32_t (&a)[8], uint32_t off, uint32_t (&r)[8])
+{
+    asm volatile("ds_read_b32 %0, %8\n\tds_read_b32 %1, %9\n\tds_read_b32 %2, %10\n\tds_read_b32 %3, %11\n\t"
+                 "ds_read_b32 %4, %12\n\tds_read_b32 %5, %13\n\tds_read_b32 %6, %14\n\tds_read_b32 %7, %15\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3]), "=&v"(r[4]), "=&v"(r[5]), "=&v"(r[6]), "=&v"(r[7])
+                 : "v"(a[0] + off), "v"(a[1] + off), "v"(a[2] + off), "v"(a[3] + off),
+                   "v"(a[4] + off), "v"(a[5] + off), "v"(a[6] + off), "v"(a[7] + off)
+                 : "memory");
+}
+
+template <int NGRP>
+__device__ __forceinline__ uint32_t meta_of(const uint4 (&m)[NGRP], int r, int grp)
+{
+    const int idx = r * NGRP + grp;
+    const uint4 u = m[idx / 4];
+    const int c = idx % 4;
+    return c == 0 ? u.x : c == 1 ? u.y : c == 2 ? u.z : u.w;
+}
+
+__device__ __forceinline__ h8_t pack8(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
+{
+    typedef uint32_t u4_t __attribute__((ext_vector_type(4)));
+    const u4_t u = {a, b, c, d};
+    return __builtin_bit_cast(h8_t, u);
+}
+
+}  // namespace
+}  // namespace alise

@@ -1,0 +1,409 @@
+// Chunked-prefill attention over the quantized, paged cache on the gfx950 matrix cores.
+//
+// The prompt's tokens are processed in one pass (ALISE Sec. 2 "LLM Inference"); with the cache
+// of Sec. 3.2 that means: the chunk's K/V are quantized and written first, then every query
+// token of the chunk attends causally (Eq. 1-2) over the cached codes -- positions 0 .. its own.
+// Query token j of an n-token chunk of a request with L cached tokens sits at position L - n + j.
+//
+// Work decomposition.  Rows of the problem are (query token, query head) pairs; the rows that
+// share a KV head share every KV byte.  A workgroup of four waves takes 64 such rows of one
+// request and one KV head (16 per wave: 16 / qper tokens x qper heads) and walks the cache once
+// from position 0 to the last position any of its rows may see.  The four waves share the
+// cache through LDS: per step of 32 tokens each wave fetches a quarter of the step (K or V
+// codes of one 16-token tile plus its scales and zero-points) with direct global -> LDS
+// loads, three stages deep, one workgroup barrier per step.  Per wave the step is the one of
+// the grouped-query decode kernel: S^T = K Q^T and O += P V on v_mfma_f32_16x16x32_f16, K
+// codes as fp16 1024 + code, V codes as fp16 subnormals, P * lambda_v split in high and low
+// fp16 parts, online softmax with a lazily raised maximum -- except that the mask is per
+// row (token <= the row's position) and that a wave skips the steps none of its rows can see.
+// There is no split along the context and therefore nothing to merge: a chunk of a few
+// hundred tokens gives thousands of workgroups.
+//
+// The block-table entries of the 64 pages around the current position sit in a register (one
+// entry per lane), refilled every 64 pages from a window fetched ahead of time into LDS.
+#include "mfma_stream.h"
+
+namespace alise {
+namespace {
+
+struct PrefillParams {
+    CacheView c;
+    const _Float16 *q;
+    _Float16 *out;
+    const int32_t *q_start;
+    const int32_t *block_tables;
+    const int32_t *context_lens;
+    int32_t max_blocks, B, H, qper, max_len;
+    float scale_log2e;
+    PrefillWorkspace ws;
+};
+
+// One workgroup: tiles per request, their prefix sums, and the table of (request, row tile)
+// pairs, a request's later tiles first (they see more of the context and take longer, and
+// the hardware hands out workgroups in table order).
+__global__ __launch_bounds__(1024) void prefill_plan_kernel(const int32_t *q_start, const int32_t *context_lens,
+                                                            int32_t B, int32_t tokens_per_wg, PrefillWorkspace ws)
+{
+    __shared__ int32_t s_wave[16];
+    __shared__ int32_t s_total;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) s_total = 0;
+    __syncthreads();
+    for (int base = 0; base < B; base += 1024) {
+        const int i = base + tid;
+        int n = 0;
+        if (i < B) {
+            n = q_start[i + 1] - q_start[i];
+            const int L = context_lens[i];
+            n = n < 0 ? 0 : (n > L ? (L > 0 ? L : 0) : n);      // a chunk cannot be longer than its request
+        }
+        const int tiles = (n + tokens_per_wg - 1) / tokens_per_wg;
+        int incl = tiles;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int u = __shfl_up(incl, d);
+            if (lane >= d) incl += u;
+        }
+        if (lane == 63) s_wave[wave] = incl;
+        __syncthreads();
+        int before = s_total;
+        for (int k = 0; k < wave; ++k) before += s_wave[k];
+        const int first = before + incl - tiles;
+        for (int t = 0; t < tiles; ++t)
+            if (first + t < ws.max_tiles) ws.table[first + t] = make_int2(i, tiles - 1 - t);
+        __syncthreads();
+        if (tid == 1023) s_total = before + incl;
+        __syncthreads();
+    }
+    if (tid == 0) *ws.n_tiles = s_total < ws.max_tiles ? s_total : ws.max_tiles;
+}
+
+template <int NGRP>
+__global__ __launch_bounds__(256) void prefill_attn_kernel(PrefillParams p)
+{
+    constexpr int D = 128, ROWB = 128, S = 3;
+    constexpr int TILEB = 4352;                 // one 16-token tile in LDS: K 2 KiB | V 2 KiB | K meta 128 B | V meta 128 B
+    constexpr int T_V = 2048, T_KM = 4096, T_VM = 4224;
+    constexpr int STEPB = 2 * TILEB;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[S * STEPB + 4 * 512];     // stages, then two page-window slots per wave
+
+    const int f = blockIdx.x;
+    if (f >= *p.ws.n_tiles) return;             // workgroup-uniform, before any barrier
+    const int2 entry = p.ws.table[f];
+    const int i = min(max(entry.x, 0), p.B - 1), rt = max(entry.y, 0);
+    const int hk = blockIdx.y;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n = lane & 15;        // column of the matrix layouts: token (K), row of the problem (S^T), channel (V, O)
+    const int g = lane >> 4;        // quarter of the wave: 8 consecutive k-slots, 4 consecutive rows
+    const int logP = p.c.logP, P = p.c.P, Hkv = p.c.Hkv, qper = p.qper, H = p.H;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)lds;
+    lptr_t const ldsp = (lptr_t)lds;
+
+    // ---- the request's chunk and this wave's rows
+    const int L = min(max(p.context_lens[i], 0), p.max_len);
+    const int qs = p.q_start[i];
+    int n_q = p.q_start[i + 1] - qs;
+    n_q = min(max(n_q, 0), L);
+    const int TT = 16 / qper;                   // query tokens per wave
+    const int first_pos = L - n_q;              // position of the chunk's first token
+    const int j0 = (rt * 4 + wave) * TT;        // this wave's first query token
+    const int j_n = j0 + n / qper, e_n = n % qper;
+    const bool row_valid = n < TT * qper && j_n < n_q;
+    const int pos_n = row_valid ? first_pos + j_n : -1;             // what row n may see: tokens <= pos_n
+    const int wave_last = first_pos + min(j0 + TT, n_q) - 1;         // last position any row of this wave sees (< first_pos + j0: none)
+    const bool wave_has_rows = j0 < n_q;
+    const int kv_end = first_pos + min((rt + 1) * 4 * TT, n_q);     // the workgroup walks positions [0, kv_end)
+    const int nsteps = (kv_end + kStep - 1) / kStep;
+    if (n_q <= 0 || nsteps <= 0) return;        // workgroup-uniform
+
+    // ---- per-lane constants of the LDS layout (see the decode kernel): a 1 KiB load covers 8
+    // token rows; row r keeps its 16-byte piece c at position c ^ r.
+    const int src_lane = (lane >> 3) * ROWB + (((lane & 7) ^ (lane >> 3)) * 16);
+    const uint32_t k_rd0 = (n >> 3) * 1024 + ((n & 7) * 8 + (g ^ (n & 7))) * 16;
+    const uint32_t k_rd1 = (n >> 3) * 1024 + ((n & 7) * 8 + ((4 + g) ^ (n & 7))) * 16;
+    uint32_t v_rd[8];               // [set * 4 + r]
+#pragma unroll
+    for (int set = 0; set < 2; ++set)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = 4 * g + r;
+            const int piece = 4 * set + (n >> 2);
+            v_rd[set * 4 + r] = T_V + (row >> 3) * 1024 + ((row & 7) * 8 + (piece ^ (row & 7))) * 16 + (n & 3) * 4;
+        }
+    const uint32_t m_rd = g * 16 * NGRP;
+
+    // ---- Q^T as the B operand of the four k-chunks: chunk jj, slot g*8+e <-> channel (jj/2)*64 + g*16 + (jj%2)*8 + e
+    h8_t qop[4];
+    float qsum[NGRP];
+    {
+        const int jc = min(j_n, n_q - 1);
+        const _Float16 *qrow = p.q + ((int64_t)(qs + jc) * H + hk * qper + e_n) * D;
+        float part_sum[NGRP];
+#pragma unroll
+        for (int gr = 0; gr < NGRP; ++gr) part_sum[gr] = 0.0f;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            h8_t v = *reinterpret_cast<const h8_t *>(qrow + (jj / 2) * 64 + g * 16 + (jj % 2) * 8);
+            if (!row_valid) v = (h8_t)(_Float16)0.0f;
+            qop[jj] = v;
+            float sacc = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sacc += (float)v[e];
+            part_sum[NGRP == 2 ? jj / 2 : 0] += sacc;
+        }
+#pragma unroll
+        for (int gr = 0; gr < NGRP; ++gr) {
+            float v = part_sum[gr];
+            v += __shfl_xor(v, 16);
+            v += __shfl_xor(v, 32);
+            qsum[gr] = v;
+        }
+    }
+
+    // ---- block-table windows: 64 entries, one per lane.  Lookups use window wa in pg_a; the
+    // windows come through LDS by direct loads (two slots per wave), fetched one window ahead,
+    // so that no vector load ever returns into a register inside the loop.
+    const int32_t *bt = p.block_tables + (int64_t)i * p.max_blocks;
+    const int last_page = (kv_end - 1) >> logP;
+    const int pg_slots = S * STEPB + wave * 512;
+    auto fetch_window = [&](int wdw) { dma4(bt + min(wdw * 64 + lane, last_page), ldsp + pg_slots + (wdw & 1) * 256); };
+    auto read_window = [&](int wdw) { return (int)lds_read4(lds0 + pg_slots + (wdw & 1) * 256 + lane * 4); };
+    int wa = 0;
+    fetch_window(0);
+    fetch_window(1);
+    ALISE_VMCNT(0);
+    int pg_a = read_window(0);
+
+    // ---- this wave's quarter of a step: tile x = wave / 2, K (even waves) or V (odd waves)
+    const int my_x = wave >> 1;
+    const bool my_v = wave & 1;
+    auto issue = [&](int k) {
+        int tx = k * kStep + my_x * 16;
+        if (tx >= kv_end) tx -= 16;                             // second tile starts past the end: repeat the first
+        const int pi = tx >> logP;
+        if ((pi >> 6) > wa) {                                   // wave-uniform; once per 64 pages
+            ++wa;
+            pg_a = read_window(wa);                             // fetched a window ago: landed long since (every step waits for all but three loads)
+            fetch_window(wa + 1);                               // into the slot of the window just left
+        }
+        const int page = min(max(__builtin_amdgcn_readlane(pg_a, pi & 63), 0), p.c.num_pages - 1);
+        const int blk = page * Hkv + hk;
+        const int off = tx & (P - 1);
+        const int64_t co = (int64_t)blk * p.c.cstride + (int64_t)off * ROWB;
+        const int64_t mo = (int64_t)blk * p.c.mstride + (int64_t)off * NGRP * 4;
+        lptr_t dst = ldsp + (k % S) * STEPB + my_x * TILEB;
+        const uint8_t *cb = (my_v ? p.c.v_codes : p.c.k_codes) + co + src_lane;
+        const uint8_t *mb = reinterpret_cast<const uint8_t *>(my_v ? p.c.v_meta : p.c.k_meta) + mo + lane * 4;
+        // the rows of a head are read again by the workgroups of its other row tiles: keep them in the L2
+        dma16(cb, dst + (my_v ? T_V : 0));
+        dma16(cb + 1024, dst + (my_v ? T_V : 0) + 1024);
+        if (lane < 16 * NGRP) dma4(mb, dst + (my_v ? T_VM : T_KM));
+    };
+
+    float m_ref = kFloor, l_part = 0.0f, z_part[NGRP];
+#pragma unroll
+    for (int gr = 0; gr < NGRP; ++gr) z_part[gr] = 0.0f;
+    f4_t o[8];                  // [set*4 + nu]: rows 4g..4g+3, column n <-> channel 64*set + 4n + nu
+#pragma unroll
+    for (int t = 0; t < 8; ++t) o[t] = (f4_t)0.0f;
+
+    issue(0);
+    if (nsteps > 1) issue(1);
+    for (int k = 0; k < nsteps; ++k) {
+        // this wave's quarter of step k has landed once at most the three loads of the step after it are in flight
+        if (k + 1 < nsteps) ALISE_VMCNT(3); else ALISE_VMCNT(0);
+        // all four quarters have landed, and every wave is done reading the stage that step k + 2 overwrites
+        asm volatile("s_barrier" ::: "memory");
+        if (k + 2 < nsteps) issue(k + 2);
+        if (!wave_has_rows || k * kStep > wave_last) continue;     // nothing here that a row of this wave may see
+        const uint32_t base = lds0 + (k % S) * STEPB;
+
+        // ---- S^T = K Q^T for the two 16-token tiles
+        float s[2][4];
+        float lamv[2][4][NGRP], zv[2][4][NGRP];
+        float mx = kNegInf;
+        uint4 kp[2][2];
+        lds_read16x4(base + k_rd0, base + k_rd1, base + TILEB + k_rd0, base + TILEB + k_rd1, kp[0][0], kp[0][1], kp[1][0], kp[1][1]);
+        uint4 kmeta[2][NGRP], vmeta[2][NGRP];
+        if constexpr (NGRP == 1) {
+            lds_read16x4(base + T_KM + m_rd, base + T_VM + m_rd, base + TILEB + T_KM + m_rd, base + TILEB + T_VM + m_rd,
+                         kmeta[0][0], vmeta[0][0], kmeta[1][0], vmeta[1][0]);
+        } else {
+            lds_read16x4(base + T_KM + m_rd, base + T_KM + m_rd + 16, base + T_VM + m_rd, base + T_VM + m_rd + 16,
+                         kmeta[0][0], kmeta[0][1], vmeta[0][0], vmeta[0][1]);
+            lds_read16x4(base + TILEB + T_KM + m_rd, base + TILEB + T_KM + m_rd + 16, base + TILEB + T_VM + m_rd,
+                         base + TILEB + T_VM + m_rd + 16, kmeta[1][0], kmeta[1][1], vmeta[1][0], vmeta[1][1]);
+        }
+#pragma unroll
+        for (int x = 0; x < 2; ++x) {
+            f4_t acc[NGRP];
+#pragma unroll
+            for (int gr = 0; gr < NGRP; ++gr) acc[gr] = (f4_t)0.0f;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                const uint4 piece = kp[x][jj / 2];
+                const uint32_t w0 = (jj % 2) ? piece.z : piece.x, w1 = (jj % 2) ? piece.w : piece.y;
+                const h8_t a = pack8(__builtin_amdgcn_perm(0x64646464u, w0, 0x04010400u),
+                                     __builtin_amdgcn_perm(0x64646464u, w0, 0x04030402u),
+                                     __builtin_amdgcn_perm(0x64646464u, w1, 0x04010400u),
+                                     __builtin_amdgcn_perm(0x64646464u, w1, 0x04030402u));
+                f4_t &dst = acc[NGRP == 2 ? jj / 2 : 0];
+                dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, qop[jj], dst, 0, 0, 0);
+            }
+            const int tok0 = k * kStep + x * 16 + g * 4;        // tokens of this lane's 4 rows of S^T
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const bool valid = tok0 + r <= pos_n;           // causal, per row of the problem
+                float sv = 0.0f;
+#pragma unroll
+                for (int gr = 0; gr < NGRP; ++gr) {
+                    const uint32_t km = meta_of<NGRP>(kmeta[x], r, gr);
+                    const uint32_t vm = valid ? meta_of<NGRP>(vmeta[x], r, gr) : 0u;
+                    const float lam = half_lo(km) * p.scale_log2e;
+                    sv += lam * (acc[gr][r] - (1024.0f + half_hi(km)) * qsum[gr]);
+                    lamv[x][r][gr] = half_lo(vm);
+                    zv[x][r][gr] = half_hi(vm);
+                }
+                s[x][r] = valid ? sv : kNegInf;
+                mx = fmaxf(mx, s[x][r]);
+            }
+        }
+
+        // ---- running maximum per row of the problem, raised lazily; all four quarters hold the same value
+        if (__builtin_amdgcn_ballot_w64(mx > m_ref + kLazy) != 0) {
+            float mq = fmaxf(mx, __shfl_xor(mx, 16));
+            mq = fmaxf(mq, __shfl_xor(mq, 32));
+            const float m_new = (mq > m_ref + kLazy) ? mq : m_ref;
+            const float fac = __builtin_amdgcn_exp2f(m_ref - m_new);
+            l_part *= fac;
+#pragma unroll
+            for (int gr = 0; gr < NGRP; ++gr) z_part[gr] *= fac;
+            m_ref = m_new;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float fr = __shfl(fac, 4 * g + r);        // factor of the problem row 4g+r
+#pragma unroll
+                for (int t = 0; t < 8; ++t) o[t][r] *= fr;
+            }
+        }
+
+        // ---- weights p * lambda_v as fp16 high + low parts, in the A-operand order (tile, row)
+        h8_t a_hi[NGRP], a_lo[NGRP];
+#pragma unroll
+        for (int x = 0; x < 2; ++x)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float pj = __builtin_amdgcn_exp2f(s[x][r] - m_ref);
+                l_part += pj;
+#pragma unroll
+                for (int gr = 0; gr < NGRP; ++gr) {
+                    const float wv = pj * lamv[x][r][gr];
+                    z_part[gr] = __builtin_fmaf(wv, zv[x][r][gr], z_part[gr]);
+                    const _Float16 hi = (_Float16)wv;
+                    const _Float16 lo = (_Float16)(wv - (float)hi);
+                    a_hi[gr][x * 4 + r] = hi;
+                    a_lo[gr][x * 4 + r] = lo;
+                }
+            }
+
+        // ---- O += P V: byte nu of the dwords of two tokens -> two fp16 subnormals
+        uint32_t vd[2][8];          // [tile][set * 4 + r]
+        lds_read4x8(v_rd, base, vd[0]);
+        lds_read4x8(v_rd, base + TILEB, vd[1]);
+#pragma unroll
+        for (int set = 0; set < 2; ++set)
+#pragma unroll
+            for (int nu = 0; nu < 4; ++nu) {
+                const uint32_t sel = 0x0c000c00u | ((4u + nu) << 16) | (uint32_t)nu;
+                const h8_t bv = pack8(__builtin_amdgcn_perm(vd[0][set * 4 + 1], vd[0][set * 4 + 0], sel),
+                                      __builtin_amdgcn_perm(vd[0][set * 4 + 3], vd[0][set * 4 + 2], sel),
+                                      __builtin_amdgcn_perm(vd[1][set * 4 + 1], vd[1][set * 4 + 0], sel),
+                                      __builtin_amdgcn_perm(vd[1][set * 4 + 3], vd[1][set * 4 + 2], sel));
+                const int gr = NGRP == 2 ? set : 0;
+                f4_t &dst = o[set * 4 + nu];
+                dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_hi[gr], bv, dst, 0, 0, 0);
+                dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_lo[gr], bv, dst, 0, 0, 0);
+            }
+    }
+
+    // ---- per row of the problem: add the four quarters; then fetch the values of this lane's rows
+    float l = l_part + __shfl_xor(l_part, 16);
+    l += __shfl_xor(l, 32);
+    float zsum[NGRP];
+#pragma unroll
+    for (int gr = 0; gr < NGRP; ++gr) {
+        float v = z_part[gr] + __shfl_xor(z_part[gr], 16);
+        v += __shfl_xor(v, 32);
+        zsum[gr] = v;
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int row = 4 * g + r;
+        const float l_row = __shfl(l, row);
+        float z_row[NGRP];
+#pragma unroll
+        for (int gr = 0; gr < NGRP; ++gr) z_row[gr] = __shfl(zsum[gr], row);
+        const int j_r = j0 + row / qper, e_r = row % qper;
+        if (row < TT * qper && j_r < n_q) {
+            const float inv_l = 1.0f / l_row;
+            _Float16 *dst = p.out + ((int64_t)(qs + j_r) * H + hk * qper + e_r) * D + 4 * n;
+#pragma unroll
+            for (int set = 0; set < 2; ++set) {
+                const float zr = z_row[NGRP == 2 ? set : 0];
+                typedef _Float16 h4_t __attribute__((ext_vector_type(4)));
+                h4_t v;
+#pragma unroll
+                for (int nu = 0; nu < 4; ++nu)
+                    v[nu] = (_Float16)(__builtin_fmaf(o[set * 4 + nu][r], 16777216.0f, -zr) * inv_l);
+                *reinterpret_cast<h4_t *>(dst + 64 * set) = v;
+            }
+        }
+    }
+}
+
+}  // namespace
+
+bool prefill_mfma_applies(const CacheView &c, int32_t H)
+{
+    const int qper = H / c.Hkv;
+    return c.bits == 8 && c.D == 128 && (c.G == 128 || c.G == 64) && c.P >= 16 && qper >= 1 && qper <= 16;
+}
+
+// Query tokens per workgroup (four waves of 16 / qper tokens each).
+int32_t prefill_tokens_per_workgroup(int32_t qper) { return 4 * (16 / qper); }
+
+hipError_t launch_prefill_attn(const CacheView &c, const void *q, void *out, const int32_t *q_start,
+                               const int32_t *block_tables, int32_t max_blocks, const int32_t *context_lens,
+                               int32_t B, int32_t H, int32_t max_context_len, float softmax_scale,
+                               const PrefillWorkspace &ws, hipStream_t s)
+{
+    if (B == 0 || ws.max_tiles == 0) return hipSuccess;
+    PrefillParams p;
+    p.c = c;
+    p.q = static_cast<const _Float16 *>(q);
+    p.out = static_cast<_Float16 *>(out);
+    p.q_start = q_start;
+    p.block_tables = block_tables;
+    p.context_lens = context_lens;
+    p.max_blocks = max_blocks;
+    p.B = B;
+    p.H = H;
+    p.qper = H / c.Hkv;
+    p.max_len = max_context_len;
+    p.scale_log2e = softmax_scale * 1.44269504088896340736f;
+    p.ws = ws;
+    hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(1024), 0, s, q_start, context_lens, B,
+                       prefill_tokens_per_workgroup(p.qper), ws);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const dim3 grid((unsigned)ws.max_tiles, (unsigned)c.Hkv);
+    if (c.D / c.G == 1)
+        hipLaunchKernelGGL(prefill_attn_kernel<1>, grid, dim3(256), 0, s, p);
+    else
+        hipLaunchKernelGGL(prefill_attn_kernel<2>, grid, dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
+}  // namespace alise

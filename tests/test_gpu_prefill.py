@@ -1,0 +1,115 @@
+"""GPU parity of chunked-prefill attention (ALISE Sec. 2 "LLM Inference", Eq. 1-2 in causal
+order, over the quantized cache of Sec. 3.2) against the CPU oracle, through the C ABI.
+The fp16 output must be within 2e-3 max-abs of the fp64 oracle, like the decode step."""
+import numpy as np
+import pytest
+
+from paper_2410_23537_amd import workloads as wl
+from tests import harness
+
+pytestmark = pytest.mark.gpu
+
+ATTN_TOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2410_23537_amd import binding
+    import oracle
+    oracle.build()
+    return binding, torch, oracle
+
+
+def _w(name, **kw):
+    base = dict(B=4, H=8, Hkv=8, D=128, P=16, bits=8, G=64, length_law="fixed:1", seed=4100, max_len=4096)
+    base.update(kw)
+    return wl.Workload(name=name, **base)
+
+
+# (workload, context lengths, chunk lengths): chunks of 0, 1, exactly one wave / one workgroup of
+# rows, ragged ones, whole prompts, a context that crosses several 64-page windows
+CASES = [
+    (_w("mha_g64_p16"), [40, 200, 65, 1, 333, 64], [40, 7, 65, 1, 0, 64]),
+    (_w("mha_g128_p32", G=128, P=32, Hkv=4, H=4), [500, 129, 96], [300, 129, 1]),
+    (_w("mha_long_context", Hkv=2, H=2), [2500, 1100], [70, 33]),
+    (_w("gqa8_g128_p32", G=128, P=32, Hkv=2, H=16), [300, 77, 150], [100, 77, 9]),
+    (_w("gqa2_g64_p16", Hkv=4, H=8), [210, 18], [210, 5]),
+    (_w("gqa16_p64", G=128, P=64, Hkv=1, H=16), [400, 50], [37, 50]),
+    (_w("gqa3_g128_p16", G=128, Hkv=2, H=6), [90, 260], [90, 41]),
+    (_w("gqa4", Hkv=2, H=8), [1, 17, 128], [1, 17, 128]),
+]
+
+
+@pytest.mark.parametrize("layout", ["interleaved", "dense"])
+@pytest.mark.parametrize("case", CASES, ids=lambda c: c[0].name)
+def test_prefill_against_oracle(env, case, layout):
+    B, torch, oracle = env
+    w, lens, chunks = case
+    w = wl.replace(w, B=len(lens))
+    print(f"case prefill {w.name} ({layout}): H={w.H} Hkv={w.Hkv} P={w.P} G={w.G} lens={lens} chunks={chunks}", flush=True)
+    pg = wl.paging(w, np.array(lens, np.int32))
+    pool = wl.value_pool(w, n_min=max(lens) * w.Hkv * w.D)
+    offs, gain = wl.request_offsets(w), wl.k_channel_gain(w)
+    orc = harness.fill_oracle_cache(oracle, w, pg, pool, offs, gain)
+    dev = harness.fill_device_cache(B, torch, w, pg, pool, offs, gain, layout=layout)
+
+    q_start = np.concatenate([[0], np.cumsum(chunks)]).astype(np.int32)
+    total = int(q_start[-1])
+    rng = np.random.default_rng([w.seed, 7, len(lens)])
+    q_np = rng.standard_normal((total, w.H, w.D)).astype(np.float16)
+    scale = 1.0 / np.sqrt(w.D)
+    want = oracle.paged_prefill_attn(orc, q_np, q_start, pg.block_tables, pg.lens, scale)
+
+    q = torch.from_numpy(q_np).cuda()
+    out = torch.full(q.shape, float("nan"), dtype=torch.float16, device="cuda")
+    guard = torch.full((64, w.H, w.D), 7.0, dtype=torch.float16, device="cuda")      # rows nobody owns
+    bt = torch.from_numpy(pg.block_tables).cuda()
+    lens_d = torch.from_numpy(pg.lens.astype(np.int32)).cuda()
+    qs_d = torch.from_numpy(q_start).cuda()
+    max_len = int(max(lens))
+    nbytes = B.alise_paged_prefill_attn_workspace_bytes(dev, len(lens), total, w.H)
+    assert nbytes > 0
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    both = torch.cat([out, guard])              # the guard sits right behind the output
+    B.alise_paged_prefill_attn(dev, q, both[:total], qs_d, bt, lens_d, max_len, scale, ws)
+    torch.cuda.synchronize()
+    got = both[:total].cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all(), "a row was not written"
+    err = np.abs(got - want).max()
+    print(f"  max-abs error {err:.3e}", flush=True)
+    assert err <= ATTN_TOL
+    assert (both[total:] == 7.0).all(), "wrote past the last row"
+
+
+def test_one_token_chunks_equal_the_decode_call(env):
+    B, torch, oracle = env
+    w = wl.replace(wl.scaled(wl.CONFIGS["llama7b"], B=12, max_len=900), name="decode_as_prefill")
+    pg = wl.paging(w)
+    pool = wl.value_pool(w, n_min=int(pg.lens.max()) * w.Hkv * w.D)
+    dev = harness.fill_device_cache(B, torch, w, pg, pool, wl.request_offsets(w), wl.k_channel_gain(w))
+    q_np = wl.queries(w)
+    dec = harness.run_device_attn(B, torch, w, dev, q_np, pg).astype(np.float64)
+    q = torch.from_numpy(q_np).cuda()
+    out = torch.full(q.shape, float("nan"), dtype=torch.float16, device="cuda")
+    qs = torch.arange(w.B + 1, dtype=torch.int32, device="cuda")
+    bt = torch.from_numpy(pg.block_tables).cuda()
+    lens_d = torch.from_numpy(pg.lens.astype(np.int32)).cuda()
+    ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(dev, w.B, w.B, w.H), dtype=torch.uint8, device="cuda")
+    B.alise_paged_prefill_attn(dev, q, out, qs, bt, lens_d, int(pg.lens.max()), 1.0 / np.sqrt(w.D), ws)
+    torch.cuda.synchronize()
+    pre = out.cpu().numpy().astype(np.float64)
+    # two kernels, two summation orders: both within the tolerance of the oracle, hence within twice of each other
+    assert np.abs(pre - dec).max() <= 2 * ATTN_TOL
+
+
+def test_unsupported_shapes_are_refused(env):
+    B, torch, oracle = env
+    c4 = B.KVCache.allocate(4, 16, 2, 128, 4, 32)           # INT4
+    assert B.alise_paged_prefill_attn_workspace_bytes(c4, 1, 8, 2) == 0
+    c64 = B.KVCache.allocate(4, 16, 2, 64, 8, 64)           # head_dim 64
+    assert B.alise_paged_prefill_attn_workspace_bytes(c64, 1, 8, 2) == 0
+    ok = B.KVCache.allocate(4, 16, 2, 128, 8, 64)
+    assert B.alise_paged_prefill_attn_workspace_bytes(ok, 1, 8, 2) > 0
+    assert B.alise_paged_prefill_attn_workspace_bytes(ok, 1, 8, 64) == 0      # 32 query heads per KV head
