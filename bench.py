@@ -149,6 +149,56 @@ def swap_leg(step):
     return out
 
 
+MFMA_F16_PEAK_TFLOPS = 2500.0
+
+
+def prefill_leg(w, step):
+    """Chunked-prefill attention over the same cache (Sec. 2 "LLM Inference"), outside the timed
+    steps: every 8th request brings its last min(512, L) tokens as a chunk of query tokens that
+    attend causally over the request's quantized cache.  Bound: the fp16 matrix cores."""
+    import numpy as np
+    import torch
+    from paper_2410_23537_amd import binding as B
+    cache = step.caches[0]
+    ws_bytes = B.alise_paged_prefill_attn_workspace_bytes(cache, w.B, 1, w.H)
+    if ws_bytes == 0:
+        return None                     # a layout the matrix-core prefill kernel does not take (INT4, head_dim 64)
+    lens = step.lens.astype(np.int64)
+    n = np.array([min(512, int(L)) if i % 8 == 0 else 0 for i, L in enumerate(lens)], np.int64)
+    q_start = np.concatenate([[0], np.cumsum(n)]).astype(np.int32)
+    total = int(q_start[-1])
+    gen = torch.Generator(device="cuda").manual_seed(w.seed)
+    q = torch.randn((total, w.H, w.D), dtype=torch.float16, device="cuda", generator=gen)
+    out = torch.empty_like(q)
+    bt = torch.from_numpy(step.pg.block_tables).cuda()
+    lens_d = torch.from_numpy(step.lens.astype(np.int32)).cuda()
+    qs = torch.from_numpy(q_start).cuda()
+    ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(cache, w.B, total, w.H), dtype=torch.uint8, device="cuda")
+    pairs = sum(int((lens[i] - n[i] + np.arange(n[i]) + 1).sum()) for i in range(w.B) if n[i])
+    flops = 4.0 * w.D * w.H * pairs     # q.k and p.v, a multiply and an add each, per (query, visible key, head)
+
+    def run():
+        B.alise_paged_prefill_attn(cache, q, out, qs, bt, lens_d, int(step.lens.max()), step.scale, ws)
+
+    for _ in range(2):
+        run()
+    torch.cuda.synchronize()
+    reps = 10
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    tflops = flops / (ms * 1e-3) / 1e12
+    return {"workload": f"every 8th request of {w.name} brings its last min(512, L) tokens: {total} query tokens, "
+                        f"{pairs} (query, visible key) pairs per head",
+            "ms": ms, "flop": flops,
+            "roofline": {"bound": "mfma", "achieved": tflops, "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": tflops / MFMA_F16_PEAK_TFLOPS, "traffic": None}}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -229,6 +279,9 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(w.name)},
     }
     result["swap"] = swap_leg(step)
+    prefill = prefill_leg(w, step)
+    if prefill is not None:
+        result["prefill"] = prefill
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, step, args.cpu_seconds)
     print(json.dumps(result), flush=True)

@@ -79,7 +79,7 @@ __global__ __launch_bounds__(1024) void prefill_plan_kernel(const int32_t *q_sta
 }
 
 template <int NGRP>
-__global__ __launch_bounds__(256) void prefill_attn_kernel(PrefillParams p)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void prefill_attn_kernel(PrefillParams p)
 {
     constexpr int D = 128, ROWB = 128, S = 3;
     constexpr int TILEB = 4352;                 // one 16-token tile in LDS: K 2 KiB | V 2 KiB | K meta 128 B | V meta 128 B
@@ -161,6 +161,12 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(PrefillParams p)
             qsum[gr] = v;
         }
     }
+    float qs_s[NGRP], q1024_s[NGRP];        // scale * sum(q) and 1024 times that
+#pragma unroll
+    for (int gr = 0; gr < NGRP; ++gr) {
+        qs_s[gr] = qsum[gr] * p.scale_log2e;
+        q1024_s[gr] = 1024.0f * qs_s[gr];
+    }
 
     // ---- block-table windows: 64 entries, one per lane.  Lookups use window wa in pg_a; the
     // windows come through LDS by direct loads (two slots per wave), fetched one window ahead,
@@ -222,7 +228,7 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(PrefillParams p)
 
         // ---- S^T = K Q^T for the two 16-token tiles
         float s[2][4];
-        float lamv[2][4][NGRP], zv[2][4][NGRP];
+        uint32_t vmraw[2][4][NGRP];        // V (scale, zero) dwords of this lane's tokens; 0 where the token is masked
         float mx = kNegInf;
         uint4 kp[2][2];
         lds_read16x4(base + k_rd0, base + k_rd1, base + TILEB + k_rd0, base + TILEB + k_rd1, kp[0][0], kp[0][1], kp[1][0], kp[1][1]);
@@ -261,10 +267,11 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(PrefillParams p)
                 for (int gr = 0; gr < NGRP; ++gr) {
                     const uint32_t km = meta_of<NGRP>(kmeta[x], r, gr);
                     const uint32_t vm = valid ? meta_of<NGRP>(vmeta[x], r, gr) : 0u;
-                    const float lam = half_lo(km) * p.scale_log2e;
-                    sv += lam * (acc[gr][r] - (1024.0f + half_hi(km)) * qsum[gr]);
-                    lamv[x][r][gr] = half_lo(vm);
-                    zv[x][r][gr] = half_hi(vm);
+                    // scale * lambda_k * (acc - (1024 + z_k) * sum(q)), the fp16 halves of the meta dword read in place
+                    const h2_t kmh = as_h2(km);
+                    const float off = __builtin_fmaf((float)kmh.y, qs_s[gr], q1024_s[gr]);
+                    sv = __builtin_fmaf((float)kmh.x, __builtin_fmaf(acc[gr][r], p.scale_log2e, -off), sv);
+                    vmraw[x][r][gr] = vm;
                 }
                 s[x][r] = valid ? sv : kNegInf;
                 mx = fmaxf(mx, s[x][r]);
@@ -299,8 +306,9 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(PrefillParams p)
                 l_part += pj;
 #pragma unroll
                 for (int gr = 0; gr < NGRP; ++gr) {
-                    const float wv = pj * lamv[x][r][gr];
-                    z_part[gr] = __builtin_fmaf(wv, zv[x][r][gr], z_part[gr]);
+                    const h2_t vmh = as_h2(vmraw[x][r][gr]);
+                    const float wv = pj * (float)vmh.x;
+                    z_part[gr] = __builtin_fmaf((float)vmh.y, wv, z_part[gr]);
                     const _Float16 hi = (_Float16)wv;
                     const _Float16 lo = (_Float16)(wv - (float)hi);
                     a_hi[gr][x * 4 + r] = hi;
