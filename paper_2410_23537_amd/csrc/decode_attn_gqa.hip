@@ -19,8 +19,11 @@
 // address unit busy over 70 % of the time and capped the kernel near 4.2 TB/s.)  The 16-byte
 // pieces of a row are stored XOR-swizzled by the row number, which is free on the way in
 // (a lane chooses which piece it fetches) and makes the operand reads conflict-free:
-//   K: a lane reads 2 x 16 bytes of one token's row; 0x6400 | code is the fp16 1024 + code;
-//      the 1024 * sum(q) offset leaves with the zero-point, per group of the row.
+//   K: a lane reads 2 x 16 bytes of one token's row; a byte permute widens each code to the
+//      fp16 subnormal code * 2^-24, which the matrix cores multiply exactly.  (The 1024 + code
+//      form of the vector kernel would put a 1024 * sum(q) offset into the accumulator, and
+//      its rounding -- harmless for small scales -- shows in the scores when outlier channels
+//      make lambda_k large.)
 //   V: the product contracts over tokens, but a row holds channels.  A lane reads one dword
 //      (4 channels) from each of its 8 tokens and a byte permute picks the same channel out
 //      of two dwords, leaving the fp16 subnormals code * 2^-24 of two tokens side by side --
@@ -261,15 +264,16 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
                 qs[gr] = v;
             }
         }
-        float qs_s[NGRP], q1024_s[NGRP];        // scale * sum(q) and 1024 times that
+        float qs_s[NGRP];                       // scale * sum(q)
+        const float scale24 = p.scale_log2e * 16777216.0f;   // the scale, and the 2^24 that the subnormal K codes lack
 #pragma unroll
         for (int gr = 0; gr < NGRP; ++gr) {
             qs_s[gr] = qs[gr] * p.scale_log2e;
-            q1024_s[gr] = 1024.0f * qs_s[gr];
         }
         ++c_entered;
 
         float m_ref = kFloor, l_part = 0.0f, z_part[NGRP];
+        float bias = kWeightBias;           // see kWeightBias; wave-uniform
 #pragma unroll
         for (int gr = 0; gr < NGRP; ++gr) z_part[gr] = 0.0f;
         f4_t o[8];                  // [set*4 + nu]: rows = query heads 4g..4g+3, column n <-> channel 64*set + 4n + nu
@@ -307,10 +311,10 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
                 for (int j = 0; j < 4; ++j) {
                     const uint4 piece = kp[x][j / 2];
                     const uint32_t w0 = (j % 2) ? piece.z : piece.x, w1 = (j % 2) ? piece.w : piece.y;
-                    const h8_t a = pack8(__builtin_amdgcn_perm(0x64646464u, w0, 0x04010400u),
-                                         __builtin_amdgcn_perm(0x64646464u, w0, 0x04030402u),
-                                         __builtin_amdgcn_perm(0x64646464u, w1, 0x04010400u),
-                                         __builtin_amdgcn_perm(0x64646464u, w1, 0x04030402u));
+                    const h8_t a = pack8(__builtin_amdgcn_perm(0u, w0, 0x0c010c00u),
+                                         __builtin_amdgcn_perm(0u, w0, 0x0c030c02u),
+                                         __builtin_amdgcn_perm(0u, w1, 0x0c010c00u),
+                                         __builtin_amdgcn_perm(0u, w1, 0x0c030c02u));
                     f4_t &dst = acc[NGRP == 2 ? j / 2 : 0];
                     dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, qop[j], dst, 0, 0, 0);
                 }
@@ -323,10 +327,10 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
                     for (int gr = 0; gr < NGRP; ++gr) {
                         const uint32_t km = meta_of<NGRP>(kmeta[x], r, gr);
                         const uint32_t vm = valid ? meta_of<NGRP>(vmeta[x], r, gr) : 0u;
-                        // scale * lambda_k * (acc - (1024 + z_k) * sum(q)), the fp16 halves of the meta dword read in place
+                        // scale * lambda_k * (2^24 acc - z_k * sum(q)), the fp16 halves of the meta dword read in place
                         const h2_t kmh = as_h2(km);
-                        const float off = __builtin_fmaf((float)kmh.y, qs_s[gr], q1024_s[gr]);
-                        sv = __builtin_fmaf((float)kmh.x, __builtin_fmaf(acc[gr][r], p.scale_log2e, -off), sv);
+                        const float off = (float)kmh.y * qs_s[gr];
+                        sv = __builtin_fmaf((float)kmh.x, __builtin_fmaf(acc[gr][r], scale24, -off), sv);
                         vmraw[x][r][gr] = vm;
                     }
                     s[x][r] = valid ? sv : kNegInf;
@@ -352,13 +356,25 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
                 }
             }
 
+            // ---- a V scale of 2 or more in this step: the biased weights could leave the fp16 range (rare, wave-uniform)
+            if (bias != 0.0f && __builtin_amdgcn_ballot_w64(max_low_half<8 * NGRP>(&vmraw[0][0][0]) >= 0x4000u) != 0) {
+                const float fb = __builtin_amdgcn_exp2f(-bias);
+                l_part *= fb;
+#pragma unroll
+                for (int gr = 0; gr < NGRP; ++gr) z_part[gr] *= fb;
+#pragma unroll
+                for (int t = 0; t < 8; ++t) o[t] *= fb;
+                bias = 0.0f;
+            }
+            const float m_use = m_ref - bias;
+
             // ---- weights p * lambda_v as fp16 high + low parts, in the A-operand order (tile, row)
             h8_t a_hi[NGRP], a_lo[NGRP];
 #pragma unroll
             for (int x = 0; x < 2; ++x)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const float pj = __builtin_amdgcn_exp2f(s[x][r] - m_ref);
+                    const float pj = __builtin_amdgcn_exp2f(s[x][r] - m_use);
                     l_part += pj;
 #pragma unroll
                     for (int gr = 0; gr < NGRP; ++gr) {
@@ -407,7 +423,7 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
         for (int r = 0; r < 4; ++r) {
             const int row = 4 * g + r;                      // query head of the group
             const float l_row = __shfl(l, row);
-            const float m_row = __shfl(m_ref, row);
+            const float m_row = __shfl(m_ref - bias, row);       // the reference the denominator and the sums are relative to
             float z_row[NGRP];
 #pragma unroll
             for (int gr = 0; gr < NGRP; ++gr) z_row[gr] = __shfl(zsum[gr], row);

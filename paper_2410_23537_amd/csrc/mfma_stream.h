@@ -76,6 +76,29 @@ __device__ __forceinline__ void lds_read4x8(const uint32_t (&a)[8], uint32_t off
                  : "memory");
 }
 
+// The weights p * lambda_v enter the second product as fp16 (high + low part).  With the
+// running maximum as the reference, p <= 2^kLazy and the largest weight of a row may be as
+// small as lambda_v itself, so that weights a million times smaller already fall under the
+// fp16 subnormal spacing of 2^-24 -- and thousands of such tokens add up to 1e-3 of the
+// result on peaked rows.  The reference is therefore lowered by kWeightBias: every weight,
+// the denominator and the weighted zero-points carry the same extra factor 2^kWeightBias,
+// which cancels in the quotient and moves the floor 64 times further down.  Weights then
+// reach 2^(kLazy + kWeightBias) * lambda_v, inside the fp16 range while lambda_v < 2; a step
+// that holds a larger V scale drops the bias for the rest of the item (rescaling what has
+// been accumulated), after which the range suffices up to lambda_v = 256.
+constexpr float kWeightBias = 6.0f;
+
+// Largest fp16 bit pattern in the low halves of `n` dwords (positive fp16: integer order is value order).
+template <int N>
+__device__ __forceinline__ uint32_t max_low_half(const uint32_t *v)
+{
+    typedef uint16_t u16x2_t __attribute__((ext_vector_type(2)));
+    u16x2_t m = {0, 0};
+#pragma unroll
+    for (int k = 0; k < N; ++k) m = __builtin_elementwise_max(m, __builtin_bit_cast(u16x2_t, v[k]));
+    return m.x;
+}
+
 template <int NGRP>
 __device__ __forceinline__ uint32_t meta_of(const uint4 (&m)[NGRP], int r, int grp)
 {

@@ -13,7 +13,7 @@
 // codes of one 16-token tile plus its scales and zero-points) with direct global -> LDS
 // loads, three stages deep, one workgroup barrier per step.  Per wave the step is the one of
 // the grouped-query decode kernel: S^T = K Q^T and O += P V on v_mfma_f32_16x16x32_f16, K
-// codes as fp16 1024 + code, V codes as fp16 subnormals, P * lambda_v split in high and low
+// and V codes as fp16 subnormals code * 2^-24, P * lambda_v split in high and low
 // fp16 parts, online softmax with a lazily raised maximum -- except that the mask is per
 // row (token <= the row's position) and that a wave skips the steps none of its rows can see.
 // There is no split along the context and therefore nothing to merge: a chunk of a few
@@ -161,11 +161,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
             qsum[gr] = v;
         }
     }
-    float qs_s[NGRP], q1024_s[NGRP];        // scale * sum(q) and 1024 times that
+    float qs_s[NGRP];                       // scale * sum(q)
+    const float scale24 = p.scale_log2e * 16777216.0f;   // the scale, and the 2^24 that the subnormal K codes lack
 #pragma unroll
     for (int gr = 0; gr < NGRP; ++gr) {
         qs_s[gr] = qsum[gr] * p.scale_log2e;
-        q1024_s[gr] = 1024.0f * qs_s[gr];
     }
 
     // ---- block-table windows: 64 entries, one per lane.  Lookups use window wa in pg_a; the
@@ -209,6 +209,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     };
 
     float m_ref = kFloor, l_part = 0.0f, z_part[NGRP];
+    float bias = kWeightBias;           // see kWeightBias; wave-uniform
 #pragma unroll
     for (int gr = 0; gr < NGRP; ++gr) z_part[gr] = 0.0f;
     f4_t o[8];                  // [set*4 + nu]: rows 4g..4g+3, column n <-> channel 64*set + 4n + nu
@@ -251,10 +252,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
             for (int jj = 0; jj < 4; ++jj) {
                 const uint4 piece = kp[x][jj / 2];
                 const uint32_t w0 = (jj % 2) ? piece.z : piece.x, w1 = (jj % 2) ? piece.w : piece.y;
-                const h8_t a = pack8(__builtin_amdgcn_perm(0x64646464u, w0, 0x04010400u),
-                                     __builtin_amdgcn_perm(0x64646464u, w0, 0x04030402u),
-                                     __builtin_amdgcn_perm(0x64646464u, w1, 0x04010400u),
-                                     __builtin_amdgcn_perm(0x64646464u, w1, 0x04030402u));
+                const h8_t a = pack8(__builtin_amdgcn_perm(0u, w0, 0x0c010c00u),
+                                     __builtin_amdgcn_perm(0u, w0, 0x0c030c02u),
+                                     __builtin_amdgcn_perm(0u, w1, 0x0c010c00u),
+                                     __builtin_amdgcn_perm(0u, w1, 0x0c030c02u));
                 f4_t &dst = acc[NGRP == 2 ? jj / 2 : 0];
                 dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, qop[jj], dst, 0, 0, 0);
             }
@@ -267,10 +268,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
                 for (int gr = 0; gr < NGRP; ++gr) {
                     const uint32_t km = meta_of<NGRP>(kmeta[x], r, gr);
                     const uint32_t vm = valid ? meta_of<NGRP>(vmeta[x], r, gr) : 0u;
-                    // scale * lambda_k * (acc - (1024 + z_k) * sum(q)), the fp16 halves of the meta dword read in place
+                    // scale * lambda_k * (2^24 acc - z_k * sum(q)), the fp16 halves of the meta dword read in place
                     const h2_t kmh = as_h2(km);
-                    const float off = __builtin_fmaf((float)kmh.y, qs_s[gr], q1024_s[gr]);
-                    sv = __builtin_fmaf((float)kmh.x, __builtin_fmaf(acc[gr][r], p.scale_log2e, -off), sv);
+                    const float off = (float)kmh.y * qs_s[gr];
+                    sv = __builtin_fmaf((float)kmh.x, __builtin_fmaf(acc[gr][r], scale24, -off), sv);
                     vmraw[x][r][gr] = vm;
                 }
                 s[x][r] = valid ? sv : kNegInf;
@@ -296,13 +297,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
             }
         }
 
+        // ---- a V scale of 2 or more in this step: the biased weights could leave the fp16 range (rare, wave-uniform)
+        if (bias != 0.0f && __builtin_amdgcn_ballot_w64(max_low_half<8 * NGRP>(&vmraw[0][0][0]) >= 0x4000u) != 0) {
+            const float fb = __builtin_amdgcn_exp2f(-bias);
+            l_part *= fb;
+#pragma unroll
+            for (int gr = 0; gr < NGRP; ++gr) z_part[gr] *= fb;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) o[t] *= fb;
+            bias = 0.0f;
+        }
+        const float m_use = m_ref - bias;
+
         // ---- weights p * lambda_v as fp16 high + low parts, in the A-operand order (tile, row)
         h8_t a_hi[NGRP], a_lo[NGRP];
 #pragma unroll
         for (int x = 0; x < 2; ++x)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const float pj = __builtin_amdgcn_exp2f(s[x][r] - m_ref);
+                const float pj = __builtin_amdgcn_exp2f(s[x][r] - m_use);
                 l_part += pj;
 #pragma unroll
                 for (int gr = 0; gr < NGRP; ++gr) {

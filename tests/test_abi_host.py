@@ -160,3 +160,37 @@ def test_swap_arguments(B):
         assert f(ctypes.byref(c), 0x10000, 17, 0x20008, need, None) == 4
         assert f(ctypes.byref(c), 0x10002, 17, 0x20000, need, None) == 4
         assert f(ctypes.byref(_cache(B, head_dim=96)), 0x10000, 17, 0x20000, need, None) == 2
+
+
+def test_prefill_arguments(B):
+    lib = B.raw()
+    c = _cache(B)                                   # INT8, D=128, G=64, pages of 16: a shape the prefill kernel takes
+    f = lib.alise_paged_prefill_attn
+    ok = [ctypes.byref(c), 0x10000, 0x20000, 0x60000, 0x30000, 16, 0x40000, 2, 300, 8, 256, 0.1, 0x50000, 1 << 30, None]
+
+    def call(**kw):
+        names = ["c", "q", "out", "qs", "bt", "mb", "lens", "B", "tq", "H", "maxlen", "scale", "ws", "wsb", "stream"]
+        a = list(ok)
+        for k, v in kw.items():
+            a[names.index(k)] = v
+        return f(*a)
+
+    need = lib.alise_paged_prefill_attn_workspace_bytes(ctypes.byref(c), 2, 300, 8)
+    assert need > 0 and need % 256 == 0
+    assert call(B=0) == 0 and call(tq=0) == 0       # nothing to do, nothing launched
+    assert call(B=-1) == 1 and call(tq=-1) == 1 and call(H=0) == 1 and call(maxlen=-1) == 1
+    assert call(H=12) == 2                          # not a multiple of the 8 KV heads
+    assert call(H=8 * 32) == 2                      # more than 16 query heads per KV head
+    assert call(mb=0) == 1 and call(mb=15) == 1     # 15 pages of 16 cannot hold 256 tokens
+    assert call(scale=0.0) == 1 and call(scale=float("nan")) == 1
+    for name in ("q", "out", "qs", "bt", "lens", "ws"):
+        assert call(**{name: 0}) == 1
+    assert call(q=0x10008) == 4 and call(out=0x20004) == 4
+    assert call(qs=0x60002) == 4 and call(bt=0x30002) == 4 and call(lens=0x40001) == 4
+    assert call(ws=0x50010) == 4
+    assert call(wsb=need - 1) == 3
+    # layouts the matrix-core kernel does not take
+    for kw in (dict(bits=4, group_size=32), dict(head_dim=64), dict(group_size=32), dict(page_size=8)):
+        bad = _cache(B, **kw)
+        assert lib.alise_paged_prefill_attn_workspace_bytes(ctypes.byref(bad), 2, 300, 8) == 0
+        assert call(c=ctypes.byref(bad)) == 2

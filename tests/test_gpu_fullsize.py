@@ -85,3 +85,50 @@ def test_full_size_step_sampled_against_oracle(env, name):
     ko, vo = oracle.kv_dequant_page(mini, 0)
     assert np.array_equal(st.dq_k.cpu().numpy().view(np.uint16)[:n0], ko.view(np.uint16)[:n0])
     assert np.array_equal(st.dq_v.cpu().numpy().view(np.uint16)[:n0], vo.view(np.uint16)[:n0])
+
+
+@pytest.mark.parametrize("name", ["llama7b", "gqa70b"])
+def test_full_size_prefill_sampled_against_oracle(env, name):
+    """The prefill leg of bench.py (every 8th request brings its last min(512, L) tokens) on the
+    full cache; sampled query tokens are recomputed by the oracle from the same seeded inputs."""
+    B, torch, oracle, DecodeStep = env
+    w = wl.CONFIGS[name]
+    st = DecodeStep(w)
+    st.populate(include_step_tokens=True)
+    cache = st.caches[0]
+    lens = st.lens.astype(np.int64)
+    n = np.array([min(512, int(L)) if i % 8 == 0 else 0 for i, L in enumerate(lens)], np.int64)
+    q_start = np.concatenate([[0], np.cumsum(n)]).astype(np.int32)
+    total = int(q_start[-1])
+    print(f"case full-size prefill {name}: {total} query tokens of {int((n > 0).sum())} requests", flush=True)
+    rng = np.random.default_rng(w.seed + 5)
+    q_np = rng.standard_normal((total, w.H, w.D)).astype(np.float16)
+    q = torch.from_numpy(q_np).cuda()
+    out = torch.full(q.shape, float("nan"), dtype=torch.float16, device="cuda")
+    bt = torch.from_numpy(st.pg.block_tables).cuda()
+    lens_d = torch.from_numpy(st.lens.astype(np.int32)).cuda()
+    qs = torch.from_numpy(q_start).cuda()
+    ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(cache, w.B, total, w.H), dtype=torch.uint8, device="cuda")
+    B.alise_paged_prefill_attn(cache, q, out, qs, bt, lens_d, int(st.lens.max()), st.scale, ws)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+
+    worst = 0.0
+    chunked = [i for i in range(w.B) if n[i] > 0]
+    for i in (chunked[0], chunked[len(chunked) // 2], chunked[-1], chunked[int(np.argmax(lens[chunked]))]):
+        L, ni = int(lens[i]), int(n[i])
+        k, v = wl.request_kv(w, st.pool_host, st.offs, i, 0, L, st.gain)
+        nblk = (L + w.P - 1) // w.P
+        mini = oracle.Cache.empty(nblk, w.P, w.Hkv, w.D, w.bits, w.G)
+        oracle.kv_quant_write(mini, k, v, np.arange(L, dtype=np.int64))
+        rows = sorted({0, ni - 1, ni // 2} | {int(r) for r in rng.integers(0, ni, 3)})
+        for j in rows:
+            # a one-token "chunk" at position L - ni + j: the request cut to that length
+            Lj = L - ni + j + 1
+            want = oracle.paged_prefill_attn(mini, q_np[q_start[i] + j][None], np.array([0, 1], np.int32),
+                                             np.arange(nblk, dtype=np.int32)[None], np.array([Lj], np.int32), st.scale)[0]
+            err = np.abs(got[q_start[i] + j] - want).max()
+            worst = max(worst, err)
+            assert err <= ATTN_TOL, f"request {i} (L={L}) query {j}: max-abs {err}"
+    print(f"  worst sampled prefill error {worst:.3e}", flush=True)

@@ -113,3 +113,51 @@ def test_unsupported_shapes_are_refused(env):
     ok = B.KVCache.allocate(4, 16, 2, 128, 8, 64)
     assert B.alise_paged_prefill_attn_workspace_bytes(ok, 1, 8, 2) > 0
     assert B.alise_paged_prefill_attn_workspace_bytes(ok, 1, 8, 64) == 0      # 32 query heads per KV head
+
+
+@pytest.mark.parametrize("vgain", [1.0, 150.0, 20000.0])
+def test_large_value_scales_decode_and_prefill(env, vgain):
+    """V groups whose scale reaches 2 and more: the matrix-core kernels lower their weight bias for
+    such steps (and only then).  The outputs are vgain times larger, so the bar is relative:
+    the tolerance of the other tests scaled by the largest output magnitude."""
+    B, torch, oracle = env
+    Hkv, H, D, P, G = 2, 16, 128, 32, 128            # 8 query heads per KV head: matrix-core decode path too
+    L, n_q = 700, 90
+    rng = np.random.default_rng(99)
+    k = rng.standard_normal((L, Hkv, D)).astype(np.float16)
+    v = (rng.standard_normal((L, Hkv, D)) * vgain / 4.0).astype(np.float16)
+    v[L // 2:] = (v[L // 2:].astype(np.float32) / vgain * 4.0).astype(np.float16)      # large scales first, ordinary ones after
+    nblk = (L + P - 1) // P
+    slots = np.arange(L, dtype=np.int64)
+    orc = oracle.Cache.empty(nblk, P, Hkv, D, 8, G)
+    oracle.kv_quant_write(orc, k, v, slots)
+    dev = B.KVCache.allocate(nblk, P, Hkv, D, 8, G, fill=0)
+    B.alise_kv_quant_write(dev, torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda(), torch.from_numpy(slots).cuda())
+    scale = 1.0 / np.sqrt(D)
+    bt_np = np.arange(nblk, dtype=np.int32)[None]
+    bt = torch.from_numpy(bt_np).cuda()
+    lens_np = np.array([L], np.int32)
+    lens_d = torch.from_numpy(lens_np).cuda()
+
+    q_np = rng.standard_normal((n_q, H, D)).astype(np.float16)
+    q = torch.from_numpy(q_np).cuda()
+    out = torch.full(q.shape, float("nan"), dtype=torch.float16, device="cuda")
+    qs_np = np.array([0, n_q], np.int32)
+    ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(dev, 1, n_q, H), dtype=torch.uint8, device="cuda")
+    B.alise_paged_prefill_attn(dev, q, out, torch.from_numpy(qs_np).cuda(), bt, lens_d, L, scale, ws)
+    want = oracle.paged_prefill_attn(orc, q_np, qs_np, bt_np, lens_np, scale)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    bar = ATTN_TOL * max(1.0, np.abs(want).max() / 2.0)
+    assert np.isfinite(got).all() and np.abs(got - want).max() <= bar, (np.abs(got - want).max(), bar)
+
+    qd_np = q_np[-1:]                                   # decode: the last query token alone, over all L tokens
+    qd = torch.from_numpy(qd_np).cuda()
+    od = torch.full(qd.shape, float("nan"), dtype=torch.float16, device="cuda")
+    wsd = torch.empty(B.alise_paged_decode_attn_workspace_bytes(dev, 1, H, L), dtype=torch.uint8, device="cuda")
+    B.alise_paged_decode_attn(dev, qd, od, bt, lens_d, L, scale, wsd)
+    torch.cuda.synchronize()
+    wd = oracle.paged_decode_attn(orc, qd_np, bt_np, lens_np, scale)
+    gd = od.cpu().numpy().astype(np.float64)
+    bar = ATTN_TOL * max(1.0, np.abs(wd).max() / 2.0)
+    assert np.isfinite(gd).all() and np.abs(gd - wd).max() <= bar, (np.abs(gd - wd).max(), bar)
