@@ -76,6 +76,35 @@ __device__ __forceinline__ void lds_read4x8(const uint32_t (&a)[8], uint32_t off
                  : "memory");
 }
 
+// The same with one address register per read and compile-time byte offsets in the instructions.
+template <int O0, int O1, int O2, int O3>
+__device__ __forceinline__ void lds_read16x4_at(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3,
+                                                uint4 &r0, uint4 &r1, uint4 &r2, uint4 &r3)
+{
+    asm volatile("ds_read_b128 %0, %4 offset:%8\n\tds_read_b128 %1, %5 offset:%9\n\t"
+                 "ds_read_b128 %2, %6 offset:%10\n\tds_read_b128 %3, %7 offset:%11\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(r0), "=&v"(r1), "=&v"(r2), "=&v"(r3)
+                 : "v"(a0), "v"(a1), "v"(a2), "v"(a3), "n"(O0), "n"(O1), "n"(O2), "n"(O3) : "memory");
+}
+// eight addresses a[set * 4 + r], each read at + r * ROW and at + r * ROW + OFF: r0[i] and r1[i]; one wait
+template <int ROW, int OFF>
+__device__ __forceinline__ void lds_read4x8x2(const uint32_t (&a)[8], uint32_t (&r0)[8], uint32_t (&r1)[8])
+{
+    asm volatile("ds_read_b32 %0, %16\n\tds_read_b32 %1, %17 offset:%24\n\tds_read_b32 %2, %18 offset:%25\n\tds_read_b32 %3, %19 offset:%26\n\t"
+                 "ds_read_b32 %4, %20\n\tds_read_b32 %5, %21 offset:%24\n\tds_read_b32 %6, %22 offset:%25\n\tds_read_b32 %7, %23 offset:%26\n\t"
+                 "ds_read_b32 %8, %16 offset:%27\n\tds_read_b32 %9, %17 offset:%28\n\t"
+                 "ds_read_b32 %10, %18 offset:%29\n\tds_read_b32 %11, %19 offset:%30\n\t"
+                 "ds_read_b32 %12, %20 offset:%27\n\tds_read_b32 %13, %21 offset:%28\n\t"
+                 "ds_read_b32 %14, %22 offset:%29\n\tds_read_b32 %15, %23 offset:%30\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(r0[0]), "=&v"(r0[1]), "=&v"(r0[2]), "=&v"(r0[3]), "=&v"(r0[4]), "=&v"(r0[5]), "=&v"(r0[6]), "=&v"(r0[7]),
+                   "=&v"(r1[0]), "=&v"(r1[1]), "=&v"(r1[2]), "=&v"(r1[3]), "=&v"(r1[4]), "=&v"(r1[5]), "=&v"(r1[6]), "=&v"(r1[7])
+                 : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7]),
+                   "n"(ROW), "n"(2 * ROW), "n"(3 * ROW), "n"(OFF), "n"(OFF + ROW), "n"(OFF + 2 * ROW), "n"(OFF + 3 * ROW)
+                 : "memory");
+}
+
 // The weights p * lambda_v enter the second product as fp16 (high + low part).  With the
 // running maximum as the reference, p <= 2^kLazy and the largest weight of a row may be as
 // small as lambda_v itself, so that weights a million times smaller already fall under the

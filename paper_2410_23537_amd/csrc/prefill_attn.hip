@@ -22,6 +22,7 @@
 // The block-table entries of the 64 pages around the current position sit in a register (one
 // entry per lane), refilled every 64 pages from a window fetched ahead of time into LDS.
 #include "mfma_stream.h"
+#include <type_traits>
 
 namespace alise {
 namespace {
@@ -79,13 +80,13 @@ __global__ __launch_bounds__(1024) void prefill_plan_kernel(const int32_t *q_sta
 }
 
 template <int NGRP>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void prefill_attn_kernel(PrefillParams p)
+__device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
 {
     constexpr int D = 128, ROWB = 128, S = 3;
     constexpr int TILEB = 4352;                 // one 16-token tile in LDS: K 2 KiB | V 2 KiB | K meta 128 B | V meta 128 B
     constexpr int T_V = 2048, T_KM = 4096, T_VM = 4224;
     constexpr int STEPB = 2 * TILEB;
-    __shared__ __attribute__((aligned(16))) uint8_t lds[S * STEPB + 4 * 512];     // stages, then two page-window slots per wave
+    __shared__ __attribute__((aligned(128))) uint8_t lds[S * STEPB + 4 * 512];     // stages, then two page-window slots per wave
 
     const int f = blockIdx.x;
     if (f >= *p.ws.n_tiles) return;             // workgroup-uniform, before any barrier
@@ -119,19 +120,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     if (n_q <= 0 || nsteps <= 0) return;        // workgroup-uniform
 
     // ---- per-lane constants of the LDS layout (see the decode kernel): a 1 KiB load covers 8
-    // token rows; row r keeps its 16-byte piece c at position c ^ r.
+    // token rows; row r keeps its 16-byte piece c at position c ^ r.  The array starts on a
+    // 128-byte boundary and every stage, tile and row is a multiple of 128 bytes long, so the
+    // swizzle of an address is an exclusive-or of its bits 4..6 with the row number.
     const int src_lane = (lane >> 3) * ROWB + (((lane & 7) ^ (lane >> 3)) * 16);
-    const uint32_t k_rd0 = (n >> 3) * 1024 + ((n & 7) * 8 + (g ^ (n & 7))) * 16;
-    const uint32_t k_rd1 = (n >> 3) * 1024 + ((n & 7) * 8 + ((4 + g) ^ (n & 7))) * 16;
-    uint32_t v_rd[8];               // [set * 4 + r]
-#pragma unroll
-    for (int set = 0; set < 2; ++set)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int row = 4 * g + r;
-            const int piece = 4 * set + (n >> 2);
-            v_rd[set * 4 + r] = T_V + (row >> 3) * 1024 + ((row & 7) * 8 + (piece ^ (row & 7))) * 16 + (n & 3) * 4;
-        }
+    // K, token n of a tile, pieces g and 4 + g (the second: the first with bit 6 flipped)
+    const uint32_t k_rd = (n >> 3) * 1024 + ((n & 7) * 8 + (g ^ (n & 7))) * 16;
+    // V, token rows 4g + r (r = 0..3), piece 4 * set + n / 4, dword n % 4 of the piece: row r of set `set` sits at
+    // (v_rd ^ (16 r + 64 set)) + 128 r
+    const uint32_t v_rd = T_V + (g >> 1) * 1024 + (g & 1) * 512 + (((n >> 2) ^ ((g & 1) * 4)) * 16) + (n & 3) * 4;
     const uint32_t m_rd = g * 16 * NGRP;
 
     // ---- Q^T as the B operand of the four k-chunks: chunk jj, slot g*8+e <-> channel (jj/2)*64 + g*16 + (jj%2)*8 + e
@@ -161,12 +158,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
             qsum[gr] = v;
         }
     }
-    float qs_s[NGRP];                       // scale * sum(q)
-    const float scale24 = p.scale_log2e * 16777216.0f;   // the scale, and the 2^24 that the subnormal K codes lack
+    // Scores are kept in the units of the accumulator: t = sum_g lambda_k (acc_g - z_k sum(q_g) 2^-24), the true
+    // score being t * scale24 (the softmax scale, log2 e and the 2^24 that the subnormal K codes lack).
+    const float scale24 = p.scale_log2e * 16777216.0f;
+    const float inv24 = 1.0f / scale24;
+    const float lazy_t = kLazy * inv24;
+    float nqs24[NGRP];                      // -sum(q) 2^-24
 #pragma unroll
-    for (int gr = 0; gr < NGRP; ++gr) {
-        qs_s[gr] = qsum[gr] * p.scale_log2e;
-    }
+    for (int gr = 0; gr < NGRP; ++gr) nqs24[gr] = -qsum[gr] * (1.0f / 16777216.0f);
 
     // ---- block-table windows: 64 entries, one per lane.  Lookups use window wa in pg_a; the
     // windows come through LDS by direct loads (two slots per wave), fetched one window ahead,
@@ -185,7 +184,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     // ---- this wave's quarter of a step: tile x = wave / 2, K (even waves) or V (odd waves)
     const int my_x = wave >> 1;
     const bool my_v = wave & 1;
-    auto issue = [&](int k) {
+    auto issue = [&](int k, int stage) {
         int tx = k * kStep + my_x * 16;
         if (tx >= kv_end) tx -= 16;                             // second tile starts past the end: repeat the first
         const int pi = tx >> logP;
@@ -199,7 +198,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
         const int off = tx & (P - 1);
         const int64_t co = (int64_t)blk * p.c.cstride + (int64_t)off * ROWB;
         const int64_t mo = (int64_t)blk * p.c.mstride + (int64_t)off * NGRP * 4;
-        lptr_t dst = ldsp + (k % S) * STEPB + my_x * TILEB;
+        lptr_t dst = ldsp + stage * STEPB + my_x * TILEB;
         const uint8_t *cb = (my_v ? p.c.v_codes : p.c.k_codes) + co + src_lane;
         const uint8_t *mb = reinterpret_cast<const uint8_t *>(my_v ? p.c.v_meta : p.c.k_meta) + mo + lane * 4;
         // the rows of a head are read again by the workgroups of its other row tiles: keep them in the L2
@@ -208,7 +207,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
         if (lane < 16 * NGRP) dma4(mb, dst + (my_v ? T_VM : T_KM));
     };
 
-    float m_ref = kFloor, l_part = 0.0f, z_part[NGRP];
+    float m_ref = kFloor * inv24, l_part = 0.0f, z_part[NGRP];      // m_ref in the units of t
     float bias = kWeightBias;           // see kWeightBias; wave-uniform
 #pragma unroll
     for (int gr = 0; gr < NGRP; ++gr) z_part[gr] = 0.0f;
@@ -216,32 +215,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
 #pragma unroll
     for (int t = 0; t < 8; ++t) o[t] = (f4_t)0.0f;
 
-    issue(0);
-    if (nsteps > 1) issue(1);
-    for (int k = 0; k < nsteps; ++k) {
-        // this wave's quarter of step k has landed once at most the three loads of the step after it are in flight
-        if (k + 1 < nsteps) ALISE_VMCNT(3); else ALISE_VMCNT(0);
-        // all four quarters have landed, and every wave is done reading the stage that step k + 2 overwrites
-        asm volatile("s_barrier" ::: "memory");
-        if (k + 2 < nsteps) issue(k + 2);
-        if (!wave_has_rows || k * kStep > wave_last) continue;     // nothing here that a row of this wave may see
-        const uint32_t base = lds0 + (k % S) * STEPB;
-
+    // One step of 32 tokens out of the LDS stage at `base`.  MASKED: some row of this wave must not see
+    // some token of the step (the steps on the diagonal); otherwise no comparison and no select is spent.
+    auto step = [&](auto masked_c, int k, uint32_t base) {
+        constexpr bool MASKED = decltype(masked_c)::value;
         // ---- S^T = K Q^T for the two 16-token tiles
         float s[2][4];
         uint32_t vmraw[2][4][NGRP];        // V (scale, zero) dwords of this lane's tokens; 0 where the token is masked
         float mx = kNegInf;
         uint4 kp[2][2];
-        lds_read16x4(base + k_rd0, base + k_rd1, base + TILEB + k_rd0, base + TILEB + k_rd1, kp[0][0], kp[0][1], kp[1][0], kp[1][1]);
+        const uint32_t ka0 = base + k_rd, ka1 = ka0 ^ 64u, ma = base + m_rd;
+        lds_read16x4_at<0, 0, TILEB, TILEB>(ka0, ka1, ka0, ka1, kp[0][0], kp[0][1], kp[1][0], kp[1][1]);
         uint4 kmeta[2][NGRP], vmeta[2][NGRP];
         if constexpr (NGRP == 1) {
-            lds_read16x4(base + T_KM + m_rd, base + T_VM + m_rd, base + TILEB + T_KM + m_rd, base + TILEB + T_VM + m_rd,
-                         kmeta[0][0], vmeta[0][0], kmeta[1][0], vmeta[1][0]);
+            lds_read16x4_at<T_KM, T_VM, TILEB + T_KM, TILEB + T_VM>(ma, ma, ma, ma, kmeta[0][0], vmeta[0][0], kmeta[1][0], vmeta[1][0]);
         } else {
-            lds_read16x4(base + T_KM + m_rd, base + T_KM + m_rd + 16, base + T_VM + m_rd, base + T_VM + m_rd + 16,
-                         kmeta[0][0], kmeta[0][1], vmeta[0][0], vmeta[0][1]);
-            lds_read16x4(base + TILEB + T_KM + m_rd, base + TILEB + T_KM + m_rd + 16, base + TILEB + T_VM + m_rd,
-                         base + TILEB + T_VM + m_rd + 16, kmeta[1][0], kmeta[1][1], vmeta[1][0], vmeta[1][1]);
+            lds_read16x4_at<T_KM, T_KM + 16, T_VM, T_VM + 16>(ma, ma, ma, ma, kmeta[0][0], kmeta[0][1], vmeta[0][0], vmeta[0][1]);
+            lds_read16x4_at<TILEB + T_KM, TILEB + T_KM + 16, TILEB + T_VM, TILEB + T_VM + 16>(ma, ma, ma, ma, kmeta[1][0], kmeta[1][1],
+                                                                                              vmeta[1][0], vmeta[1][1]);
         }
 #pragma unroll
         for (int x = 0; x < 2; ++x) {
@@ -259,20 +250,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
                 f4_t &dst = acc[NGRP == 2 ? jj / 2 : 0];
                 dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, qop[jj], dst, 0, 0, 0);
             }
-            const int tok0 = k * kStep + x * 16 + g * 4;        // tokens of this lane's 4 rows of S^T
+            const int room = pos_n - (k * kStep + x * 16 + g * 4);     // row r of this lane's S^T block is visible iff r <= room
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const bool valid = tok0 + r <= pos_n;           // causal, per row of the problem
+                const bool valid = !MASKED || r <= room;        // causal, per row of the problem
                 float sv = 0.0f;
 #pragma unroll
                 for (int gr = 0; gr < NGRP; ++gr) {
-                    const uint32_t km = meta_of<NGRP>(kmeta[x], r, gr);
-                    const uint32_t vm = valid ? meta_of<NGRP>(vmeta[x], r, gr) : 0u;
-                    // scale * lambda_k * (2^24 acc - z_k * sum(q)), the fp16 halves of the meta dword read in place
-                    const h2_t kmh = as_h2(km);
-                    const float off = (float)kmh.y * qs_s[gr];
-                    sv = __builtin_fmaf((float)kmh.x, __builtin_fmaf(acc[gr][r], scale24, -off), sv);
-                    vmraw[x][r][gr] = vm;
+                    const h2_t kmh = as_h2(meta_of<NGRP>(kmeta[x], r, gr));     // the fp16 halves of the meta dword, read in place
+                    const float u = __builtin_fmaf((float)kmh.y, nqs24[gr], acc[gr][r]);
+                    sv = __builtin_fmaf((float)kmh.x, u, sv);
+                    const uint32_t vm = meta_of<NGRP>(vmeta[x], r, gr);
+                    vmraw[x][r][gr] = valid ? vm : 0u;
                 }
                 s[x][r] = valid ? sv : kNegInf;
                 mx = fmaxf(mx, s[x][r]);
@@ -280,11 +269,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
         }
 
         // ---- running maximum per row of the problem, raised lazily; all four quarters hold the same value
-        if (__builtin_amdgcn_ballot_w64(mx > m_ref + kLazy) != 0) {
+        if (__builtin_amdgcn_ballot_w64(mx > m_ref + lazy_t) != 0) {
             float mq = fmaxf(mx, __shfl_xor(mx, 16));
             mq = fmaxf(mq, __shfl_xor(mq, 32));
-            const float m_new = (mq > m_ref + kLazy) ? mq : m_ref;
-            const float fac = __builtin_amdgcn_exp2f(m_ref - m_new);
+            const float m_new = (mq > m_ref + lazy_t) ? mq : m_ref;
+            const float fac = __builtin_amdgcn_exp2f((m_ref - m_new) * scale24);
             l_part *= fac;
 #pragma unroll
             for (int gr = 0; gr < NGRP; ++gr) z_part[gr] *= fac;
@@ -307,32 +296,45 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
             for (int t = 0; t < 8; ++t) o[t] *= fb;
             bias = 0.0f;
         }
-        const float m_use = m_ref - bias;
+        const float c_use = __builtin_fmaf(-m_ref, scale24, bias);      // p = 2^(t scale24 - (m_ref scale24 - bias))
 
-        // ---- weights p * lambda_v as fp16 high + low parts, in the A-operand order (tile, row)
+        // ---- weights p * lambda_v as fp16 high + low parts, in the A-operand order (tile, row).  The high
+        // part is the product truncated to fp16, the low part what is left of the exact product.
         h8_t a_hi[NGRP], a_lo[NGRP];
 #pragma unroll
         for (int x = 0; x < 2; ++x)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float pj = __builtin_amdgcn_exp2f(s[x][r] - m_use);
-                l_part += pj;
+            for (int rr = 0; rr < 4; rr += 2) {
+                float pj[2];
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    pj[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[x][rr + e], scale24, c_use));
+                    l_part += pj[e];
+                }
 #pragma unroll
                 for (int gr = 0; gr < NGRP; ++gr) {
-                    const h2_t vmh = as_h2(vmraw[x][r][gr]);
-                    const float wv = pj * (float)vmh.x;
-                    z_part[gr] = __builtin_fmaf((float)vmh.y, wv, z_part[gr]);
-                    const _Float16 hi = (_Float16)wv;
-                    const _Float16 lo = (_Float16)(wv - (float)hi);
-                    a_hi[gr][x * 4 + r] = hi;
-                    a_lo[gr][x * 4 + r] = lo;
+                    float wv[2];
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        const h2_t vmh = as_h2(vmraw[x][rr + e][gr]);
+                        wv[e] = __builtin_fmaf((float)vmh.x, pj[e], 0.0f);
+                        z_part[gr] = __builtin_fmaf((float)vmh.y, wv[e], z_part[gr]);
+                    }
+                    const h2_t hi = __builtin_bit_cast(h2_t, __builtin_amdgcn_cvt_pkrtz(wv[0], wv[1]));
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        a_hi[gr][x * 4 + rr + e] = hi[e];
+                        a_lo[gr][x * 4 + rr + e] = (_Float16)__builtin_fmaf((float)as_h2(vmraw[x][rr + e][gr]).x, pj[e], -(float)hi[e]);
+                    }
                 }
             }
 
         // ---- O += P V: byte nu of the dwords of two tokens -> two fp16 subnormals
-        uint32_t vd[2][8];          // [tile][set * 4 + r]
-        lds_read4x8(v_rd, base, vd[0]);
-        lds_read4x8(v_rd, base + TILEB, vd[1]);
+        uint32_t va[8], vd[2][8];          // vd[tile][set * 4 + r]
+        va[0] = v_rd + base;
+#pragma unroll
+        for (int t = 1; t < 8; ++t) va[t] = va[0] ^ (uint32_t)((t & 3) * 16 + (t >> 2) * 64);
+        lds_read4x8x2<ROWB, TILEB>(va, vd[0], vd[1]);
 #pragma unroll
         for (int set = 0; set < 2; ++set)
 #pragma unroll
@@ -347,6 +349,34 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
                 dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_hi[gr], bv, dst, 0, 0, 0);
                 dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_lo[gr], bv, dst, 0, 0, 0);
             }
+    };
+
+    // Every wave passes the same nsteps barriers; what it computes in between is its own business.  The steps
+    // that lie wholly before the wave's first row come first and need no mask, then the steps on its diagonal
+    // (masked), then steps that none of its rows may see (skipped).
+    int stage = 0;                              // k % S, kept as a counter
+    auto advance = [&](int k) -> uint32_t {
+        // this wave's quarter of step k has landed once at most the three loads of the step after it are in flight
+        if (k + 1 < nsteps) ALISE_VMCNT(3); else ALISE_VMCNT(0);
+        // all four quarters have landed, and every wave is done reading the stage that step k + 2 overwrites
+        asm volatile("s_barrier" ::: "memory");
+        if (k + 2 < nsteps) issue(k + 2, stage == 0 ? 2 : stage - 1);
+        const uint32_t base = lds0 + stage * STEPB;
+        stage = stage == S - 1 ? 0 : stage + 1;
+        return base;
+    };
+    const int n_open = wave_has_rows ? min(nsteps, (first_pos + j0 + 1) / kStep) : 0;   // steps k with k*32 + 31 <= the wave's first position
+    issue(0, 0);
+    if (nsteps > 1) issue(1, 1);
+    int k = 0;
+    for (; k < n_open; ++k) {
+        const uint32_t base = advance(k);
+        step(std::false_type{}, k, base);
+    }
+    for (; k < nsteps; ++k) {
+        const uint32_t base = advance(k);
+        if (!wave_has_rows || k * kStep > wave_last) continue;     // nothing here that a row of this wave may see
+        step(std::true_type{}, k, base);
     }
 
     // ---- per row of the problem: add the four quarters; then fetch the values of this lane's rows
@@ -382,6 +412,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
             }
         }
     }
+}
+
+// One scale group per head (G = 128) fits the register budget of four waves per SIMD, two groups that of three.
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void prefill_attn_kernel_g1(PrefillParams p)
+{
+    prefill_attn_body<1>(p);
+}
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void prefill_attn_kernel_g2(PrefillParams p)
+{
+    prefill_attn_body<2>(p);
 }
 
 }  // namespace
@@ -421,9 +461,9 @@ hipError_t launch_prefill_attn(const CacheView &c, const void *q, void *out, con
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)ws.max_tiles, (unsigned)c.Hkv);
     if (c.D / c.G == 1)
-        hipLaunchKernelGGL(prefill_attn_kernel<1>, grid, dim3(256), 0, s, p);
+        hipLaunchKernelGGL(prefill_attn_kernel_g1, grid, dim3(256), 0, s, p);
     else
-        hipLaunchKernelGGL(prefill_attn_kernel<2>, grid, dim3(256), 0, s, p);
+        hipLaunchKernelGGL(prefill_attn_kernel_g2, grid, dim3(256), 0, s, p);
     return hipGetLastError();
 }
 
