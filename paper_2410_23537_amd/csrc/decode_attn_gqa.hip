@@ -40,6 +40,7 @@
 // Softmax state (running maximum, denominator, weighted zero-points) lives in the lanes of
 // the S^T layout and is brought to the rows of O only at the end of a tile.
 #include "mfma_stream.h"
+#include <type_traits>
 
 namespace alise {
 namespace {
@@ -57,7 +58,7 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
     constexpr int QSLOT = QROWS * 256;
     constexpr int OFF_DESC = S * STEPB, OFF_PG = OFF_DESC + RD * 16, OFF_Q = OFF_PG + RG * 256;
     static_assert(S >= 2 && S <= 4, "stage marks occupy four lanes");
-    __shared__ __attribute__((aligned(16))) uint8_t lds[OFF_Q + RQ * QSLOT];
+    __shared__ __attribute__((aligned(128))) uint8_t lds[OFF_Q + RQ * QSLOT];
 
     const int lane = threadIdx.x;
     const int n = lane & 15;        // column of the matrix layouts: token (K), query head (S^T), channel (V, O)
@@ -69,21 +70,14 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
     const uint32_t *order_words = reinterpret_cast<const uint32_t *>(p.ws.order);
 
     // ---- per-lane constants of the LDS layout.  A 1 KiB load covers 8 token rows; row r keeps
-    // its 16-byte piece c at position c ^ r.
+    // its 16-byte piece c at position c ^ r.  The array starts on a 128-byte boundary and every
+    // stage, tile and row is a multiple of 128 bytes long, so the swizzle of an address is an
+    // exclusive-or of its bits 4..6 with the row number.
     const int src_lane = (lane >> 3) * ROWB + (((lane & 7) ^ (lane >> 3)) * 16);     // what this lane fetches of the 1 KiB
-    // K operand: row n, pieces g and 4 + g
-    const uint32_t k_rd0 = (n >> 3) * 1024 + ((n & 7) * 8 + (g ^ (n & 7))) * 16;
-    const uint32_t k_rd1 = (n >> 3) * 1024 + ((n & 7) * 8 + ((4 + g) ^ (n & 7))) * 16;
-    // V operand: rows 4g + r, channels 64 * set + 4n .. (a dword)
-    uint32_t v_rd[8];               // [set * 4 + r]
-#pragma unroll
-    for (int set = 0; set < 2; ++set)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int row = 4 * g + r;
-            const int piece = 4 * set + (n >> 2);
-            v_rd[set * 4 + r] = T_V + (row >> 3) * 1024 + ((row & 7) * 8 + (piece ^ (row & 7))) * 16 + (n & 3) * 4;
-        }
+    // K operand: row n, pieces g and 4 + g (the second: the first with bit 6 flipped)
+    const uint32_t k_rd = (n >> 3) * 1024 + ((n & 7) * 8 + (g ^ (n & 7))) * 16;
+    // V operand: rows 4g + r, channels 64 * set + 4n .. (a dword): row r of set `set` sits at (v_rd ^ (16 r + 64 set)) + 128 r
+    const uint32_t v_rd = T_V + (g >> 1) * 1024 + (g & 1) * 512 + (((n >> 2) ^ ((g & 1) * 4)) * 16) + (n & 3) * 4;
     const uint32_t m_rd = g * 16 * NGRP;        // meta of this lane's 4 tokens
 
     // ---- this wave's list of items (an item is a tile for one KV head)
@@ -264,43 +258,45 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
                 qs[gr] = v;
             }
         }
-        float qs_s[NGRP];                       // scale * sum(q)
-        const float scale24 = p.scale_log2e * 16777216.0f;   // the scale, and the 2^24 that the subnormal K codes lack
+        // Scores are kept in the units of the accumulator: t = sum_g lambda_k (acc_g - z_k sum(q_g) 2^-24), the true
+        // score being t * scale24 (the softmax scale, log2 e and the 2^24 that the subnormal K codes lack).
+        const float scale24 = p.scale_log2e * 16777216.0f;
+        const float inv24 = 1.0f / scale24;
+        const float lazy_t = kLazy * inv24;
+        float nqs24[NGRP];                      // -sum(q) 2^-24
 #pragma unroll
-        for (int gr = 0; gr < NGRP; ++gr) {
-            qs_s[gr] = qs[gr] * p.scale_log2e;
-        }
+        for (int gr = 0; gr < NGRP; ++gr) nqs24[gr] = -qs[gr] * (1.0f / 16777216.0f);
         ++c_entered;
 
-        float m_ref = kFloor, l_part = 0.0f, z_part[NGRP];
+        // m_ref: the running maximum in the units of t.  c_ref = bias - m_ref scale24: a weight is 2^(t scale24 + c_ref),
+        // so -c_ref is the reference that the denominator and the sums are relative to.
+        float m_ref = kFloor * inv24, l_part = 0.0f, z_part[NGRP];
         float bias = kWeightBias;           // see kWeightBias; wave-uniform
+        float c_ref = __builtin_fmaf(-m_ref, scale24, bias);
 #pragma unroll
         for (int gr = 0; gr < NGRP; ++gr) z_part[gr] = 0.0f;
         f4_t o[8];                  // [set*4 + nu]: rows = query heads 4g..4g+3, column n <-> channel 64*set + 4n + nu
 #pragma unroll
         for (int t = 0; t < 8; ++t) o[t] = (f4_t)0.0f;
 
-        for (int k = 0; k < nsteps; ++k) {
-            fill();
-            const int sg = steps_consumed % S;
-            wait_newer(newer_than(32 + sg));
-            const uint32_t base = lds0 + sg * STEPB;
-
+        // One step of 32 tokens out of the LDS stage at `base`.  MASKED: the item's last step, which may hold
+        // tokens past the item's end; the other steps spend no comparison and no select.
+        auto step = [&](auto masked_c, int k, uint32_t base) {
+            constexpr bool MASKED = decltype(masked_c)::value;
             // ---- S^T = K Q^T for the two 16-token tiles
             float s[2][4];
             uint32_t vmraw[2][4][NGRP];        // V (scale, zero) dwords of this lane's tokens; 0 where the token is masked
             float mx = kNegInf;
             uint4 kp[2][2];
-            lds_read16x4(base + k_rd0, base + k_rd1, base + TILEB + k_rd0, base + TILEB + k_rd1, kp[0][0], kp[0][1], kp[1][0], kp[1][1]);
+            const uint32_t ka0 = base + k_rd, ka1 = ka0 ^ 64u, ma = base + m_rd;
+            lds_read16x4_at<0, 0, TILEB, TILEB>(ka0, ka1, ka0, ka1, kp[0][0], kp[0][1], kp[1][0], kp[1][1]);
             uint4 kmeta[2][NGRP], vmeta[2][NGRP];
             if constexpr (NGRP == 1) {
-                lds_read16x4(base + T_KM + m_rd, base + T_VM + m_rd, base + TILEB + T_KM + m_rd, base + TILEB + T_VM + m_rd,
-                             kmeta[0][0], vmeta[0][0], kmeta[1][0], vmeta[1][0]);
+                lds_read16x4_at<T_KM, T_VM, TILEB + T_KM, TILEB + T_VM>(ma, ma, ma, ma, kmeta[0][0], vmeta[0][0], kmeta[1][0], vmeta[1][0]);
             } else {
-                lds_read16x4(base + T_KM + m_rd, base + T_KM + m_rd + 16, base + T_VM + m_rd, base + T_VM + m_rd + 16,
-                             kmeta[0][0], kmeta[0][1], vmeta[0][0], vmeta[0][1]);
-                lds_read16x4(base + TILEB + T_KM + m_rd, base + TILEB + T_KM + m_rd + 16, base + TILEB + T_VM + m_rd,
-                             base + TILEB + T_VM + m_rd + 16, kmeta[1][0], kmeta[1][1], vmeta[1][0], vmeta[1][1]);
+                lds_read16x4_at<T_KM, T_KM + 16, T_VM, T_VM + 16>(ma, ma, ma, ma, kmeta[0][0], kmeta[0][1], vmeta[0][0], vmeta[0][1]);
+                lds_read16x4_at<TILEB + T_KM, TILEB + T_KM + 16, TILEB + T_VM, TILEB + T_VM + 16>(ma, ma, ma, ma, kmeta[1][0], kmeta[1][1],
+                                                                                                  vmeta[1][0], vmeta[1][1]);
             }
 #pragma unroll
             for (int x = 0; x < 2; ++x) {
@@ -318,20 +314,18 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
                     f4_t &dst = acc[NGRP == 2 ? j / 2 : 0];
                     dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, qop[j], dst, 0, 0, 0);
                 }
-                const int tok0 = t0 + k * kStep + x * 16 + g * 4;       // nominal tokens of this lane's 4 rows
+                const int room = t1 - (t0 + k * kStep + x * 16 + g * 4);        // row r of this lane's S^T block is a token of the item iff r < room
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const bool valid = tok0 + r < t1;
+                    const bool valid = !MASKED || r < room;
                     float sv = 0.0f;
 #pragma unroll
                     for (int gr = 0; gr < NGRP; ++gr) {
-                        const uint32_t km = meta_of<NGRP>(kmeta[x], r, gr);
-                        const uint32_t vm = valid ? meta_of<NGRP>(vmeta[x], r, gr) : 0u;
-                        // scale * lambda_k * (2^24 acc - z_k * sum(q)), the fp16 halves of the meta dword read in place
-                        const h2_t kmh = as_h2(km);
-                        const float off = (float)kmh.y * qs_s[gr];
-                        sv = __builtin_fmaf((float)kmh.x, __builtin_fmaf(acc[gr][r], scale24, -off), sv);
-                        vmraw[x][r][gr] = vm;
+                        const h2_t kmh = as_h2(meta_of<NGRP>(kmeta[x], r, gr));     // the fp16 halves of the meta dword, read in place
+                        const float u = __builtin_fmaf((float)kmh.y, nqs24[gr], acc[gr][r]);
+                        sv = __builtin_fmaf((float)kmh.x, u, sv);
+                        const uint32_t vm = meta_of<NGRP>(vmeta[x], r, gr);
+                        vmraw[x][r][gr] = valid ? vm : 0u;
                     }
                     s[x][r] = valid ? sv : kNegInf;
                     mx = fmaxf(mx, s[x][r]);
@@ -339,15 +333,16 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
             }
 
             // ---- running maximum per query head, raised lazily; all four quarters hold the same value
-            if (__builtin_amdgcn_ballot_w64(mx > m_ref + kLazy) != 0) {
+            if (__builtin_amdgcn_ballot_w64(mx > m_ref + lazy_t) != 0) {
                 float mq = fmaxf(mx, __shfl_xor(mx, 16));
                 mq = fmaxf(mq, __shfl_xor(mq, 32));
-                const float m_new = (mq > m_ref + kLazy) ? mq : m_ref;
-                const float f = __builtin_amdgcn_exp2f(m_ref - m_new);
+                m_ref = (mq > m_ref + lazy_t) ? mq : m_ref;
+                const float c_new = __builtin_fmaf(-m_ref, scale24, bias);
+                const float f = __builtin_amdgcn_exp2f(c_new - c_ref);
+                c_ref = c_new;
                 l_part *= f;
 #pragma unroll
                 for (int gr = 0; gr < NGRP; ++gr) z_part[gr] *= f;
-                m_ref = m_new;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const float fr = __shfl(f, 4 * g + r);          // factor of the query head in row 4g+r
@@ -358,40 +353,54 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
 
             // ---- a V scale of 2 or more in this step: the biased weights could leave the fp16 range (rare, wave-uniform)
             if (bias != 0.0f && __builtin_amdgcn_ballot_w64(max_low_half<8 * NGRP>(&vmraw[0][0][0]) >= 0x4000u) != 0) {
-                const float fb = __builtin_amdgcn_exp2f(-bias);
+                bias = 0.0f;
+                const float c_new = __builtin_fmaf(-m_ref, scale24, 0.0f);
+                const float fb = __builtin_amdgcn_exp2f(c_new - c_ref);
+                c_ref = c_new;
                 l_part *= fb;
 #pragma unroll
                 for (int gr = 0; gr < NGRP; ++gr) z_part[gr] *= fb;
 #pragma unroll
                 for (int t = 0; t < 8; ++t) o[t] *= fb;
-                bias = 0.0f;
             }
-            const float m_use = m_ref - bias;
 
-            // ---- weights p * lambda_v as fp16 high + low parts, in the A-operand order (tile, row)
+            // ---- weights p * lambda_v as fp16 high + low parts, in the A-operand order (tile, row).  The high
+            // part is the product truncated to fp16, the low part what is left of the exact product.
             h8_t a_hi[NGRP], a_lo[NGRP];
 #pragma unroll
             for (int x = 0; x < 2; ++x)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float pj = __builtin_amdgcn_exp2f(s[x][r] - m_use);
-                    l_part += pj;
+                for (int rr = 0; rr < 4; rr += 2) {
+                    float pj[2];
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        pj[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[x][rr + e], scale24, c_ref));
+                        l_part += pj[e];
+                    }
 #pragma unroll
                     for (int gr = 0; gr < NGRP; ++gr) {
-                        const h2_t vmh = as_h2(vmraw[x][r][gr]);
-                        const float wv = pj * (float)vmh.x;
-                        z_part[gr] = __builtin_fmaf((float)vmh.y, wv, z_part[gr]);
-                        const _Float16 hi = (_Float16)wv;
-                        const _Float16 lo = (_Float16)(wv - (float)hi);
-                        a_hi[gr][x * 4 + r] = hi;
-                        a_lo[gr][x * 4 + r] = lo;
+                        float wv[2];
+#pragma unroll
+                        for (int e = 0; e < 2; ++e) {
+                            const h2_t vmh = as_h2(vmraw[x][rr + e][gr]);
+                            wv[e] = __builtin_fmaf((float)vmh.x, pj[e], 0.0f);
+                            z_part[gr] = __builtin_fmaf((float)vmh.y, wv[e], z_part[gr]);
+                        }
+                        const h2_t hi = __builtin_bit_cast(h2_t, __builtin_amdgcn_cvt_pkrtz(wv[0], wv[1]));
+#pragma unroll
+                        for (int e = 0; e < 2; ++e) {
+                            a_hi[gr][x * 4 + rr + e] = hi[e];
+                            a_lo[gr][x * 4 + rr + e] = (_Float16)__builtin_fmaf((float)as_h2(vmraw[x][rr + e][gr]).x, pj[e], -(float)hi[e]);
+                        }
                     }
                 }
 
             // ---- O += P V: byte nu of the dwords of two tokens -> two fp16 subnormals
-            uint32_t vd[2][8];          // [tile][set * 4 + r]
-            lds_read4x8(v_rd, base, vd[0]);
-            lds_read4x8(v_rd, base + TILEB, vd[1]);
+            uint32_t va[8], vd[2][8];          // vd[tile][set * 4 + r]
+            va[0] = v_rd + base;
+#pragma unroll
+            for (int t = 1; t < 8; ++t) va[t] = va[0] ^ (uint32_t)((t & 3) * 16 + (t >> 2) * 64);
+            lds_read4x8x2<ROWB, TILEB>(va, vd[0], vd[1]);
 #pragma unroll
             for (int set = 0; set < 2; ++set)
 #pragma unroll
@@ -406,6 +415,22 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
                     dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_hi[gr], bv, dst, 0, 0, 0);
                     dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_lo[gr], bv, dst, 0, 0, 0);
                 }
+        };
+        auto next_stage = [&]() -> uint32_t {
+            fill();
+            const int sg = steps_consumed % S;
+            wait_newer(newer_than(32 + sg));
+            return lds0 + sg * STEPB;
+        };
+
+        for (int k = 0; k < nsteps - 1; ++k) {
+            const uint32_t base = next_stage();
+            step(std::false_type{}, k, base);
+            ++steps_consumed;
+        }
+        {
+            const uint32_t base = next_stage();
+            step(std::true_type{}, nsteps - 1, base);
             ++steps_consumed;
         }
 
@@ -423,7 +448,7 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
         for (int r = 0; r < 4; ++r) {
             const int row = 4 * g + r;                      // query head of the group
             const float l_row = __shfl(l, row);
-            const float m_row = __shfl(m_ref - bias, row);       // the reference the denominator and the sums are relative to
+            const float m_row = __shfl(-c_ref, row);             // the reference the denominator and the sums are relative to
             float z_row[NGRP];
 #pragma unroll
             for (int gr = 0; gr < NGRP; ++gr) z_row[gr] = __shfl(zsum[gr], row);

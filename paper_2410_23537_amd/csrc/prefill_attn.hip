@@ -207,8 +207,10 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
         if (lane < 16 * NGRP) dma4(mb, dst + (my_v ? T_VM : T_KM));
     };
 
-    float m_ref = kFloor * inv24, l_part = 0.0f, z_part[NGRP];      // m_ref in the units of t
+    // m_ref: the running maximum in the units of t.  c_ref = bias - m_ref scale24: a weight is 2^(t scale24 + c_ref).
+    float m_ref = kFloor * inv24, l_part = 0.0f, z_part[NGRP];
     float bias = kWeightBias;           // see kWeightBias; wave-uniform
+    float c_ref = __builtin_fmaf(-m_ref, scale24, bias);
 #pragma unroll
     for (int gr = 0; gr < NGRP; ++gr) z_part[gr] = 0.0f;
     f4_t o[8];                  // [set*4 + nu]: rows 4g..4g+3, column n <-> channel 64*set + 4n + nu
@@ -272,12 +274,13 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
         if (__builtin_amdgcn_ballot_w64(mx > m_ref + lazy_t) != 0) {
             float mq = fmaxf(mx, __shfl_xor(mx, 16));
             mq = fmaxf(mq, __shfl_xor(mq, 32));
-            const float m_new = (mq > m_ref + lazy_t) ? mq : m_ref;
-            const float fac = __builtin_amdgcn_exp2f((m_ref - m_new) * scale24);
+            m_ref = (mq > m_ref + lazy_t) ? mq : m_ref;
+            const float c_new = __builtin_fmaf(-m_ref, scale24, bias);
+            const float fac = __builtin_amdgcn_exp2f(c_new - c_ref);
+            c_ref = c_new;
             l_part *= fac;
 #pragma unroll
             for (int gr = 0; gr < NGRP; ++gr) z_part[gr] *= fac;
-            m_ref = m_new;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const float fr = __shfl(fac, 4 * g + r);        // factor of the problem row 4g+r
@@ -288,15 +291,16 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
 
         // ---- a V scale of 2 or more in this step: the biased weights could leave the fp16 range (rare, wave-uniform)
         if (bias != 0.0f && __builtin_amdgcn_ballot_w64(max_low_half<8 * NGRP>(&vmraw[0][0][0]) >= 0x4000u) != 0) {
-            const float fb = __builtin_amdgcn_exp2f(-bias);
+            bias = 0.0f;
+            const float c_new = __builtin_fmaf(-m_ref, scale24, 0.0f);
+            const float fb = __builtin_amdgcn_exp2f(c_new - c_ref);
+            c_ref = c_new;
             l_part *= fb;
 #pragma unroll
             for (int gr = 0; gr < NGRP; ++gr) z_part[gr] *= fb;
 #pragma unroll
             for (int t = 0; t < 8; ++t) o[t] *= fb;
-            bias = 0.0f;
         }
-        const float c_use = __builtin_fmaf(-m_ref, scale24, bias);      // p = 2^(t scale24 - (m_ref scale24 - bias))
 
         // ---- weights p * lambda_v as fp16 high + low parts, in the A-operand order (tile, row).  The high
         // part is the product truncated to fp16, the low part what is left of the exact product.
@@ -308,7 +312,7 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
                 float pj[2];
 #pragma unroll
                 for (int e = 0; e < 2; ++e) {
-                    pj[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[x][rr + e], scale24, c_use));
+                    pj[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[x][rr + e], scale24, c_ref));
                     l_part += pj[e];
                 }
 #pragma unroll
