@@ -76,6 +76,13 @@ def lib():
         L.oracle_kv_dequant_page.restype = ctypes.c_int
         L.oracle_kv_dequant_page.argtypes = [ctypes.POINTER(_CCache), ctypes.c_int32,
                                              ctypes.c_void_p, ctypes.c_void_p]
+        L.oracle_d2h_rne.restype = ctypes.c_uint16
+        L.oracle_d2h_rne.argtypes = [ctypes.c_double]
+        L.oracle_add_layernorm.restype = ctypes.c_int
+        L.oracle_add_layernorm.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_double,
+                                           ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
+        L.oracle_bias_relu.restype = ctypes.c_int
+        L.oracle_bias_relu.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p]
         L.oracle_dense_attn.restype = None
         L.oracle_dense_attn.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                         ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_void_p]
@@ -231,3 +238,40 @@ def paged_prefill_attn(cache: Cache, q: np.ndarray, q_start: np.ndarray, block_t
     if rc:
         raise ValueError("a chunk is longer than its request")
     return out
+
+
+def d2h(x: float) -> int:
+    """binary64 -> binary16 bit pattern, round to nearest even, one rounding."""
+    return int(lib().oracle_d2h_rne(float(x)))
+
+
+def add_layernorm(x, residual, gamma, beta, eps):
+    """R19.  x, residual (or None): fp16 [rows, hidden]; gamma, beta: fp16 [hidden].
+    Returns (h fp16 [rows, hidden], y fp64 [rows, hidden])."""
+    x = np.ascontiguousarray(x, np.float16)
+    rows, hidden = x.shape
+    res = None if residual is None else np.ascontiguousarray(residual, np.float16)
+    assert res is None or res.shape == x.shape
+    gamma = np.ascontiguousarray(gamma, np.float16)
+    beta = np.ascontiguousarray(beta, np.float16)
+    assert gamma.shape == (hidden,) and beta.shape == (hidden,)
+    h = np.empty((rows, hidden), np.float16)
+    y = np.empty((rows, hidden), np.float64)
+    rc = lib().oracle_add_layernorm(_ptr(x), None if res is None else _ptr(res), _ptr(gamma), _ptr(beta), float(eps),
+                                    rows, hidden, _ptr(h), _ptr(y))
+    if rc != 0:
+        raise ValueError("oracle_add_layernorm: bad arguments")
+    return h, y
+
+
+def bias_relu(x, bias):
+    """R20.  x: fp16 [rows, cols]; bias: fp16 [cols] or None.  Returns fp16 [rows, cols]."""
+    x = np.ascontiguousarray(x, np.float16)
+    rows, cols = x.shape
+    b = None if bias is None else np.ascontiguousarray(bias, np.float16)
+    assert b is None or b.shape == (cols,)
+    y = np.empty((rows, cols), np.float16)
+    rc = lib().oracle_bias_relu(_ptr(x), None if b is None else _ptr(b), rows, cols, _ptr(y))
+    if rc != 0:
+        raise ValueError("oracle_bias_relu: bad arguments")
+    return y

@@ -37,6 +37,14 @@
  *   R18 prefill in chunks: the chunk's own K/V are written first (quantized, R12), then
  *       query j of an n-token chunk of a request with L cached tokens sits at position
  *       L - n + j and attends to positions 0 .. L - n + j (causal), all from the cache.
+ *   R19 the fused LayerNorm (Sec. 3.3 "Implementation") takes the residual connection with it
+ *       (Sec. 2 "Transformer Architecture": LayerNorm and residual connection surround the
+ *       attention and FFN modules): h = fp16(x + residual), the exact sum rounded once;
+ *       y = gamma (h - mean) / sqrt(var + eps) + beta over the hidden dimension of the
+ *       fp16 h, var the biased variance (divide by N); the definition of layer normalization.
+ *       The oracle returns y in fp64; the product rounds it to fp16.
+ *   R20 the fused ReLU takes the bias of the FFN's first linear layer with it:
+ *       y = fp16(max(x + bias, 0)), the exact sum rounded once, -0 becomes +0.
  *   R17 the offloaded form of a request is its pages in logical order, whole pages
  *       (every slot of the last page too), each as [K codes | V codes | K meta | V meta]
  *       per KV head: compressed bytes move as they are, nothing is requantized.
@@ -439,4 +447,73 @@ int oracle_kv_swap_out(const oracle_cache *c, const int32_t *block_table, int32_
 int oracle_kv_swap_in(oracle_cache *c, const int32_t *block_table, int32_t num_tokens, const uint8_t *packed)
 {
     return swap_walk(c, block_table, num_tokens, (uint8_t *)packed, 1);
+}
+
+/* ---------------------------------------------------------------- fused LayerNorm and ReLU (R19, R20) */
+
+/* binary64 -> binary16, round to nearest, ties to even, in one rounding. */
+uint16_t oracle_d2h_rne(double d)
+{
+    uint16_t sign = (uint16_t)(signbit(d) ? 0x8000u : 0u);
+    if (isnan(d)) return (uint16_t)(sign | 0x7e00u);
+    double a = fabs(d);
+    if (a >= 65520.0) return (uint16_t)(sign | 0x7c00u);
+    if (a == 0.0) return sign;
+    int e;
+    (void)frexp(a, &e);
+    int ulp_exp = e - 11;
+    if (ulp_exp < -24) ulp_exp = -24;
+    double r = nearbyint(ldexp(a, -ulp_exp));       /* the scaling is exact; ties to even */
+    double val = ldexp(r, ulp_exp);
+    if (val == 0.0) return sign;
+    if (val < ldexp(1.0, -14)) return (uint16_t)(sign | (uint32_t)ldexp(val, 24));
+    int e2;
+    double m2 = frexp(val, &e2);
+    return (uint16_t)(sign | ((uint32_t)(e2 - 1 + 15) << 10) | ((uint32_t)ldexp(m2, 11) - 0x400u));
+}
+
+/*
+ * Residual add + LayerNorm over the rows of a [rows, hidden] matrix (R19).
+ * residual may be NULL (h = x).  h_out: fp16 bit patterns [rows, hidden]; y_out: fp64.
+ */
+int oracle_add_layernorm(const uint16_t *x, const uint16_t *residual, const uint16_t *gamma, const uint16_t *beta,
+                         double eps, int64_t rows, int32_t hidden, uint16_t *h_out, double *y_out)
+{
+    if (rows < 0 || hidden <= 0) return -1;
+    for (int64_t i = 0; i < rows; ++i) {
+        const uint16_t *xr = x + i * hidden;
+        uint16_t *hr = h_out + i * hidden;
+        double *yr = y_out + i * hidden;
+        for (int j = 0; j < hidden; ++j) {
+            double sum = (double)oracle_h2f(xr[j]);
+            if (residual) sum += (double)oracle_h2f(residual[i * hidden + j]);    /* exact in binary64 */
+            hr[j] = oracle_d2h_rne(sum);
+        }
+        double mean = 0.0;
+        for (int j = 0; j < hidden; ++j) mean += (double)oracle_h2f(hr[j]);
+        mean /= hidden;
+        double var = 0.0;
+        for (int j = 0; j < hidden; ++j) {
+            const double dlt = (double)oracle_h2f(hr[j]) - mean;
+            var += dlt * dlt;
+        }
+        var /= hidden;
+        const double denom = sqrt(var + eps);
+        for (int j = 0; j < hidden; ++j)
+            yr[j] = (double)oracle_h2f(gamma[j]) * (((double)oracle_h2f(hr[j]) - mean) / denom) + (double)oracle_h2f(beta[j]);
+    }
+    return 0;
+}
+
+/* Bias + ReLU over a [rows, cols] matrix (R20).  bias may be NULL. */
+int oracle_bias_relu(const uint16_t *x, const uint16_t *bias, int64_t rows, int32_t cols, uint16_t *y_out)
+{
+    if (rows < 0 || cols <= 0) return -1;
+    for (int64_t i = 0; i < rows; ++i)
+        for (int j = 0; j < cols; ++j) {
+            double v = (double)oracle_h2f(x[i * cols + j]);
+            if (bias) v += (double)oracle_h2f(bias[j]);
+            y_out[i * cols + j] = v > 0.0 ? oracle_d2h_rne(v) : (uint16_t)0;
+        }
+    return 0;
 }
