@@ -34,6 +34,7 @@ EXPORTS = ("alise_kv_codes_bytes", "alise_kv_meta_bytes", "alise_kv_quant_write"
            "alise_paged_decode_attn_workspace_bytes", "alise_paged_decode_attn",
            "alise_kv_dequant_page", "alise_kv_swap_bytes", "alise_kv_swap_out", "alise_kv_swap_in",
            "alise_paged_prefill_attn_workspace_bytes", "alise_paged_prefill_attn",
+           "alise_add_layernorm", "alise_bias_relu",
            "alise_status_string")
 
 
@@ -76,6 +77,12 @@ _lib.alise_kv_swap_out.restype = ctypes.c_int
 _lib.alise_kv_swap_out.argtypes = [_P, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
 _lib.alise_kv_swap_in.restype = ctypes.c_int
 _lib.alise_kv_swap_in.argtypes = [_P, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+_lib.alise_add_layernorm.restype = ctypes.c_int
+_lib.alise_add_layernorm.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float,
+                                     ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p]
+_lib.alise_bias_relu.restype = ctypes.c_int
+_lib.alise_bias_relu.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32,
+                                 ctypes.c_void_p]
 _lib.alise_status_string.restype = ctypes.c_char_p
 _lib.alise_status_string.argtypes = [ctypes.c_int]
 
@@ -249,6 +256,33 @@ def alise_kv_swap_in(cache: KVCache, block_table: torch.Tensor, num_tokens: int,
     st = _lib.alise_kv_swap_in(ctypes.byref(cache.c_struct()), _dp(block_table), int(num_tokens), _dp(packed),
                                packed.numel(), _stream())
     _check(st, "alise_kv_swap_in")
+
+
+def _is_matrix(t) -> bool:
+    return t.dtype == torch.float16 and t.is_cuda and t.is_contiguous() and t.dim() == 2
+
+
+def alise_add_layernorm(x: torch.Tensor, residual, gamma: torch.Tensor, beta: torch.Tensor, eps: float,
+                        h_out, y_out: torch.Tensor) -> None:
+    """x, residual (or None), h_out (or None), y_out: fp16 [rows, hidden]; gamma, beta: fp16 [hidden]."""
+    assert _is_matrix(x) and _is_matrix(y_out) and y_out.shape == x.shape
+    assert residual is None or (_is_matrix(residual) and residual.shape == x.shape)
+    assert h_out is None or (_is_matrix(h_out) and h_out.shape == x.shape)
+    rows, hidden = x.shape
+    for v in (gamma, beta):
+        assert v.dtype == torch.float16 and v.is_cuda and v.is_contiguous() and v.shape == (hidden,)
+    st = _lib.alise_add_layernorm(_dp(x), _dp(residual), _dp(gamma), _dp(beta), float(eps), _dp(h_out), _dp(y_out),
+                                  rows, hidden, _stream())
+    _check(st, "alise_add_layernorm")
+
+
+def alise_bias_relu(x: torch.Tensor, bias, y_out: torch.Tensor) -> None:
+    """x, y_out: fp16 [rows, cols] (y_out may be x); bias: fp16 [cols] or None."""
+    assert _is_matrix(x) and _is_matrix(y_out) and y_out.shape == x.shape
+    rows, cols = x.shape
+    assert bias is None or (bias.dtype == torch.float16 and bias.is_cuda and bias.is_contiguous() and bias.shape == (cols,))
+    st = _lib.alise_bias_relu(_dp(x), _dp(bias), _dp(y_out), rows, cols, _stream())
+    _check(st, "alise_bias_relu")
 
 
 def raw():

@@ -7,7 +7,7 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "alise_kv.h")
+HEADERS = [os.path.join(ROOT, "include", f) for f in sorted(os.listdir(os.path.join(ROOT, "include"))) if f.endswith(".h")]
 
 
 @pytest.fixture(scope="module")
@@ -17,7 +17,7 @@ def B():
 
 
 def _declared_functions():
-    text = open(HEADER).read()
+    text = "\n".join(open(h).read() for h in HEADERS)
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(alise_[a-z0-9_]+)\s*\(", text)))
 
@@ -194,3 +194,36 @@ def test_prefill_arguments(B):
         bad = _cache(B, **kw)
         assert lib.alise_paged_prefill_attn_workspace_bytes(ctypes.byref(bad), 2, 300, 8) == 0
         assert call(c=ctypes.byref(bad)) == 2
+
+
+def test_fused_op_arguments(B):
+    lib = B.raw()
+    A = 0x1000          # any 16-byte aligned, non-null address: the checks below fail before a pointer is used
+    ln = lambda x=A, res=A, g=A, b=A, eps=1e-5, h=A + 64, y=A + 128, rows=4, hidden=64: lib.alise_add_layernorm(
+        x, res, g, b, eps, h, y, rows, hidden, None)
+    assert ln(x=None) == B.ALISE_INVALID_ARGUMENT
+    assert ln(g=None) == B.ALISE_INVALID_ARGUMENT
+    assert ln(b=None) == B.ALISE_INVALID_ARGUMENT
+    assert ln(y=None) == B.ALISE_INVALID_ARGUMENT
+    assert ln(rows=-1) == B.ALISE_INVALID_ARGUMENT
+    assert ln(eps=-1.0) == B.ALISE_INVALID_ARGUMENT
+    assert ln(eps=float("nan")) == B.ALISE_INVALID_ARGUMENT
+    assert ln(eps=float("inf")) == B.ALISE_INVALID_ARGUMENT
+    assert ln(h=A + 128) == B.ALISE_INVALID_ARGUMENT            # h_out and y_out the same buffer
+    for hidden in (0, 4, 12, 16392, 1 << 20):
+        assert ln(hidden=hidden) == B.ALISE_UNSUPPORTED
+    assert ln(x=A + 2) == B.ALISE_MISALIGNED
+    assert ln(res=A + 8) == B.ALISE_MISALIGNED
+    assert ln(y=A + 130) == B.ALISE_MISALIGNED
+    assert ln(rows=0) == B.ALISE_OK                               # nothing to do, nothing launched
+    assert ln(rows=0, res=None, h=None) == B.ALISE_OK
+
+    relu = lambda x=A, b=A, y=A, rows=4, cols=64: lib.alise_bias_relu(x, b, y, rows, cols, None)
+    assert relu(x=None) == B.ALISE_INVALID_ARGUMENT
+    assert relu(y=None) == B.ALISE_INVALID_ARGUMENT
+    assert relu(rows=-3) == B.ALISE_INVALID_ARGUMENT
+    for cols in (0, 7, 20):
+        assert relu(cols=cols) == B.ALISE_UNSUPPORTED
+    assert relu(b=A + 4) == B.ALISE_MISALIGNED
+    assert relu(rows=0) == B.ALISE_OK
+    assert relu(rows=0, b=None) == B.ALISE_OK
