@@ -199,6 +199,42 @@ def prefill_leg(w, step):
                          "frac": tflops / MFMA_F16_PEAK_TFLOPS, "traffic": None}}
 
 
+def fused_ops_leg(w):
+    """The two other fused operators of the layer (Sec. 3.3 "Implementation"), outside the timed
+    steps, on a token batch of this workload's model: 16384 tokens (prefill chunks of an iteration;
+    large enough that the matrices, 0.5 to 2.7 GB, cannot sit in the 256 MB last-level cache between
+    repetitions), hidden = H * D, FFN width 4 * hidden.  Bound: HBM -- 8 bytes per element for the
+    residual add + LayerNorm (x, residual in; sum, normalized row out), 4 for bias + ReLU in place."""
+    import torch
+    from paper_2410_23537_amd import binding as B
+    rows, hidden = 16384, w.H * w.D
+    gen = torch.Generator(device="cuda").manual_seed(w.seed + 1)
+    mk = lambda *shape: torch.randn(shape, dtype=torch.float16, device="cuda", generator=gen)
+    x, res, gamma, beta = mk(rows, hidden), mk(rows, hidden), mk(hidden), mk(hidden)
+    h, y = torch.empty_like(x), torch.empty_like(x)
+    f, fb = mk(rows, 4 * hidden), mk(4 * hidden)
+    out = {}
+    for name, fn, nbytes in (("add_layernorm", lambda: B.alise_add_layernorm(x, res, gamma, beta, 1e-5, h, y), 8 * rows * hidden),
+                             ("bias_relu", lambda: B.alise_bias_relu(f, fb, f), 4 * rows * 4 * hidden)):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        reps = 20
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        gbs = nbytes / (ms * 1e-3) / 1e9
+        out[name] = {"shape": [rows, hidden if name == "add_layernorm" else 4 * hidden], "ms": ms, "bytes": nbytes,
+                     "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                  "frac": gbs / HBM_PEAK_GBS, "traffic": None}}
+    out["note"] = "a plain device-to-device copy (read + write) reaches about 5200 GB/s on this box"
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -282,6 +318,7 @@ def main():
     prefill = prefill_leg(w, step)
     if prefill is not None:
         result["prefill"] = prefill
+    result["fused_ops"] = fused_ops_leg(w)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, step, args.cpu_seconds)
     print(json.dumps(result), flush=True)

@@ -56,8 +56,8 @@ int alise_add_layernorm(const void *x, const void *residual, const void *gamma, 
  *
  * x: device, fp16 [rows, cols], read.   bias: device, fp16 [cols], read; NULL = no bias.
  * y_out: device, fp16 [rows, cols], written; may be x itself (in place).
- * rows >= 0 (0: nothing is done and no pointer is looked at); cols >= 8, a multiple of 8, else
- * ALISE_UNSUPPORTED.
+ * rows >= 0 (0: nothing is done and no pointer is looked at); cols >= 8, a multiple of 8, and
+ * rows * cols below 2^35 elements, else ALISE_UNSUPPORTED.
  */
 int alise_bias_relu(const void *x, const void *bias, void *y_out, int64_t rows, int32_t cols,
                     void *hip_stream);

@@ -12,8 +12,8 @@
 //   over the row with wave shuffles (and four LDS words across the waves of a workgroup);
 //   normalise, scale, shift, round once, store.  8 bytes of HBM traffic per element.
 //
-//   bias + ReLU: a thread owns a 16-byte column piece, keeps its bias in registers and walks
-//   down the rows; packed fp16 add, then a signed 16-bit integer maximum with 0, which turns
+//   bias + ReLU: the matrix in memory order, 16 bytes per thread and four 4 KiB runs per
+//   workgroup; packed fp16 add, then a signed 16-bit integer maximum with 0, which turns
 //   every negative pattern (-0 included) into +0 and leaves the positive ones alone.
 #include "../../include/alise_ops.h"
 
@@ -130,38 +130,40 @@ hipError_t launch_ln(const void *x, const void *residual, const void *gamma, con
     return hipGetLastError();
 }
 
-// Threads are laid out TX wide (column pieces) by 256 / TX high (rows); a thread keeps its bias
-// piece and strides down the rows, UNROLL rows in flight.
+// The matrix is walked in memory order, 16-byte pieces, a workgroup taking UNROLL consecutive 4 KiB runs: long
+// sequential bursts are what HBM likes best.  The bias piece of a run comes out of the cache.
 template <bool BIAS>
 __global__ __launch_bounds__(256) void bias_relu_kernel(const _Float16 *x, const _Float16 *__restrict__ bias, _Float16 *y,
-                                                        int64_t rows, int32_t cols, int32_t log_tx)
+                                                        uint32_t n_pieces, uint32_t pieces_per_row)
 {
     constexpr int UNROLL = 4;
-    const int tx = threadIdx.x & ((1 << log_tx) - 1), ty = threadIdx.x >> log_tx;
-    const int ty_n = 256 >> log_tx;
-    const int piece = (blockIdx.x << log_tx) + tx;
-    if (piece >= (cols >> 3)) return;
-    half8_t b = (half8_t)(_Float16)0.0f;
-    if constexpr (BIAS) b = load8(bias + piece * 8);
-    const int64_t stride = (int64_t)gridDim.y * ty_n;
+    const uint32_t first = blockIdx.x * (256u * UNROLL) + threadIdx.x;
+    uint32_t col = 0;
+    if constexpr (BIAS) col = first % pieces_per_row;
+    const uint32_t hop = 256u % pieces_per_row;          // how far the column moves from one run to the next
     const short8_t zero = (short8_t)(short)0;
-    for (int64_t r0 = (int64_t)blockIdx.y * ty_n + ty; r0 < rows; r0 += stride * UNROLL) {
-        half8_t v[UNROLL];
+    half8_t v[UNROLL], b[UNROLL];
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const int64_t r = r0 + u * stride;
-            if (r < rows) v[u] = load8_stream(x + r * cols + piece * 8);
+    for (int u = 0; u < UNROLL; ++u) {
+        const uint32_t id = first + u * 256u;
+        if (id < n_pieces) {
+            v[u] = load8_stream(x + (uint64_t)id * 8);
+            if constexpr (BIAS) b[u] = load8(bias + col * 8);
         }
+        if constexpr (BIAS) {
+            col += hop;
+            col = col >= pieces_per_row ? col - pieces_per_row : col;
+        }
+    }
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const int64_t r = r0 + u * stride;
-            if (r < rows) {
-                half8_t s = v[u];
-                if constexpr (BIAS) s = s + b;              // packed fp16 adds: the exact sum, rounded once
-                // as 16-bit integers every negative fp16 (and -0) is negative and every positive one keeps its order
-                const short8_t m = __builtin_elementwise_max(__builtin_bit_cast(short8_t, s), zero);
-                store8(y + r * cols + piece * 8, __builtin_bit_cast(half8_t, m));
-            }
+    for (int u = 0; u < UNROLL; ++u) {
+        const uint32_t id = first + u * 256u;
+        if (id < n_pieces) {
+            half8_t s = v[u];
+            if constexpr (BIAS) s = s + b[u];               // packed fp16 adds: the exact sum, rounded once
+            // as 16-bit integers every negative fp16 (and -0) is negative and every positive one keeps its order
+            const short8_t m = __builtin_elementwise_max(__builtin_bit_cast(short8_t, s), zero);
+            store8(y + (uint64_t)id * 8, __builtin_bit_cast(half8_t, m));
         }
     }
 }
@@ -210,23 +212,16 @@ int alise_bias_relu(const void *x, const void *bias, void *y_out, int64_t rows, 
     if (!x || !y_out) return ALISE_INVALID_ARGUMENT;
     if (!aligned16(x) || !aligned16(bias) || !aligned16(y_out)) return ALISE_MISALIGNED;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const int pieces = cols >> 3;
-    int log_tx = 0;
-    while ((1 << log_tx) < pieces && log_tx < 8) ++log_tx;          // the row of threads: the pieces rounded up to a power of two, at most 256
-    const int ty_n = 256 >> log_tx;
-    const unsigned gx = (unsigned)((pieces + (1 << log_tx) - 1) >> log_tx);
-    // enough workgroups for eight per compute unit of a 256-unit chip, no more than the rows give
-    int64_t gy = (2048 + gx - 1) / gx;
-    const int64_t gy_max = (rows + ty_n - 1) / ty_n;
-    if (gy > gy_max) gy = gy_max;
-    if (gy > 65535) gy = 65535;
-    const dim3 grid(gx, (unsigned)gy);
+    const uint32_t ppr = (uint32_t)(cols >> 3);
+    const uint64_t total = (uint64_t)rows * ppr;
+    if (total > 0xffffffffull - 1024u) return ALISE_UNSUPPORTED;      // the piece index is 32 bits wide (64 GiB of fp16)
+    const dim3 grid((unsigned)((total + 1023u) / 1024u));
     if (bias)
         hipLaunchKernelGGL(bias_relu_kernel<true>, grid, dim3(256), 0, s, static_cast<const _Float16 *>(x),
-                           static_cast<const _Float16 *>(bias), static_cast<_Float16 *>(y_out), rows, cols, log_tx);
+                           static_cast<const _Float16 *>(bias), static_cast<_Float16 *>(y_out), (uint32_t)total, ppr);
     else
         hipLaunchKernelGGL(bias_relu_kernel<false>, grid, dim3(256), 0, s, static_cast<const _Float16 *>(x),
-                           static_cast<const _Float16 *>(bias), static_cast<_Float16 *>(y_out), rows, cols, log_tx);
+                           static_cast<const _Float16 *>(bias), static_cast<_Float16 *>(y_out), (uint32_t)total, ppr);
     return hipGetLastError() == hipSuccess ? ALISE_OK : ALISE_HIP_ERROR;
 }
 
