@@ -35,6 +35,8 @@ EXPORTS = ("alise_kv_codes_bytes", "alise_kv_meta_bytes", "alise_kv_quant_write"
            "alise_kv_dequant_page", "alise_kv_swap_bytes", "alise_kv_swap_out", "alise_kv_swap_in",
            "alise_paged_prefill_attn_workspace_bytes", "alise_paged_prefill_attn",
            "alise_add_layernorm", "alise_bias_relu",
+           "alise_sched_create", "alise_sched_destroy", "alise_sched_add_job", "alise_sched_num_jobs",
+           "alise_sched_step", "alise_sched_commit",
            "alise_status_string")
 
 
@@ -283,6 +285,82 @@ def alise_bias_relu(x: torch.Tensor, bias, y_out: torch.Tensor) -> None:
     assert bias is None or (bias.dtype == torch.float16 and bias.is_cuda and bias.is_contiguous() and bias.shape == (cols,))
     st = _lib.alise_bias_relu(_dp(x), _dp(bias), _dp(y_out), rows, cols, _stream())
     _check(st, "alise_bias_relu")
+
+
+class alise_sched_config(ctypes.Structure):
+    _fields_ = [("num_queues", ctypes.c_int32), ("max_batch", ctypes.c_int32), ("gpu_job_limit", ctypes.c_int32),
+                ("reserved", ctypes.c_int32), ("limit0", ctypes.c_int64), ("age_threshold", ctypes.c_int64),
+                ("t0", ctypes.c_int64), ("alpha", ctypes.c_int64), ("beta", ctypes.c_int64)]
+
+
+_I64P, _I32P = ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int32)
+
+
+class alise_sched_decision(ctypes.Structure):
+    _fields_ = [("batch_ids", _I64P), ("batch_phase", _I32P), ("batch_cap", ctypes.c_int32), ("n_batch", ctypes.c_int32),
+                ("upload_ids", _I64P), ("upload_cap", ctypes.c_int32), ("n_upload", ctypes.c_int32),
+                ("offload_ids", _I64P), ("offload_cap", ctypes.c_int32), ("n_offload", ctypes.c_int32),
+                ("order_ids", _I64P), ("order_queue", _I32P), ("order_ewt", _I64P), ("order_cap", ctypes.c_int32),
+                ("n_order", ctypes.c_int32), ("model_time", ctypes.c_int64)]
+
+
+_lib.alise_sched_create.restype = ctypes.c_int
+_lib.alise_sched_create.argtypes = [ctypes.POINTER(alise_sched_config), ctypes.POINTER(ctypes.c_void_p)]
+_lib.alise_sched_destroy.restype = None
+_lib.alise_sched_destroy.argtypes = [ctypes.c_void_p]
+_lib.alise_sched_add_job.restype = ctypes.c_int
+_lib.alise_sched_add_job.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32]
+_lib.alise_sched_num_jobs.restype = ctypes.c_int32
+_lib.alise_sched_num_jobs.argtypes = [ctypes.c_void_p]
+_lib.alise_sched_step.restype = ctypes.c_int
+_lib.alise_sched_step.argtypes = [ctypes.c_void_p, ctypes.POINTER(alise_sched_decision)]
+_lib.alise_sched_commit.restype = ctypes.c_int
+_lib.alise_sched_commit.argtypes = [ctypes.c_void_p, ctypes.c_int64, _I64P, ctypes.c_int32]
+
+
+class Scheduler:
+    """The scheduler object of alise_sched.h; argument marshalling only.  ``step()`` returns a dict of lists."""
+
+    def __init__(self, num_queues, limit0, age_threshold, max_batch, gpu_job_limit, t0, alpha, beta, want_order=True):
+        self.cfg = alise_sched_config(num_queues, max_batch, gpu_job_limit, 0, limit0, age_threshold, t0, alpha, beta)
+        self._h = ctypes.c_void_p()
+        _check(_lib.alise_sched_create(ctypes.byref(self.cfg), ctypes.byref(self._h)), "alise_sched_create")
+        self.want_order = want_order
+        self._cap = 0
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            _lib.alise_sched_destroy(self._h)
+            self._h = None
+
+    def add_job(self, id, arrival, prompt_len, predicted_len):
+        _check(_lib.alise_sched_add_job(self._h, int(id), int(arrival), int(prompt_len), int(predicted_len)), "alise_sched_add_job")
+
+    def num_jobs(self):
+        return int(_lib.alise_sched_num_jobs(self._h))
+
+    def _buffers(self, n):
+        if n > self._cap:
+            self._cap = max(16, 2 * n)
+            c = self._cap
+            self._b = ((ctypes.c_int64 * c)(), (ctypes.c_int32 * c)(), (ctypes.c_int64 * c)(), (ctypes.c_int64 * c)(),
+                       (ctypes.c_int64 * c)(), (ctypes.c_int32 * c)(), (ctypes.c_int64 * c)())
+        return self._b
+
+    def step(self):
+        n = self.num_jobs()
+        bi, bp, up, off, oi, oq, oe = self._buffers(n)
+        c = self._cap
+        d = alise_sched_decision(bi, bp, c, 0, up, c, 0, off, c, 0,
+                                 oi if self.want_order else None, oq if self.want_order else None,
+                                 oe if self.want_order else None, c if self.want_order else 0, 0, 0)
+        _check(_lib.alise_sched_step(self._h, ctypes.byref(d)), "alise_sched_step")
+        return {"batch": bi[:d.n_batch], "phase": bp[:d.n_batch], "upload": up[:d.n_upload], "offload": off[:d.n_offload],
+                "order": oi[:d.n_order], "queue": oq[:d.n_order], "ewt": oe[:d.n_order], "model_time": int(d.model_time)}
+
+    def commit(self, elapsed, finished):
+        f = (ctypes.c_int64 * max(1, len(finished)))(*finished)
+        _check(_lib.alise_sched_commit(self._h, int(elapsed), f, len(finished)), "alise_sched_commit")
 
 
 def raw():
