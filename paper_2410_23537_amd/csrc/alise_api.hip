@@ -74,8 +74,10 @@ int check_cache_pointers(const alise_kv_cache *c)
 // the default (a multiple of 64) for tuning.
 // A split never spans more than 64 pages: the attention kernel keeps a split's
 // block-table entries in one register, one entry per lane.
-// The matrix-core path hands a whole group of query heads to one wave, so it has fewer
-// items per tile and takes shorter tiles (ALISE_SPLIT_TOKENS_GQA overrides).
+// The matrix-core path hands a whole group of query heads to one wave; starting and ending
+// an item costs it several microseconds (query rows, partial results of up to 16 heads), so
+// it takes the longest splits the 64-page window allows, up to 2048 tokens
+// (ALISE_SPLIT_TOKENS_GQA overrides).
 // Returns the largest split; *min_split is the smallest the plan kernel may fall back to
 // when a batch is too small to give every wave several items (equal to the largest when
 // the environment fixes the split).
@@ -84,7 +86,7 @@ int32_t split_tokens(int32_t page_size, bool gqa, int32_t *min_split)
     const char *e = std::getenv(gqa ? "ALISE_SPLIT_TOKENS_GQA" : "ALISE_SPLIT_TOKENS");
     long v = e ? std::strtol(e, nullptr, 10) : 0;
     const bool fixed = !(v < 64 || v > (1 << 20) || (v % 64) != 0);
-    if (!fixed) v = 1024;
+    if (!fixed) v = gqa ? 2048 : 1024;
     if (v > 64L * page_size) v = 64L * page_size;
     long lo = fixed ? v : 256;
     if (lo > v) lo = v;

@@ -715,8 +715,8 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
     const bool gqa = gqa_mfma_applies(c, H);
     // the plan kernel shortens the splits until every wave of a full grid (about eight waves
     // per compute unit) would get this many items; the matrix-core kernel, whose items are
-    // heavier to start, asks for fewer
-    p.ws.min_items = num_cus * 8 * (min_items_per_wave > 0 ? min_items_per_wave : (gqa ? 2 : 8));
+    // heavier to start, asks for one
+    p.ws.min_items = num_cus * 8 * (min_items_per_wave > 0 ? min_items_per_wave : (gqa ? 1 : 8));
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, s, context_lens, B, H, gqa ? c.Hkv : H, max_context_len, p.ws,
                        p.out, c.D);
     hipError_t e = hipGetLastError();

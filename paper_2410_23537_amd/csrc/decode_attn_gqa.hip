@@ -435,6 +435,7 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
         }
 
         // ---- per query head: add the four quarters; then fetch the values of this lane's rows
+        fill();                     // the stage just freed: keep loads in flight through the item's end and the next one's start
         float l = l_part + __shfl_xor(l_part, 16);
         l += __shfl_xor(l, 32);
         float zsum[NGRP];
