@@ -72,8 +72,10 @@ int check_cache_pointers(const alise_kv_cache *c)
 // Tokens per split.  Long requests are cut into splits of this many tokens so that
 // one long and many short requests fill the chip alike; ALISE_SPLIT_TOKENS overrides
 // the default (a multiple of 64) for tuning.
-// A split never spans more than 64 pages: the attention kernel keeps a split's
-// block-table entries in one register, one entry per lane.
+// A split never spans more than 128 pages (64 on the matrix-core path): the attention
+// kernel keeps a split's block-table entries in two registers (one), one entry per lane.
+// Every item costs a wave a few microseconds at its end (the reduction over its token slots,
+// the partial result), so splits are as long as that allows, up to 2048 tokens.
 // The matrix-core path hands a whole group of query heads to one wave; starting and ending
 // an item costs it several microseconds (query rows, partial results of up to 16 heads), so
 // it takes the longest splits the 64-page window allows, up to 2048 tokens
@@ -86,8 +88,9 @@ int32_t split_tokens(int32_t page_size, bool gqa, int32_t *min_split)
     const char *e = std::getenv(gqa ? "ALISE_SPLIT_TOKENS_GQA" : "ALISE_SPLIT_TOKENS");
     long v = e ? std::strtol(e, nullptr, 10) : 0;
     const bool fixed = !(v < 64 || v > (1 << 20) || (v % 64) != 0);
-    if (!fixed) v = gqa ? 2048 : 1024;
-    if (v > 64L * page_size) v = 64L * page_size;
+    if (!fixed) v = 2048;
+    const long window = gqa ? 64 : 128;         // pages whose block-table entries a wave keeps at hand
+    if (v > window * page_size) v = window * page_size;
     long lo = fixed ? v : 256;
     if (lo > v) lo = v;
     if (min_split) *min_split = (int32_t)lo;

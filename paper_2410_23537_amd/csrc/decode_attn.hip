@@ -363,6 +363,11 @@ __device__ __forceinline__ void consume_one(const uint4 kc, const uint4 vc, cons
     }
 }
 
+// The block-table entries of a tile's pages: entry win_first + lane in `lo`, win_first + 64 + lane in `hi`.
+struct PageWindow {
+    int lo, hi;
+};
+
 // One work item: a tile (request, token range) for one query head.  Everything is
 // wave-uniform except `pg`, which holds the tile's block-table entries, one per lane.
 struct TileCtx {
@@ -436,10 +441,14 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(AttnParams p)
         c.win_first = c.t0 >> logP;
         return c;
     };
-    // a tile spans at most 64 pages, so one entry per lane covers it
+    // a tile spans at most 128 pages, so two entries per lane cover it
     auto load_pg = [&](const TileCtx &c) {
         const int32_t *bt = p.block_tables + (int64_t)c.i * p.max_blocks;
-        return bt[min(c.win_first + lane, (c.t1 - 1) >> logP)];
+        const int last = (c.t1 - 1) >> logP;
+        PageWindow w;
+        w.lo = bt[min(c.win_first + lane, last)];
+        w.hi = bt[min(c.win_first + 64 + lane, last)];
+        return w;
     };
     auto load_q_raw = [&](const TileCtx &c, uint32_t (&raw)[SL / 2]) {
         const uint32_t *qsrc = reinterpret_cast<const uint32_t *>(p.q + ((int64_t)c.i * p.H + c.h) * D + ch0);
@@ -454,13 +463,15 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(AttnParams p)
     // around a load would make the compiler wait for every outstanding load at the join,
     // which serialises the two buffers.  Wave-loads past the end of the tile re-read its
     // last wave-load; their tokens are masked when consumed.
-    auto issue = [&](Buf<NB> &buf, const TileCtx &c, int pg, int k) {
+    auto issue = [&](Buf<NB> &buf, const TileCtx &c, const PageWindow &pg, int k) {
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
             const int w = min(k * NB + j, c.nw - 1);
             const int tw = c.t0 + w * TPW;
             if constexpr (UNI) {
-                const int page = __builtin_amdgcn_readlane(pg, (tw >> logP) - c.win_first);
+                const int idx = (tw >> logP) - c.win_first;             // wave-uniform, 0 .. 127
+                const int e_lo = __builtin_amdgcn_readlane(pg.lo, idx & 63), e_hi = __builtin_amdgcn_readlane(pg.hi, idx & 63);
+                const int page = idx < 64 ? e_lo : e_hi;
                 const int blk = page * Hkv + c.hk;                    // < 2^31, checked on the host
                 const int off = tw & (P - 1);
                 const int64_t co = (int64_t)blk * p.c.cstride + off * ROWB;
@@ -472,7 +483,9 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(AttnParams p)
             } else {
                 const int tok = tw + slot;
                 const int tc = tok < c.t1 ? tok : c.t1 - 1;        // stay on a real token
-                const int page = __shfl(pg, (tc >> logP) - c.win_first);
+                const int idx = (tc >> logP) - c.win_first;
+                const int e_lo = __shfl(pg.lo, idx & 63), e_hi = __shfl(pg.hi, idx & 63);
+                const int page = idx < 64 ? e_lo : e_hi;
                 const int blk = page * Hkv + c.hk;
                 const int off = tc & (P - 1);
                 const int64_t co = (int64_t)blk * p.c.cstride + off * ROWB + sub * 16;
@@ -491,8 +504,8 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(AttnParams p)
     TileCtx cur = make_ctx(it0, desc_of(it0));
     if (!cur.valid) return;                     // wave-uniform
     TileCtx nxt = make_ctx(it1, desc_of(it1));
-    int pg_cur = load_pg(cur);
-    int pg_nxt = load_pg(nxt);
+    PageWindow pg_cur = load_pg(cur);
+    PageWindow pg_nxt = load_pg(nxt);
     uint32_t qraw[SL / 2];
     load_q_raw(cur, qraw);
     Buf<NB> bufA, bufB;
@@ -716,7 +729,7 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
     // the plan kernel shortens the splits until every wave of a full grid (about eight waves
     // per compute unit) would get this many items; the matrix-core kernel, whose items are
     // heavier to start, asks for one
-    p.ws.min_items = num_cus * 8 * (min_items_per_wave > 0 ? min_items_per_wave : (gqa ? 1 : 8));
+    p.ws.min_items = num_cus * 8 * (min_items_per_wave > 0 ? min_items_per_wave : (gqa ? 1 : 4));
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, s, context_lens, B, H, gqa ? c.Hkv : H, max_context_len, p.ws,
                        p.out, c.D);
     hipError_t e = hipGetLastError();
