@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published peak HBM3E bandwidth
 
 # HBM bytes per attention launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a
 # copy kernel of known size; see profiles/.  None where not measured.
-MEASURED_TRAFFIC_BYTES = {"int4": 7200323825, "gqa70b": 1112229165, "llama7b": 1999709357}
+MEASURED_TRAFFIC_BYTES = {"int4": 7186998285, "gqa70b": 1103043357, "llama7b": 1998455357}
 
 
 def parse():
@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--workload", default="int4")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only-steps", action="store_true",
+                    help="skip the legs outside the timed steps (swap, prefill, fused operators, scheduler): for profiler runs")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also launch an elementwise kernel that reads and writes exactly 1 GiB, so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run of this command can be scaled")
@@ -398,12 +400,13 @@ def main():
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(w.name)},
     }
-    result["swap"] = swap_leg(step)
-    prefill = prefill_leg(w, step)
-    if prefill is not None:
-        result["prefill"] = prefill
-    result["fused_ops"] = fused_ops_leg(w)
-    result["scheduler"] = scheduled_run_leg(w)
+    if not args.only_steps:
+        result["swap"] = swap_leg(step)
+        prefill = prefill_leg(w, step)
+        if prefill is not None:
+            result["prefill"] = prefill
+        result["fused_ops"] = fused_ops_leg(w)
+        result["scheduler"] = scheduled_run_leg(w)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, step, args.cpu_seconds)
     print(json.dumps(result), flush=True)
