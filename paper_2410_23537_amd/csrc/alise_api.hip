@@ -284,7 +284,7 @@ int alise_kv_dequant_page(const alise_kv_cache *c, int32_t page, void *k_out, vo
 static size_t carve_prefill(const CacheView &cv, int32_t B, int32_t total_q, int32_t H, void *base,
                             alise::PrefillWorkspace *ws)
 {
-    const int tpw = alise::prefill_tokens_per_workgroup(H / cv.Hkv);
+    const int tpw = alise::prefill_tokens_per_workgroup(H / cv.Hkv, 1);      // the smaller tile: an upper bound on the tile count
     const int64_t max_tiles = ((int64_t)total_q + tpw - 1) / tpw + B;
     const size_t bytes = align_up(256 + sizeof(int32_t) * 2 * (size_t)max_tiles, 256);
     if (ws) {

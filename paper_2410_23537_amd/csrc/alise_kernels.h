@@ -45,7 +45,7 @@ struct PrefillWorkspace {
 
 // Shapes the matrix-core prefill kernel takes (INT8, D = 128, G in {64, 128}, P >= 16, 1..16 query heads per KV head).
 bool prefill_mfma_applies(const CacheView &c, int32_t H);
-int32_t prefill_tokens_per_workgroup(int32_t qper);
+int32_t prefill_tokens_per_workgroup(int32_t qper, int32_t row_tiles);
 
 hipError_t launch_prefill_attn(const CacheView &c, const void *q, void *out, const int32_t *q_start,
                                const int32_t *block_tables, int32_t max_blocks, const int32_t *context_lens,

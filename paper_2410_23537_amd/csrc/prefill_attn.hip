@@ -22,6 +22,7 @@
 // The block-table entries of the 64 pages around the current position sit in a register (one
 // entry per lane), refilled every 64 pages from a window fetched ahead of time into LDS.
 #include "mfma_stream.h"
+#include <cstdlib>
 #include <type_traits>
 
 namespace alise {
@@ -79,7 +80,8 @@ __global__ __launch_bounds__(1024) void prefill_plan_kernel(const int32_t *q_sta
     if (tid == 0) *ws.n_tiles = s_total < ws.max_tiles ? s_total : ws.max_tiles;
 }
 
-template <int NGRP>
+// RT: 16-row tiles per wave.  Two tiles share every code -> fp16 conversion and every LDS read of a step.
+template <int NGRP, int RT>
 __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
 {
     constexpr int D = 128, ROWB = 128, S = 3;
@@ -107,12 +109,20 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
     const int qs = p.q_start[i];
     int n_q = p.q_start[i + 1] - qs;
     n_q = min(max(n_q, 0), L);
-    const int TT = 16 / qper;                   // query tokens per wave
+    const int TT = 16 * RT / qper;              // query tokens per wave
     const int first_pos = L - n_q;              // position of the chunk's first token
     const int j0 = (rt * 4 + wave) * TT;        // this wave's first query token
-    const int j_n = j0 + n / qper, e_n = n % qper;
-    const bool row_valid = n < TT * qper && j_n < n_q;
-    const int pos_n = row_valid ? first_pos + j_n : -1;             // what row n may see: tokens <= pos_n
+    // row tile t, column n of the matrix layouts <-> row 16 t + n of the wave's 16 RT rows <-> (token, head of the group)
+    int j_n[RT], e_n[RT], pos_n[RT];
+    bool row_valid[RT];
+#pragma unroll
+    for (int t = 0; t < RT; ++t) {
+        const int row = 16 * t + n;
+        j_n[t] = j0 + row / qper;
+        e_n[t] = row % qper;
+        row_valid[t] = row < TT * qper && j_n[t] < n_q;
+        pos_n[t] = row_valid[t] ? first_pos + j_n[t] : -1;          // what the row may see: tokens <= pos_n
+    }
     const int wave_last = first_pos + min(j0 + TT, n_q) - 1;         // last position any row of this wave sees (< first_pos + j0: none)
     const bool wave_has_rows = j0 < n_q;
     const int kv_end = first_pos + min((rt + 1) * 4 * TT, n_q);     // the workgroup walks positions [0, kv_end)
@@ -132,19 +142,20 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
     const uint32_t m_rd = g * 16 * NGRP;
 
     // ---- Q^T as the B operand of the four k-chunks: chunk jj, slot g*8+e <-> channel (jj/2)*64 + g*16 + (jj%2)*8 + e
-    h8_t qop[4];
-    float qsum[NGRP];
-    {
-        const int jc = min(j_n, n_q - 1);
-        const _Float16 *qrow = p.q + ((int64_t)(qs + jc) * H + hk * qper + e_n) * D;
+    h8_t qop[RT][4];
+    float nqs24[RT][NGRP];                  // -sum(q) 2^-24 over the channels of a group
+#pragma unroll
+    for (int t = 0; t < RT; ++t) {
+        const int jc = min(j_n[t], n_q - 1);
+        const _Float16 *qrow = p.q + ((int64_t)(qs + jc) * H + hk * qper + e_n[t]) * D;
         float part_sum[NGRP];
 #pragma unroll
         for (int gr = 0; gr < NGRP; ++gr) part_sum[gr] = 0.0f;
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
             h8_t v = *reinterpret_cast<const h8_t *>(qrow + (jj / 2) * 64 + g * 16 + (jj % 2) * 8);
-            if (!row_valid) v = (h8_t)(_Float16)0.0f;
-            qop[jj] = v;
+            if (!row_valid[t]) v = (h8_t)(_Float16)0.0f;
+            qop[t][jj] = v;
             float sacc = 0.0f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) sacc += (float)v[e];
@@ -155,7 +166,7 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
             float v = part_sum[gr];
             v += __shfl_xor(v, 16);
             v += __shfl_xor(v, 32);
-            qsum[gr] = v;
+            nqs24[t][gr] = -v * (1.0f / 16777216.0f);
         }
     }
     // Scores are kept in the units of the accumulator: t = sum_g lambda_k (acc_g - z_k sum(q_g) 2^-24), the true
@@ -163,9 +174,6 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
     const float scale24 = p.scale_log2e * 16777216.0f;
     const float inv24 = 1.0f / scale24;
     const float lazy_t = kLazy * inv24;
-    float nqs24[NGRP];                      // -sum(q) 2^-24
-#pragma unroll
-    for (int gr = 0; gr < NGRP; ++gr) nqs24[gr] = -qsum[gr] * (1.0f / 16777216.0f);
 
     // ---- block-table windows: 64 entries, one per lane.  Lookups use window wa in pg_a; the
     // windows come through LDS by direct loads (two slots per wave), fetched one window ahead,
@@ -208,23 +216,30 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
     };
 
     // m_ref: the running maximum in the units of t.  c_ref = bias - m_ref scale24: a weight is 2^(t scale24 + c_ref).
-    float m_ref = kFloor * inv24, l_part = 0.0f, z_part[NGRP];
-    float bias = kWeightBias;           // see kWeightBias; wave-uniform
-    float c_ref = __builtin_fmaf(-m_ref, scale24, bias);
+    float m_ref[RT], c_ref[RT], l_part[RT], z_part[RT][NGRP];
+    float bias = kWeightBias;           // see kWeightBias; wave-uniform, common to the row tiles
+    f4_t o[RT][8];              // [tile][set*4 + nu]: rows 4g..4g+3 of the tile, column n <-> channel 64*set + 4n + nu
 #pragma unroll
-    for (int gr = 0; gr < NGRP; ++gr) z_part[gr] = 0.0f;
-    f4_t o[8];                  // [set*4 + nu]: rows 4g..4g+3, column n <-> channel 64*set + 4n + nu
+    for (int t = 0; t < RT; ++t) {
+        m_ref[t] = kFloor * inv24;
+        c_ref[t] = __builtin_fmaf(-m_ref[t], scale24, bias);
+        l_part[t] = 0.0f;
 #pragma unroll
-    for (int t = 0; t < 8; ++t) o[t] = (f4_t)0.0f;
+        for (int gr = 0; gr < NGRP; ++gr) z_part[t][gr] = 0.0f;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) o[t][c] = (f4_t)0.0f;
+    }
 
     // One step of 32 tokens out of the LDS stage at `base`.  MASKED: some row of this wave must not see
     // some token of the step (the steps on the diagonal); otherwise no comparison and no select is spent.
     auto step = [&](auto masked_c, int k, uint32_t base) {
         constexpr bool MASKED = decltype(masked_c)::value;
-        // ---- S^T = K Q^T for the two 16-token tiles
-        float s[2][4];
-        uint32_t vmraw[2][4][NGRP];        // V (scale, zero) dwords of this lane's tokens; 0 where the token is masked
-        float mx = kNegInf;
+        // ---- S^T = K Q^T for the two 16-token tiles, every row tile against the same K operands
+        float s[RT][2][4];
+        uint32_t vmraw[MASKED ? RT : 1][2][4][NGRP];   // V (scale, zero) dwords of this lane's tokens; 0 where a row tile must not see the token
+        float mx[RT];
+#pragma unroll
+        for (int t = 0; t < RT; ++t) mx[t] = kNegInf;
         uint4 kp[2][2];
         const uint32_t ka0 = base + k_rd, ka1 = ka0 ^ 64u, ma = base + m_rd;
         lds_read16x4_at<0, 0, TILEB, TILEB>(ka0, ka1, ka0, ka1, kp[0][0], kp[0][1], kp[1][0], kp[1][1]);
@@ -238,9 +253,11 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
         }
 #pragma unroll
         for (int x = 0; x < 2; ++x) {
-            f4_t acc[NGRP];
+            f4_t acc[RT][NGRP];
 #pragma unroll
-            for (int gr = 0; gr < NGRP; ++gr) acc[gr] = (f4_t)0.0f;
+            for (int t = 0; t < RT; ++t)
+#pragma unroll
+                for (int gr = 0; gr < NGRP; ++gr) acc[t][gr] = (f4_t)0.0f;
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) {
                 const uint4 piece = kp[x][jj / 2];
@@ -249,95 +266,115 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
                                      __builtin_amdgcn_perm(0u, w0, 0x0c030c02u),
                                      __builtin_amdgcn_perm(0u, w1, 0x0c010c00u),
                                      __builtin_amdgcn_perm(0u, w1, 0x0c030c02u));
-                f4_t &dst = acc[NGRP == 2 ? jj / 2 : 0];
-                dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, qop[jj], dst, 0, 0, 0);
-            }
-            const int room = pos_n - (k * kStep + x * 16 + g * 4);     // row r of this lane's S^T block is visible iff r <= room
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const bool valid = !MASKED || r <= room;        // causal, per row of the problem
-                float sv = 0.0f;
-#pragma unroll
-                for (int gr = 0; gr < NGRP; ++gr) {
-                    const h2_t kmh = as_h2(meta_of<NGRP>(kmeta[x], r, gr));     // the fp16 halves of the meta dword, read in place
-                    const float u = __builtin_fmaf((float)kmh.y, nqs24[gr], acc[gr][r]);
-                    sv = __builtin_fmaf((float)kmh.x, u, sv);
-                    const uint32_t vm = meta_of<NGRP>(vmeta[x], r, gr);
-                    vmraw[x][r][gr] = valid ? vm : 0u;
+                for (int t = 0; t < RT; ++t) {
+                    f4_t &dst = acc[t][NGRP == 2 ? jj / 2 : 0];
+                    dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, qop[t][jj], dst, 0, 0, 0);
                 }
-                s[x][r] = valid ? sv : kNegInf;
-                mx = fmaxf(mx, s[x][r]);
+            }
+            const int tok0 = k * kStep + x * 16 + g * 4;                // first token of this lane's 4 rows of S^T
+#pragma unroll
+            for (int t = 0; t < RT; ++t) {
+                const int room = pos_n[t] - tok0;                       // row r of the block is visible iff r <= room
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const bool valid = !MASKED || r <= room;            // causal, per row of the problem
+                    float sv = 0.0f;
+#pragma unroll
+                    for (int gr = 0; gr < NGRP; ++gr) {
+                        const h2_t kmh = as_h2(meta_of<NGRP>(kmeta[x], r, gr));     // the fp16 halves of the meta dword, read in place
+                        const float u = __builtin_fmaf((float)kmh.y, nqs24[t][gr], acc[t][gr][r]);
+                        sv = __builtin_fmaf((float)kmh.x, u, sv);
+                        if (MASKED || t == 0) {
+                            const uint32_t vm = meta_of<NGRP>(vmeta[x], r, gr);
+                            vmraw[MASKED ? t : 0][x][r][gr] = valid ? vm : 0u;
+                        }
+                    }
+                    s[t][x][r] = valid ? sv : kNegInf;
+                    mx[t] = fmaxf(mx[t], s[t][x][r]);
+                }
             }
         }
 
         // ---- running maximum per row of the problem, raised lazily; all four quarters hold the same value
-        if (__builtin_amdgcn_ballot_w64(mx > m_ref + lazy_t) != 0) {
-            float mq = fmaxf(mx, __shfl_xor(mx, 16));
-            mq = fmaxf(mq, __shfl_xor(mq, 32));
-            m_ref = (mq > m_ref + lazy_t) ? mq : m_ref;
-            const float c_new = __builtin_fmaf(-m_ref, scale24, bias);
-            const float fac = __builtin_amdgcn_exp2f(c_new - c_ref);
-            c_ref = c_new;
-            l_part *= fac;
 #pragma unroll
-            for (int gr = 0; gr < NGRP; ++gr) z_part[gr] *= fac;
+        for (int t = 0; t < RT; ++t) {
+            if (__builtin_amdgcn_ballot_w64(mx[t] > m_ref[t] + lazy_t) != 0) {
+                float mq = fmaxf(mx[t], __shfl_xor(mx[t], 16));
+                mq = fmaxf(mq, __shfl_xor(mq, 32));
+                m_ref[t] = (mq > m_ref[t] + lazy_t) ? mq : m_ref[t];
+                const float c_new = __builtin_fmaf(-m_ref[t], scale24, bias);
+                const float fac = __builtin_amdgcn_exp2f(c_new - c_ref[t]);
+                c_ref[t] = c_new;
+                l_part[t] *= fac;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float fr = __shfl(fac, 4 * g + r);        // factor of the problem row 4g+r
+                for (int gr = 0; gr < NGRP; ++gr) z_part[t][gr] *= fac;
 #pragma unroll
-                for (int t = 0; t < 8; ++t) o[t][r] *= fr;
+                for (int r = 0; r < 4; ++r) {
+                    const float fr = __shfl(fac, 4 * g + r);        // factor of the problem row 4g+r
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) o[t][c][r] *= fr;
+                }
             }
         }
 
         // ---- a V scale of 2 or more in this step: the biased weights could leave the fp16 range (rare, wave-uniform)
-        if (bias != 0.0f && __builtin_amdgcn_ballot_w64(max_low_half<8 * NGRP>(&vmraw[0][0][0]) >= 0x4000u) != 0) {
+        if (bias != 0.0f &&
+            __builtin_amdgcn_ballot_w64(max_low_half<(MASKED ? RT : 1) * 8 * NGRP>(&vmraw[0][0][0][0]) >= 0x4000u) != 0) {
             bias = 0.0f;
-            const float c_new = __builtin_fmaf(-m_ref, scale24, 0.0f);
-            const float fb = __builtin_amdgcn_exp2f(c_new - c_ref);
-            c_ref = c_new;
-            l_part *= fb;
 #pragma unroll
-            for (int gr = 0; gr < NGRP; ++gr) z_part[gr] *= fb;
+            for (int t = 0; t < RT; ++t) {
+                const float c_new = __builtin_fmaf(-m_ref[t], scale24, 0.0f);
+                const float fb = __builtin_amdgcn_exp2f(c_new - c_ref[t]);
+                c_ref[t] = c_new;
+                l_part[t] *= fb;
 #pragma unroll
-            for (int t = 0; t < 8; ++t) o[t] *= fb;
+                for (int gr = 0; gr < NGRP; ++gr) z_part[t][gr] *= fb;
+#pragma unroll
+                for (int c = 0; c < 8; ++c) o[t][c] *= fb;
+            }
         }
 
         // ---- weights p * lambda_v as fp16 high + low parts, in the A-operand order (tile, row).  The high
         // part is the product truncated to fp16, the low part what is left of the exact product.
-        h8_t a_hi[NGRP], a_lo[NGRP];
+        h8_t a_hi[RT][NGRP], a_lo[RT][NGRP];
 #pragma unroll
-        for (int x = 0; x < 2; ++x)
+        for (int t = 0; t < RT; ++t)
 #pragma unroll
-            for (int rr = 0; rr < 4; rr += 2) {
-                float pj[2];
+            for (int x = 0; x < 2; ++x)
 #pragma unroll
-                for (int e = 0; e < 2; ++e) {
-                    pj[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[x][rr + e], scale24, c_ref));
-                    l_part += pj[e];
-                }
-#pragma unroll
-                for (int gr = 0; gr < NGRP; ++gr) {
-                    float wv[2];
+                for (int rr = 0; rr < 4; rr += 2) {
+                    float pj[2];
 #pragma unroll
                     for (int e = 0; e < 2; ++e) {
-                        const h2_t vmh = as_h2(vmraw[x][rr + e][gr]);
-                        wv[e] = __builtin_fmaf((float)vmh.x, pj[e], 0.0f);
-                        z_part[gr] = __builtin_fmaf((float)vmh.y, wv[e], z_part[gr]);
+                        pj[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[t][x][rr + e], scale24, c_ref[t]));
+                        l_part[t] += pj[e];
                     }
-                    const h2_t hi = __builtin_bit_cast(h2_t, __builtin_amdgcn_cvt_pkrtz(wv[0], wv[1]));
 #pragma unroll
-                    for (int e = 0; e < 2; ++e) {
-                        a_hi[gr][x * 4 + rr + e] = hi[e];
-                        a_lo[gr][x * 4 + rr + e] = (_Float16)__builtin_fmaf((float)as_h2(vmraw[x][rr + e][gr]).x, pj[e], -(float)hi[e]);
+                    for (int gr = 0; gr < NGRP; ++gr) {
+                        float wv[2];
+                        uint32_t vm[2];
+#pragma unroll
+                        for (int e = 0; e < 2; ++e) {
+                            vm[e] = vmraw[MASKED ? t : 0][x][rr + e][gr];
+                            const h2_t vmh = as_h2(vm[e]);
+                            wv[e] = __builtin_fmaf((float)vmh.x, pj[e], 0.0f);
+                            z_part[t][gr] = __builtin_fmaf((float)vmh.y, wv[e], z_part[t][gr]);
+                        }
+                        const h2_t hi = __builtin_bit_cast(h2_t, __builtin_amdgcn_cvt_pkrtz(wv[0], wv[1]));
+#pragma unroll
+                        for (int e = 0; e < 2; ++e) {
+                            a_hi[t][gr][x * 4 + rr + e] = hi[e];
+                            a_lo[t][gr][x * 4 + rr + e] = (_Float16)__builtin_fmaf((float)as_h2(vm[e]).x, pj[e], -(float)hi[e]);
+                        }
                     }
                 }
-            }
 
-        // ---- O += P V: byte nu of the dwords of two tokens -> two fp16 subnormals
+        // ---- O += P V: byte nu of the dwords of two tokens -> two fp16 subnormals, once for all row tiles
         uint32_t va[8], vd[2][8];          // vd[tile][set * 4 + r]
         va[0] = v_rd + base;
 #pragma unroll
-        for (int t = 1; t < 8; ++t) va[t] = va[0] ^ (uint32_t)((t & 3) * 16 + (t >> 2) * 64);
+        for (int c = 1; c < 8; ++c) va[c] = va[0] ^ (uint32_t)((c & 3) * 16 + (c >> 2) * 64);
         lds_read4x8x2<ROWB, TILEB>(va, vd[0], vd[1]);
 #pragma unroll
         for (int set = 0; set < 2; ++set)
@@ -349,9 +386,12 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
                                       __builtin_amdgcn_perm(vd[1][set * 4 + 1], vd[1][set * 4 + 0], sel),
                                       __builtin_amdgcn_perm(vd[1][set * 4 + 3], vd[1][set * 4 + 2], sel));
                 const int gr = NGRP == 2 ? set : 0;
-                f4_t &dst = o[set * 4 + nu];
-                dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_hi[gr], bv, dst, 0, 0, 0);
-                dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_lo[gr], bv, dst, 0, 0, 0);
+#pragma unroll
+                for (int t = 0; t < RT; ++t) {
+                    f4_t &dst = o[t][set * 4 + nu];
+                    dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_hi[t][gr], bv, dst, 0, 0, 0);
+                    dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_lo[t][gr], bv, dst, 0, 0, 0);
+                }
             }
     };
 
@@ -384,48 +424,61 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
     }
 
     // ---- per row of the problem: add the four quarters; then fetch the values of this lane's rows
-    float l = l_part + __shfl_xor(l_part, 16);
-    l += __shfl_xor(l, 32);
-    float zsum[NGRP];
 #pragma unroll
-    for (int gr = 0; gr < NGRP; ++gr) {
-        float v = z_part[gr] + __shfl_xor(z_part[gr], 16);
-        v += __shfl_xor(v, 32);
-        zsum[gr] = v;
-    }
+    for (int t = 0; t < RT; ++t) {
+        float l = l_part[t] + __shfl_xor(l_part[t], 16);
+        l += __shfl_xor(l, 32);
+        float zsum[NGRP];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int row = 4 * g + r;
-        const float l_row = __shfl(l, row);
-        float z_row[NGRP];
+        for (int gr = 0; gr < NGRP; ++gr) {
+            float v = z_part[t][gr] + __shfl_xor(z_part[t][gr], 16);
+            v += __shfl_xor(v, 32);
+            zsum[gr] = v;
+        }
 #pragma unroll
-        for (int gr = 0; gr < NGRP; ++gr) z_row[gr] = __shfl(zsum[gr], row);
-        const int j_r = j0 + row / qper, e_r = row % qper;
-        if (row < TT * qper && j_r < n_q) {
-            const float inv_l = 1.0f / l_row;
-            _Float16 *dst = p.out + ((int64_t)(qs + j_r) * H + hk * qper + e_r) * D + 4 * n;
+        for (int r = 0; r < 4; ++r) {
+            const int col = 4 * g + r;                  // column of the S^T layout that holds the row's l and z
+            const float l_row = __shfl(l, col);
+            float z_row[NGRP];
 #pragma unroll
-            for (int set = 0; set < 2; ++set) {
-                const float zr = z_row[NGRP == 2 ? set : 0];
-                typedef _Float16 h4_t __attribute__((ext_vector_type(4)));
-                h4_t v;
+            for (int gr = 0; gr < NGRP; ++gr) z_row[gr] = __shfl(zsum[gr], col);
+            const int row = 16 * t + col;
+            const int j_r = j0 + row / qper, e_r = row % qper;
+            if (row < TT * qper && j_r < n_q) {
+                const float inv_l = 1.0f / l_row;
+                _Float16 *dst = p.out + ((int64_t)(qs + j_r) * H + hk * qper + e_r) * D + 4 * n;
 #pragma unroll
-                for (int nu = 0; nu < 4; ++nu)
-                    v[nu] = (_Float16)(__builtin_fmaf(o[set * 4 + nu][r], 16777216.0f, -zr) * inv_l);
-                *reinterpret_cast<h4_t *>(dst + 64 * set) = v;
+                for (int set = 0; set < 2; ++set) {
+                    const float zr = z_row[NGRP == 2 ? set : 0];
+                    typedef _Float16 h4_t __attribute__((ext_vector_type(4)));
+                    h4_t v;
+#pragma unroll
+                    for (int nu = 0; nu < 4; ++nu)
+                        v[nu] = (_Float16)(__builtin_fmaf(o[t][set * 4 + nu][r], 16777216.0f, -zr) * inv_l);
+                    *reinterpret_cast<h4_t *>(dst + 64 * set) = v;
+                }
             }
         }
     }
 }
 
-// One scale group per head (G = 128) fits the register budget of four waves per SIMD, two groups that of three.
+// Register budgets: one 16-row tile per wave with one scale group per head (G = 128) fits four waves per
+// SIMD, with two groups three; two row tiles per wave take two waves per SIMD.
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void prefill_attn_kernel_g1(PrefillParams p)
 {
-    prefill_attn_body<1>(p);
+    prefill_attn_body<1, 1>(p);
 }
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void prefill_attn_kernel_g2(PrefillParams p)
 {
-    prefill_attn_body<2>(p);
+    prefill_attn_body<2, 1>(p);
+}
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_attn_kernel_g1_r2(PrefillParams p)
+{
+    prefill_attn_body<1, 2>(p);
+}
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_attn_kernel_g2_r2(PrefillParams p)
+{
+    prefill_attn_body<2, 2>(p);
 }
 
 }  // namespace
@@ -436,8 +489,15 @@ bool prefill_mfma_applies(const CacheView &c, int32_t H)
     return c.bits == 8 && c.D == 128 && (c.G == 128 || c.G == 64) && c.P >= 16 && qper >= 1 && qper <= 16;
 }
 
-// Query tokens per workgroup (four waves of 16 / qper tokens each).
-int32_t prefill_tokens_per_workgroup(int32_t qper) { return 4 * (16 / qper); }
+// Query tokens per workgroup: four waves of `row_tiles` 16-row tiles, a row being a (token, head of the group) pair.
+int32_t prefill_tokens_per_workgroup(int32_t qper, int32_t row_tiles) { return 4 * (16 * row_tiles / qper); }
+
+// Row tiles per wave: two, unless ALISE_PREFILL_ROW_TILES=1 (for tuning).
+static int32_t prefill_row_tiles()
+{
+    const char *e = std::getenv("ALISE_PREFILL_ROW_TILES");
+    return (e && e[0] == '1' && e[1] == 0) ? 1 : 2;
+}
 
 hipError_t launch_prefill_attn(const CacheView &c, const void *q, void *out, const int32_t *q_start,
                                const int32_t *block_tables, int32_t max_blocks, const int32_t *context_lens,
@@ -459,15 +519,20 @@ hipError_t launch_prefill_attn(const CacheView &c, const void *q, void *out, con
     p.max_len = max_context_len;
     p.scale_log2e = softmax_scale * 1.44269504088896340736f;
     p.ws = ws;
+    const int32_t rt = prefill_row_tiles();
     hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(1024), 0, s, q_start, context_lens, B,
-                       prefill_tokens_per_workgroup(p.qper), ws);
+                       prefill_tokens_per_workgroup(p.qper, rt), ws);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const dim3 grid((unsigned)ws.max_tiles, (unsigned)c.Hkv);
-    if (c.D / c.G == 1)
-        hipLaunchKernelGGL(prefill_attn_kernel_g1, grid, dim3(256), 0, s, p);
-    else
-        hipLaunchKernelGGL(prefill_attn_kernel_g2, grid, dim3(256), 0, s, p);
+    const dim3 grid((unsigned)ws.max_tiles, (unsigned)c.Hkv);         // sized for one row tile per wave: enough for two
+    const bool one_group = c.D / c.G == 1;
+    if (rt == 1) {
+        if (one_group) hipLaunchKernelGGL(prefill_attn_kernel_g1, grid, dim3(256), 0, s, p);
+        else hipLaunchKernelGGL(prefill_attn_kernel_g2, grid, dim3(256), 0, s, p);
+    } else {
+        if (one_group) hipLaunchKernelGGL(prefill_attn_kernel_g1_r2, grid, dim3(256), 0, s, p);
+        else hipLaunchKernelGGL(prefill_attn_kernel_g2_r2, grid, dim3(256), 0, s, p);
+    }
     return hipGetLastError();
 }
 
