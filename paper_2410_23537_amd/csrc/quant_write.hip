@@ -104,17 +104,19 @@ __global__ __launch_bounds__(256) void quant_write_kernel(QuantParams p)
         uint2 w;
         w.x = code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24);
         w.y = code[4] | (code[5] << 8) | (code[6] << 16) | (code[7] << 24);
-        *reinterpret_cast<uint2 *>(codes + lane_in_row * 8) = w;
+        typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+        const u32x2_t wv = {w.x, w.y};
+        __builtin_nontemporal_store(wv, reinterpret_cast<u32x2_t *>(codes + lane_in_row * 8));
     } else {
         uint32_t w = 0;
 #pragma unroll
         for (int i = 0; i < 8; ++i) w |= code[i] << (4 * i);   // channel 2i low nibble, 2i+1 high
-        *reinterpret_cast<uint32_t *>(codes + lane_in_row * 4) = w;
+        __builtin_nontemporal_store(w, reinterpret_cast<uint32_t *>(codes + lane_in_row * 4));
     }
     if ((lane_in_row % LPG) == 0) {
         const int grp = lane_in_row / LPG;
         const uint16_t zb = __builtin_bit_cast(uint16_t, (_Float16)zf);
-        meta[grp] = (uint32_t)hb | ((uint32_t)zb << 16);
+        __builtin_nontemporal_store((uint32_t)hb | ((uint32_t)zb << 16), meta + grp);
     }
 }
 
