@@ -154,10 +154,10 @@ def swap_leg(step):
 MFMA_F16_PEAK_TFLOPS = 2500.0
 
 
-def prefill_leg(w, step):
+def prefill_leg(w, step, every=8):
     """Chunked-prefill attention over the same cache (Sec. 2 "LLM Inference"), outside the timed
-    steps: every 8th request brings its last min(512, L) tokens as a chunk of query tokens that
-    attend causally over the request's quantized cache.  Bound: the fp16 matrix cores."""
+    steps: every `every`-th request brings its last min(512, L) tokens as a chunk of query tokens
+    that attend causally over the request's quantized cache.  Bound: the fp16 matrix cores."""
     import numpy as np
     import torch
     from paper_2410_23537_amd import binding as B
@@ -166,7 +166,7 @@ def prefill_leg(w, step):
     if ws_bytes == 0:
         return None                     # a layout the matrix-core prefill kernel does not take (INT4, head_dim 64)
     lens = step.lens.astype(np.int64)
-    n = np.array([min(512, int(L)) if i % 8 == 0 else 0 for i, L in enumerate(lens)], np.int64)
+    n = np.array([min(512, int(L)) if i % every == 0 else 0 for i, L in enumerate(lens)], np.int64)
     q_start = np.concatenate([[0], np.cumsum(n)]).astype(np.int32)
     total = int(q_start[-1])
     gen = torch.Generator(device="cuda").manual_seed(w.seed)
@@ -194,7 +194,8 @@ def prefill_leg(w, step):
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / reps
     tflops = flops / (ms * 1e-3) / 1e12
-    return {"workload": f"every 8th request of {w.name} brings its last min(512, L) tokens: {total} query tokens, "
+    which = "every request" if every == 1 else f"every {every}th request"
+    return {"workload": f"{which} of {w.name} brings its last min(512, L) tokens: {total} query tokens, "
                         f"{pairs} (query, visible key) pairs per head",
             "ms": ms, "flop": flops,
             "roofline": {"bound": "mfma", "achieved": tflops, "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -405,6 +406,7 @@ def main():
         prefill = prefill_leg(w, step)
         if prefill is not None:
             result["prefill"] = prefill
+            result["prefill_full_batch"] = prefill_leg(w, step, every=1)      # the same with a grid that fills the chip
         result["fused_ops"] = fused_ops_leg(w)
         result["scheduler"] = scheduled_run_leg(w)
     if not args.no_cpu_baseline:

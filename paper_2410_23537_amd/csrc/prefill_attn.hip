@@ -40,44 +40,61 @@ struct PrefillParams {
     PrefillWorkspace ws;
 };
 
-// One workgroup: tiles per request, their prefix sums, and the table of (request, row tile)
-// pairs, a request's later tiles first (they see more of the context and take longer, and
-// the hardware hands out workgroups in table order).
-__global__ __launch_bounds__(1024) void prefill_plan_kernel(const int32_t *q_start, const int32_t *context_lens,
-                                                            int32_t B, int32_t tokens_per_wg, PrefillWorkspace ws)
+// One workgroup writes the table of (request, row tile) pairs, ordered by decreasing work: a tile
+// walks the cache from position 0 to the last position its rows may see, so that position is its
+// cost, and the hardware hands out workgroups in table order -- longest first, which keeps the
+// tail of the grid short (a counting sort over 1024 length buckets; inside a bucket any order).
+__global__ __launch_bounds__(1024) void prefill_plan_kernel(const int32_t *q_start, const int32_t *context_lens, int32_t B,
+                                                            int32_t tokens_per_wg, int32_t max_len, PrefillWorkspace ws)
 {
+    __shared__ int32_t s_hist[1024];
     __shared__ int32_t s_wave[16];
-    __shared__ int32_t s_total;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid == 0) s_total = 0;
+    s_hist[tid] = 0;
     __syncthreads();
-    for (int base = 0; base < B; base += 1024) {
-        const int i = base + tid;
-        int n = 0;
-        if (i < B) {
-            n = q_start[i + 1] - q_start[i];
-            const int L = context_lens[i];
-            n = n < 0 ? 0 : (n > L ? (L > 0 ? L : 0) : n);      // a chunk cannot be longer than its request
-        }
+    auto chunk_of = [&](int i, int &n, int &first_pos) {
+        const int L = min(max(context_lens[i], 0), max_len);
+        n = min(max(q_start[i + 1] - q_start[i], 0), L);       // a chunk cannot be longer than its request
+        first_pos = L - n;
+    };
+    auto bucket_of = [&](int kv_end) {                          // bucket 0 holds the longest walks
+        const int b = (int)(((int64_t)(max_len - kv_end) * 1024) / ((int64_t)max_len + 1));
+        return min(max(b, 0), 1023);
+    };
+    for (int i = tid; i < B; i += 1024) {
+        int n, first_pos;
+        chunk_of(i, n, first_pos);
         const int tiles = (n + tokens_per_wg - 1) / tokens_per_wg;
-        int incl = tiles;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const int u = __shfl_up(incl, d);
-            if (lane >= d) incl += u;
-        }
-        if (lane == 63) s_wave[wave] = incl;
-        __syncthreads();
-        int before = s_total;
-        for (int k = 0; k < wave; ++k) before += s_wave[k];
-        const int first = before + incl - tiles;
-        for (int t = 0; t < tiles; ++t)
-            if (first + t < ws.max_tiles) ws.table[first + t] = make_int2(i, tiles - 1 - t);
-        __syncthreads();
-        if (tid == 1023) s_total = before + incl;
-        __syncthreads();
+        for (int t = 0; t < tiles; ++t) atomicAdd(&s_hist[bucket_of(first_pos + min((t + 1) * tokens_per_wg, n))], 1);
     }
-    if (tid == 0) *ws.n_tiles = s_total < ws.max_tiles ? s_total : ws.max_tiles;
+    __syncthreads();
+    // exclusive scan of the bucket counts: the first table position of every bucket
+    const int mine = s_hist[tid];
+    int incl = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int u = __shfl_up(incl, d);
+        if (lane >= d) incl += u;
+    }
+    if (lane == 63) s_wave[wave] = incl;
+    __syncthreads();
+    int before = 0, total = 0;
+    for (int k = 0; k < 16; ++k) {
+        if (k < wave) before += s_wave[k];
+        total += s_wave[k];
+    }
+    s_hist[tid] = before + incl - mine;
+    __syncthreads();
+    for (int i = tid; i < B; i += 1024) {
+        int n, first_pos;
+        chunk_of(i, n, first_pos);
+        const int tiles = (n + tokens_per_wg - 1) / tokens_per_wg;
+        for (int t = 0; t < tiles; ++t) {
+            const int pos = atomicAdd(&s_hist[bucket_of(first_pos + min((t + 1) * tokens_per_wg, n))], 1);
+            if (pos < ws.max_tiles) ws.table[pos] = make_int2(i, t);
+        }
+    }
+    if (tid == 0) *ws.n_tiles = total < ws.max_tiles ? total : ws.max_tiles;
 }
 
 // RT: 16-row tiles per wave.  Two tiles share every code -> fp16 conversion and every LDS read of a step.
@@ -521,7 +538,7 @@ hipError_t launch_prefill_attn(const CacheView &c, const void *q, void *out, con
     p.ws = ws;
     const int32_t rt = prefill_row_tiles();
     hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(1024), 0, s, q_start, context_lens, B,
-                       prefill_tokens_per_workgroup(p.qper, rt), ws);
+                       prefill_tokens_per_workgroup(p.qper, rt), max_context_len, ws);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)ws.max_tiles, (unsigned)c.Hkv);         // sized for one row tile per wave: enough for two
