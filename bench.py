@@ -309,35 +309,40 @@ def scheduled_run_leg(w):
     pv = torch.randn((pool_n + max_ctx, w.Hkv, w.D), dtype=torch.float16, device="cuda", generator=gen)
     pq = torch.randn((pool_n + max_ctx, w.H, w.D), dtype=torch.float16, device="cuda", generator=gen)
 
-    def source(id, a, b):
-        o = (id * 7919) % pool_n
-        return pk[o + a:o + b], pv[o + a:o + b], pq[o + a:o + b]
+    def source(spans):
+        # rows of the pools, gathered with one index per iteration
+        idx = torch.from_numpy(np.concatenate([np.arange((id * 7919) % pool_n + a, (id * 7919) % pool_n + b) for id, a, b in spans])).cuda()
+        return pk.index_select(0, idx), pv.index_select(0, idx), pq.index_select(0, idx)
 
-    rp = Replay(w, B.Scheduler(**cfg, want_order=False), num_pages=2 * (M + 1) * pages_per_job, max_context=max_ctx, kv_source=source)
-    order = sorted(range(n_jobs), key=lambda i: (arrival[i], i))
-    k, now, produced = 0, 0, [0] * n_jobs
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    while True:
-        while k < n_jobs and arrival[order[k]] <= now:
-            i = order[k]
-            rp.add_job(i, arrival[i], s[i], n_pred[i])
-            k += 1
-        if rp.sched.num_jobs() == 0:
-            if k == n_jobs:
-                break
-            now = arrival[order[k]]
-            continue
-        d = rp.iterate()
-        fin = []
-        for id in d["batch"]:
-            produced[id] += 1
-            if produced[id] >= n_true[id]:
-                fin.append(id)
-        rp.commit(d["model_time"], fin)
-        now += d["model_time"]
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    def run_once():
+        rp = Replay(w, B.Scheduler(**cfg, want_order=False), num_pages=2 * (M + 1) * pages_per_job, max_context=max_ctx, kv_source=source)
+        order = sorted(range(n_jobs), key=lambda i: (arrival[i], i))
+        k, now, produced = 0, 0, [0] * n_jobs
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        while True:
+            while k < n_jobs and arrival[order[k]] <= now:
+                i = order[k]
+                rp.add_job(i, arrival[i], s[i], n_pred[i])
+                k += 1
+            if rp.sched.num_jobs() == 0:
+                if k == n_jobs:
+                    break
+                now = arrival[order[k]]
+                continue
+            d = rp.iterate()
+            fin = []
+            for id in d["batch"]:
+                produced[id] += 1
+                if produced[id] >= n_true[id]:
+                    fin.append(id)
+            rp.commit(d["model_time"], fin)
+            now += d["model_time"]
+        torch.cuda.synchronize()
+        return rp, time.perf_counter() - t0
+
+    run_once()                      # the first run pays for pinned allocations and one-time queries
+    rp, dt = run_once()
     st = rp.stats
     out["scheduled_run"] = {
         "workload": f"{n_jobs} jobs (Poisson arrivals, log-normal prompts <= 1024 and outputs <= 96, 15 % underpredicted 4x), "
@@ -346,7 +351,8 @@ def scheduled_run_leg(w):
         "prefill_tokens": st["prefill_tokens"], "decode_tokens": st["decode_tokens"],
         "tokens_per_s": (st["prefill_tokens"] + st["decode_tokens"]) / dt,
         "offloads": st["offloads"], "uploads": st["uploads"], "swapped_bytes": st["offload_bytes"] + st["upload_bytes"],
-        "note": "wall clock of the Python loop around the library calls; the clock the scheduler sees is its own model time"}
+        "note": "wall clock of the Python loop around the library calls, second run of the same trace; "
+                "the clock the scheduler sees is its own model time"}
     return out
 
 

@@ -31,8 +31,9 @@ class _Job:
 
 
 class Replay:
-    """kv_source(job_id, t0, t1) -> (k, v, q): device fp16 tensors [t1 - t0, Hkv, D], same, and
-    [t1 - t0, H, D] for the job's tokens t0 .. t1 - 1 (prompt tokens first, then generated ones)."""
+    """kv_source(spans) -> (k, v, q): spans is a list of (job_id, t0, t1); the answer holds, span after
+    span, the device fp16 tensors [tokens, Hkv, D], same, and [tokens, H, D] of the jobs' tokens
+    t0 .. t1 - 1 (prompt tokens first, then generated ones).  One call per iteration."""
 
     def __init__(self, shape, sched: B.Scheduler, num_pages: int, max_context: int, kv_source, overlap_swaps: bool = True):
         self.w = shape
@@ -133,28 +134,27 @@ class Replay:
         # ---- new K/V of the batch: whole prompts (phase 0), one token (phase 1)
         pre = [id for id, ph in zip(d["batch"], d["phase"]) if ph == 0]
         dec = [id for id, ph in zip(d["batch"], d["phase"]) if ph == 1]
-        ks, vs, slots, q_pre, q_dec = [], [], [], [], []
+        spans, slots = [], []
         for id in pre + dec:
             j = self.jobs[id]
             t0, t1 = (0, j.s) if j.L == 0 else (j.L, j.L + 1)
             need = (t1 + w.P - 1) // w.P - len(j.pages)
             if need > 0:
                 j.pages.extend(self._alloc(need))
-            k, v, q = self.kv_source(id, t0, t1)
-            ks.append(k)
-            vs.append(v)
-            (q_pre if j.L == 0 else q_dec).append(q)
+            spans.append((id, t0, t1))
             t = np.arange(t0, t1)
             slots.append(np.asarray(j.pages, np.int64)[t // w.P] * w.P + t % w.P)
             j.L = t1
         out = dict(d)
         out.update(prefill_ids=pre, decode_ids=dec, prefill_out=None, decode_out=None, offloaded=offloaded)
-        if ks:
-            B.alise_kv_quant_write(cache, torch.cat(ks), torch.cat(vs), torch.from_numpy(np.concatenate(slots)).cuda())
+        n_pre = sum(self.jobs[id].s for id in pre)
+        if spans:
+            k_all, v_all, q_all = self.kv_source(spans)
+            B.alise_kv_quant_write(cache, k_all, v_all, torch.from_numpy(np.concatenate(slots)).cuda())
         if pre:
             lens = np.array([self.jobs[id].L for id in pre], np.int32)
             q_start = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
-            q = torch.cat(q_pre)
+            q = q_all[:n_pre]
             o = torch.empty_like(q)
             ws = self._workspace("_ws_pre", B.alise_paged_prefill_attn_workspace_bytes(cache, len(pre), int(q_start[-1]), w.H))
             B.alise_paged_prefill_attn(cache, q, o, torch.from_numpy(q_start).cuda(), self._bt(pre), torch.from_numpy(lens).cuda(),
@@ -163,7 +163,7 @@ class Replay:
             self.stats["prefill_tokens"] += int(q_start[-1])
         if dec:
             lens = np.array([self.jobs[id].L for id in dec], np.int32)
-            q = torch.cat(q_dec)
+            q = q_all[n_pre:]
             o = torch.empty_like(q)
             ws = self._workspace("_ws_dec", B.alise_paged_decode_attn_workspace_bytes(cache, len(dec), w.H, int(lens.max())))
             B.alise_paged_decode_attn(cache, q, o, self._bt(dec), torch.from_numpy(lens).cuda(), int(lens.max()), self.scale, ws)

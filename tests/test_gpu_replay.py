@@ -63,9 +63,8 @@ def test_scheduled_run_against_the_oracle(env, shape_name, overlap):
                    rng.standard_normal((T, w.Hkv, w.D)).astype(np.float16),
                    rng.standard_normal((T, w.H, w.D)).astype(np.float16))
 
-    def source(id, t0, t1):
-        k, v, q = data[id]
-        return torch.from_numpy(k[t0:t1]).cuda(), torch.from_numpy(v[t0:t1]).cuda(), torch.from_numpy(q[t0:t1]).cuda()
+    def source(spans):
+        return tuple(torch.from_numpy(np.concatenate([data[id][c][t0:t1] for id, t0, t1 in spans])).cuda() for c in range(3))
 
     max_ctx = max(s[i] + n_true[i] for i in range(n_jobs)) + 1
     pages_per_job = (max_ctx + w.P - 1) // w.P
