@@ -164,7 +164,7 @@ def prefill_leg(w, step, every=8):
     cache = step.caches[0]
     ws_bytes = B.alise_paged_prefill_attn_workspace_bytes(cache, w.B, 1, w.H)
     if ws_bytes == 0:
-        return None                     # a layout the matrix-core prefill kernel does not take (INT4, head_dim 64)
+        return None                     # a layout the matrix-core prefill kernel does not take (head_dim 64, other group sizes)
     lens = step.lens.astype(np.int64)
     n = np.array([min(512, int(L)) if i % every == 0 else 0 for i, L in enumerate(lens)], np.int64)
     q_start = np.concatenate([[0], np.cumsum(n)]).astype(np.int32)
@@ -296,7 +296,7 @@ def scheduled_run_leg(w):
                               "note": "alise_sched_step + alise_sched_commit through ctypes, 1024 live jobs, batch 64, M 256"}
     # ---- (2) a scheduled run on the GPU
     if B.alise_paged_prefill_attn_workspace_bytes(B.KVCache.allocate(1, w.P, w.Hkv, w.D, w.bits, w.G), 1, 1, w.H) == 0:
-        out["scheduled_run"] = None             # no prefill kernel for this layout (INT4, head_dim 64)
+        out["scheduled_run"] = None             # no prefill kernel for this layout (head_dim 64, other group sizes)
         return out
     n_jobs, M, batch = 192, 48, 32
     arrival, s, n_true, n_pred = (a.tolist() for a in wl.job_trace(n_jobs, 17, mean_gap=120.0, max_prompt=1024, max_output=96))

@@ -105,6 +105,34 @@ __device__ __forceinline__ void lds_read4x8x2(const uint32_t (&a)[8], uint32_t (
                  : "memory");
 }
 
+// four addresses, each read at +0 and at +OFF: r0[i] = [a[i]], r1[i] = [a[i] + OFF]; one wait
+template <int OFF>
+__device__ __forceinline__ void lds_read4x4x2(const uint32_t (&a)[4], uint32_t (&r0)[4], uint32_t (&r1)[4])
+{
+    asm volatile("ds_read_b32 %0, %8\n\tds_read_b32 %1, %9\n\tds_read_b32 %2, %10\n\tds_read_b32 %3, %11\n\t"
+                 "ds_read_b32 %4, %8 offset:%12\n\tds_read_b32 %5, %9 offset:%12\n\t"
+                 "ds_read_b32 %6, %10 offset:%12\n\tds_read_b32 %7, %11 offset:%12\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(r0[0]), "=&v"(r0[1]), "=&v"(r0[2]), "=&v"(r0[3]), "=&v"(r1[0]), "=&v"(r1[1]), "=&v"(r1[2]), "=&v"(r1[3])
+                 : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "n"(OFF)
+                 : "memory");
+}
+// two addresses, each read at + r * ROW (r = 0..3) and at + r * ROW + OFF: a0 -> (p0, p1), a1 -> (q0, q1); one wait
+template <int ROW, int OFF>
+__device__ __forceinline__ void lds_read4_rows2x2(uint32_t a0, uint32_t a1, uint32_t (&p0)[4], uint32_t (&p1)[4],
+                                                  uint32_t (&q0)[4], uint32_t (&q1)[4])
+{
+    asm volatile("ds_read_b32 %0, %16\n\tds_read_b32 %1, %16 offset:%18\n\tds_read_b32 %2, %16 offset:%19\n\tds_read_b32 %3, %16 offset:%20\n\t"
+                 "ds_read_b32 %4, %16 offset:%21\n\tds_read_b32 %5, %16 offset:%22\n\tds_read_b32 %6, %16 offset:%23\n\tds_read_b32 %7, %16 offset:%24\n\t"
+                 "ds_read_b32 %8, %17\n\tds_read_b32 %9, %17 offset:%18\n\tds_read_b32 %10, %17 offset:%19\n\tds_read_b32 %11, %17 offset:%20\n\t"
+                 "ds_read_b32 %12, %17 offset:%21\n\tds_read_b32 %13, %17 offset:%22\n\tds_read_b32 %14, %17 offset:%23\n\tds_read_b32 %15, %17 offset:%24\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(p0[0]), "=&v"(p0[1]), "=&v"(p0[2]), "=&v"(p0[3]), "=&v"(p1[0]), "=&v"(p1[1]), "=&v"(p1[2]), "=&v"(p1[3]),
+                   "=&v"(q0[0]), "=&v"(q0[1]), "=&v"(q0[2]), "=&v"(q0[3]), "=&v"(q1[0]), "=&v"(q1[1]), "=&v"(q1[2]), "=&v"(q1[3])
+                 : "v"(a0), "v"(a1), "n"(ROW), "n"(2 * ROW), "n"(3 * ROW), "n"(OFF), "n"(OFF + ROW), "n"(OFF + 2 * ROW), "n"(OFF + 3 * ROW)
+                 : "memory");
+}
+
 // The weights p * lambda_v enter the second product as fp16 (high + low part).  With the
 // running maximum as the reference, p <= 2^kLazy and the largest weight of a row may be as
 // small as lambda_v itself, so that weights a million times smaller already fall under the

@@ -98,13 +98,26 @@ __global__ __launch_bounds__(1024) void prefill_plan_kernel(const int32_t *q_sta
 }
 
 // RT: 16-row tiles per wave.  Two tiles share every code -> fp16 conversion and every LDS read of a step.
-template <int NGRP, int RT>
+// BITS: 8, or 4 (two channels per byte, channel 2i in the low nibble): see the INT4 notes below.
+template <int BITS, int NGRP, int RT>
 __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
 {
-    constexpr int D = 128, ROWB = 128, S = 3;
-    constexpr int TILEB = 4352;                 // one 16-token tile in LDS: K 2 KiB | V 2 KiB | K meta 128 B | V meta 128 B
-    constexpr int T_V = 2048, T_KM = 4096, T_VM = 4224;
+    constexpr int D = 128, ROWB = D * BITS / 8, S = 3;
+    // one 16-token tile in LDS: K codes | V codes | K meta | V meta (INT8, two groups: 2 KiB | 2 KiB | 128 B | 128 B)
+    constexpr int T_V = 16 * ROWB, T_KM = 32 * ROWB, T_VM = T_KM + 64 * NGRP;
+    constexpr int TILEB = BITS == 8 ? 4352 : T_VM + 64 * NGRP;
+    static_assert(TILEB % 128 == 0 && TILEB >= T_VM + 64 * NGRP, "tile layout");
     constexpr int STEPB = 2 * TILEB;
+    constexpr int LOADS_PER_STEP = BITS == 8 ? 3 : 2;       // direct loads a wave issues per step
+    // INT4.  A token's row is 64 bytes, so one 1 KiB load brings a whole 16-token tile; row r keeps its
+    // 16-byte piece c at position c ^ (r / 4 % 4).  K: chunk jj of the first product is the 32 channels
+    // of piece jj (one scale group when G = 32); a lane's dword of it holds 8 nibbles, which two masks on
+    // the dword and two on the dword shifted by a byte turn into fp16 pairs code * 2^-24 (even
+    // channels) and 16 code * 2^-24 (odd channels) -- k-slots in the order 0 4 1 5 2 6 3 7, Q permuted
+    // likewise with its odd channels divided by 16.  V: columns of a product are 16 channels of one
+    // 32-channel block b: lane n takes the byte n % 4 of dword n / 4 of the block, i.e. channels
+    // 32 b + 2 n and 32 b + 2 n + 1 -- the low nibbles go to one product, the high nibbles (times 16,
+    // undone at the output) to another.
     __shared__ __attribute__((aligned(128))) uint8_t lds[S * STEPB + 4 * 512];     // stages, then two page-window slots per wave
 
     const int f = blockIdx.x;
@@ -146,17 +159,22 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
     const int nsteps = (kv_end + kStep - 1) / kStep;
     if (n_q <= 0 || nsteps <= 0) return;        // workgroup-uniform
 
-    // ---- per-lane constants of the LDS layout (see the decode kernel): a 1 KiB load covers 8
+    // ---- per-lane constants of the LDS layout (see the decode kernel): INT8: a 1 KiB load covers 8
     // token rows; row r keeps its 16-byte piece c at position c ^ r.  The array starts on a
-    // 128-byte boundary and every stage, tile and row is a multiple of 128 bytes long, so the
-    // swizzle of an address is an exclusive-or of its bits 4..6 with the row number.
-    const int src_lane = (lane >> 3) * ROWB + (((lane & 7) ^ (lane >> 3)) * 16);
-    // K, token n of a tile, pieces g and 4 + g (the second: the first with bit 6 flipped)
-    const uint32_t k_rd = (n >> 3) * 1024 + ((n & 7) * 8 + (g ^ (n & 7))) * 16;
-    // V, token rows 4g + r (r = 0..3), piece 4 * set + n / 4, dword n % 4 of the piece: row r of set `set` sits at
-    // (v_rd ^ (16 r + 64 set)) + 128 r
-    const uint32_t v_rd = T_V + (g >> 1) * 1024 + (g & 1) * 512 + (((n >> 2) ^ ((g & 1) * 4)) * 16) + (n & 3) * 4;
+    // 128-byte boundary and every stage, tile and row is a multiple of 64 bytes long, so the
+    // swizzle of an address is an exclusive-or of address bits with the row number.
+    const int src_lane = BITS == 8 ? (lane >> 3) * ROWB + (((lane & 7) ^ (lane >> 3)) * 16)
+                                   : (lane >> 2) * ROWB + (((lane & 3) ^ ((lane >> 4) & 3)) * 16);
+    // K, INT8: token n of a tile, pieces g and 4 + g (the second: the first with bit 6 flipped);
+    // INT4: token n, dword g of piece jj at (k_rd ^ 16 jj)
+    const uint32_t k_rd = BITS == 8 ? (n >> 3) * 1024 + ((n & 7) * 8 + (g ^ (n & 7))) * 16
+                                    : n * 64 + ((n >> 2) & 3) * 16 + g * 4;
+    // V, INT8: token rows 4g + r (r = 0..3), piece 4 * set + n / 4, dword n % 4 of the piece: row r of set `set`
+    // sits at (v_rd ^ (16 r + 64 set)) + 128 r;  INT4: rows 4g + r, dword n / 4 of block b at (v_rd ^ 16 b) + 64 r
+    const uint32_t v_rd = BITS == 8 ? T_V + (g >> 1) * 1024 + (g & 1) * 512 + (((n >> 2) ^ ((g & 1) * 4)) * 16) + (n & 3) * 4
+                                    : T_V + g * 256 + g * 16 + (n >> 2) * 4;
     const uint32_t m_rd = g * 16 * NGRP;
+    const uint32_t v_sel = 0x0c000c00u | ((4u + (n & 3)) << 16) | (uint32_t)(n & 3);     // INT4: byte n % 4 of two dwords into the low bytes of two halves
 
     // ---- Q^T as the B operand of the four k-chunks: chunk jj, slot g*8+e <-> channel (jj/2)*64 + g*16 + (jj%2)*8 + e
     h8_t qop[RT][4];
@@ -170,13 +188,19 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
         for (int gr = 0; gr < NGRP; ++gr) part_sum[gr] = 0.0f;
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
-            h8_t v = *reinterpret_cast<const h8_t *>(qrow + (jj / 2) * 64 + g * 16 + (jj % 2) * 8);
+            // INT8: chunk jj, slot g*8+e <-> channel (jj/2)*64 + g*16 + (jj%2)*8 + e;  INT4: channel 32 jj + 8 g + {0 4 1 5 2 6 3 7}[e]
+            h8_t v = *reinterpret_cast<const h8_t *>(qrow + (BITS == 8 ? (jj / 2) * 64 + g * 16 + (jj % 2) * 8 : jj * 32 + g * 8));
             if (!row_valid[t]) v = (h8_t)(_Float16)0.0f;
-            qop[t][jj] = v;
             float sacc = 0.0f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) sacc += (float)v[e];
-            part_sum[NGRP == 2 ? jj / 2 : 0] += sacc;
+            part_sum[jj * NGRP / 4] += sacc;
+            if constexpr (BITS == 4) {
+                const _Float16 sixteenth = (_Float16)0.0625f;       // the odd nibbles arrive 16 times too large
+                const h8_t w = {v[0], v[4], v[1] * sixteenth, v[5] * sixteenth, v[2], v[6], v[3] * sixteenth, v[7] * sixteenth};
+                v = w;
+            }
+            qop[t][jj] = v;
         }
 #pragma unroll
         for (int gr = 0; gr < NGRP; ++gr) {
@@ -228,14 +252,14 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
         const uint8_t *mb = reinterpret_cast<const uint8_t *>(my_v ? p.c.v_meta : p.c.k_meta) + mo + lane * 4;
         // the rows of a head are read again by the workgroups of its other row tiles: keep them in the L2
         dma16(cb, dst + (my_v ? T_V : 0));
-        dma16(cb + 1024, dst + (my_v ? T_V : 0) + 1024);
+        if constexpr (BITS == 8) dma16(cb + 1024, dst + (my_v ? T_V : 0) + 1024);
         if (lane < 16 * NGRP) dma4(mb, dst + (my_v ? T_VM : T_KM));
     };
 
     // m_ref: the running maximum in the units of t.  c_ref = bias - m_ref scale24: a weight is 2^(t scale24 + c_ref).
     float m_ref[RT], c_ref[RT], l_part[RT], z_part[RT][NGRP];
     float bias = kWeightBias;           // see kWeightBias; wave-uniform, common to the row tiles
-    f4_t o[RT][8];              // [tile][set*4 + nu]: rows 4g..4g+3 of the tile, column n <-> channel 64*set + 4n + nu
+    f4_t o[RT][8];              // INT8: [tile][set*4 + nu]: rows 4g..4g+3 of the tile, column n <-> channel 64*set + 4n + nu;  INT4: [tile][2b + m] <-> channel 32b + 2n + m
 #pragma unroll
     for (int t = 0; t < RT; ++t) {
         m_ref[t] = kFloor * inv24;
@@ -257,11 +281,27 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
         float mx[RT];
 #pragma unroll
         for (int t = 0; t < RT; ++t) mx[t] = kNegInf;
-        uint4 kp[2][2];
-        const uint32_t ka0 = base + k_rd, ka1 = ka0 ^ 64u, ma = base + m_rd;
-        lds_read16x4_at<0, 0, TILEB, TILEB>(ka0, ka1, ka0, ka1, kp[0][0], kp[0][1], kp[1][0], kp[1][1]);
+        uint4 kp[2][2];                // INT8: [tile][piece];  INT4: kp[tile][0] holds the dwords of the four chunks
+        const uint32_t ka0 = base + k_rd, ma = base + m_rd;
+        if constexpr (BITS == 8) {
+            const uint32_t ka1 = ka0 ^ 64u;
+            lds_read16x4_at<0, 0, TILEB, TILEB>(ka0, ka1, ka0, ka1, kp[0][0], kp[0][1], kp[1][0], kp[1][1]);
+        } else {
+            const uint32_t ka[4] = {ka0, ka0 ^ 16u, ka0 ^ 32u, ka0 ^ 48u};
+            uint32_t k0[4], k1[4];
+            lds_read4x4x2<TILEB>(ka, k0, k1);
+            kp[0][0] = make_uint4(k0[0], k0[1], k0[2], k0[3]);
+            kp[1][0] = make_uint4(k1[0], k1[1], k1[2], k1[3]);
+        }
         uint4 kmeta[2][NGRP], vmeta[2][NGRP];
-        if constexpr (NGRP == 1) {
+        if constexpr (NGRP == 4) {
+            lds_read16x4_at<T_KM, T_KM + 16, T_KM + 32, T_KM + 48>(ma, ma, ma, ma, kmeta[0][0], kmeta[0][1], kmeta[0][2], kmeta[0][3]);
+            lds_read16x4_at<T_VM, T_VM + 16, T_VM + 32, T_VM + 48>(ma, ma, ma, ma, vmeta[0][0], vmeta[0][1], vmeta[0][2], vmeta[0][3]);
+            lds_read16x4_at<TILEB + T_KM, TILEB + T_KM + 16, TILEB + T_KM + 32, TILEB + T_KM + 48>(ma, ma, ma, ma, kmeta[1][0], kmeta[1][1],
+                                                                                                   kmeta[1][2], kmeta[1][3]);
+            lds_read16x4_at<TILEB + T_VM, TILEB + T_VM + 16, TILEB + T_VM + 32, TILEB + T_VM + 48>(ma, ma, ma, ma, vmeta[1][0], vmeta[1][1],
+                                                                                                   vmeta[1][2], vmeta[1][3]);
+        } else if constexpr (NGRP == 1) {
             lds_read16x4_at<T_KM, T_VM, TILEB + T_KM, TILEB + T_VM>(ma, ma, ma, ma, kmeta[0][0], vmeta[0][0], kmeta[1][0], vmeta[1][0]);
         } else {
             lds_read16x4_at<T_KM, T_KM + 16, T_VM, T_VM + 16>(ma, ma, ma, ma, kmeta[0][0], kmeta[0][1], vmeta[0][0], vmeta[0][1]);
@@ -277,15 +317,20 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
                 for (int gr = 0; gr < NGRP; ++gr) acc[t][gr] = (f4_t)0.0f;
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) {
-                const uint4 piece = kp[x][jj / 2];
-                const uint32_t w0 = (jj % 2) ? piece.z : piece.x, w1 = (jj % 2) ? piece.w : piece.y;
-                const h8_t a = pack8(__builtin_amdgcn_perm(0u, w0, 0x0c010c00u),
-                                     __builtin_amdgcn_perm(0u, w0, 0x0c030c02u),
-                                     __builtin_amdgcn_perm(0u, w1, 0x0c010c00u),
-                                     __builtin_amdgcn_perm(0u, w1, 0x0c030c02u));
+                h8_t a;
+                if constexpr (BITS == 8) {
+                    const uint4 piece = kp[x][jj / 2];
+                    const uint32_t w0 = (jj % 2) ? piece.z : piece.x, w1 = (jj % 2) ? piece.w : piece.y;
+                    a = pack8(__builtin_amdgcn_perm(0u, w0, 0x0c010c00u), __builtin_amdgcn_perm(0u, w0, 0x0c030c02u),
+                              __builtin_amdgcn_perm(0u, w1, 0x0c010c00u), __builtin_amdgcn_perm(0u, w1, 0x0c030c02u));
+                } else {
+                    const uint4 d4 = kp[x][0];
+                    const uint32_t w0 = jj == 0 ? d4.x : jj == 1 ? d4.y : jj == 2 ? d4.z : d4.w, w1 = w0 >> 8;
+                    a = pack8(w0 & 0x000F000Fu, w0 & 0x00F000F0u, w1 & 0x000F000Fu, w1 & 0x00F000F0u);
+                }
 #pragma unroll
                 for (int t = 0; t < RT; ++t) {
-                    f4_t &dst = acc[t][NGRP == 2 ? jj / 2 : 0];
+                    f4_t &dst = acc[t][jj * NGRP / 4];
                     dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, qop[t][jj], dst, 0, 0, 0);
                 }
             }
@@ -387,29 +432,58 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
                     }
                 }
 
-        // ---- O += P V: byte nu of the dwords of two tokens -> two fp16 subnormals, once for all row tiles
-        uint32_t va[8], vd[2][8];          // vd[tile][set * 4 + r]
-        va[0] = v_rd + base;
+        // ---- O += P V, the B operands built once for all row tiles
+        if constexpr (BITS == 8) {
+            // byte nu of the dwords of two tokens -> two fp16 subnormals
+            uint32_t va[8], vd[2][8];          // vd[tile][set * 4 + r]
+            va[0] = v_rd + base;
 #pragma unroll
-        for (int c = 1; c < 8; ++c) va[c] = va[0] ^ (uint32_t)((c & 3) * 16 + (c >> 2) * 64);
-        lds_read4x8x2<ROWB, TILEB>(va, vd[0], vd[1]);
+            for (int c = 1; c < 8; ++c) va[c] = va[0] ^ (uint32_t)((c & 3) * 16 + (c >> 2) * 64);
+            lds_read4x8x2<ROWB, TILEB>(va, vd[0], vd[1]);
 #pragma unroll
-        for (int set = 0; set < 2; ++set)
+            for (int set = 0; set < 2; ++set)
 #pragma unroll
-            for (int nu = 0; nu < 4; ++nu) {
-                const uint32_t sel = 0x0c000c00u | ((4u + nu) << 16) | (uint32_t)nu;
-                const h8_t bv = pack8(__builtin_amdgcn_perm(vd[0][set * 4 + 1], vd[0][set * 4 + 0], sel),
-                                      __builtin_amdgcn_perm(vd[0][set * 4 + 3], vd[0][set * 4 + 2], sel),
-                                      __builtin_amdgcn_perm(vd[1][set * 4 + 1], vd[1][set * 4 + 0], sel),
-                                      __builtin_amdgcn_perm(vd[1][set * 4 + 3], vd[1][set * 4 + 2], sel));
-                const int gr = NGRP == 2 ? set : 0;
+                for (int nu = 0; nu < 4; ++nu) {
+                    const uint32_t sel = 0x0c000c00u | ((4u + nu) << 16) | (uint32_t)nu;
+                    const h8_t bv = pack8(__builtin_amdgcn_perm(vd[0][set * 4 + 1], vd[0][set * 4 + 0], sel),
+                                          __builtin_amdgcn_perm(vd[0][set * 4 + 3], vd[0][set * 4 + 2], sel),
+                                          __builtin_amdgcn_perm(vd[1][set * 4 + 1], vd[1][set * 4 + 0], sel),
+                                          __builtin_amdgcn_perm(vd[1][set * 4 + 3], vd[1][set * 4 + 2], sel));
+                    const int gr = NGRP == 2 ? set : 0;
 #pragma unroll
-                for (int t = 0; t < RT; ++t) {
-                    f4_t &dst = o[t][set * 4 + nu];
-                    dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_hi[t][gr], bv, dst, 0, 0, 0);
-                    dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_lo[t][gr], bv, dst, 0, 0, 0);
+                    for (int t = 0; t < RT; ++t) {
+                        f4_t &dst = o[t][set * 4 + nu];
+                        dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_hi[t][gr], bv, dst, 0, 0, 0);
+                        dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_lo[t][gr], bv, dst, 0, 0, 0);
+                    }
+                }
+        } else {
+            // byte n % 4 of the block's dword of two tokens -> (low nibbles) and (high nibbles * 16) as fp16 subnormals
+            const uint32_t va0 = v_rd + base;
+#pragma unroll
+            for (int bb = 0; bb < 4; bb += 2) {
+                uint32_t vd[2][2][4];          // [block of the pair][tile][r]
+                lds_read4_rows2x2<ROWB, TILEB>(va0 ^ (uint32_t)(bb * 16), va0 ^ (uint32_t)((bb + 1) * 16), vd[0][0], vd[0][1], vd[1][0], vd[1][1]);
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int b = bb + h;
+                    const uint32_t p0 = __builtin_amdgcn_perm(vd[h][0][1], vd[h][0][0], v_sel), p1 = __builtin_amdgcn_perm(vd[h][0][3], vd[h][0][2], v_sel);
+                    const uint32_t p2 = __builtin_amdgcn_perm(vd[h][1][1], vd[h][1][0], v_sel), p3 = __builtin_amdgcn_perm(vd[h][1][3], vd[h][1][2], v_sel);
+#pragma unroll
+                    for (int m = 0; m < 2; ++m) {
+                        const uint32_t mask = m ? 0x00F000F0u : 0x000F000Fu;
+                        const h8_t bv = pack8(p0 & mask, p1 & mask, p2 & mask, p3 & mask);
+                        const int gr = b * NGRP / 4;
+#pragma unroll
+                        for (int t = 0; t < RT; ++t) {
+                            f4_t &dst = o[t][b * 2 + m];
+                            dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_hi[t][gr], bv, dst, 0, 0, 0);
+                            dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_lo[t][gr], bv, dst, 0, 0, 0);
+                        }
+                    }
                 }
             }
+        }
     };
 
     // Every wave passes the same nsteps barriers; what it computes in between is its own business.  The steps
@@ -418,7 +492,7 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
     int stage = 0;                              // k % S, kept as a counter
     auto advance = [&](int k) -> uint32_t {
         // this wave's quarter of step k has landed once at most the three loads of the step after it are in flight
-        if (k + 1 < nsteps) ALISE_VMCNT(3); else ALISE_VMCNT(0);
+        if (k + 1 < nsteps) ALISE_VMCNT(LOADS_PER_STEP); else ALISE_VMCNT(0);
         // all four quarters have landed, and every wave is done reading the stage that step k + 2 overwrites
         asm volatile("s_barrier" ::: "memory");
         if (k + 2 < nsteps) issue(k + 2, stage == 0 ? 2 : stage - 1);
@@ -463,16 +537,28 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
             const int j_r = j0 + row / qper, e_r = row % qper;
             if (row < TT * qper && j_r < n_q) {
                 const float inv_l = 1.0f / l_row;
-                _Float16 *dst = p.out + ((int64_t)(qs + j_r) * H + hk * qper + e_r) * D + 4 * n;
+                _Float16 *orow = p.out + ((int64_t)(qs + j_r) * H + hk * qper + e_r) * D;
+                if constexpr (BITS == 8) {
+                    _Float16 *dst = orow + 4 * n;
 #pragma unroll
-                for (int set = 0; set < 2; ++set) {
-                    const float zr = z_row[NGRP == 2 ? set : 0];
-                    typedef _Float16 h4_t __attribute__((ext_vector_type(4)));
-                    h4_t v;
+                    for (int set = 0; set < 2; ++set) {
+                        const float zr = z_row[NGRP == 2 ? set : 0];
+                        typedef _Float16 h4_t __attribute__((ext_vector_type(4)));
+                        h4_t v;
 #pragma unroll
-                    for (int nu = 0; nu < 4; ++nu)
-                        v[nu] = (_Float16)(__builtin_fmaf(o[t][set * 4 + nu][r], 16777216.0f, -zr) * inv_l);
-                    *reinterpret_cast<h4_t *>(dst + 64 * set) = v;
+                        for (int nu = 0; nu < 4; ++nu)
+                            v[nu] = (_Float16)(__builtin_fmaf(o[t][set * 4 + nu][r], 16777216.0f, -zr) * inv_l);
+                        *reinterpret_cast<h4_t *>(dst + 64 * set) = v;
+                    }
+                } else {
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const float zr = z_row[b * NGRP / 4];
+                        h2_t v;
+                        v.x = (_Float16)(__builtin_fmaf(o[t][b * 2 + 0][r], 16777216.0f, -zr) * inv_l);
+                        v.y = (_Float16)(__builtin_fmaf(o[t][b * 2 + 1][r], 1048576.0f, -zr) * inv_l);      // 2^24 / 16
+                        *reinterpret_cast<h2_t *>(orow + 32 * b + 2 * n) = v;
+                    }
                 }
             }
         }
@@ -483,19 +569,24 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
 // SIMD, with two groups three; two row tiles per wave take two waves per SIMD.
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void prefill_attn_kernel_g1(PrefillParams p)
 {
-    prefill_attn_body<1, 1>(p);
+    prefill_attn_body<8, 1, 1>(p);
 }
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void prefill_attn_kernel_g2(PrefillParams p)
 {
-    prefill_attn_body<2, 1>(p);
+    prefill_attn_body<8, 2, 1>(p);
 }
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_attn_kernel_g1_r2(PrefillParams p)
 {
-    prefill_attn_body<1, 2>(p);
+    prefill_attn_body<8, 1, 2>(p);
 }
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_attn_kernel_g2_r2(PrefillParams p)
 {
-    prefill_attn_body<2, 2>(p);
+    prefill_attn_body<8, 2, 2>(p);
+}
+// INT4 with groups of 32 channels: four scale groups per head, one row tile per wave.
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void prefill_attn_kernel_i4(PrefillParams p)
+{
+    prefill_attn_body<4, 4, 1>(p);
 }
 
 }  // namespace
@@ -503,7 +594,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 bool prefill_mfma_applies(const CacheView &c, int32_t H)
 {
     const int qper = H / c.Hkv;
-    return c.bits == 8 && c.D == 128 && (c.G == 128 || c.G == 64) && c.P >= 16 && qper >= 1 && qper <= 16;
+    if (c.D != 128 || c.P < 16 || qper < 1 || qper > 16) return false;
+    return (c.bits == 8 && (c.G == 128 || c.G == 64)) || (c.bits == 4 && c.G == 32);
 }
 
 // Query tokens per workgroup: four waves of `row_tiles` 16-row tiles, a row being a (token, head of the group) pair.
@@ -536,14 +628,16 @@ hipError_t launch_prefill_attn(const CacheView &c, const void *q, void *out, con
     p.max_len = max_context_len;
     p.scale_log2e = softmax_scale * 1.44269504088896340736f;
     p.ws = ws;
-    const int32_t rt = prefill_row_tiles();
+    const int32_t rt = c.bits == 4 ? 1 : prefill_row_tiles();
     hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(1024), 0, s, q_start, context_lens, B,
                        prefill_tokens_per_workgroup(p.qper, rt), max_context_len, ws);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)ws.max_tiles, (unsigned)c.Hkv);         // sized for one row tile per wave: enough for two
     const bool one_group = c.D / c.G == 1;
-    if (rt == 1) {
+    if (c.bits == 4) {
+        hipLaunchKernelGGL(prefill_attn_kernel_i4, grid, dim3(256), 0, s, p);
+    } else if (rt == 1) {
         if (one_group) hipLaunchKernelGGL(prefill_attn_kernel_g1, grid, dim3(256), 0, s, p);
         else hipLaunchKernelGGL(prefill_attn_kernel_g2, grid, dim3(256), 0, s, p);
     } else {

@@ -87,7 +87,7 @@ def test_full_size_step_sampled_against_oracle(env, name):
     assert np.array_equal(st.dq_v.cpu().numpy().view(np.uint16)[:n0], vo.view(np.uint16)[:n0])
 
 
-@pytest.mark.parametrize("name", ["llama7b", "gqa70b"])
+@pytest.mark.parametrize("name", ["llama7b", "gqa70b", "int4"])
 def test_full_size_prefill_sampled_against_oracle(env, name):
     """The prefill leg of bench.py (every 8th request brings its last min(512, L) tokens) on the
     full cache; sampled query tokens are recomputed by the oracle from the same seeded inputs."""

@@ -39,6 +39,9 @@ CASES = [
     (_w("gqa16_p64", G=128, P=64, Hkv=1, H=16), [400, 50], [37, 50]),
     (_w("gqa3_g128_p16", G=128, Hkv=2, H=6), [90, 260], [90, 41]),
     (_w("gqa4", Hkv=2, H=8), [1, 17, 128], [1, 17, 128]),
+    (_w("int4_g32_mha", bits=4, G=32, Hkv=4, H=4), [40, 200, 65, 1, 333, 64], [40, 7, 65, 1, 0, 64]),
+    (_w("int4_g32_long", bits=4, G=32, Hkv=2, H=2), [2500, 1100], [70, 33]),
+    (_w("int4_g32_gqa4_p32", bits=4, G=32, P=32, Hkv=2, H=8), [300, 77, 150], [100, 77, 9]),
 ]
 
 
@@ -106,8 +109,9 @@ def test_one_token_chunks_equal_the_decode_call(env):
 
 def test_unsupported_shapes_are_refused(env):
     B, torch, oracle = env
-    c4 = B.KVCache.allocate(4, 16, 2, 128, 4, 32)           # INT4
+    c4 = B.KVCache.allocate(4, 16, 2, 128, 4, 64)           # INT4 with groups of 64 (groups of 32 are taken)
     assert B.alise_paged_prefill_attn_workspace_bytes(c4, 1, 8, 2) == 0
+    assert B.alise_paged_prefill_attn_workspace_bytes(B.KVCache.allocate(4, 16, 2, 128, 4, 32), 1, 8, 2) > 0
     c64 = B.KVCache.allocate(4, 16, 2, 64, 8, 64)           # head_dim 64
     assert B.alise_paged_prefill_attn_workspace_bytes(c64, 1, 8, 2) == 0
     ok = B.KVCache.allocate(4, 16, 2, 128, 8, 64)

@@ -40,6 +40,7 @@ def _mark_tokens(oracle, oc, L):
 SHAPES = {
     "mha_g64": dict(H=4, Hkv=4, D=128, P=16, bits=8, G=64),
     "gqa4_g128_p32": dict(H=8, Hkv=2, D=128, P=32, bits=8, G=128),
+    "int4_g32": dict(H=4, Hkv=4, D=128, P=16, bits=4, G=32),
 }
 
 
