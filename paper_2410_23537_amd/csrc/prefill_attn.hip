@@ -6,18 +6,22 @@
 // Query token j of an n-token chunk of a request with L cached tokens sits at position L - n + j.
 //
 // Work decomposition.  Rows of the problem are (query token, query head) pairs; the rows that
-// share a KV head share every KV byte.  A workgroup of four waves takes 64 such rows of one
-// request and one KV head (16 per wave: 16 / qper tokens x qper heads) and walks the cache once
-// from position 0 to the last position any of its rows may see.  The four waves share the
-// cache through LDS: per step of 32 tokens each wave fetches a quarter of the step (K or V
-// codes of one 16-token tile plus its scales and zero-points) with direct global -> LDS
-// loads, three stages deep, one workgroup barrier per step.  Per wave the step is the one of
-// the grouped-query decode kernel: S^T = K Q^T and O += P V on v_mfma_f32_16x16x32_f16, K
-// and V codes as fp16 subnormals code * 2^-24, P * lambda_v split in high and low
-// fp16 parts, online softmax with a lazily raised maximum -- except that the mask is per
-// row (token <= the row's position) and that a wave skips the steps none of its rows can see.
+// share a KV head share every KV byte.  A workgroup of four waves takes 64 or 128 such rows of one
+// request and one KV head (one or two 16-row tiles per wave; a tile is 16 / qper tokens x qper
+// heads) and walks the cache once from position 0 to the last position any of its rows may see.
+// The four waves share the cache through LDS: per step of 32 tokens each wave fetches a quarter
+// of the step (K or V codes of one 16-token tile plus its scales and zero-points) with direct
+// global -> LDS loads, three stages deep, one workgroup barrier per step.  Per wave the step is
+// the one of the grouped-query decode kernel: S^T = K Q^T and O += P V on
+// v_mfma_f32_16x16x32_f16, K and V codes as fp16 subnormals code * 2^-24, P * lambda_v split in
+// high and low fp16 parts, online softmax with a lazily raised maximum -- except that the mask
+// is per row (token <= the row's position), that only the steps on a wave's diagonal are masked
+// at all, and that a wave skips the steps none of its rows can see.  Two row tiles of a wave
+// share the operands built from the cache.  INT8 caches (one or two scale groups per head) and
+// INT4 caches with groups of 32 channels are taken; the INT4 operand formats are described at the
+// top of the kernel body.
 // There is no split along the context and therefore nothing to merge: a chunk of a few
-// hundred tokens gives thousands of workgroups.
+// hundred tokens gives thousands of workgroups, handed out longest walk first.
 //
 // The block-table entries of the 64 pages around the current position sit in a register (one
 // entry per lane), refilled every 64 pages from a window fetched ahead of time into LDS.
