@@ -1,8 +1,8 @@
 // Paged single-query attention for grouped-query layouts on the gfx950 matrix cores.
 //
 // With H / Hkv = qper query heads per KV head, every KV byte is used by qper queries, so
-// q K^T and P V are real (small) matrix products (ALISE Sec. 2, Eq. 1-2, over the INT8
-// cache of Sec. 3.2).  One wave serves all query heads of one KV head for one tile of
+// q K^T and P V are real (small) matrix products (ALISE Sec. 2, Eq. 1-2, over the quantized
+// cache of Sec. 3.2: INT8, or INT4 with groups of 32 channels -- see the note at the kernel).  One wave serves all query heads of one KV head for one tile of
 // tokens; the work items of a tile are its KV heads.  Per step of 32 tokens:
 //
 //   S^T = K Q^T   v_mfma_f32_16x16x32_f16, A = K codes as fp16 (16 tokens x 32 channels),
@@ -45,15 +45,28 @@
 namespace alise {
 namespace {
 
-// NGRP = groups per token row (1 or 2); QROWS = query rows kept per item (8 or 16, >= qper);
-// S = stages of one step each.
-template <int NGRP, int QROWS, int S>
+// BITS = code width (8, or 4 with two channels per byte); NGRP = groups per token row (1, 2 or 4);
+// QROWS = query rows kept per item (8 or 16, >= qper); S = stages of one step each.
+//
+// INT4 (groups of 32 channels).  A token's row is 64 bytes, so one 1 KiB load brings a whole
+// 16-token tile; row r keeps its 16-byte piece c at position c ^ (r / 4 % 4).  K: chunk j of the
+// first product is the 32 channels of piece j (one scale group); a lane's dword of it holds 8
+// nibbles, which two masks on the dword and two on the dword shifted by a byte turn into fp16
+// pairs code * 2^-24 (even channels) and 16 code * 2^-24 (odd channels) -- k-slots in the order
+// 0 4 1 5 2 6 3 7, Q permuted likewise with its odd channels divided by 16.  V: the columns of a
+// product are 16 channels of one 32-channel block b: lane n takes byte n % 4 of dword n / 4 of the
+// block, i.e. channels 32 b + 2 n and 32 b + 2 n + 1 -- the low nibbles go to one product, the high
+// nibbles (times 16, undone at the output) to another.
+template <int BITS, int NGRP, int QROWS, int S>
 __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
 {
-    constexpr int D = 128, ROWB = 128;
-    constexpr int TILEB = 4352;                 // one 16-token tile in LDS: K 2 KiB | V 2 KiB | K meta 128 B | V meta 128 B
-    constexpr int T_V = 2048, T_KM = 4096, T_VM = 4224;
+    constexpr int D = 128, ROWB = D * BITS / 8;
+    // one 16-token tile in LDS: K codes | V codes | K meta | V meta (INT8, two groups: 2 KiB | 2 KiB | 128 B | 128 B)
+    constexpr int T_V = 16 * ROWB, T_KM = 32 * ROWB, T_VM = T_KM + 64 * NGRP;
+    constexpr int TILEB = BITS == 8 ? 4352 : T_VM + 64 * NGRP;
+    static_assert(TILEB % 128 == 0 && TILEB >= T_VM + 64 * NGRP, "tile layout");
     constexpr int STEPB = 2 * TILEB;
+    constexpr int LOADS_PER_STEP = BITS == 8 ? 12 : 8;       // direct loads of one step
     constexpr int RD = 4, RG = 2, RQ = 1;       // rings: descriptors, page windows, query rows
     constexpr int QSLOT = QROWS * 256;
     constexpr int OFF_DESC = S * STEPB, OFF_PG = OFF_DESC + RD * 16, OFF_Q = OFF_PG + RG * 256;
@@ -73,12 +86,19 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
     // its 16-byte piece c at position c ^ r.  The array starts on a 128-byte boundary and every
     // stage, tile and row is a multiple of 128 bytes long, so the swizzle of an address is an
     // exclusive-or of its bits 4..6 with the row number.
-    const int src_lane = (lane >> 3) * ROWB + (((lane & 7) ^ (lane >> 3)) * 16);     // what this lane fetches of the 1 KiB
-    // K operand: row n, pieces g and 4 + g (the second: the first with bit 6 flipped)
-    const uint32_t k_rd = (n >> 3) * 1024 + ((n & 7) * 8 + (g ^ (n & 7))) * 16;
-    // V operand: rows 4g + r, channels 64 * set + 4n .. (a dword): row r of set `set` sits at (v_rd ^ (16 r + 64 set)) + 128 r
-    const uint32_t v_rd = T_V + (g >> 1) * 1024 + (g & 1) * 512 + (((n >> 2) ^ ((g & 1) * 4)) * 16) + (n & 3) * 4;
+    // what this lane fetches of a 1 KiB load
+    const int src_lane = BITS == 8 ? (lane >> 3) * ROWB + (((lane & 7) ^ (lane >> 3)) * 16)
+                                   : (lane >> 2) * ROWB + (((lane & 3) ^ ((lane >> 4) & 3)) * 16);
+    // K operand, INT8: row n, pieces g and 4 + g (the second: the first with bit 6 flipped);
+    // INT4: row n, dword g of piece j at (k_rd ^ 16 j)
+    const uint32_t k_rd = BITS == 8 ? (n >> 3) * 1024 + ((n & 7) * 8 + (g ^ (n & 7))) * 16
+                                    : n * 64 + ((n >> 2) & 3) * 16 + g * 4;
+    // V operand, INT8: rows 4g + r, channels 64 * set + 4n .. (a dword): row r of set `set` sits at (v_rd ^ (16 r + 64 set)) + 128 r;
+    // INT4: rows 4g + r, dword n / 4 of block b at (v_rd ^ 16 b) + 64 r
+    const uint32_t v_rd = BITS == 8 ? T_V + (g >> 1) * 1024 + (g & 1) * 512 + (((n >> 2) ^ ((g & 1) * 4)) * 16) + (n & 3) * 4
+                                    : T_V + g * 256 + g * 16 + (n >> 2) * 4;
     const uint32_t m_rd = g * 16 * NGRP;        // meta of this lane's 4 tokens
+    const uint32_t v_sel = 0x0c000c00u | ((4u + (n & 3)) << 16) | (uint32_t)(n & 3);     // INT4: byte n % 4 of two dwords into the low bytes of two halves
 
     // ---- this wave's list of items (an item is a tile for one KV head)
     const int W = gridDim.x, w = blockIdx.x;
@@ -178,15 +198,15 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
             const uint8_t *kb = p.c.k_codes + co + src_lane;
             const uint8_t *vb = p.c.v_codes + co + src_lane;
             dma16_stream(kb, dst);
-            dma16_stream(kb + 1024, dst + 1024);
+            if constexpr (BITS == 8) dma16_stream(kb + 1024, dst + 1024);
             dma16_stream(vb, dst + T_V);
-            dma16_stream(vb + 1024, dst + T_V + 1024);
+            if constexpr (BITS == 8) dma16_stream(vb + 1024, dst + T_V + 1024);
             if (lane < 16 * NGRP) {
                 dma4_stream(reinterpret_cast<const uint8_t *>(p.c.k_meta) + mo + lane * 4, dst + T_KM);
                 dma4_stream(reinterpret_cast<const uint8_t *>(p.c.v_meta) + mo + lane * 4, dst + T_VM);
             }
         }
-        issued += 12;
+        issued += LOADS_PER_STEP;
         set_mark(32 + st);
         ++steps_issued;
         if (++p_s == p_ns) p_next = 1;                      // the item is fetched; the next one is entered when allowed
@@ -236,7 +256,9 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
             // query row n sits at (n / 4) * 1024 + (n % 4) * 256 of the slot: row c*4+g was written by quarter g of load c
             const uint32_t qa = lds0 + OFF_Q + (cr % RQ) * QSLOT + ((n % QROWS) >> 2) * 1024 + (n & 3) * 256;
             uint4 raw[4];
-            lds_read16x4(qa + g * 32, qa + g * 32 + 16, qa + 128 + g * 32, qa + 128 + g * 32 + 16, raw[0], raw[1], raw[2], raw[3]);
+            // INT8: chunk j, slot g*8+e <-> channel (j/2)*64 + g*16 + (j%2)*8 + e;  INT4: channel 32 j + 8 g + {0 4 1 5 2 6 3 7}[e]
+            if constexpr (BITS == 8) lds_read16x4(qa + g * 32, qa + g * 32 + 16, qa + 128 + g * 32, qa + 128 + g * 32 + 16, raw[0], raw[1], raw[2], raw[3]);
+            else lds_read16x4(qa + g * 16, qa + 64 + g * 16, qa + 128 + g * 16, qa + 192 + g * 16, raw[0], raw[1], raw[2], raw[3]);
             float part_sum[NGRP];
 #pragma unroll
             for (int gr = 0; gr < NGRP; ++gr) part_sum[gr] = 0.0f;
@@ -244,11 +266,16 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
             for (int j = 0; j < 4; ++j) {
                 h8_t v = pack8(raw[j].x, raw[j].y, raw[j].z, raw[j].w);
                 if (n >= qper) v = (h8_t)(_Float16)0.0f;
-                qop[j] = v;
                 float sacc = 0.0f;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) sacc += (float)v[e];
-                part_sum[NGRP == 2 ? j / 2 : 0] += sacc;
+                part_sum[j * NGRP / 4] += sacc;
+                if constexpr (BITS == 4) {
+                    const _Float16 sixteenth = (_Float16)0.0625f;       // the odd nibbles arrive 16 times too large
+                    const h8_t w = {v[0], v[4], v[1] * sixteenth, v[5] * sixteenth, v[2], v[6], v[3] * sixteenth, v[7] * sixteenth};
+                    v = w;
+                }
+                qop[j] = v;
             }
 #pragma unroll
             for (int gr = 0; gr < NGRP; ++gr) {
@@ -287,11 +314,27 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
             float s[2][4];
             uint32_t vmraw[2][4][NGRP];        // V (scale, zero) dwords of this lane's tokens; 0 where the token is masked
             float mx = kNegInf;
-            uint4 kp[2][2];
-            const uint32_t ka0 = base + k_rd, ka1 = ka0 ^ 64u, ma = base + m_rd;
-            lds_read16x4_at<0, 0, TILEB, TILEB>(ka0, ka1, ka0, ka1, kp[0][0], kp[0][1], kp[1][0], kp[1][1]);
+            uint4 kp[2][2];                // INT8: [tile][piece];  INT4: kp[tile][0] holds the dwords of the four chunks
+            const uint32_t ka0 = base + k_rd, ma = base + m_rd;
+            if constexpr (BITS == 8) {
+                const uint32_t ka1 = ka0 ^ 64u;
+                lds_read16x4_at<0, 0, TILEB, TILEB>(ka0, ka1, ka0, ka1, kp[0][0], kp[0][1], kp[1][0], kp[1][1]);
+            } else {
+                const uint32_t ka[4] = {ka0, ka0 ^ 16u, ka0 ^ 32u, ka0 ^ 48u};
+                uint32_t k0[4], k1[4];
+                lds_read4x4x2<TILEB>(ka, k0, k1);
+                kp[0][0] = make_uint4(k0[0], k0[1], k0[2], k0[3]);
+                kp[1][0] = make_uint4(k1[0], k1[1], k1[2], k1[3]);
+            }
             uint4 kmeta[2][NGRP], vmeta[2][NGRP];
-            if constexpr (NGRP == 1) {
+            if constexpr (NGRP == 4) {
+                lds_read16x4_at<T_KM, T_KM + 16, T_KM + 32, T_KM + 48>(ma, ma, ma, ma, kmeta[0][0], kmeta[0][1], kmeta[0][2], kmeta[0][3]);
+                lds_read16x4_at<T_VM, T_VM + 16, T_VM + 32, T_VM + 48>(ma, ma, ma, ma, vmeta[0][0], vmeta[0][1], vmeta[0][2], vmeta[0][3]);
+                lds_read16x4_at<TILEB + T_KM, TILEB + T_KM + 16, TILEB + T_KM + 32, TILEB + T_KM + 48>(ma, ma, ma, ma, kmeta[1][0], kmeta[1][1],
+                                                                                                       kmeta[1][2], kmeta[1][3]);
+                lds_read16x4_at<TILEB + T_VM, TILEB + T_VM + 16, TILEB + T_VM + 32, TILEB + T_VM + 48>(ma, ma, ma, ma, vmeta[1][0], vmeta[1][1],
+                                                                                                       vmeta[1][2], vmeta[1][3]);
+            } else if constexpr (NGRP == 1) {
                 lds_read16x4_at<T_KM, T_VM, TILEB + T_KM, TILEB + T_VM>(ma, ma, ma, ma, kmeta[0][0], vmeta[0][0], kmeta[1][0], vmeta[1][0]);
             } else {
                 lds_read16x4_at<T_KM, T_KM + 16, T_VM, T_VM + 16>(ma, ma, ma, ma, kmeta[0][0], kmeta[0][1], vmeta[0][0], vmeta[0][1]);
@@ -305,13 +348,18 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
                 for (int gr = 0; gr < NGRP; ++gr) acc[gr] = (f4_t)0.0f;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const uint4 piece = kp[x][j / 2];
-                    const uint32_t w0 = (j % 2) ? piece.z : piece.x, w1 = (j % 2) ? piece.w : piece.y;
-                    const h8_t a = pack8(__builtin_amdgcn_perm(0u, w0, 0x0c010c00u),
-                                         __builtin_amdgcn_perm(0u, w0, 0x0c030c02u),
-                                         __builtin_amdgcn_perm(0u, w1, 0x0c010c00u),
-                                         __builtin_amdgcn_perm(0u, w1, 0x0c030c02u));
-                    f4_t &dst = acc[NGRP == 2 ? j / 2 : 0];
+                    h8_t a;
+                    if constexpr (BITS == 8) {
+                        const uint4 piece = kp[x][j / 2];
+                        const uint32_t w0 = (j % 2) ? piece.z : piece.x, w1 = (j % 2) ? piece.w : piece.y;
+                        a = pack8(__builtin_amdgcn_perm(0u, w0, 0x0c010c00u), __builtin_amdgcn_perm(0u, w0, 0x0c030c02u),
+                                  __builtin_amdgcn_perm(0u, w1, 0x0c010c00u), __builtin_amdgcn_perm(0u, w1, 0x0c030c02u));
+                    } else {
+                        const uint4 d4 = kp[x][0];
+                        const uint32_t w0 = j == 0 ? d4.x : j == 1 ? d4.y : j == 2 ? d4.z : d4.w, w1 = w0 >> 8;
+                        a = pack8(w0 & 0x000F000Fu, w0 & 0x00F000F0u, w1 & 0x000F000Fu, w1 & 0x00F000F0u);
+                    }
+                    f4_t &dst = acc[j * NGRP / 4];
                     dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, qop[j], dst, 0, 0, 0);
                 }
                 const int room = t1 - (t0 + k * kStep + x * 16 + g * 4);        // row r of this lane's S^T block is a token of the item iff r < room
@@ -395,26 +443,52 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
                     }
                 }
 
-            // ---- O += P V: byte nu of the dwords of two tokens -> two fp16 subnormals
-            uint32_t va[8], vd[2][8];          // vd[tile][set * 4 + r]
-            va[0] = v_rd + base;
+            // ---- O += P V
+            if constexpr (BITS == 8) {
+                // byte nu of the dwords of two tokens -> two fp16 subnormals
+                uint32_t va[8], vd[2][8];          // vd[tile][set * 4 + r]
+                va[0] = v_rd + base;
 #pragma unroll
-            for (int t = 1; t < 8; ++t) va[t] = va[0] ^ (uint32_t)((t & 3) * 16 + (t >> 2) * 64);
-            lds_read4x8x2<ROWB, TILEB>(va, vd[0], vd[1]);
+                for (int t = 1; t < 8; ++t) va[t] = va[0] ^ (uint32_t)((t & 3) * 16 + (t >> 2) * 64);
+                lds_read4x8x2<ROWB, TILEB>(va, vd[0], vd[1]);
 #pragma unroll
-            for (int set = 0; set < 2; ++set)
+                for (int set = 0; set < 2; ++set)
 #pragma unroll
-                for (int nu = 0; nu < 4; ++nu) {
-                    const uint32_t sel = 0x0c000c00u | ((4u + nu) << 16) | (uint32_t)nu;
-                    const h8_t bv = pack8(__builtin_amdgcn_perm(vd[0][set * 4 + 1], vd[0][set * 4 + 0], sel),
-                                          __builtin_amdgcn_perm(vd[0][set * 4 + 3], vd[0][set * 4 + 2], sel),
-                                          __builtin_amdgcn_perm(vd[1][set * 4 + 1], vd[1][set * 4 + 0], sel),
-                                          __builtin_amdgcn_perm(vd[1][set * 4 + 3], vd[1][set * 4 + 2], sel));
-                    const int gr = NGRP == 2 ? set : 0;
-                    f4_t &dst = o[set * 4 + nu];
-                    dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_hi[gr], bv, dst, 0, 0, 0);
-                    dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_lo[gr], bv, dst, 0, 0, 0);
+                    for (int nu = 0; nu < 4; ++nu) {
+                        const uint32_t sel = 0x0c000c00u | ((4u + nu) << 16) | (uint32_t)nu;
+                        const h8_t bv = pack8(__builtin_amdgcn_perm(vd[0][set * 4 + 1], vd[0][set * 4 + 0], sel),
+                                              __builtin_amdgcn_perm(vd[0][set * 4 + 3], vd[0][set * 4 + 2], sel),
+                                              __builtin_amdgcn_perm(vd[1][set * 4 + 1], vd[1][set * 4 + 0], sel),
+                                              __builtin_amdgcn_perm(vd[1][set * 4 + 3], vd[1][set * 4 + 2], sel));
+                        const int gr = NGRP == 2 ? set : 0;
+                        f4_t &dst = o[set * 4 + nu];
+                        dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_hi[gr], bv, dst, 0, 0, 0);
+                        dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_lo[gr], bv, dst, 0, 0, 0);
+                    }
+            } else {
+                // byte n % 4 of the block's dword of two tokens -> (low nibbles) and (high nibbles * 16) as fp16 subnormals
+                const uint32_t va0 = v_rd + base;
+#pragma unroll
+                for (int bb = 0; bb < 4; bb += 2) {
+                    uint32_t vd[2][2][4];          // [block of the pair][tile][r]
+                    lds_read4_rows2x2<ROWB, TILEB>(va0 ^ (uint32_t)(bb * 16), va0 ^ (uint32_t)((bb + 1) * 16), vd[0][0], vd[0][1], vd[1][0], vd[1][1]);
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const int b = bb + h;
+                        const uint32_t p0 = __builtin_amdgcn_perm(vd[h][0][1], vd[h][0][0], v_sel), p1 = __builtin_amdgcn_perm(vd[h][0][3], vd[h][0][2], v_sel);
+                        const uint32_t p2 = __builtin_amdgcn_perm(vd[h][1][1], vd[h][1][0], v_sel), p3 = __builtin_amdgcn_perm(vd[h][1][3], vd[h][1][2], v_sel);
+#pragma unroll
+                        for (int m = 0; m < 2; ++m) {
+                            const uint32_t mask = m ? 0x00F000F0u : 0x000F000Fu;
+                            const h8_t bv = pack8(p0 & mask, p1 & mask, p2 & mask, p3 & mask);
+                            const int gr = b * NGRP / 4;
+                            f4_t &dst = o[b * 2 + m];
+                            dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_hi[gr], bv, dst, 0, 0, 0);
+                            dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_lo[gr], bv, dst, 0, 0, 0);
+                        }
+                    }
                 }
+            }
         };
         auto next_stage = [&]() -> uint32_t {
             fill();
@@ -457,20 +531,42 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
                 const int qh = hk * qper + row;
                 if (part < 0) {
                     const float inv_l = 1.0f / l_row;
-                    _Float16 *dst = p.out + ((int64_t)i * H + qh) * D + 4 * n;
+                    _Float16 *orow = p.out + ((int64_t)i * H + qh) * D;
+                    if constexpr (BITS == 8) {
+                        _Float16 *dst = orow + 4 * n;
 #pragma unroll
-                    for (int set = 0; set < 2; ++set) {
-                        const float zr = z_row[NGRP == 2 ? set : 0];
-                        typedef _Float16 h4_t __attribute__((ext_vector_type(4)));
-                        h4_t v;
+                        for (int set = 0; set < 2; ++set) {
+                            const float zr = z_row[NGRP == 2 ? set : 0];
+                            typedef _Float16 h4_t __attribute__((ext_vector_type(4)));
+                            h4_t v;
 #pragma unroll
-                        for (int nu = 0; nu < 4; ++nu)
-                            v[nu] = (_Float16)(__builtin_fmaf(o[set * 4 + nu][r], 16777216.0f, -zr) * inv_l);
-                        *reinterpret_cast<h4_t *>(dst + 64 * set) = v;
+                            for (int nu = 0; nu < 4; ++nu)
+                                v[nu] = (_Float16)(__builtin_fmaf(o[set * 4 + nu][r], 16777216.0f, -zr) * inv_l);
+                            *reinterpret_cast<h4_t *>(dst + 64 * set) = v;
+                        }
+                    } else {
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) {           // column n of block b: channels 32 b + 2 n and 32 b + 2 n + 1
+                            const float zr = z_row[b * NGRP / 4];
+                            h2_t v;
+                            v.x = (_Float16)(__builtin_fmaf(o[b * 2 + 0][r], 16777216.0f, -zr) * inv_l);
+                            v.y = (_Float16)(__builtin_fmaf(o[b * 2 + 1][r], 1048576.0f, -zr) * inv_l);      // 2^24 / 16
+                            *reinterpret_cast<h2_t *>(orow + 32 * b + 2 * n) = v;
+                        }
                     }
                 } else {
                     float *dst = p.ws.part + ((int64_t)part * H + qh) * (D + 2);
                     if (n == 0) { dst[0] = m_row; dst[1] = l_row; }
+                    if constexpr (BITS == 4) {
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) {
+                            const float zr = z_row[b * NGRP / 4];
+                            float2 v2;
+                            v2.x = __builtin_fmaf(o[b * 2 + 0][r], 16777216.0f, -zr);
+                            v2.y = __builtin_fmaf(o[b * 2 + 1][r], 1048576.0f, -zr);
+                            *reinterpret_cast<float2 *>(dst + 2 + 32 * b + 2 * n) = v2;
+                        }
+                    } else
 #pragma unroll
                     for (int set = 0; set < 2; ++set) {
                         const float zr = z_row[NGRP == 2 ? set : 0];
@@ -490,21 +586,21 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
     ALISE_VMCNT(0);     // nothing may still be on its way into LDS when the wave ends
 }
 
-template <int NGRP, int QROWS, int S>
+template <int BITS, int NGRP, int QROWS, int S>
 hipError_t launch_gqa_t(const AttnParams &p, int32_t num_cus, int32_t waves_per_cu, hipStream_t s)
 {
     // one wave per workgroup; as many as the LDS lets a compute unit hold, unless the caller fixes the number
     static int occ = 0;
     if (occ == 0) {
         int n = 0;
-        hipError_t oe = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, decode_attn_gqa_kernel<NGRP, QROWS, S>, 64, 0);
+        hipError_t oe = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, decode_attn_gqa_kernel<BITS, NGRP, QROWS, S>, 64, 0);
         occ = (oe == hipSuccess && n > 0) ? n : 4;
     }
     int waves = num_cus * (waves_per_cu > 0 ? waves_per_cu : occ);
     const int64_t max_items = (int64_t)p.ws.max_tiles * p.c.Hkv;
     if (waves > max_items) waves = (int)max_items;
     if (waves < 1) waves = 1;
-    hipLaunchKernelGGL((decode_attn_gqa_kernel<NGRP, QROWS, S>), dim3(waves), dim3(64), 0, s, p);
+    hipLaunchKernelGGL((decode_attn_gqa_kernel<BITS, NGRP, QROWS, S>), dim3(waves), dim3(64), 0, s, p);
     return hipGetLastError();
 }
 
@@ -513,7 +609,8 @@ hipError_t launch_gqa_t(const AttnParams &p, int32_t num_cus, int32_t waves_per_
 bool gqa_mfma_applies(const CacheView &c, int32_t H)
 {
     const int qper = H / c.Hkv;
-    return c.bits == 8 && c.D == 128 && (c.G == 128 || c.G == 64) && c.P >= 16 && qper >= 2 && qper <= 16;
+    if (c.D != 128 || c.P < 16 || qper < 2 || qper > 16) return false;
+    return (c.bits == 8 && (c.G == 128 || c.G == 64)) || (c.bits == 4 && c.G == 32);
 }
 
 hipError_t launch_gqa_mfma(const AttnParams &p, int32_t num_cus, int32_t waves_per_cu, int32_t stages, hipStream_t s)
@@ -522,12 +619,16 @@ hipError_t launch_gqa_mfma(const AttnParams &p, int32_t num_cus, int32_t waves_p
     const bool small = p.qper <= 8;
 #define ALISE_GQA_DISPATCH(SV)                                                                                        \
     do {                                                                                                              \
+        if (p.c.bits == 4)                                                                                            \
+            return small ? launch_gqa_t<4, 4, 8, SV>(p, num_cus, waves_per_cu, s) : launch_gqa_t<4, 4, 16, SV>(p, num_cus, waves_per_cu, s); \
         if (ngrp == 1)                                                                                                \
-            return small ? launch_gqa_t<1, 8, SV>(p, num_cus, waves_per_cu, s) : launch_gqa_t<1, 16, SV>(p, num_cus, waves_per_cu, s); \
-        return small ? launch_gqa_t<2, 8, SV>(p, num_cus, waves_per_cu, s) : launch_gqa_t<2, 16, SV>(p, num_cus, waves_per_cu, s);     \
+            return small ? launch_gqa_t<8, 1, 8, SV>(p, num_cus, waves_per_cu, s) : launch_gqa_t<8, 1, 16, SV>(p, num_cus, waves_per_cu, s); \
+        return small ? launch_gqa_t<8, 2, 8, SV>(p, num_cus, waves_per_cu, s) : launch_gqa_t<8, 2, 16, SV>(p, num_cus, waves_per_cu, s);     \
     } while (0)
     // Two stages and more resident waves beat deeper prefetch with fewer waves (measured on the
     // 8-heads-per-KV-head workload: 209 us against 217-222 us for three and four stages).
+    // INT4 stages are half the size and its steps are longer (four scale groups): three stages measured best there.
+    if (stages == 0 && p.c.bits == 4) stages = 3;
     if (stages == 3) ALISE_GQA_DISPATCH(3);
     if (stages == 4) ALISE_GQA_DISPATCH(4);
     ALISE_GQA_DISPATCH(2);
