@@ -1,0 +1,107 @@
+"""Every kernel variant that a tuning knob can select (environment variables read per call) must
+compute the same attention (ALISE Sec. 2, Eq. 1-2 over the cache of Sec. 3.2): stage counts and
+wave-loads per block, waves per compute unit, split lengths, the floor of items per wave, and
+the one-row-tile prefill kernels.  Each setting is run on small batches of the four layouts
+(MHA INT8, MHA INT4, GQA INT8, GQA INT4) and compared with the oracle."""
+import os
+
+import numpy as np
+import pytest
+
+from paper_2410_23537_amd import workloads as wl
+from tests import harness
+
+pytestmark = pytest.mark.gpu
+
+ATTN_TOL = 2e-3
+KNOBS = ("ALISE_SPLIT_TOKENS", "ALISE_SPLIT_TOKENS_GQA", "ALISE_WAVES_PER_CU", "ALISE_LOADS_PER_BLOCK",
+         "ALISE_MIN_ITEMS_PER_WAVE", "ALISE_PREFILL_ROW_TILES")
+
+LAYOUTS = [
+    wl.replace(wl.scaled(wl.CONFIGS["llama7b"], B=6, max_len=2600, name="mha_int8"), Hkv=4, H=4, length_law="uniform:1,2600"),
+    wl.replace(wl.scaled(wl.CONFIGS["int4"], B=6, max_len=2600, name="mha_int4"), Hkv=4, H=4, length_law="uniform:1,2600"),
+    wl.replace(wl.scaled(wl.CONFIGS["gqa70b"], B=5, max_len=2600, name="gqa_int8"), Hkv=2, H=16, length_law="uniform:1,2600"),
+    wl.replace(wl.scaled(wl.CONFIGS["gqa70b"], B=5, max_len=2600, name="gqa_int4"), bits=4, G=32, Hkv=2, H=16,
+               length_law="uniform:1,2600"),
+]
+
+SETTINGS = [
+    {"ALISE_LOADS_PER_BLOCK": "3"}, {"ALISE_LOADS_PER_BLOCK": "4"}, {"ALISE_LOADS_PER_BLOCK": "2"},
+    {"ALISE_WAVES_PER_CU": "4"}, {"ALISE_WAVES_PER_CU": "8"},
+    {"ALISE_SPLIT_TOKENS": "256", "ALISE_SPLIT_TOKENS_GQA": "256"}, {"ALISE_SPLIT_TOKENS": "512", "ALISE_SPLIT_TOKENS_GQA": "512"},
+    {"ALISE_SPLIT_TOKENS": "1024", "ALISE_SPLIT_TOKENS_GQA": "1024"},
+    {"ALISE_MIN_ITEMS_PER_WAVE": "1"}, {"ALISE_MIN_ITEMS_PER_WAVE": "16"},
+    {"ALISE_LOADS_PER_BLOCK": "4", "ALISE_WAVES_PER_CU": "4", "ALISE_SPLIT_TOKENS": "512", "ALISE_SPLIT_TOKENS_GQA": "512"},
+]
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2410_23537_amd import binding
+    import oracle
+    oracle.build()
+    return binding, torch, oracle
+
+
+@pytest.fixture(scope="module")
+def problems(env):
+    B, torch, oracle = env
+    out = {}
+    for w in LAYOUTS:
+        pg = wl.paging(w)
+        pool = wl.value_pool(w, n_min=int(pg.lens.max()) * w.Hkv * w.D)
+        offs, gain = wl.request_offsets(w), wl.k_channel_gain(w)
+        orc = harness.fill_oracle_cache(oracle, w, pg, pool, offs, gain)
+        dev = harness.fill_device_cache(B, torch, w, pg, pool, offs, gain)
+        q = wl.queries(w)
+        want = oracle.paged_decode_attn(orc, q, pg.block_tables, pg.lens, 1.0 / np.sqrt(w.D))
+        out[w.name] = (w, pg, orc, dev, q, want)
+    return out
+
+
+@pytest.fixture(autouse=True)
+def clean_environment():
+    saved = {k: os.environ.pop(k, None) for k in KNOBS}
+    yield
+    for k in KNOBS:
+        os.environ.pop(k, None)
+        if saved[k] is not None:
+            os.environ[k] = saved[k]
+
+
+@pytest.mark.parametrize("setting", SETTINGS, ids=lambda s: ",".join(f"{k[6:].lower()}={v}" for k, v in s.items()))
+def test_decode_under_every_knob(env, problems, setting):
+    B, torch, oracle = env
+    os.environ.update(setting)
+    for name, (w, pg, orc, dev, q, want) in problems.items():
+        print(f"case knobs {setting} {name}", flush=True)
+        got = harness.run_device_attn(B, torch, w, dev, q, pg).astype(np.float64)
+        err = float(np.abs(got - want).max())
+        assert np.isfinite(got).all() and err <= ATTN_TOL, f"{name} under {setting}: {err:.3e}"
+
+
+@pytest.mark.parametrize("tiles", ["1", "2"])
+def test_prefill_with_one_and_two_row_tiles(env, problems, tiles):
+    B, torch, oracle = env
+    os.environ["ALISE_PREFILL_ROW_TILES"] = tiles
+    for name, (w, pg, orc, dev, q, _) in problems.items():
+        print(f"case knobs prefill row tiles {tiles} {name}", flush=True)
+        lens = pg.lens.astype(np.int64)
+        n = np.minimum(lens, [150, 1, 97, 33, 64, 200][:w.B])
+        q_start = np.concatenate([[0], np.cumsum(n)]).astype(np.int32)
+        total = int(q_start[-1])
+        rng = np.random.default_rng([w.seed, 3])
+        q_np = rng.standard_normal((total, w.H, w.D)).astype(np.float16)
+        scale = 1.0 / np.sqrt(w.D)
+        want = oracle.paged_prefill_attn(orc, q_np, q_start, pg.block_tables, pg.lens, scale)
+        qd = torch.from_numpy(q_np).cuda()
+        out = torch.full(qd.shape, float("nan"), dtype=torch.float16, device="cuda")
+        ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(dev, w.B, total, w.H), dtype=torch.uint8, device="cuda")
+        B.alise_paged_prefill_attn(dev, qd, out, torch.from_numpy(q_start).cuda(), torch.from_numpy(pg.block_tables).cuda(),
+                                   torch.from_numpy(pg.lens.astype(np.int32)).cuda(), int(lens.max()), scale, ws)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().astype(np.float64)
+        err = float(np.abs(got - want).max())
+        assert np.isfinite(got).all() and err <= ATTN_TOL, f"{name} with {tiles} row tiles: {err:.3e}"
