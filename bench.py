@@ -410,7 +410,8 @@ def main():
         torch.cuda.synchronize()
 
     ms_per_step = elapsed / args.steps * 1e3
-    attn_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    attn_all = [a.elapsed_time(b) for a, b in ev]
+    attn_ms = float(np.mean(attn_all))
     write_ms = float(np.mean([a.elapsed_time(b) for a, b in evw]))
     b_attn, b_write, b_dq = step.bytes_attn(), step.bytes_write(), step.bytes_dequant()
     total_bytes = b_attn + b_write + b_dq
@@ -428,7 +429,8 @@ def main():
         "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
         "kv_tokens_per_s": step.kv_tokens() / (ms_per_step * 1e-3),
         "bytes_per_step": {"attn": b_attn, "quant_write": b_write, "dequant_page": b_dq},
-        "kernel_ms": {"paged_decode_attn": attn_ms, "quant_write": write_ms},
+        "kernel_ms": {"paged_decode_attn": attn_ms, "quant_write": write_ms,
+                      "paged_decode_attn_min": float(np.min(attn_all)), "paged_decode_attn_median": float(np.median(attn_all))},
         "roofline": {"bound": "hbm",
                      "kernel": "alise_paged_decode_attn = plan_kernel + decode_attn(_gqa)_kernel + merge_kernel, "
                                "timed as one call; the attention kernel is >97 % of it",
