@@ -165,6 +165,39 @@ __device__ __forceinline__ uint32_t meta_of(const uint4 (&m)[NGRP], int r, int g
     return c == 0 ? u.x : c == 1 ? u.y : c == 2 ? u.z : u.w;
 }
 
+// Mixed-precision multiply-adds that read an fp16 factor in place out of a dword (v_fma_mix_*), written
+// out because the compiler mostly converts the half to fp32 first and then spends a plain fp32
+// multiply-add on it all the same: one instruction more per half.  The compiler does not see into these
+// statements, so it inserts none of the wait states that an operand just written by a matrix or a
+// transcendental instruction needs: no operand of the first three may come straight from a matrix
+// instruction (use them on values that ordinary vector instructions or LDS reads produced), and the one
+// that takes the softmax weights (fresh from v_exp_f32) brings its own wait state.
+// lo(h) * b + c in fp32:
+__device__ __forceinline__ float fma_lo_half(uint32_t h, float b, float c)
+{
+    float d;
+    asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel_hi:[1,0,0]" : "=v"(d) : "v"(h), "v"(b), "v"(c));
+    return d;
+}
+// hi(a) * (half E of b) + c in fp32, both factors fp16:
+template <int E>
+__device__ __forceinline__ float fma_hi_by_half(uint32_t a, uint32_t b, float c)
+{
+    float d;
+    if constexpr (E == 0) asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[1,0,0] op_sel_hi:[1,1,0]" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+    else asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[1,1,0] op_sel_hi:[1,1,0]" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+    return d;
+}
+// (lo(h0) * p0, lo(h1) * p1), each rounded to fp16 (nearest even), as one dword; p0 and p1 may be
+// results of a transcendental instruction issued just before (one wait state, spent here).
+__device__ __forceinline__ uint32_t mul_lo_halves_to_h2(uint32_t h0, float p0, uint32_t h1, float p1)
+{
+    uint32_t d;
+    asm("s_nop 0\n\tv_fma_mixlo_f16 %0, %1, %2, 0 op_sel_hi:[1,0,0]\n\tv_fma_mixhi_f16 %0, %3, %4, 0 op_sel_hi:[1,0,0]"
+        : "=&v"(d) : "v"(h0), "v"(p0), "v"(h1), "v"(p1));
+    return d;
+}
+
 __device__ __forceinline__ h8_t pack8(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
 {
     typedef uint32_t u4_t __attribute__((ext_vector_type(4)));

@@ -13,11 +13,15 @@
 // of the step (K or V codes of one 16-token tile plus its scales and zero-points) with direct
 // global -> LDS loads, three stages deep, one workgroup barrier per step.  Per wave the step is
 // the one of the grouped-query decode kernel: S^T = K Q^T and O += P V on
-// v_mfma_f32_16x16x32_f16, K and V codes as fp16 subnormals code * 2^-24, P * lambda_v split in
-// high and low fp16 parts, online softmax with a lazily raised maximum -- except that the mask
-// is per row (token <= the row's position), that only the steps on a wave's diagonal are masked
-// at all, and that a wave skips the steps none of its rows can see.  Two row tiles of a wave
-// share the operands built from the cache.  INT8 caches (one or two scale groups per head) and
+// v_mfma_f32_16x16x32_f16, K and V codes as fp16 subnormals code * 2^-24, online softmax with a
+// lazily raised maximum -- except that the mask is per row (token <= the row's position), that
+// only the steps on a wave's diagonal are masked at all, that a wave skips the steps none of its
+// rows can see, and that a weight P * lambda_v is one fp16 number (rounded to nearest even) instead
+// of a high and a low part: the kernel is bound by its vector instructions, the second product per
+// weight and the instruction that forms the low part were a sixth of them, and with the zero-point
+// sum taken over the same rounded weights the rounding only perturbs each weight by 2^-12 relative
+// (no cancellation between the code sum and the zero-point sum), i.e. the output by at most
+// 2^-12 max|v|.  Two row tiles of a wave share the operands built from the cache.  INT8 caches (one or two scale groups per head) and
 // INT4 caches with groups of 32 channels are taken; the INT4 operand formats are described at the
 // top of the kernel body.
 // There is no split along the context and therefore nothing to merge: a chunk of a few
@@ -348,9 +352,10 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
                     float sv = 0.0f;
 #pragma unroll
                     for (int gr = 0; gr < NGRP; ++gr) {
-                        const h2_t kmh = as_h2(meta_of<NGRP>(kmeta[x], r, gr));     // the fp16 halves of the meta dword, read in place
-                        const float u = __builtin_fmaf((float)kmh.y, nqs24[t][gr], acc[t][gr][r]);
-                        sv = __builtin_fmaf((float)kmh.x, u, sv);
+                        const uint32_t km = meta_of<NGRP>(kmeta[x], r, gr);         // (scale, zero-point)
+                        // the reader of the matrix result is left to the compiler (wait states), the scale is read in place
+                        const float u = __builtin_fmaf((float)as_h2(km).y, nqs24[t][gr], acc[t][gr][r]);
+                        sv = fma_lo_half(km, u, sv);
                         if (MASKED || t == 0) {
                             const uint32_t vm = meta_of<NGRP>(vmeta[x], r, gr);
                             vmraw[MASKED ? t : 0][x][r][gr] = valid ? vm : 0u;
@@ -401,9 +406,8 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
             }
         }
 
-        // ---- weights p * lambda_v as fp16 high + low parts, in the A-operand order (tile, row).  The high
-        // part is the product truncated to fp16, the low part what is left of the exact product.
-        h8_t a_hi[RT][NGRP], a_lo[RT][NGRP];
+        // ---- weights p * lambda_v in fp16, rounded to nearest even, in the A-operand order (tile, row)
+        h8_t a_w[RT][NGRP];
 #pragma unroll
         for (int t = 0; t < RT; ++t)
 #pragma unroll
@@ -418,21 +422,13 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
                     }
 #pragma unroll
                     for (int gr = 0; gr < NGRP; ++gr) {
-                        float wv[2];
-                        uint32_t vm[2];
-#pragma unroll
-                        for (int e = 0; e < 2; ++e) {
-                            vm[e] = vmraw[MASKED ? t : 0][x][rr + e][gr];
-                            const h2_t vmh = as_h2(vm[e]);
-                            wv[e] = __builtin_fmaf((float)vmh.x, pj[e], 0.0f);
-                            z_part[t][gr] = __builtin_fmaf((float)vmh.y, wv[e], z_part[t][gr]);
-                        }
-                        const h2_t hi = __builtin_bit_cast(h2_t, __builtin_amdgcn_cvt_pkrtz(wv[0], wv[1]));
-#pragma unroll
-                        for (int e = 0; e < 2; ++e) {
-                            a_hi[t][gr][x * 4 + rr + e] = hi[e];
-                            a_lo[t][gr][x * 4 + rr + e] = (_Float16)__builtin_fmaf((float)as_h2(vm[e]).x, pj[e], -(float)hi[e]);
-                        }
+                        const uint32_t vm0 = vmraw[MASKED ? t : 0][x][rr][gr], vm1 = vmraw[MASKED ? t : 0][x][rr + 1][gr];
+                        const uint32_t w16 = mul_lo_halves_to_h2(vm0, pj[0], vm1, pj[1]);
+                        // the zero-point sum takes the rounded weight, the one the matrix product multiplies the codes with
+                        z_part[t][gr] = fma_hi_by_half<0>(vm0, w16, z_part[t][gr]);
+                        z_part[t][gr] = fma_hi_by_half<1>(vm1, w16, z_part[t][gr]);
+                        a_w[t][gr][x * 4 + rr] = as_h2(w16).x;
+                        a_w[t][gr][x * 4 + rr + 1] = as_h2(w16).y;
                     }
                 }
 
@@ -457,8 +453,7 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
 #pragma unroll
                     for (int t = 0; t < RT; ++t) {
                         f4_t &dst = o[t][set * 4 + nu];
-                        dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_hi[t][gr], bv, dst, 0, 0, 0);
-                        dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_lo[t][gr], bv, dst, 0, 0, 0);
+                        dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_w[t][gr], bv, dst, 0, 0, 0);
                     }
                 }
         } else {
@@ -481,8 +476,7 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
 #pragma unroll
                         for (int t = 0; t < RT; ++t) {
                             f4_t &dst = o[t][b * 2 + m];
-                            dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_hi[t][gr], bv, dst, 0, 0, 0);
-                            dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_lo[t][gr], bv, dst, 0, 0, 0);
+                            dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_w[t][gr], bv, dst, 0, 0, 0);
                         }
                     }
                 }
