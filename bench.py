@@ -230,6 +230,31 @@ def graph_leg(step, total_bytes, steps):
             "note": "one captured step replayed; the headline figures above are the eager calls"}
 
 
+def read_ceiling_leg():
+    """The second denominator: what a kernel that only reads sustains on this device (the library's
+    streaming-read probe over 4 GiB, sixteen times the last-level cache), beside the published peak."""
+    import numpy as np
+    import torch
+    from paper_2410_23537_amd import binding as B
+    src = torch.empty(1 << 32, dtype=torch.uint8, device="cuda")
+    src.view(torch.int32).random_()
+    out = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for _ in range(2):
+        B.alise_hbm_read_probe(src, out)
+    ts = []
+    for _ in range(10):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        B.alise_hbm_read_probe(src, out)
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1))
+    ms = float(np.median(ts))
+    return {"GBs": src.numel() / (ms * 1e-3) / 1e9, "bytes": src.numel(), "ms": ms,
+            "note": "alise_hbm_read_probe over 4 GiB: 16-byte non-temporal loads from a persistent grid, two 8 KiB blocks in flight per wave, "
+                    "nothing else; median of 10 calls, the call's two launches included"}
+
+
 def fused_ops_leg(w):
     """The two other fused operators of the layer (Sec. 3.3 "Implementation"), outside the timed
     steps, on a token batch of this workload's model: 16384 tokens (prefill chunks of an iteration;
@@ -438,6 +463,9 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(w.name)},
     }
     if not args.only_steps:
+        ceiling = read_ceiling_leg()
+        result["hbm_read_ceiling"] = ceiling
+        result["roofline"]["frac_of_read_ceiling"] = achieved / ceiling["GBs"]
         result["graph_replay"] = graph_leg(step, total_bytes, args.steps)
         result["swap"] = swap_leg(step)
         prefill = prefill_leg(w, step)

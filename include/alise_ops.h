@@ -1,6 +1,7 @@
 /*
  * alise_ops.h -- C ABI of the two fused elementwise / row operators of the transformer layer
- * for MI355X (gfx950): residual add + LayerNorm, and bias + ReLU.
+ * for MI355X (gfx950): residual add + LayerNorm, and bias + ReLU; plus the streaming-read probe
+ * that the measurements use as their bandwidth ceiling.
  *
  * ALISE (arXiv 2410.23537) Sec. 3.3 "Implementation" lists fused kernels for LayerNorm,
  * Attention and ReLU and batches LayerNorm and ReLU over the irregularly shaped token batches
@@ -61,6 +62,21 @@ int alise_add_layernorm(const void *x, const void *residual, const void *gamma, 
  */
 int alise_bias_relu(const void *x, const void *bias, void *y_out, int64_t rows, int32_t cols,
                     void *hip_stream);
+
+/*
+ * Streaming-read probe: a measurement utility, not an operation of the paper.  The decode step is
+ * "memory-bound" (Sec. 4.2) and its figure of merit here is the fraction of the HBM bandwidth it
+ * sustains; this call measures what a kernel that does nothing but read sustains on the same
+ * device, the ceiling beside the published peak.
+ *
+ * Reads `bytes` bytes at src once (16-byte non-temporal loads from a persistent grid) and stores
+ * the exclusive-or of all 32-bit words read into *xor_out (0 for bytes == 0).
+ *
+ * src: device, 16-byte aligned, read.   bytes: a multiple of 16, else ALISE_UNSUPPORTED.
+ * xor_out: device, one uint32, written (cleared first, then combined with atomics: do not read it
+ * before the stream has passed the call).
+ */
+int alise_hbm_read_probe(const void *src, size_t bytes, void *xor_out, void *hip_stream);
 
 #ifdef __cplusplus
 }

@@ -34,7 +34,7 @@ EXPORTS = ("alise_kv_codes_bytes", "alise_kv_meta_bytes", "alise_kv_quant_write"
            "alise_paged_decode_attn_workspace_bytes", "alise_paged_decode_attn",
            "alise_kv_dequant_page", "alise_kv_swap_bytes", "alise_kv_swap_out", "alise_kv_swap_in",
            "alise_paged_prefill_attn_workspace_bytes", "alise_paged_prefill_attn",
-           "alise_add_layernorm", "alise_bias_relu",
+           "alise_add_layernorm", "alise_bias_relu", "alise_hbm_read_probe",
            "alise_sched_create", "alise_sched_destroy", "alise_sched_add_job", "alise_sched_num_jobs",
            "alise_sched_step", "alise_sched_commit",
            "alise_status_string")
@@ -85,6 +85,8 @@ _lib.alise_add_layernorm.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_
 _lib.alise_bias_relu.restype = ctypes.c_int
 _lib.alise_bias_relu.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32,
                                  ctypes.c_void_p]
+_lib.alise_hbm_read_probe.restype = ctypes.c_int
+_lib.alise_hbm_read_probe.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
 _lib.alise_status_string.restype = ctypes.c_char_p
 _lib.alise_status_string.argtypes = [ctypes.c_int]
 
@@ -285,6 +287,13 @@ def alise_bias_relu(x: torch.Tensor, bias, y_out: torch.Tensor) -> None:
     assert bias is None or (bias.dtype == torch.float16 and bias.is_cuda and bias.is_contiguous() and bias.shape == (cols,))
     st = _lib.alise_bias_relu(_dp(x), _dp(bias), _dp(y_out), rows, cols, _stream())
     _check(st, "alise_bias_relu")
+
+
+def alise_hbm_read_probe(src: torch.Tensor, xor_out: torch.Tensor) -> None:
+    """src: any contiguous device tensor whose size in bytes is a multiple of 16; xor_out: int32 or uint32 [1], device."""
+    assert src.is_cuda and src.is_contiguous() and xor_out.is_cuda and xor_out.numel() == 1 and xor_out.element_size() == 4
+    st = _lib.alise_hbm_read_probe(_dp(src), src.numel() * src.element_size(), _dp(xor_out), _stream())
+    _check(st, "alise_hbm_read_probe")
 
 
 class alise_sched_config(ctypes.Structure):

@@ -1,0 +1,86 @@
+// Streaming-read probe for gfx950: the rate at which the chip can read HBM with nothing else to do.
+//
+// The decode path is bound by HBM reads; the published peak (8 TB/s) is a pin rate that no kernel
+// reaches.  This kernel reads a buffer once with 16-byte non-temporal loads, as many in flight as a
+// persistent grid of full workgroups can keep, and folds what it read into one 32-bit word (the
+// exclusive-or of all dwords), which makes the read observable and the call testable.  Its rate
+// on a buffer larger than the last-level cache is the second denominator of the measurements.
+#include "alise_kernels.h"
+#include "../../include/alise_ops.h"
+
+namespace alise {
+namespace {
+
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+// A wave reads blocks of kProbeLoads KiB (one load instruction = 1 KiB of consecutive addresses), the
+// waves of the persistent grid take the blocks in turn, and a wave keeps two blocks in flight: the loads of
+// the next block are issued before the last one is folded.  The tail (less than a block) goes to the first
+// waves, 16 bytes per lane.  The sink is cleared by sink_clear_kernel first; one atomic per wave at the end.
+constexpr int kProbeLoads = 8;
+
+__global__ void sink_clear_kernel(uint32_t *sink) { *sink = 0u; }
+
+__global__ __launch_bounds__(256) void read_probe_kernel(const u32x4_t *__restrict__ src, uint64_t n16, uint32_t *sink)
+{
+    const int lane = threadIdx.x & 63;
+    const uint64_t wave = ((uint64_t)blockIdx.x * 256u + threadIdx.x) >> 6, n_waves = ((uint64_t)gridDim.x * 256u) >> 6;
+    constexpr uint64_t kBlock = (uint64_t)kProbeLoads * 64u;       // 16-byte units per block
+    const uint64_t n_blocks = n16 / kBlock;
+    uint32_t acc = 0u;
+    u32x4_t a[kProbeLoads], b[kProbeLoads];
+    auto issue = [&](u32x4_t (&v)[kProbeLoads], uint64_t blk) {
+#pragma unroll
+        for (int u = 0; u < kProbeLoads; ++u) v[u] = __builtin_nontemporal_load(src + blk * kBlock + (uint64_t)u * 64u + lane);
+    };
+    auto fold = [&](const u32x4_t (&v)[kProbeLoads]) {
+#pragma unroll
+        for (int u = 0; u < kProbeLoads; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    };
+    uint64_t blk = wave;
+    if (blk < n_blocks) {
+        issue(a, blk);
+        for (;;) {
+            blk += n_waves;
+            if (blk >= n_blocks) { fold(a); break; }
+            issue(b, blk);
+            fold(a);
+            blk += n_waves;
+            if (blk >= n_blocks) { fold(b); break; }
+            issue(a, blk);
+            fold(b);
+        }
+    }
+    for (uint64_t i = n_blocks * kBlock + wave * 64u + lane; i < n16; i += n_waves * 64u) {
+        const u32x4_t v = __builtin_nontemporal_load(src + i);
+        acc ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) acc ^= __shfl_xor(acc, d);
+    if (lane == 0 && acc != 0u) atomicXor(sink, acc);
+}
+
+}  // namespace
+}  // namespace alise
+
+extern "C" int alise_hbm_read_probe(const void *src, size_t bytes, void *xor_out, void *hip_stream)
+{
+    using namespace alise;
+    if (!xor_out || (bytes && !src)) return ALISE_INVALID_ARGUMENT;
+    if (bytes & 15u) return ALISE_UNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(src) & 15u) || (reinterpret_cast<uintptr_t>(xor_out) & 3u)) return ALISE_MISALIGNED;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        return ALISE_HIP_ERROR;
+    hipLaunchKernelGGL(sink_clear_kernel, dim3(1), dim3(1), 0, s, static_cast<uint32_t *>(xor_out));
+    if (hipGetLastError() != hipSuccess) return ALISE_HIP_ERROR;
+    const uint64_t n16 = bytes >> 4;
+    if (n16 == 0) return ALISE_OK;
+    uint64_t blocks = (n16 + 255u) / 256u;
+    const uint64_t resident = (uint64_t)cus * 4u;               // four workgroups of four waves per compute unit
+    if (blocks > resident) blocks = resident;
+    hipLaunchKernelGGL(read_probe_kernel, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const u32x4_t *>(src), n16,
+                       static_cast<uint32_t *>(xor_out));
+    return hipGetLastError() == hipSuccess ? ALISE_OK : ALISE_HIP_ERROR;
+}

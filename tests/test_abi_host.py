@@ -229,3 +229,11 @@ def test_fused_op_arguments(B):
     assert relu(b=A + 4) == B.ALISE_MISALIGNED
     assert relu(rows=0) == B.ALISE_OK
     assert relu(rows=0, b=None) == B.ALISE_OK
+
+    probe = lambda src=A, n=4096, out=A: lib.alise_hbm_read_probe(src, n, out, None)
+    assert probe(out=None) == B.ALISE_INVALID_ARGUMENT
+    assert probe(src=None) == B.ALISE_INVALID_ARGUMENT
+    for n in (8, 17, 4100):
+        assert probe(n=n) == B.ALISE_UNSUPPORTED                  # whole 16-byte units only
+    assert probe(src=A + 8) == B.ALISE_MISALIGNED
+    assert probe(out=A + 2) == B.ALISE_MISALIGNED

@@ -150,3 +150,18 @@ def test_bias_relu_against_oracle(env, shape, mode):
     torch.cuda.synchronize()
     assert (buf[rows:] == 5.0).all(), "wrote past the last row"
     assert np.array_equal(buf[:rows].cpu().numpy().view(np.uint16), want.view(np.uint16))
+
+
+@pytest.mark.parametrize("n16", [0, 1, 255, 256 * 8 * 3 + 5, 1 << 20, (1 << 22) + 12345])
+def test_read_probe_folds_every_word_once(env, n16):
+    """The streaming-read probe returns the exclusive-or of all 32-bit words of the buffer: every
+    16-byte unit is read exactly once, whatever the size is relative to the grid and its unrolling."""
+    B, torch, _ = env
+    rng = np.random.default_rng([77, n16])
+    host = rng.integers(0, 1 << 32, size=n16 * 4, dtype=np.uint32)
+    src = torch.from_numpy(host.view(np.int32)).cuda()
+    out = torch.full((1,), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
+    B.alise_hbm_read_probe(src, out)
+    torch.cuda.synchronize()
+    want = int(np.bitwise_xor.reduce(host)) if n16 else 0
+    assert int(out.cpu().numpy().view(np.uint32)[0]) == want
