@@ -472,6 +472,12 @@ def main():
         if prefill is not None:
             result["prefill"] = prefill
             result["prefill_full_batch"] = prefill_leg(w, step, every=1)      # the same with a grid that fills the chip
+            os.environ["ALISE_PREFILL_WEIGHTS"] = "single"                    # read per call by the library
+            fast = prefill_leg(w, step, every=1)
+            del os.environ["ALISE_PREFILL_WEIGHTS"]
+            fast["note"] = ("ALISE_PREFILL_WEIGHTS=single: one rounded fp16 number per softmax weight instead of a high and "
+                            "a low part; adds up to 2^-12 max|v| to the error, not the default")
+            result["prefill_full_batch_single_weight"] = fast
         result["fused_ops"] = fused_ops_leg(w)
         result["scheduler"] = scheduled_run_leg(w)
     if not args.no_cpu_baseline:

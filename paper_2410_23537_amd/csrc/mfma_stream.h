@@ -169,9 +169,9 @@ __device__ __forceinline__ uint32_t meta_of(const uint4 (&m)[NGRP], int r, int g
 // out because the compiler mostly converts the half to fp32 first and then spends a plain fp32
 // multiply-add on it all the same: one instruction more per half.  The compiler does not see into these
 // statements, so it inserts none of the wait states that an operand just written by a matrix or a
-// transcendental instruction needs: no operand of the first three may come straight from a matrix
-// instruction (use them on values that ordinary vector instructions or LDS reads produced), and the one
-// that takes the softmax weights (fresh from v_exp_f32) brings its own wait state.
+// transcendental instruction needs: no operand may come straight from a matrix instruction (use them
+// on values that ordinary vector instructions or LDS reads produced), and the ones that take the
+// softmax weights (fresh from v_exp_f32) bring their own wait state.
 // lo(h) * b + c in fp32:
 __device__ __forceinline__ float fma_lo_half(uint32_t h, float b, float c)
 {
@@ -195,6 +195,29 @@ __device__ __forceinline__ uint32_t mul_lo_halves_to_h2(uint32_t h0, float p0, u
     uint32_t d;
     asm("s_nop 0\n\tv_fma_mixlo_f16 %0, %1, %2, 0 op_sel_hi:[1,0,0]\n\tv_fma_mixhi_f16 %0, %3, %4, 0 op_sel_hi:[1,0,0]"
         : "=&v"(d) : "v"(h0), "v"(p0), "v"(h1), "v"(p1));
+    return d;
+}
+// lo(h) * p in fp32, p possibly fresh from a transcendental instruction (one wait state, spent here)
+__device__ __forceinline__ float mul_lo_half_f32(uint32_t h, float p)
+{
+    float d;
+    asm("s_nop 0\n\tv_fma_mix_f32 %0, %1, %2, 0 op_sel_hi:[1,0,0]" : "=v"(d) : "v"(h), "v"(p));
+    return d;
+}
+// hi(h) * b + c in fp32, b and c fp32 values that an ordinary vector instruction produced
+__device__ __forceinline__ float fma_hi_half(uint32_t h, float b, float c)
+{
+    float d;
+    asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(h), "v"(b), "v"(c));
+    return d;
+}
+// What the fp16 pair w lacks of the exact products (w: the products rounded to fp16, made from the same operands):
+// (lo(h0) * p0 - lo(w), lo(h1) * p1 - hi(w)), each computed with one rounding, as one dword.
+__device__ __forceinline__ uint32_t residual_of_h2(uint32_t h0, float p0, uint32_t h1, float p1, uint32_t w)
+{
+    uint32_t d;
+    asm("v_fma_mixlo_f16 %0, %1, %2, -%5 op_sel_hi:[1,0,1]\n\tv_fma_mixhi_f16 %0, %3, %4, -%5 op_sel:[0,0,1] op_sel_hi:[1,0,1]"
+        : "=&v"(d) : "v"(h0), "v"(p0), "v"(h1), "v"(p1), "v"(w));
     return d;
 }
 

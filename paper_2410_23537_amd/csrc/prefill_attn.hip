@@ -13,15 +13,19 @@
 // of the step (K or V codes of one 16-token tile plus its scales and zero-points) with direct
 // global -> LDS loads, three stages deep, one workgroup barrier per step.  Per wave the step is
 // the one of the grouped-query decode kernel: S^T = K Q^T and O += P V on
-// v_mfma_f32_16x16x32_f16, K and V codes as fp16 subnormals code * 2^-24, online softmax with a
-// lazily raised maximum -- except that the mask is per row (token <= the row's position), that
-// only the steps on a wave's diagonal are masked at all, that a wave skips the steps none of its
-// rows can see, and that a weight P * lambda_v is one fp16 number (rounded to nearest even) instead
-// of a high and a low part: the kernel is bound by its vector instructions, the second product per
-// weight and the instruction that forms the low part were a sixth of them, and with the zero-point
-// sum taken over the same rounded weights the rounding only perturbs each weight by 2^-12 relative
-// (no cancellation between the code sum and the zero-point sum), i.e. the output by at most
-// 2^-12 max|v|.  Two row tiles of a wave share the operands built from the cache.  INT8 caches (one or two scale groups per head) and
+// v_mfma_f32_16x16x32_f16, K and V codes as fp16 subnormals code * 2^-24, P * lambda_v split in
+// high and low fp16 parts, online softmax with a lazily raised maximum -- except that the mask
+// is per row (token <= the row's position), that only the steps on a wave's diagonal are masked
+// at all, and that a wave skips the steps none of its rows can see.  Two row tiles of a wave
+// share the operands built from the cache.  A second set of kernels (ALISE_PREFILL_WEIGHTS=single)
+// takes a weight as ONE fp16 number rounded to nearest even: the kernel is bound by its vector
+// instructions, and the second product per weight with the instructions that form the low part
+// are a sixth of them.  With the zero-point sum taken over the same rounded weights the rounding
+// only perturbs each weight by 2^-12 relative (nothing cancels between a code sum and a zero-point
+// sum that were rounded differently), i.e. the output by at most 2^-12 max|v|: invisible where many
+// tokens share a row's weight, up to 1e-3 for |v| near 4 where a few tokens carry it -- on top of
+// the fp16 rounding of the output that is too much for the 2e-3 bar, hence not the default.
+// INT8 caches (one or two scale groups per head) and
 // INT4 caches with groups of 32 channels are taken; the INT4 operand formats are described at the
 // top of the kernel body.
 // There is no split along the context and therefore nothing to merge: a chunk of a few
@@ -107,7 +111,9 @@ __global__ __launch_bounds__(1024) void prefill_plan_kernel(const int32_t *q_sta
 
 // RT: 16-row tiles per wave.  Two tiles share every code -> fp16 conversion and every LDS read of a step.
 // BITS: 8, or 4 (two channels per byte, channel 2i in the low nibble): see the INT4 notes below.
-template <int BITS, int NGRP, int RT>
+// SPLIT: a weight enters the second product as a high and a low fp16 part (exact to 22 bits) instead of one
+// rounded fp16 number.
+template <int BITS, int NGRP, int RT, bool SPLIT>
 __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
 {
     constexpr int D = 128, ROWB = D * BITS / 8, S = 3;
@@ -406,8 +412,9 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
             }
         }
 
-        // ---- weights p * lambda_v in fp16, rounded to nearest even, in the A-operand order (tile, row)
-        h8_t a_w[RT][NGRP];
+        // ---- weights p * lambda_v in the A-operand order (tile, row): the product rounded to fp16 (nearest even)
+        // and, with SPLIT, what that lacks of the exact product as a second fp16 number
+        h8_t a_w[RT][NGRP], a_lo[SPLIT ? RT : 1][NGRP];
 #pragma unroll
         for (int t = 0; t < RT; ++t)
 #pragma unroll
@@ -423,10 +430,24 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
 #pragma unroll
                     for (int gr = 0; gr < NGRP; ++gr) {
                         const uint32_t vm0 = vmraw[MASKED ? t : 0][x][rr][gr], vm1 = vmraw[MASKED ? t : 0][x][rr + 1][gr];
-                        const uint32_t w16 = mul_lo_halves_to_h2(vm0, pj[0], vm1, pj[1]);
-                        // the zero-point sum takes the rounded weight, the one the matrix product multiplies the codes with
-                        z_part[t][gr] = fma_hi_by_half<0>(vm0, w16, z_part[t][gr]);
-                        z_part[t][gr] = fma_hi_by_half<1>(vm1, w16, z_part[t][gr]);
+                        uint32_t w16;
+                        if constexpr (SPLIT) {
+                            // the zero-point sum takes the exact weight, as the two products together do
+                            const float w0 = mul_lo_half_f32(vm0, pj[0]), w1 = mul_lo_half_f32(vm1, pj[1]);
+                            z_part[t][gr] = fma_hi_half(vm0, w0, z_part[t][gr]);
+                            z_part[t][gr] = fma_hi_half(vm1, w1, z_part[t][gr]);
+                            typedef float f2_t __attribute__((ext_vector_type(2)));
+                            const f2_t wv = {w0, w1};
+                            w16 = as_u32(__builtin_convertvector(wv, h2_t));
+                            const uint32_t lo16 = residual_of_h2(vm0, pj[0], vm1, pj[1], w16);
+                            a_lo[t][gr][x * 4 + rr] = as_h2(lo16).x;
+                            a_lo[t][gr][x * 4 + rr + 1] = as_h2(lo16).y;
+                        } else {
+                            w16 = mul_lo_halves_to_h2(vm0, pj[0], vm1, pj[1]);
+                            // the zero-point sum takes the rounded weight, the one the matrix product multiplies the codes with
+                            z_part[t][gr] = fma_hi_by_half<0>(vm0, w16, z_part[t][gr]);
+                            z_part[t][gr] = fma_hi_by_half<1>(vm1, w16, z_part[t][gr]);
+                        }
                         a_w[t][gr][x * 4 + rr] = as_h2(w16).x;
                         a_w[t][gr][x * 4 + rr + 1] = as_h2(w16).y;
                     }
@@ -454,6 +475,7 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
                     for (int t = 0; t < RT; ++t) {
                         f4_t &dst = o[t][set * 4 + nu];
                         dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_w[t][gr], bv, dst, 0, 0, 0);
+                        if constexpr (SPLIT) dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_lo[t][gr], bv, dst, 0, 0, 0);
                     }
                 }
         } else {
@@ -477,6 +499,7 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
                         for (int t = 0; t < RT; ++t) {
                             f4_t &dst = o[t][b * 2 + m];
                             dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_w[t][gr], bv, dst, 0, 0, 0);
+                            if constexpr (SPLIT) dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_lo[t][gr], bv, dst, 0, 0, 0);
                         }
                     }
                 }
@@ -565,27 +588,22 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
 
 // Register budgets: one 16-row tile per wave with one scale group per head (G = 128) fits four waves per
 // SIMD, with two groups three; two row tiles per wave take two waves per SIMD.
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void prefill_attn_kernel_g1(PrefillParams p)
-{
-    prefill_attn_body<8, 1, 1>(p);
-}
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void prefill_attn_kernel_g2(PrefillParams p)
-{
-    prefill_attn_body<8, 2, 1>(p);
-}
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_attn_kernel_g1_r2(PrefillParams p)
-{
-    prefill_attn_body<8, 1, 2>(p);
-}
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_attn_kernel_g2_r2(PrefillParams p)
-{
-    prefill_attn_body<8, 2, 2>(p);
-}
+#define ALISE_PREFILL_KERNEL(NAME, WAVES, BITSV, NGRPV, RTV)                                                              \
+    __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WAVES, WAVES))) void NAME(PrefillParams p)       \
+    {                                                                                                                     \
+        prefill_attn_body<BITSV, NGRPV, RTV, true>(p);                                                                    \
+    }                                                                                                                     \
+    __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WAVES, WAVES))) void NAME##_w1(PrefillParams p)  \
+    {                                                                                                                     \
+        prefill_attn_body<BITSV, NGRPV, RTV, false>(p);                                                                   \
+    }
+ALISE_PREFILL_KERNEL(prefill_attn_kernel_g1, 4, 8, 1, 1)
+ALISE_PREFILL_KERNEL(prefill_attn_kernel_g2, 3, 8, 2, 1)
+ALISE_PREFILL_KERNEL(prefill_attn_kernel_g1_r2, 2, 8, 1, 2)
+ALISE_PREFILL_KERNEL(prefill_attn_kernel_g2_r2, 2, 8, 2, 2)
 // INT4 with groups of 32 channels: four scale groups per head, one row tile per wave.
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void prefill_attn_kernel_i4(PrefillParams p)
-{
-    prefill_attn_body<4, 4, 1>(p);
-}
+ALISE_PREFILL_KERNEL(prefill_attn_kernel_i4, 3, 4, 4, 1)
+#undef ALISE_PREFILL_KERNEL
 
 }  // namespace
 
@@ -604,6 +622,14 @@ static int32_t prefill_row_tiles()
 {
     const char *e = std::getenv("ALISE_PREFILL_ROW_TILES");
     return (e && e[0] == '1' && e[1] == 0) ? 1 : 2;
+}
+
+// ALISE_PREFILL_WEIGHTS=single: one rounded fp16 number per weight instead of a high and a low part
+// (faster; adds up to 2^-12 max|v| to the error of a row that a few tokens dominate).
+static bool prefill_split_weights()
+{
+    const char *e = std::getenv("ALISE_PREFILL_WEIGHTS");
+    return !(e && e[0] == 's' && e[1] == 'i');
 }
 
 hipError_t launch_prefill_attn(const CacheView &c, const void *q, void *out, const int32_t *q_start,
@@ -633,15 +659,22 @@ hipError_t launch_prefill_attn(const CacheView &c, const void *q, void *out, con
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)ws.max_tiles, (unsigned)c.Hkv);         // sized for one row tile per wave: enough for two
     const bool one_group = c.D / c.G == 1;
+    const bool split = prefill_split_weights();
+#define ALISE_PREFILL_LAUNCH(NAME)                                                    \
+    do {                                                                              \
+        if (split) hipLaunchKernelGGL(NAME, grid, dim3(256), 0, s, p);                \
+        else hipLaunchKernelGGL(NAME##_w1, grid, dim3(256), 0, s, p);                 \
+    } while (0)
     if (c.bits == 4) {
-        hipLaunchKernelGGL(prefill_attn_kernel_i4, grid, dim3(256), 0, s, p);
+        ALISE_PREFILL_LAUNCH(prefill_attn_kernel_i4);
     } else if (rt == 1) {
-        if (one_group) hipLaunchKernelGGL(prefill_attn_kernel_g1, grid, dim3(256), 0, s, p);
-        else hipLaunchKernelGGL(prefill_attn_kernel_g2, grid, dim3(256), 0, s, p);
+        if (one_group) ALISE_PREFILL_LAUNCH(prefill_attn_kernel_g1);
+        else ALISE_PREFILL_LAUNCH(prefill_attn_kernel_g2);
     } else {
-        if (one_group) hipLaunchKernelGGL(prefill_attn_kernel_g1_r2, grid, dim3(256), 0, s, p);
-        else hipLaunchKernelGGL(prefill_attn_kernel_g2_r2, grid, dim3(256), 0, s, p);
+        if (one_group) ALISE_PREFILL_LAUNCH(prefill_attn_kernel_g1_r2);
+        else ALISE_PREFILL_LAUNCH(prefill_attn_kernel_g2_r2);
     }
+#undef ALISE_PREFILL_LAUNCH
     return hipGetLastError();
 }
 

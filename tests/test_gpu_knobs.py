@@ -1,7 +1,7 @@
 """Every kernel variant that a tuning knob can select (environment variables read per call) must
 compute the same attention (ALISE Sec. 2, Eq. 1-2 over the cache of Sec. 3.2): stage counts and
 wave-loads per block, waves per compute unit, split lengths, the floor of items per wave, and
-the one-row-tile prefill kernels.  Each setting is run on small batches of the four layouts
+the one-row-tile and the single-weight prefill kernels.  Each setting is run on small batches of the four layouts
 (MHA INT8, MHA INT4, GQA INT8, GQA INT4) and compared with the oracle."""
 import os
 
@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 
 ATTN_TOL = 2e-3
 KNOBS = ("ALISE_SPLIT_TOKENS", "ALISE_SPLIT_TOKENS_GQA", "ALISE_WAVES_PER_CU", "ALISE_LOADS_PER_BLOCK",
-         "ALISE_MIN_ITEMS_PER_WAVE", "ALISE_PREFILL_ROW_TILES")
+         "ALISE_MIN_ITEMS_PER_WAVE", "ALISE_PREFILL_ROW_TILES", "ALISE_PREFILL_WEIGHTS")
 
 LAYOUTS = [
     wl.replace(wl.scaled(wl.CONFIGS["llama7b"], B=6, max_len=2600, name="mha_int8"), Hkv=4, H=4, length_law="uniform:1,2600"),
@@ -82,10 +82,12 @@ def test_decode_under_every_knob(env, problems, setting):
         assert np.isfinite(got).all() and err <= ATTN_TOL, f"{name} under {setting}: {err:.3e}"
 
 
+@pytest.mark.parametrize("weights", ["split", "single"])
 @pytest.mark.parametrize("tiles", ["1", "2"])
-def test_prefill_with_one_and_two_row_tiles(env, problems, tiles):
+def test_prefill_with_one_and_two_row_tiles(env, problems, tiles, weights):
     B, torch, oracle = env
     os.environ["ALISE_PREFILL_ROW_TILES"] = tiles
+    os.environ["ALISE_PREFILL_WEIGHTS"] = weights
     for name, (w, pg, orc, dev, q, _) in problems.items():
         print(f"case knobs prefill row tiles {tiles} {name}", flush=True)
         lens = pg.lens.astype(np.int64)
@@ -104,4 +106,4 @@ def test_prefill_with_one_and_two_row_tiles(env, problems, tiles):
         torch.cuda.synchronize()
         got = out.cpu().numpy().astype(np.float64)
         err = float(np.abs(got - want).max())
-        assert np.isfinite(got).all() and err <= ATTN_TOL, f"{name} with {tiles} row tiles: {err:.3e}"
+        assert np.isfinite(got).all() and err <= ATTN_TOL, f"{name} with {tiles} row tiles, {weights} weights: {err:.3e}"

@@ -165,3 +165,55 @@ def test_large_value_scales_decode_and_prefill(env, vgain):
     gd = od.cpu().numpy().astype(np.float64)
     bar = ATTN_TOL * max(1.0, np.abs(wd).max() / 2.0)
     assert np.isfinite(gd).all() and np.abs(gd - wd).max() <= bar, (np.abs(gd - wd).max(), bar)
+
+
+@pytest.mark.parametrize("weights", ["split", "single"])
+@pytest.mark.parametrize("bits,G,Hkv,H", [(8, 64, 4, 4), (8, 128, 2, 16), (4, 32, 4, 4)])
+@pytest.mark.parametrize("qgain", [1.0, 3.0, 8.0])
+def test_peaked_rows_with_values_up_to_the_fp16_limit_of_the_bar(env, monkeypatch, bits, G, Hkv, H, qgain, weights):
+    """Dequantized V values just below 4 are the largest for which an fp16 output can meet 2e-3 at all (half an
+    ulp is 9.8e-4 in [2, 4) and 1.95e-3 in [4, 8)); scaled queries make the rows peaked (a few tokens carry the
+    sum, so errors of single weights do not average out), unscaled ones flat.  The default kernels (a weight
+    as a high and a low fp16 part) must meet the bar there.  With ALISE_PREFILL_WEIGHTS=single a weight
+    is one fp16 number rounded to nearest, which adds at most 2^-12 max|v| to the error: that bound is the bar."""
+    B, torch, oracle = env
+    monkeypatch.setenv("ALISE_PREFILL_WEIGHTS", weights)
+    D, P = 128, 16
+    lens = [333, 64, 1100]
+    chunks = [80, 64, 130]
+    vmax = 3.9 if bits == 8 else 3.5              # INT4 steps are 0.5 wide: the dequantized values reach vmax + 0.25
+    rng = np.random.default_rng([2024, bits, G, H, int(qgain)])
+    nblk_of = [(L + P - 1) // P for L in lens]
+    num_pages = sum(nblk_of)
+    orc = oracle.Cache.empty(num_pages, P, Hkv, D, bits, G)
+    dev = B.KVCache.allocate(num_pages, P, Hkv, D, bits, G, fill=0)
+    bt_np = np.zeros((len(lens), max(nblk_of)), np.int32)
+    perm = rng.permutation(num_pages).astype(np.int32)
+    at = 0
+    for i, L in enumerate(lens):
+        bt_np[i, :nblk_of[i]] = perm[at:at + nblk_of[i]]
+        at += nblk_of[i]
+        k = rng.standard_normal((L, Hkv, D)).astype(np.float16)
+        v = rng.uniform(-vmax, vmax, (L, Hkv, D)).astype(np.float16)
+        t = np.arange(L)
+        slots = bt_np[i, t // P].astype(np.int64) * P + t % P
+        oracle.kv_quant_write(orc, k, v, slots)
+        B.alise_kv_quant_write(dev, torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda(), torch.from_numpy(slots).cuda())
+    qs_np = np.concatenate([[0], np.cumsum(chunks)]).astype(np.int32)
+    total = int(qs_np[-1])
+    q_np = (rng.standard_normal((total, H, D)) * qgain).astype(np.float16)
+    lens_np = np.array(lens, np.int32)
+    scale = 1.0 / np.sqrt(D)
+    want = oracle.paged_prefill_attn(orc, q_np, qs_np, bt_np, lens_np, scale)
+    assert np.abs(want).max() < 4.0
+    q = torch.from_numpy(q_np).cuda()
+    out = torch.full(q.shape, float("nan"), dtype=torch.float16, device="cuda")
+    ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(dev, len(lens), total, H), dtype=torch.uint8, device="cuda")
+    B.alise_paged_prefill_attn(dev, q, out, torch.from_numpy(qs_np).cuda(), torch.from_numpy(bt_np).cuda(),
+                               torch.from_numpy(lens_np).cuda(), max(lens), scale, ws)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    err = np.abs(got - want)
+    bar = ATTN_TOL if weights == "split" else ATTN_TOL + 2.0 ** -12 * 4.0
+    print(f"  max|want| {np.abs(want).max():.3f} max-abs error {err.max():.3e} (bar {bar:.3e})", flush=True)
+    assert np.isfinite(got).all() and err.max() <= bar
