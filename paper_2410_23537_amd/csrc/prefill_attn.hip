@@ -123,6 +123,10 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
     static_assert(TILEB % 128 == 0 && TILEB >= T_VM + 64 * NGRP, "tile layout");
     constexpr int STEPB = 2 * TILEB;
     constexpr int LOADS_PER_STEP = BITS == 8 ? 3 : 2;       // direct loads a wave issues per step
+    // With two row tiles every scale and zero-point has two uses, and the compiler then converts the half to
+    // fp32 first instead of reading it in place: the hand-written multiply-adds of mfma_stream.h take over.
+    // With one tile it reads them in place by itself and schedules better around its own instructions.
+    constexpr bool IN_PLACE = RT > 1 || !SPLIT;
     // INT4.  A token's row is 64 bytes, so one 1 KiB load brings a whole 16-token tile; row r keeps its
     // 16-byte piece c at position c ^ (r / 4 % 4).  K: chunk jj of the first product is the 32 channels
     // of piece jj (one scale group when G = 32); a lane's dword of it holds 8 nibbles, which two masks on
@@ -361,7 +365,8 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
                         const uint32_t km = meta_of<NGRP>(kmeta[x], r, gr);         // (scale, zero-point)
                         // the reader of the matrix result is left to the compiler (wait states), the scale is read in place
                         const float u = __builtin_fmaf((float)as_h2(km).y, nqs24[t][gr], acc[t][gr][r]);
-                        sv = fma_lo_half(km, u, sv);
+                        if constexpr (IN_PLACE) sv = fma_lo_half(km, u, sv);
+                        else sv = __builtin_fmaf((float)as_h2(km).x, u, sv);
                         if (MASKED || t == 0) {
                             const uint32_t vm = meta_of<NGRP>(vmeta[x], r, gr);
                             vmraw[MASKED ? t : 0][x][r][gr] = valid ? vm : 0u;
@@ -433,13 +438,26 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
                         uint32_t w16;
                         if constexpr (SPLIT) {
                             // the zero-point sum takes the exact weight, as the two products together do
-                            const float w0 = mul_lo_half_f32(vm0, pj[0]), w1 = mul_lo_half_f32(vm1, pj[1]);
-                            z_part[t][gr] = fma_hi_half(vm0, w0, z_part[t][gr]);
-                            z_part[t][gr] = fma_hi_half(vm1, w1, z_part[t][gr]);
                             typedef float f2_t __attribute__((ext_vector_type(2)));
-                            const f2_t wv = {w0, w1};
-                            w16 = as_u32(__builtin_convertvector(wv, h2_t));
-                            const uint32_t lo16 = residual_of_h2(vm0, pj[0], vm1, pj[1], w16);
+                            uint32_t lo16;
+                            if constexpr (IN_PLACE) {
+                                const float w0 = mul_lo_half_f32(vm0, pj[0]), w1 = mul_lo_half_f32(vm1, pj[1]);
+                                z_part[t][gr] = fma_hi_half(vm0, w0, z_part[t][gr]);
+                                z_part[t][gr] = fma_hi_half(vm1, w1, z_part[t][gr]);
+                                const f2_t wv = {w0, w1};
+                                w16 = as_u32(__builtin_convertvector(wv, h2_t));
+                                lo16 = residual_of_h2(vm0, pj[0], vm1, pj[1], w16);
+                            } else {
+                                const h2_t m0 = as_h2(vm0), m1 = as_h2(vm1);
+                                const f2_t wv = {__builtin_fmaf((float)m0.x, pj[0], 0.0f), __builtin_fmaf((float)m1.x, pj[1], 0.0f)};
+                                z_part[t][gr] = __builtin_fmaf((float)m0.y, wv.x, z_part[t][gr]);
+                                z_part[t][gr] = __builtin_fmaf((float)m1.y, wv.y, z_part[t][gr]);
+                                const h2_t hi = __builtin_convertvector(wv, h2_t);
+                                const h2_t lo = {(_Float16)__builtin_fmaf((float)m0.x, pj[0], -(float)hi.x),
+                                                 (_Float16)__builtin_fmaf((float)m1.x, pj[1], -(float)hi.y)};
+                                w16 = as_u32(hi);
+                                lo16 = as_u32(lo);
+                            }
                             a_lo[t][gr][x * 4 + rr] = as_h2(lo16).x;
                             a_lo[t][gr][x * 4 + rr + 1] = as_h2(lo16).y;
                         } else {
