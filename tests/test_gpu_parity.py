@@ -247,3 +247,35 @@ def test_invariances_on_device(env):
     pg3 = wl.Paging(pg.lens[order], pg.block_tables[order], pg.num_pages, pg.poison_page, pg.max_blocks)
     out3 = harness.run_device_attn(B, torch, w, dev, q[order], pg3)
     assert np.array_equal(base[order].view(np.uint16), out3.view(np.uint16))
+
+
+@pytest.mark.parametrize("bits,G,Hkv,H", [(8, 64, 4, 4), (4, 32, 4, 4), (8, 128, 2, 16), (4, 32, 2, 16), (8, 64, 2, 6)])
+@pytest.mark.parametrize("qgain", [1.0, 3.0, 8.0])
+def test_peaked_rows_with_values_up_to_the_fp16_limit_of_the_bar(env, bits, G, Hkv, H, qgain):
+    """Dequantized V values just below 4 are the largest for which an fp16 output can meet 2e-3 at all (half an
+    ulp is 9.8e-4 in [2, 4) and 1.95e-3 in [4, 8)).  Scaled queries make the rows peaked: a few tokens carry the
+    sum and whatever error their weights have reaches the output unaveraged.  Vector kernel (MHA) and
+    matrix-core kernel (GQA), INT8 and INT4, long requests split into tiles."""
+    B, torch, oracle = env
+    print(f"case peaked bits {bits} G {G} Hkv {Hkv} H {H} qgain {qgain}", flush=True)
+    D, P = 128, 16
+    lens = np.array([333, 1, 64, 2600, 17], np.int32)
+    vmax = 3.9 if bits == 8 else 3.5              # INT4 steps are 0.5 wide: the dequantized values reach vmax + 0.25
+    rng = np.random.default_rng([2025, bits, G, H, int(qgain)])
+    w = wl.Workload("peaked", B=len(lens), H=H, Hkv=Hkv, D=D, P=P, bits=bits, G=G, length_law="fixed:1", seed=11, max_len=int(lens.max()))
+    pg = wl.paging(w, lens)
+    orc = oracle.Cache.empty(pg.num_pages, P, Hkv, D, bits, G)
+    dev = B.KVCache.allocate(pg.num_pages, P, Hkv, D, bits, G, fill=0)
+    for i, L in enumerate(lens):
+        k = rng.standard_normal((int(L), Hkv, D)).astype(np.float16)
+        v = rng.uniform(-vmax, vmax, (int(L), Hkv, D)).astype(np.float16)
+        slots = wl.slots_of(w, pg, i, 0, int(L))
+        oracle.kv_quant_write(orc, k, v, slots)
+        B.alise_kv_quant_write(dev, torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda(), torch.from_numpy(slots).cuda())
+    q = (rng.standard_normal((len(lens), H, D)) * qgain).astype(np.float16)
+    want = oracle.paged_decode_attn(orc, q, pg.block_tables, pg.lens, 1.0 / np.sqrt(D))
+    assert np.abs(want).max() < 4.0
+    got = harness.run_device_attn(B, torch, w, dev, q, pg).astype(np.float64)
+    err = np.abs(got - want).max()
+    print(f"  max|want| {np.abs(want).max():.3f} max-abs error {err:.3e}", flush=True)
+    assert np.isfinite(got).all() and err <= ATTN_TOL
