@@ -24,6 +24,13 @@
  *     duplicate slots in one call, context_lens[i] > max_context_len) are not
  *     checked: out-of-range indices are undefined behaviour; lengths above
  *     max_context_len are clamped to it.
+ *   - With ALISE_DEBUG_VALIDATE=1 in the environment the calls check those contents
+ *     too and return ALISE_INVALID_ARGUMENT without launching anything: slots outside
+ *     the cache or used twice in one write, lengths outside [0, max_context_len],
+ *     block-table entries that a length reaches outside [0, num_pages), a request
+ *     longer than its block-table row, chunk boundaries that decrease or a chunk
+ *     longer than its request, pages named twice in a swap.  This copies the arrays
+ *     to the host and waits for the stream: a debugging aid, not for serving.
  *
  * Exact arithmetic of the quantizer (so that codes and meta are reproducible bit
  * for bit).  With x_0..x_{G-1} one group widened to fp32, qmax = 2^bits - 1 and

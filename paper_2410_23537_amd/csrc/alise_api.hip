@@ -1,9 +1,12 @@
 // C-ABI layer: argument validation (host only, before any HIP call), workspace
-// carving and kernel launches.  See include/alise_kv.h for the contract.
+// carving and kernel launches; with ALISE_DEBUG_VALIDATE=1 also checks of the device arrays.
+// See include/alise_kv.h for the contract.
 #include "../../include/alise_kv.h"
 #include "alise_kernels.h"
 
+#include <algorithm>
 #include <cstdlib>
+#include <vector>
 
 namespace {
 
@@ -128,6 +131,46 @@ int32_t min_items_per_wave()
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// ALISE_DEBUG_VALIDATE=1: the calls also check what they are given in device memory (slots, lengths, block
+// tables, chunk boundaries).  That takes a copy to the host and a wait for the stream, so it is for debugging
+// only: without it the contents of device arrays are the caller's responsibility.
+bool debug_validate()
+{
+    const char *e = std::getenv("ALISE_DEBUG_VALIDATE");
+    return e && e[0] == '1' && e[1] == 0;
+}
+
+template <class T>
+int fetch_to_host(std::vector<T> &host, const T *dev, size_t n, hipStream_t s)
+{
+    host.resize(n);
+    if (n == 0) return ALISE_OK;
+    if (hipMemcpyAsync(host.data(), dev, n * sizeof(T), hipMemcpyDeviceToHost, s) != hipSuccess) return ALISE_HIP_ERROR;
+    return hipStreamSynchronize(s) == hipSuccess ? ALISE_OK : ALISE_HIP_ERROR;
+}
+
+// Lengths within [0, max_len], and the block-table entries that those lengths reach within [0, num_pages).
+int validate_lens_and_tables(const CacheView &cv, const int32_t *block_tables, int32_t max_blocks, const int32_t *context_lens,
+                             int32_t B, int32_t max_len, std::vector<int32_t> *lens_out, hipStream_t s)
+{
+    std::vector<int32_t> lens, bt;
+    int st = fetch_to_host(lens, context_lens, (size_t)B, s);
+    if (st != ALISE_OK) return st;
+    st = fetch_to_host(bt, block_tables, (size_t)B * max_blocks, s);
+    if (st != ALISE_OK) return st;
+    for (int32_t i = 0; i < B; ++i) {
+        if (lens[i] < 0 || lens[i] > max_len) return ALISE_INVALID_ARGUMENT;
+        const int64_t nblk = ((int64_t)lens[i] + cv.P - 1) / cv.P;
+        if (nblk > max_blocks) return ALISE_INVALID_ARGUMENT;
+        for (int64_t b = 0; b < nblk; ++b) {
+            const int32_t page = bt[(size_t)i * max_blocks + b];
+            if (page < 0 || page >= cv.num_pages) return ALISE_INVALID_ARGUMENT;
+        }
+    }
+    if (lens_out) lens_out->swap(lens);
+    return ALISE_OK;
+}
+
 // Workspace layout: [n_items, n_merge | tile_base[B+1] | req_full_base[B] | merge_req[B] |
 // order[max_tiles] | part].
 size_t carve_workspace(const CacheView &c, int32_t B, int32_t H, int32_t max_len, void *base,
@@ -222,6 +265,17 @@ int alise_kv_quant_write(const alise_kv_cache *c, const void *k, const void *v,
     if (st != ALISE_OK) return st;
     if (!aligned16(k) || !aligned16(v)) return ALISE_MISALIGNED;
     if ((reinterpret_cast<uintptr_t>(slot_mapping) & 7u) != 0) return ALISE_MISALIGNED;
+    if (debug_validate()) {
+        std::vector<int64_t> slots;
+        st = fetch_to_host(slots, slot_mapping, (size_t)T, static_cast<hipStream_t>(hip_stream));
+        if (st != ALISE_OK) return st;
+        const int64_t n_slots = (int64_t)cv.num_pages * cv.P;
+        slots.erase(std::remove_if(slots.begin(), slots.end(), [](int64_t v) { return v < 0; }), slots.end());   // skipped tokens
+        for (int64_t v : slots)
+            if (v >= n_slots) return ALISE_INVALID_ARGUMENT;
+        std::sort(slots.begin(), slots.end());
+        if (std::adjacent_find(slots.begin(), slots.end()) != slots.end()) return ALISE_INVALID_ARGUMENT;    // two tokens, one slot
+    }
     hipError_t e = alise::launch_quant_write(cv, k, v, slot_mapping, T, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? ALISE_OK : ALISE_HIP_ERROR;
 }
@@ -260,6 +314,11 @@ int alise_paged_decode_attn(const alise_kv_cache *c, const void *q, void *out,
     AttnWorkspace ws;
     const size_t need = carve_workspace(cv, B, num_q_heads, max_context_len, workspace, &ws);
     if (workspace_bytes < need) return ALISE_WORKSPACE_TOO_SMALL;
+    if (debug_validate()) {
+        st = validate_lens_and_tables(cv, block_tables, max_blocks_per_seq, context_lens, B, max_context_len, nullptr,
+                                      static_cast<hipStream_t>(hip_stream));
+        if (st != ALISE_OK) return st;
+    }
     hipError_t e = alise::launch_decode_attn(cv, q, out, block_tables, max_blocks_per_seq, context_lens, B,
                                              num_q_heads, max_context_len, softmax_scale, ws,
                                              num_compute_units(), waves_per_cu(), loads_per_block(), min_items_per_wave(),
@@ -340,6 +399,17 @@ int alise_paged_prefill_attn(const alise_kv_cache *c, const void *q, void *out, 
     alise::PrefillWorkspace ws;
     const size_t need = carve_prefill(cv, B, total_q_tokens, num_q_heads, workspace, &ws);
     if (workspace_bytes < need) return ALISE_WORKSPACE_TOO_SMALL;
+    if (debug_validate()) {
+        hipStream_t hs = static_cast<hipStream_t>(hip_stream);
+        std::vector<int32_t> lens, qs;
+        st = validate_lens_and_tables(cv, block_tables, max_blocks_per_seq, context_lens, B, max_context_len, &lens, hs);
+        if (st != ALISE_OK) return st;
+        st = fetch_to_host(qs, q_start, (size_t)B + 1, hs);
+        if (st != ALISE_OK) return st;
+        if (qs[0] < 0 || qs[B] > total_q_tokens) return ALISE_INVALID_ARGUMENT;
+        for (int32_t i = 0; i < B; ++i)
+            if (qs[i + 1] < qs[i] || qs[i + 1] - qs[i] > lens[i]) return ALISE_INVALID_ARGUMENT;     // a chunk is part of its request
+    }
     hipError_t e = alise::launch_prefill_attn(cv, q, out, q_start, block_tables, max_blocks_per_seq, context_lens, B,
                                               num_q_heads, max_context_len, softmax_scale, ws,
                                               static_cast<hipStream_t>(hip_stream));
@@ -368,6 +438,15 @@ static int swap_call(const alise_kv_cache *c, const int32_t *block_table, int32_
     st = check_cache_pointers(c);
     if (st != ALISE_OK) return st;
     if (!aligned16(packed) || (reinterpret_cast<uintptr_t>(block_table) & 3u)) return ALISE_MISALIGNED;
+    if (debug_validate()) {
+        std::vector<int32_t> bt;
+        st = fetch_to_host(bt, block_table, (size_t)(((int64_t)num_tokens + cv.P - 1) / cv.P), static_cast<hipStream_t>(hip_stream));
+        if (st != ALISE_OK) return st;
+        for (int32_t page : bt)
+            if (page < 0 || page >= cv.num_pages) return ALISE_INVALID_ARGUMENT;
+        std::sort(bt.begin(), bt.end());
+        if (std::adjacent_find(bt.begin(), bt.end()) != bt.end()) return ALISE_INVALID_ARGUMENT;      // one page, two places in the request
+    }
     hipError_t e = alise::launch_swap(cv, block_table, num_tokens, packed, upload, num_compute_units(),
                                       static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? ALISE_OK : ALISE_HIP_ERROR;
