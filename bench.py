@@ -110,7 +110,18 @@ def cpu_baseline(w, step, target_seconds):
     dt = time.perf_counter() - t0
     nbytes = (wl.algorithmic_bytes_attn(ws, sub_lens) + wl.algorithmic_bytes_write(ws, len(chosen))
               + wl.algorithmic_bytes_dequant(ws, 1))
-    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+    # the same attention on one thread, over the first sampled requests that fit about two seconds
+    n1, tok1 = 0, 0
+    while n1 < len(chosen) and (n1 == 0 or (tok1 + int(sub_lens[n1])) * attn_per_token * threads <= 2.0):
+        tok1 += int(sub_lens[n1])
+        n1 += 1
+    t0 = time.perf_counter()
+    oracle.paged_decode_attn(cache, q[:n1], pgs.block_tables[:n1], pgs.lens[:n1], step.scale, num_threads=1)
+    dt1 = time.perf_counter() - t0
+    one_thread = {"value": wl.algorithmic_bytes_attn(wl.replace(ws, B=n1), sub_lens[:n1]) / dt1 / 1e9, "unit": "GB/s", "cores": 1,
+                  "sample": f"attention only, the first {n1} sampled requests ({tok1} KV tokens)", "seconds": dt1,
+                  "kv_tokens_per_s": tok1 / dt1}
+    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle", "one_thread": one_thread,
             "sample": f"{len(chosen)} of {w.B} requests (every {stride}-th in batch order, {tot} of "
                       f"{int(lens.astype(np.int64).sum())} KV tokens), one decode token each, "
                       f"attention split over {threads} threads",
