@@ -178,7 +178,7 @@ int alise_kv_dequant_page(const alise_kv_cache *c, int32_t page, void *k_out, vo
  *                 as for alise_paged_decode_attn; the workspace size comes from
  *                 alise_paged_prefill_attn_workspace_bytes.
  * Supported shapes: head_dim = 128, page_size >= 16, num_q_heads / num_kv_heads between 1 and
- * 16, and either bits = 8 with group_size 64 or 128, or bits = 4 with group_size 32; anything
+ * 16, and either bits = 8 with group_size 64 or 128, or bits = 4 with group_size 32, 64 or 128; anything
  * else returns ALISE_UNSUPPORTED (and a workspace size of 0).
  * out[t][h] = sum_u softmax_u(softmax_scale * q[t][h] . k^_u) v^_u over u <= position of t,
  * accumulated in fp32, rounded once to fp16.

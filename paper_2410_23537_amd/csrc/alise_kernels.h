@@ -43,7 +43,8 @@ struct PrefillWorkspace {
     int32_t max_tiles;
 };
 
-// Shapes the matrix-core prefill kernel takes (INT8, D = 128, G in {64, 128}, P >= 16, 1..16 query heads per KV head).
+// Shapes the matrix-core prefill kernels take (D = 128, P >= 16, 1..16 query heads per KV head; INT8 with G in {64, 128},
+// INT4 with G in {32, 64, 128}).
 bool prefill_mfma_applies(const CacheView &c, int32_t H);
 int32_t prefill_tokens_per_workgroup(int32_t qper, int32_t row_tiles);
 

@@ -2,7 +2,7 @@
 //
 // With H / Hkv = qper query heads per KV head, every KV byte is used by qper queries, so
 // q K^T and P V are real (small) matrix products (ALISE Sec. 2, Eq. 1-2, over the quantized
-// cache of Sec. 3.2: INT8, or INT4 with groups of 32 channels -- see the note at the kernel).  One wave serves all query heads of one KV head for one tile of
+// cache of Sec. 3.2: INT8 with groups of 64 or 128 channels, INT4 with groups of 32, 64 or 128 -- see the note at the kernel).  One wave serves all query heads of one KV head for one tile of
 // tokens; the work items of a tile are its KV heads.  Per step of 32 tokens:
 //
 //   S^T = K Q^T   v_mfma_f32_16x16x32_f16, A = K codes as fp16 (16 tokens x 32 channels),
@@ -48,7 +48,7 @@ namespace {
 // BITS = code width (8, or 4 with two channels per byte); NGRP = groups per token row (1, 2 or 4);
 // QROWS = query rows kept per item (8 or 16, >= qper); S = stages of one step each.
 //
-// INT4 (groups of 32 channels).  A token's row is 64 bytes, so one 1 KiB load brings a whole
+// INT4 (groups of 32, 64 or 128 channels: four, two or one accumulator per tile).  A token's row is 64 bytes, so one 1 KiB load brings a whole
 // 16-token tile; row r keeps its 16-byte piece c at position c ^ (r / 4 % 4).  K: chunk j of the
 // first product is the 32 channels of piece j (one scale group); a lane's dword of it holds 8
 // nibbles, which two masks on the dword and two on the dword shifted by a byte turn into fp16
@@ -610,7 +610,7 @@ bool gqa_mfma_applies(const CacheView &c, int32_t H)
 {
     const int qper = H / c.Hkv;
     if (c.D != 128 || c.P < 16 || qper < 2 || qper > 16) return false;
-    return (c.bits == 8 && (c.G == 128 || c.G == 64)) || (c.bits == 4 && c.G == 32);
+    return (c.bits == 8 && (c.G == 128 || c.G == 64)) || (c.bits == 4 && (c.G == 128 || c.G == 64 || c.G == 32));
 }
 
 hipError_t launch_gqa_mfma(const AttnParams &p, int32_t num_cus, int32_t waves_per_cu, int32_t stages, hipStream_t s)
@@ -619,8 +619,12 @@ hipError_t launch_gqa_mfma(const AttnParams &p, int32_t num_cus, int32_t waves_p
     const bool small = p.qper <= 8;
 #define ALISE_GQA_DISPATCH(SV)                                                                                        \
     do {                                                                                                              \
-        if (p.c.bits == 4)                                                                                            \
+        if (p.c.bits == 4 && ngrp == 4)                                                                               \
             return small ? launch_gqa_t<4, 4, 8, SV>(p, num_cus, waves_per_cu, s) : launch_gqa_t<4, 4, 16, SV>(p, num_cus, waves_per_cu, s); \
+        if (p.c.bits == 4 && ngrp == 2)                                                                               \
+            return small ? launch_gqa_t<4, 2, 8, SV>(p, num_cus, waves_per_cu, s) : launch_gqa_t<4, 2, 16, SV>(p, num_cus, waves_per_cu, s); \
+        if (p.c.bits == 4)                                                                                            \
+            return small ? launch_gqa_t<4, 1, 8, SV>(p, num_cus, waves_per_cu, s) : launch_gqa_t<4, 1, 16, SV>(p, num_cus, waves_per_cu, s); \
         if (ngrp == 1)                                                                                                \
             return small ? launch_gqa_t<8, 1, 8, SV>(p, num_cus, waves_per_cu, s) : launch_gqa_t<8, 1, 16, SV>(p, num_cus, waves_per_cu, s); \
         return small ? launch_gqa_t<8, 2, 8, SV>(p, num_cus, waves_per_cu, s) : launch_gqa_t<8, 2, 16, SV>(p, num_cus, waves_per_cu, s);     \

@@ -26,7 +26,7 @@
 // tokens share a row's weight, up to 1e-3 for |v| near 4 where a few tokens carry it -- on top of
 // the fp16 rounding of the output that is too much for the 2e-3 bar, hence not the default.
 // INT8 caches (one or two scale groups per head) and
-// INT4 caches with groups of 32 channels are taken; the INT4 operand formats are described at the
+// INT4 caches with groups of 32, 64 or 128 channels are taken; the INT4 operand formats are described at the
 // top of the kernel body.
 // There is no split along the context and therefore nothing to merge: a chunk of a few
 // hundred tokens gives thousands of workgroups, handed out longest walk first.
@@ -129,7 +129,7 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
     constexpr bool IN_PLACE = RT > 1 || !SPLIT;
     // INT4.  A token's row is 64 bytes, so one 1 KiB load brings a whole 16-token tile; row r keeps its
     // 16-byte piece c at position c ^ (r / 4 % 4).  K: chunk jj of the first product is the 32 channels
-    // of piece jj (one scale group when G = 32); a lane's dword of it holds 8 nibbles, which two masks on
+    // of piece jj (one scale group when G = 32, half or a quarter of one when G = 64 or 128); a lane's dword of it holds 8 nibbles, which two masks on
     // the dword and two on the dword shifted by a byte turn into fp16 pairs code * 2^-24 (even
     // channels) and 16 code * 2^-24 (odd channels) -- k-slots in the order 0 4 1 5 2 6 3 7, Q permuted
     // likewise with its odd channels divided by 16.  V: columns of a product are 16 channels of one
@@ -621,6 +621,11 @@ ALISE_PREFILL_KERNEL(prefill_attn_kernel_g1_r2, 2, 8, 1, 2)
 ALISE_PREFILL_KERNEL(prefill_attn_kernel_g2_r2, 2, 8, 2, 2)
 // INT4 with groups of 32 channels: four scale groups per head, one row tile per wave.
 ALISE_PREFILL_KERNEL(prefill_attn_kernel_i4, 3, 4, 4, 1)
+// INT4 with groups of 64 and 128 channels: two scale groups per head, or one
+ALISE_PREFILL_KERNEL(prefill_attn_kernel_i4_g2, 3, 4, 2, 1)
+ALISE_PREFILL_KERNEL(prefill_attn_kernel_i4_g1, 4, 4, 1, 1)
+ALISE_PREFILL_KERNEL(prefill_attn_kernel_i4_g2_r2, 2, 4, 2, 2)
+ALISE_PREFILL_KERNEL(prefill_attn_kernel_i4_g1_r2, 2, 4, 1, 2)
 #undef ALISE_PREFILL_KERNEL
 
 }  // namespace
@@ -629,7 +634,7 @@ bool prefill_mfma_applies(const CacheView &c, int32_t H)
 {
     const int qper = H / c.Hkv;
     if (c.D != 128 || c.P < 16 || qper < 1 || qper > 16) return false;
-    return (c.bits == 8 && (c.G == 128 || c.G == 64)) || (c.bits == 4 && c.G == 32);
+    return (c.bits == 8 && (c.G == 128 || c.G == 64)) || (c.bits == 4 && (c.G == 128 || c.G == 64 || c.G == 32));
 }
 
 // Query tokens per workgroup: four waves of `row_tiles` 16-row tiles, a row being a (token, head of the group) pair.
@@ -670,7 +675,7 @@ hipError_t launch_prefill_attn(const CacheView &c, const void *q, void *out, con
     p.max_len = max_context_len;
     p.scale_log2e = softmax_scale * 1.44269504088896340736f;
     p.ws = ws;
-    const int32_t rt = c.bits == 4 ? 1 : prefill_row_tiles();
+    const int32_t rt = (c.bits == 4 && c.D / c.G == 4) ? 1 : prefill_row_tiles();     // four scale groups: one row tile
     hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(1024), 0, s, q_start, context_lens, B,
                        prefill_tokens_per_workgroup(p.qper, rt), max_context_len, ws);
     hipError_t e = hipGetLastError();
@@ -684,7 +689,11 @@ hipError_t launch_prefill_attn(const CacheView &c, const void *q, void *out, con
         else hipLaunchKernelGGL(NAME##_w1, grid, dim3(256), 0, s, p);                 \
     } while (0)
     if (c.bits == 4) {
-        ALISE_PREFILL_LAUNCH(prefill_attn_kernel_i4);
+        if (c.D / c.G == 4) ALISE_PREFILL_LAUNCH(prefill_attn_kernel_i4);
+        else if (c.D / c.G == 2 && rt == 1) ALISE_PREFILL_LAUNCH(prefill_attn_kernel_i4_g2);
+        else if (c.D / c.G == 2) ALISE_PREFILL_LAUNCH(prefill_attn_kernel_i4_g2_r2);
+        else if (rt == 1) ALISE_PREFILL_LAUNCH(prefill_attn_kernel_i4_g1);
+        else ALISE_PREFILL_LAUNCH(prefill_attn_kernel_i4_g1_r2);
     } else if (rt == 1) {
         if (one_group) ALISE_PREFILL_LAUNCH(prefill_attn_kernel_g1);
         else ALISE_PREFILL_LAUNCH(prefill_attn_kernel_g2);

@@ -41,7 +41,7 @@ class Replay:
         self.kv_source = kv_source
         self.cache = B.KVCache.allocate(num_pages, shape.P, shape.Hkv, shape.D, shape.bits, shape.G, fill=0)
         if B.alise_paged_prefill_attn_workspace_bytes(self.cache, 1, 1, shape.H) == 0:
-            raise ValueError("this cache layout has no prefill attention kernel (head_dim 128 with INT8 and G 64 or 128, or INT4 and G 32)")
+            raise ValueError("this cache layout has no prefill attention kernel (head_dim 128 with INT8 and G 64 or 128, or INT4 and G 32, 64 or 128)")
         self.free = list(range(num_pages - 1, -1, -1))
         self.pending_free: list[int] = []
         self.max_context = max_context

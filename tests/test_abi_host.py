@@ -190,12 +190,13 @@ def test_prefill_arguments(B):
     assert call(ws=0x50010) == 4
     assert call(wsb=need - 1) == 3
     # layouts the matrix-core kernel does not take
-    for kw in (dict(bits=4, group_size=64), dict(head_dim=64), dict(group_size=32), dict(page_size=8)):
+    for kw in (dict(head_dim=64), dict(group_size=32), dict(page_size=8)):
         bad = _cache(B, **kw)
         assert lib.alise_paged_prefill_attn_workspace_bytes(ctypes.byref(bad), 2, 300, 8) == 0
         assert call(c=ctypes.byref(bad)) == 2
-    c4 = _cache(B, bits=4, group_size=32)               # INT4 with groups of 32 is taken
-    assert lib.alise_paged_prefill_attn_workspace_bytes(ctypes.byref(c4), 2, 300, 8) > 0
+    for g in (32, 64, 128):                             # INT4 is taken with groups of 32, 64 and 128
+        c4 = _cache(B, bits=4, group_size=g)
+        assert lib.alise_paged_prefill_attn_workspace_bytes(ctypes.byref(c4), 2, 300, 8) > 0
 
 
 def test_fused_op_arguments(B):

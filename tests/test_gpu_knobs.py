@@ -2,7 +2,7 @@
 compute the same attention (ALISE Sec. 2, Eq. 1-2 over the cache of Sec. 3.2): stage counts and
 wave-loads per block, waves per compute unit, split lengths, the floor of items per wave, and
 the one-row-tile and the single-weight prefill kernels.  Each setting is run on small batches of the four layouts
-(MHA INT8, MHA INT4, GQA INT8, GQA INT4) and compared with the oracle."""
+(MHA INT8, MHA INT4, GQA INT8, GQA INT4 with groups of 32 and of 128) and compared with the oracle."""
 import os
 
 import numpy as np
@@ -22,6 +22,8 @@ LAYOUTS = [
     wl.replace(wl.scaled(wl.CONFIGS["int4"], B=6, max_len=2600, name="mha_int4"), Hkv=4, H=4, length_law="uniform:1,2600"),
     wl.replace(wl.scaled(wl.CONFIGS["gqa70b"], B=5, max_len=2600, name="gqa_int8"), Hkv=2, H=16, length_law="uniform:1,2600"),
     wl.replace(wl.scaled(wl.CONFIGS["gqa70b"], B=5, max_len=2600, name="gqa_int4"), bits=4, G=32, Hkv=2, H=16,
+               length_law="uniform:1,2600"),
+    wl.replace(wl.scaled(wl.CONFIGS["gqa70b"], B=5, max_len=2600, name="gqa_int4_g128"), bits=4, G=128, Hkv=2, H=8,
                length_law="uniform:1,2600"),
 ]
 

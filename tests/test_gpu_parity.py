@@ -64,6 +64,11 @@ SMALL = [
                length_law="uniform:1,2600"),
     wl.replace(wl.scaled(wl.CONFIGS["gqa70b"], B=4, max_len=600, name="gqa_int4_q16_p16"), bits=4, G=32, P=16, Hkv=1, H=16,
                length_law="uniform:30,600"),
+    # INT4 with one and two scale groups per head on the matrix-core path
+    wl.replace(wl.scaled(wl.CONFIGS["gqa70b"], B=5, max_len=2600, name="gqa_int4_g64_q8"), bits=4, G=64, P=16, Hkv=2, H=16,
+               length_law="uniform:1,2600"),
+    wl.replace(wl.scaled(wl.CONFIGS["gqa70b"], B=5, max_len=1500, name="gqa_int4_g128_q4"), bits=4, G=128, P=32, Hkv=2, H=8,
+               length_law="uniform:1,1500"),
     wl.replace(wl.scaled(wl.CONFIGS["gqa70b"], B=6, max_len=300, name="gqa_int4_q3"), bits=4, G=32, P=64, Hkv=2, H=6,
                length_law="uniform:1,300"),
 ]

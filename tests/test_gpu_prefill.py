@@ -42,6 +42,10 @@ CASES = [
     (_w("int4_g32_mha", bits=4, G=32, Hkv=4, H=4), [40, 200, 65, 1, 333, 64], [40, 7, 65, 1, 0, 64]),
     (_w("int4_g32_long", bits=4, G=32, Hkv=2, H=2), [2500, 1100], [70, 33]),
     (_w("int4_g32_gqa4_p32", bits=4, G=32, P=32, Hkv=2, H=8), [300, 77, 150], [100, 77, 9]),
+    (_w("int4_g64_mha", bits=4, G=64, Hkv=4, H=4), [40, 200, 65, 1, 333, 64], [40, 7, 65, 1, 0, 64]),
+    (_w("int4_g64_gqa8_long", bits=4, G=64, P=32, Hkv=1, H=8), [2500, 1100], [70, 33]),
+    (_w("int4_g128_mha_long", bits=4, G=128, Hkv=2, H=2), [2500, 300], [130, 300]),
+    (_w("int4_g128_gqa4_p64", bits=4, G=128, P=64, Hkv=2, H=8), [300, 77, 150], [100, 77, 9]),
 ]
 
 
@@ -109,9 +113,10 @@ def test_one_token_chunks_equal_the_decode_call(env):
 
 def test_unsupported_shapes_are_refused(env):
     B, torch, oracle = env
-    c4 = B.KVCache.allocate(4, 16, 2, 128, 4, 64)           # INT4 with groups of 64 (groups of 32 are taken)
-    assert B.alise_paged_prefill_attn_workspace_bytes(c4, 1, 8, 2) == 0
-    assert B.alise_paged_prefill_attn_workspace_bytes(B.KVCache.allocate(4, 16, 2, 128, 4, 32), 1, 8, 2) > 0
+    c32 = B.KVCache.allocate(4, 16, 2, 128, 8, 32)          # INT8 with groups of 32 (INT4 takes 32, 64 and 128)
+    assert B.alise_paged_prefill_attn_workspace_bytes(c32, 1, 8, 2) == 0
+    for g in (32, 64, 128):
+        assert B.alise_paged_prefill_attn_workspace_bytes(B.KVCache.allocate(4, 16, 2, 128, 4, g), 1, 8, 2) > 0
     c64 = B.KVCache.allocate(4, 16, 2, 64, 8, 64)           # head_dim 64
     assert B.alise_paged_prefill_attn_workspace_bytes(c64, 1, 8, 2) == 0
     ok = B.KVCache.allocate(4, 16, 2, 128, 8, 64)
