@@ -154,8 +154,11 @@ void oracle_quant_group(const uint16_t *x, int G, int bits,
 static float dequant_f32(uint8_t code, uint16_t scale_h, uint16_t zero_h)
 {
     float lam = oracle_h2f(scale_h);
-    int z = (int)oracle_h2f(zero_h);
-    return lam * (float)((int)code - z);
+    float z = oracle_h2f(zero_h);
+    /* code and every stored zero-point are integers of at most 8 bits: the fp32 difference is exact.
+     * (Taken in fp32 rather than in int so that the meta of a slot nobody wrote -- any bit pattern,
+     * NaN included -- gives garbage without a float-to-int conversion that C leaves undefined.) */
+    return lam * ((float)code - z);
 }
 
 /* ---------------------------------------------------------------- cache layout
