@@ -284,3 +284,41 @@ def test_peaked_rows_with_values_up_to_the_fp16_limit_of_the_bar(env, bits, G, H
     err = np.abs(got - want).max()
     print(f"  max|want| {np.abs(want).max():.3f} max-abs error {err:.3e}", flush=True)
     assert np.isfinite(got).all() and err <= ATTN_TOL
+
+
+@pytest.mark.parametrize("bits,G,Hkv,H", [(8, 64, 2, 2), (4, 32, 2, 2), (8, 128, 1, 8)])
+def test_more_requests_than_a_plan_pass_holds(env, bits, G, Hkv, H):
+    """2 300 requests: the plan kernels take the batch 1024 requests at a time (scans carried from pass to
+    pass, merge list and tile bases across passes).  Mostly short requests, empty ones, and a few long
+    enough to be split, scattered over the batch; decode on the vector and the matrix-core path, then
+    prefill chunks of a few tokens for every third request."""
+    B, torch, oracle = env
+    rng = np.random.default_rng([31, bits, H])
+    n = 2300
+    lens = rng.integers(0, 40, n).astype(np.int32)
+    lens[rng.choice(n, 12, replace=False)] = rng.integers(600, 2500, 12).astype(np.int32)
+    w = wl.Workload("many", B=n, H=H, Hkv=Hkv, D=128, P=16, bits=bits, G=G, length_law="fixed:1", seed=123, max_len=int(lens.max()))
+    print(f"case many requests bits={bits} G={G} H={H}", flush=True)
+    pg, pool, offs, gain = _problem(w, lens)
+    orc = harness.fill_oracle_cache(oracle, w, pg, pool, offs, gain)
+    dev = harness.fill_device_cache(B, torch, w, pg, pool, offs, gain)
+    q = wl.queries(w)
+    want = oracle.paged_decode_attn(orc, q, pg.block_tables, pg.lens, 1.0 / np.sqrt(w.D), num_threads=8)
+    got = harness.run_device_attn(B, torch, w, dev, q, pg).astype(np.float64)
+    assert np.isfinite(got).all() and not got[lens == 0].any()
+    assert np.abs(got - want).max() <= ATTN_TOL
+
+    chunk = np.where(np.arange(n) % 3 == 0, np.minimum(lens, 5), 0).astype(np.int64)
+    chunk[lens >= 600] = 70
+    q_start = np.concatenate([[0], np.cumsum(chunk)]).astype(np.int32)
+    total = int(q_start[-1])
+    qp_np = rng.standard_normal((total, H, 128)).astype(np.float16)
+    wantp = oracle.paged_prefill_attn(orc, qp_np, q_start, pg.block_tables, pg.lens, 1.0 / np.sqrt(w.D))
+    qp = torch.from_numpy(qp_np).cuda()
+    op = torch.full(qp.shape, float("nan"), dtype=torch.float16, device="cuda")
+    ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(dev, n, total, H), dtype=torch.uint8, device="cuda")
+    B.alise_paged_prefill_attn(dev, qp, op, torch.from_numpy(q_start).cuda(), torch.from_numpy(pg.block_tables).cuda(),
+                               torch.from_numpy(pg.lens.astype(np.int32)).cuda(), int(lens.max()), 1.0 / np.sqrt(w.D), ws)
+    torch.cuda.synchronize()
+    gotp = op.cpu().numpy().astype(np.float64)
+    assert np.isfinite(gotp).all() and np.abs(gotp - wantp).max() <= ATTN_TOL
