@@ -109,3 +109,33 @@ def test_prefill_with_one_and_two_row_tiles(env, problems, tiles, weights):
         got = out.cpu().numpy().astype(np.float64)
         err = float(np.abs(got - want).max())
         assert np.isfinite(got).all() and err <= ATTN_TOL, f"{name} with {tiles} row tiles, {weights} weights: {err:.3e}"
+
+
+@pytest.mark.parametrize("bits,G,Hkv,H", [(8, 64, 2, 2), (8, 128, 1, 8), (4, 32, 1, 4)])
+def test_more_than_64_splits_of_one_request(env, bits, G, Hkv, H):
+    """A request of 20 000 tokens in splits of 256: 79 partial results, more than the 64 that the merge
+    kernel combines in one pass of a wave, beside short requests that need no merge at all."""
+    B, torch, oracle = env
+    saved = {k: os.environ.pop(k, None) for k in KNOBS}
+    os.environ["ALISE_SPLIT_TOKENS"] = "256"
+    os.environ["ALISE_SPLIT_TOKENS_GQA"] = "256"
+    try:
+        lens = np.array([20000, 3, 700, 0, 257], np.int32)
+        w = wl.Workload("many_splits", B=len(lens), H=H, Hkv=Hkv, D=128, P=16, bits=bits, G=G, length_law="fixed:1", seed=9,
+                        max_len=int(lens.max()))
+        print(f"case knobs many splits bits={bits} H={H}", flush=True)
+        pg = wl.paging(w, lens)
+        pool = wl.value_pool(w, n_min=int(lens.max()) * Hkv * 128)
+        offs, gain = wl.request_offsets(w), wl.k_channel_gain(w)
+        orc = harness.fill_oracle_cache(oracle, w, pg, pool, offs, gain)
+        dev = harness.fill_device_cache(B, torch, w, pg, pool, offs, gain)
+        q = wl.queries(w)
+        want = oracle.paged_decode_attn(orc, q, pg.block_tables, pg.lens, 1.0 / np.sqrt(w.D), num_threads=8)
+        got = harness.run_device_attn(B, torch, w, dev, q, pg).astype(np.float64)
+        err = float(np.abs(got - want).max())
+        assert np.isfinite(got).all() and err <= ATTN_TOL, f"{err:.3e}"
+    finally:
+        for k in KNOBS:
+            os.environ.pop(k, None)
+            if saved[k] is not None:
+                os.environ[k] = saved[k]
