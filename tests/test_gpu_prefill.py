@@ -42,6 +42,8 @@ CASES = [
     (_w("int4_g32_mha", bits=4, G=32, Hkv=4, H=4), [40, 200, 65, 1, 333, 64], [40, 7, 65, 1, 0, 64]),
     (_w("int4_g32_long", bits=4, G=32, Hkv=2, H=2), [2500, 1100], [70, 33]),
     (_w("int4_g32_gqa4_p32", bits=4, G=32, P=32, Hkv=2, H=8), [300, 77, 150], [100, 77, 9]),
+    (_w("mha_p256", P=256, Hkv=2, H=2), [700, 256, 257, 40], [300, 256, 1, 40]),
+    (_w("gqa8_int4_p128", bits=4, G=32, P=128, Hkv=1, H=8), [1500, 129, 128], [200, 129, 7]),
     (_w("int4_g64_mha", bits=4, G=64, Hkv=4, H=4), [40, 200, 65, 1, 333, 64], [40, 7, 65, 1, 0, 64]),
     (_w("int4_g64_gqa8_long", bits=4, G=64, P=32, Hkv=1, H=8), [2500, 1100], [70, 33]),
     (_w("int4_g128_mha_long", bits=4, G=128, Hkv=2, H=2), [2500, 300], [130, 300]),
