@@ -64,6 +64,11 @@ SMALL = [
                length_law="uniform:1,2600"),
     wl.replace(wl.scaled(wl.CONFIGS["gqa70b"], B=4, max_len=600, name="gqa_int4_q16_p16"), bits=4, G=32, P=16, Hkv=1, H=16,
                length_law="uniform:30,600"),
+    # grouped-query layouts that stay on the vector kernel: head_dim 64, and 32 query heads per KV head
+    wl.replace(wl.scaled(wl.CONFIGS["gqa70b"], B=6, max_len=900, name="gqa_d64_vector"), D=64, G=64, P=16, Hkv=2, H=8,
+               length_law="uniform:1,900"),
+    wl.replace(wl.scaled(wl.CONFIGS["gqa70b"], B=4, max_len=700, name="gqa_q32_vector"), G=128, P=32, Hkv=1, H=32,
+               length_law="uniform:1,700"),
     # the largest pages: 128 and 256 tokens, vector and matrix-core path
     wl.replace(wl.scaled(wl.CONFIGS["llama7b"], B=7, max_len=2300, name="mha_p256"), P=256, Hkv=2, H=2, length_law="uniform:1,2300"),
     wl.replace(wl.scaled(wl.CONFIGS["int4"], B=7, max_len=2300, name="mha_int4_p128"), P=128, Hkv=2, H=2, length_law="uniform:1,2300"),
