@@ -241,6 +241,31 @@ def graph_leg(step, total_bytes, steps):
             "note": "one captured step replayed; the headline figures above are the eager calls"}
 
 
+def planned_leg(step, copies, b_attn, steps):
+    """The attention call of one layer when the plan is made once per decode iteration
+    (alise_paged_decode_attn_plan) and every layer runs alise_paged_decode_attn_planned on it."""
+    import numpy as np
+    import torch
+    from paper_2410_23537_amd import binding as B
+    B.alise_paged_decode_attn_plan(step.caches[0], step.context_lens, step.w.H, step.max_len, step.workspace)
+
+    def run(c):
+        B.alise_paged_decode_attn_planned(step.caches[c], step.q, step.out, step.block_tables, step.context_lens,
+                                          step.max_len, step.scale, step.workspace)
+    for s in range(3):
+        run(s % copies)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for s, (e0, e1) in enumerate(ev):
+        e0.record()
+        run(s % copies)
+        e1.record()
+    torch.cuda.synchronize()
+    ms = float(np.mean([e0.elapsed_time(e1) for e0, e1 in ev]))
+    return {"ms": ms, "GBs": b_attn / (ms * 1e-3) / 1e9, "frac": b_attn / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "note": "alise_paged_decode_attn_planned: the layers of one decode iteration share the plan (their lengths are the same); "
+                    "the headline figures above make the plan in every call"}
+
+
 def read_ceiling_leg():
     """The second denominator: what a kernel that only reads sustains on this device (the library's
     streaming-read probe over 4 GiB, sixteen times the last-level cache), beside the published peak.
@@ -476,6 +501,7 @@ def main():
         ceiling = read_ceiling_leg()
         result["hbm_read_ceiling"] = ceiling
         result["roofline"]["frac_of_read_ceiling"] = achieved / ceiling["GBs"]
+        result["planned_attention"] = planned_leg(step, copies, b_attn, args.steps)
         result["graph_replay"] = graph_leg(step, total_bytes, args.steps)
         result["swap"] = swap_leg(step)
         prefill = prefill_leg(w, step)

@@ -151,6 +151,29 @@ int alise_paged_decode_attn(const alise_kv_cache *c, const void *q, void *out,
                             void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * The same attention in two calls, for a model of many layers              [Sec. 2, Eq. 1-2]
+ *
+ * How a batch is cut into work items depends on the lengths alone, and the lengths are the same for
+ * every layer of one decode iteration.  alise_paged_decode_attn_plan does that part once (it reads
+ * context_lens and writes the workspace); alise_paged_decode_attn_planned is
+ * alise_paged_decode_attn without it, for each layer's cache, q and out in turn, on the same
+ * workspace.  The cache geometry, B, num_q_heads, max_context_len and the contents of context_lens
+ * must be those the plan was made with, and the tuning environment unchanged; the workspace must
+ * not be touched in between except by these calls.  Results are bit for bit those of the single
+ * call.  Arguments, checks and status codes as for alise_paged_decode_attn (the plan looks at no
+ * cache pointer, so c->k_codes etc. may be NULL for it).
+ */
+int alise_paged_decode_attn_plan(const alise_kv_cache *c, const int32_t *context_lens, int32_t B,
+                                 int32_t num_q_heads, int32_t max_context_len,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+int alise_paged_decode_attn_planned(const alise_kv_cache *c, const void *q, void *out,
+                                    const int32_t *block_tables, int32_t max_blocks_per_seq,
+                                    const int32_t *context_lens, int32_t B, int32_t num_q_heads,
+                                    int32_t max_context_len, float softmax_scale,
+                                    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Dequantize one page back to fp16                                 [Sec. 3.2]
  *   k_out, v_out  device, fp16 [page_size][num_kv_heads][head_dim], 16-byte aligned.
  * Every slot of the page is converted, written or not:

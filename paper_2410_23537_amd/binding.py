@@ -32,6 +32,7 @@ ALISE_HIP_ERROR = 5
 
 EXPORTS = ("alise_kv_codes_bytes", "alise_kv_meta_bytes", "alise_kv_quant_write",
            "alise_paged_decode_attn_workspace_bytes", "alise_paged_decode_attn",
+           "alise_paged_decode_attn_plan", "alise_paged_decode_attn_planned",
            "alise_kv_dequant_page", "alise_kv_swap_bytes", "alise_kv_swap_out", "alise_kv_swap_in",
            "alise_paged_prefill_attn_workspace_bytes", "alise_paged_prefill_attn",
            "alise_add_layernorm", "alise_bias_relu", "alise_hbm_read_probe",
@@ -64,6 +65,11 @@ _lib.alise_paged_decode_attn.argtypes = [_P, ctypes.c_void_p, ctypes.c_void_p, c
                                          ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
                                          ctypes.c_int32, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t,
                                          ctypes.c_void_p]
+_lib.alise_paged_decode_attn_planned.restype = ctypes.c_int
+_lib.alise_paged_decode_attn_planned.argtypes = _lib.alise_paged_decode_attn.argtypes
+_lib.alise_paged_decode_attn_plan.restype = ctypes.c_int
+_lib.alise_paged_decode_attn_plan.argtypes = [_P, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                              ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
 _lib.alise_kv_dequant_page.restype = ctypes.c_int
 _lib.alise_kv_dequant_page.argtypes = [_P, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
 _lib.alise_paged_prefill_attn_workspace_bytes.restype = ctypes.c_size_t
@@ -208,6 +214,32 @@ def alise_paged_decode_attn(cache: KVCache, q: torch.Tensor, out: torch.Tensor, 
                                       float(softmax_scale), _dp(workspace),
                                       int(workspace.numel() * workspace.element_size()), _stream())
     _check(st, "alise_paged_decode_attn")
+
+
+def alise_paged_decode_attn_plan(cache: KVCache, context_lens: torch.Tensor, num_q_heads: int, max_context_len: int,
+                                 workspace: torch.Tensor) -> None:
+    """The part of alise_paged_decode_attn that depends on the lengths alone: once per decode iteration."""
+    assert context_lens.dtype == torch.int32 and context_lens.is_contiguous() and context_lens.is_cuda
+    st = _lib.alise_paged_decode_attn_plan(ctypes.byref(cache.c_struct()), _dp(context_lens), int(context_lens.numel()),
+                                           int(num_q_heads), int(max_context_len), _dp(workspace),
+                                           int(workspace.numel() * workspace.element_size()), _stream())
+    _check(st, "alise_paged_decode_attn_plan")
+
+
+def alise_paged_decode_attn_planned(cache: KVCache, q: torch.Tensor, out: torch.Tensor, block_tables: torch.Tensor,
+                                    context_lens: torch.Tensor, max_context_len: int, softmax_scale: float,
+                                    workspace: torch.Tensor) -> None:
+    """alise_paged_decode_attn on the plan that alise_paged_decode_attn_plan left in the workspace: once per layer."""
+    B, H, D = q.shape
+    assert q.dtype == torch.float16 and out.dtype == torch.float16 and tuple(out.shape) == (B, H, D)
+    assert block_tables.dtype == torch.int32 and context_lens.dtype == torch.int32
+    assert q.is_contiguous() and out.is_contiguous() and block_tables.is_contiguous() and context_lens.is_contiguous()
+    assert block_tables.shape[0] == B and context_lens.numel() == B
+    st = _lib.alise_paged_decode_attn_planned(ctypes.byref(cache.c_struct()), _dp(q), _dp(out), _dp(block_tables),
+                                              int(block_tables.shape[1]), _dp(context_lens), B, H, int(max_context_len),
+                                              float(softmax_scale), _dp(workspace),
+                                              int(workspace.numel() * workspace.element_size()), _stream())
+    _check(st, "alise_paged_decode_attn_planned")
 
 
 def alise_kv_dequant_page(cache: KVCache, page: int, k_out: torch.Tensor, v_out: torch.Tensor) -> None:

@@ -289,41 +289,84 @@ size_t alise_paged_decode_attn_workspace_bytes(const alise_kv_cache *c, int32_t 
     return carve_workspace(cv, B, num_q_heads, max_context_len, nullptr, nullptr);
 }
 
-int alise_paged_decode_attn(const alise_kv_cache *c, const void *q, void *out,
+// The three forms of the attention call: plan + run in one (the lengths are new every time), the plan alone
+// (once per decode step), the run alone (once per layer of that step, on the plan in the workspace).
+static int decode_attn_call(const alise_kv_cache *c, const void *q, void *out,
                             const int32_t *block_tables, int32_t max_blocks_per_seq,
                             const int32_t *context_lens, int32_t B, int32_t num_q_heads,
                             int32_t max_context_len, float softmax_scale,
-                            void *workspace, size_t workspace_bytes, void *hip_stream)
+                            void *workspace, size_t workspace_bytes, int32_t phases, void *hip_stream)
 {
+    const bool run = (phases & alise::kPhaseRun) != 0;
     CacheView cv;
     int st = check_cache(c, &cv);
     if (st != ALISE_OK) return st;
     st = check_attn_sizes(cv, B, num_q_heads, max_context_len);
     if (st != ALISE_OK) return st;
     if (B == 0) return ALISE_OK;
-    if (max_blocks_per_seq <= 0) return ALISE_INVALID_ARGUMENT;
-    if ((int64_t)max_blocks_per_seq * cv.P < max_context_len) return ALISE_INVALID_ARGUMENT;
-    if (!(softmax_scale == softmax_scale) || softmax_scale <= 0.0f) return ALISE_INVALID_ARGUMENT;
-    if (!q || !out || !block_tables || !context_lens || !workspace) return ALISE_INVALID_ARGUMENT;
-    st = check_cache_pointers(c);
-    if (st != ALISE_OK) return st;
-    if (!aligned16(q) || !aligned16(out)) return ALISE_MISALIGNED;
-    if ((reinterpret_cast<uintptr_t>(block_tables) & 3u) || (reinterpret_cast<uintptr_t>(context_lens) & 3u))
-        return ALISE_MISALIGNED;
+    if (run) {
+        if (max_blocks_per_seq <= 0) return ALISE_INVALID_ARGUMENT;
+        if ((int64_t)max_blocks_per_seq * cv.P < max_context_len) return ALISE_INVALID_ARGUMENT;
+        if (!(softmax_scale == softmax_scale) || softmax_scale <= 0.0f) return ALISE_INVALID_ARGUMENT;
+        if (!q || !out || !block_tables) return ALISE_INVALID_ARGUMENT;
+    }
+    if (!context_lens || !workspace) return ALISE_INVALID_ARGUMENT;
+    if (run) {
+        st = check_cache_pointers(c);
+        if (st != ALISE_OK) return st;
+        if (!aligned16(q) || !aligned16(out)) return ALISE_MISALIGNED;
+        if (reinterpret_cast<uintptr_t>(block_tables) & 3u) return ALISE_MISALIGNED;
+    }
+    if (reinterpret_cast<uintptr_t>(context_lens) & 3u) return ALISE_MISALIGNED;
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return ALISE_MISALIGNED;
     AttnWorkspace ws;
     const size_t need = carve_workspace(cv, B, num_q_heads, max_context_len, workspace, &ws);
     if (workspace_bytes < need) return ALISE_WORKSPACE_TOO_SMALL;
     if (debug_validate()) {
-        st = validate_lens_and_tables(cv, block_tables, max_blocks_per_seq, context_lens, B, max_context_len, nullptr,
-                                      static_cast<hipStream_t>(hip_stream));
-        if (st != ALISE_OK) return st;
+        hipStream_t hs = static_cast<hipStream_t>(hip_stream);
+        if (run) {
+            st = validate_lens_and_tables(cv, block_tables, max_blocks_per_seq, context_lens, B, max_context_len, nullptr, hs);
+            if (st != ALISE_OK) return st;
+        } else {
+            std::vector<int32_t> lens;
+            st = fetch_to_host(lens, context_lens, (size_t)B, hs);
+            if (st != ALISE_OK) return st;
+            for (int32_t L : lens)
+                if (L < 0 || L > max_context_len) return ALISE_INVALID_ARGUMENT;
+        }
     }
     hipError_t e = alise::launch_decode_attn(cv, q, out, block_tables, max_blocks_per_seq, context_lens, B,
                                              num_q_heads, max_context_len, softmax_scale, ws,
                                              num_compute_units(), waves_per_cu(), loads_per_block(), min_items_per_wave(),
-                                             static_cast<hipStream_t>(hip_stream));
+                                             phases, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? ALISE_OK : ALISE_HIP_ERROR;
+}
+
+int alise_paged_decode_attn(const alise_kv_cache *c, const void *q, void *out,
+                            const int32_t *block_tables, int32_t max_blocks_per_seq,
+                            const int32_t *context_lens, int32_t B, int32_t num_q_heads,
+                            int32_t max_context_len, float softmax_scale,
+                            void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return decode_attn_call(c, q, out, block_tables, max_blocks_per_seq, context_lens, B, num_q_heads, max_context_len,
+                            softmax_scale, workspace, workspace_bytes, alise::kPhasePlan | alise::kPhaseRun, hip_stream);
+}
+
+int alise_paged_decode_attn_plan(const alise_kv_cache *c, const int32_t *context_lens, int32_t B, int32_t num_q_heads,
+                                 int32_t max_context_len, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return decode_attn_call(c, nullptr, nullptr, nullptr, 0, context_lens, B, num_q_heads, max_context_len, 1.0f, workspace,
+                            workspace_bytes, alise::kPhasePlan, hip_stream);
+}
+
+int alise_paged_decode_attn_planned(const alise_kv_cache *c, const void *q, void *out,
+                                    const int32_t *block_tables, int32_t max_blocks_per_seq,
+                                    const int32_t *context_lens, int32_t B, int32_t num_q_heads,
+                                    int32_t max_context_len, float softmax_scale,
+                                    void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return decode_attn_call(c, q, out, block_tables, max_blocks_per_seq, context_lens, B, num_q_heads, max_context_len,
+                            softmax_scale, workspace, workspace_bytes, alise::kPhaseRun, hip_stream);
 }
 
 int alise_kv_dequant_page(const alise_kv_cache *c, int32_t page, void *k_out, void *v_out, void *hip_stream)

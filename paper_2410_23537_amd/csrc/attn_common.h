@@ -22,6 +22,7 @@ struct AttnParams {
     const int32_t *context_lens;
     int32_t max_blocks, B, H, qper, max_len;
     float scale_log2e;
+    int32_t zero_empty;         // the merge kernel writes the zero rows of empty requests (the plan kernel had no output to write to)
     AttnWorkspace ws;
 };
 

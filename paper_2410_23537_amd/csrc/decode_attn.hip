@@ -152,7 +152,7 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t *context_lens,
             ws.req_full_base[i] = total_full + s_full - nfull;
             if (nrem) atomicAdd(&s_hist[rem_bucket(r, C)], 1);
             if (nfull + nrem > 1) ws.merge_req[atomicAdd(&s_merge, 1)] = i;
-            if (L == 0)
+            if (L == 0 && out)           // out == nullptr: a plan made ahead of the calls that use it; they zero these rows
                 for (int e = 0; e < H * D; ++e) out[(int64_t)i * H * D + e] = (_Float16)0.0f;
         }
         total += t_all;
@@ -622,6 +622,14 @@ __global__ __launch_bounds__(256) void merge_kernel(AttnParams p)
 {
     const int lane = threadIdx.x & 63;
     const int n_waves = gridDim.x * 4;
+    if (p.zero_empty) {                     // the plan was made without an output to write to: empty requests give zero rows
+        for (int pair = blockIdx.x * 4 + (threadIdx.x >> 6); pair < p.B * p.H; pair += n_waves)
+            if (p.context_lens[pair / p.H] <= 0) {
+                _Float16 *dst = p.out + (int64_t)pair * D;
+#pragma unroll
+                for (int r = 0; r < D / 64; ++r) dst[r * 64 + lane] = (_Float16)0.0f;
+            }
+    }
     const int n_pairs = *p.ws.n_merge * p.H;
     for (int pair = blockIdx.x * 4 + (threadIdx.x >> 6); pair < n_pairs; pair += n_waves) {
         const int i = p.ws.merge_req[pair / p.H], h = pair % p.H;
@@ -709,7 +717,7 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
                               const int32_t *context_lens, int32_t B, int32_t H,
                               int32_t max_context_len, float softmax_scale,
                               const AttnWorkspace &ws, int32_t num_cus, int32_t waves_per_cu,
-                              int32_t loads_per_block, int32_t min_items_per_wave, hipStream_t s)
+                              int32_t loads_per_block, int32_t min_items_per_wave, int32_t phases, hipStream_t s)
 {
     if (B == 0) return hipSuccess;
     AttnParams p;
@@ -730,10 +738,15 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
     // per compute unit) would get this many items; the matrix-core kernel, whose items are
     // heavier to start, asks for one
     p.ws.min_items = num_cus * 8 * (min_items_per_wave > 0 ? min_items_per_wave : (gqa ? 1 : 4));
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, s, context_lens, B, H, gqa ? c.Hkv : H, max_context_len, p.ws,
-                       p.out, c.D);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    p.zero_empty = (phases & kPhasePlan) ? 0 : 1;
+    hipError_t e = hipSuccess;
+    if (phases & kPhasePlan) {
+        hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, s, context_lens, B, H, gqa ? c.Hkv : H, max_context_len, p.ws,
+                           p.out, c.D);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (!(phases & kPhaseRun)) return hipSuccess;
     e = hipErrorInvalidValue;
     if (gqa) {
         e = launch_gqa_mfma(p, num_cus, waves_per_cu, loads_per_block, s);

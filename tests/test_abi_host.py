@@ -100,10 +100,11 @@ def test_dequant_page_arguments(B):
     assert lib.alise_kv_dequant_page(ctypes.byref(c), 0, 0x10002, 0x20000, None) == 4
 
 
-def test_attention_arguments(B):
+@pytest.mark.parametrize("entry", ["alise_paged_decode_attn", "alise_paged_decode_attn_planned"])
+def test_attention_arguments(B, entry):
     lib = B.raw()
     c = _cache(B)
-    f = lib.alise_paged_decode_attn
+    f = getattr(lib, entry)
     ok = [ctypes.byref(c), 0x10000, 0x20000, 0x30000, 16, 0x40000, 2, 8, 256, 0.1, 0x50000, 1 << 30, None]
 
     def call(**kw):
@@ -137,6 +138,24 @@ def test_attention_arguments(B):
     # the workspace grows with the batch and with the longest context
     assert lib.alise_paged_decode_attn_workspace_bytes(ctypes.byref(c), 64, 8, 256) > need
     assert lib.alise_paged_decode_attn_workspace_bytes(ctypes.byref(c), 2, 8, 1 << 16) > need
+
+
+def test_attention_plan_arguments(B):
+    lib = B.raw()
+    c = _cache(B)
+    need = lib.alise_paged_decode_attn_workspace_bytes(ctypes.byref(c), 2, 8, 256)
+    f = lambda c_=ctypes.byref(c), lens=0x40000, B_=2, H=8, maxlen=256, ws=0x50000, wsb=need: \
+        lib.alise_paged_decode_attn_plan(c_, lens, B_, H, maxlen, ws, wsb, None)
+    assert f(B_=0) == 0
+    assert f(B_=-1) == 1 and f(H=0) == 1 and f(maxlen=-1) == 1
+    assert f(H=12) == 2
+    assert f(lens=0) == 1 and f(ws=0) == 1
+    assert f(lens=0x40002) == 4 and f(ws=0x50010) == 4
+    assert f(wsb=need - 1) == 3
+    assert f(c_=None) == 1
+    nop = _cache(B)                                 # the plan looks at no cache pointer
+    nop.k_codes = nop.v_codes = nop.k_meta = nop.v_meta = None
+    assert f(c_=ctypes.byref(nop), B_=0) == 0
 
 
 def test_swap_arguments(B):
