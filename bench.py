@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published peak HBM3E bandwidth
 
 # HBM bytes per attention launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a
 # copy kernel of known size; see profiles/.  None where not measured.
-MEASURED_TRAFFIC_BYTES = {"int4": 7186554861, "gqa70b": 1102926788, "llama7b": 1993394133}
+MEASURED_TRAFFIC_BYTES = {"int4": 7186751762, "gqa70b": 1102993195, "llama7b": 1993467750, "opt13b": 416174753}
 
 
 def parse():
