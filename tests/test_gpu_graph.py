@@ -119,3 +119,78 @@ def test_captured_decode_step_replays_like_eager(env, w):
         assert np.isfinite(got).all() and err <= ATTN_TOL
         # eager work of the program's own between replays
         (q.float() * 2.0).sum().item()
+
+
+@pytest.mark.parametrize("w", CASES[:2], ids=lambda w: w.name)
+def test_captured_iteration_of_three_layers_with_one_plan(env, w):
+    """What a serving loop captures: the plan once, then per layer the write of the new token and the planned
+    attention call, each layer with a cache of its own.  Replayed with other lengths and tokens, every layer's
+    output must equal the single (plan + run) call done eagerly on a twin cache, bit for bit."""
+    B, torch, oracle = env
+    print(f"case graph planned {w.name}", flush=True)
+    n_layers = 3
+    pg = wl.paging(w)
+    scale = 1.0 / np.sqrt(w.D)
+    max_len = int(pg.lens.max())
+    bt = torch.from_numpy(pg.block_tables).cuda()
+    caches_g, caches_e = [], []
+    for layer in range(n_layers):
+        wl_layer = wl.replace(w, seed=w.seed + 100 * layer)
+        pool = wl.value_pool(wl_layer, n_min=max_len * w.Hkv * w.D)
+        offs, gain = wl.request_offsets(wl_layer), wl.k_channel_gain(wl_layer)
+        caches_g.append(harness.fill_device_cache(B, torch, wl_layer, pg, pool, offs, gain))
+        caches_e.append(harness.fill_device_cache(B, torch, wl_layer, pg, pool, offs, gain))
+    q = torch.zeros((n_layers, w.B, w.H, w.D), dtype=torch.float16, device="cuda")
+    k_new = torch.zeros((n_layers, w.B, w.Hkv, w.D), dtype=torch.float16, device="cuda")
+    v_new = torch.zeros_like(k_new)
+    slots = torch.zeros(w.B, dtype=torch.int64, device="cuda")
+    lens = torch.ones(w.B, dtype=torch.int32, device="cuda")
+    out = torch.zeros_like(q)
+    ws = torch.empty(B.alise_paged_decode_attn_workspace_bytes(caches_g[0], w.B, w.H, max_len), dtype=torch.uint8, device="cuda")
+
+    def iteration():
+        B.alise_paged_decode_attn_plan(caches_g[0], lens, w.H, max_len, ws)
+        for layer in range(n_layers):
+            B.alise_kv_quant_write(caches_g[layer], k_new[layer], v_new[layer], slots)
+            B.alise_paged_decode_attn_planned(caches_g[layer], q[layer], out[layer], bt, lens, max_len, scale, ws)
+
+    def load(r):
+        rng = np.random.default_rng([w.seed, r, 23])
+        L = np.array([rng.integers(0, int(x)) for x in pg.lens], np.int64)
+        if r == 2:
+            L[0] = 0                                    # a one-token request
+        s = pg.block_tables[np.arange(w.B), L // w.P].astype(np.int64) * w.P + L % w.P
+        q.copy_(torch.from_numpy(rng.standard_normal(tuple(q.shape)).astype(np.float16)))
+        k_new.copy_(torch.from_numpy(rng.standard_normal(tuple(k_new.shape)).astype(np.float16)))
+        v_new.copy_(torch.from_numpy(rng.standard_normal(tuple(v_new.shape)).astype(np.float16)))
+        slots.copy_(torch.from_numpy(s))
+        lens.copy_(torch.from_numpy((L + 1).astype(np.int32)))
+
+    def eager():
+        e_out = torch.zeros_like(out)
+        e_ws = torch.empty_like(ws)
+        for layer in range(n_layers):
+            B.alise_kv_quant_write(caches_e[layer], k_new[layer], v_new[layer], slots)
+            B.alise_paged_decode_attn(caches_e[layer], q[layer], e_out[layer], bt, lens, max_len, scale, e_ws)
+        torch.cuda.synchronize()
+        return e_out
+
+    load(0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        iteration()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        iteration()
+    eager()                                             # the twin caches get replay 0's tokens too
+    for r in range(1, 5):
+        load(r)
+        out.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        want = eager()
+        assert torch.equal(out.view(torch.int16), want.view(torch.int16)), f"replay {r} differs from the eager single calls"
+        _ = (q.float() @ q.float().transpose(-1, -2)).sum().item()          # eager work of the program's own between replays
