@@ -21,12 +21,14 @@ struct AttnWorkspace {
     int32_t *req_full_base; // [B] scratch of the plan kernel: first full tile of each request in the work order
     int32_t *merge_req;     // [B] requests with more than one split, in no particular order
     int32_t *n_merge;       // [1] how many of them
+    int32_t *n_shared;      // [1] items before this one are dealt out among all waves, the rest among the favoured half
     int4 *order;            // [max_tiles] work order: (request, first token, end token, split buffer index or -1)
     float *part;            // [max_tiles * H][D + 2] = (m, l, o[D]) of every split
     int32_t max_tiles;
     int32_t chunk_tokens;   // largest tokens per split; the plan kernel halves it (down to min_chunk_tokens)
     int32_t min_chunk_tokens;   // while the batch would give fewer than min_items work items
     int32_t min_items;
+    int32_t skew_permille;  // share of the work (its shortest items) that goes to the favoured waves only
 };
 
 // True when the attention call takes the matrix-core path for grouped-query layouts

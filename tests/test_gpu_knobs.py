@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 
 ATTN_TOL = 2e-3
 KNOBS = ("ALISE_SPLIT_TOKENS", "ALISE_SPLIT_TOKENS_GQA", "ALISE_WAVES_PER_CU", "ALISE_LOADS_PER_BLOCK",
-         "ALISE_MIN_ITEMS_PER_WAVE", "ALISE_PREFILL_ROW_TILES", "ALISE_PREFILL_WEIGHTS")
+         "ALISE_MIN_ITEMS_PER_WAVE", "ALISE_PREFILL_ROW_TILES", "ALISE_PREFILL_WEIGHTS", "ALISE_XCD_SKEW")
 
 LAYOUTS = [
     wl.replace(wl.scaled(wl.CONFIGS["llama7b"], B=6, max_len=2600, name="mha_int8"), Hkv=4, H=4, length_law="uniform:1,2600"),
@@ -134,6 +134,38 @@ def test_more_than_64_splits_of_one_request(env, bits, G, Hkv, H):
         got = harness.run_device_attn(B, torch, w, dev, q, pg).astype(np.float64)
         err = float(np.abs(got - want).max())
         assert np.isfinite(got).all() and err <= ATTN_TOL, f"{err:.3e}"
+    finally:
+        for k in KNOBS:
+            os.environ.pop(k, None)
+            if saved[k] is not None:
+                os.environ[k] = saved[k]
+
+
+@pytest.mark.parametrize("skew", ["0", "50", "200"])
+def test_short_items_dealt_to_half_of_the_waves(env, skew):
+    """ALISE_XCD_SKEW: the shortest items of a large batch go to the waves of even workgroups only.  The plan
+    applies it when a wave gets many items, so: 420 requests, 8 heads, splits of 256 tokens and an item floor of
+    one (6 700 items and more against a threshold of 6 144).  Every (request, head) must still be attended to
+    exactly once: compared with the oracle."""
+    B, torch, oracle = env
+    saved = {k: os.environ.pop(k, None) for k in KNOBS}
+    os.environ.update({"ALISE_XCD_SKEW": skew, "ALISE_MIN_ITEMS_PER_WAVE": "1", "ALISE_SPLIT_TOKENS": "256"})
+    try:
+        rng = np.random.default_rng(31)
+        lens = rng.integers(0, 600, 420).astype(np.int32)
+        lens[:5] = [0, 1, 256, 257, 3000]
+        w = wl.Workload("skew", B=len(lens), H=8, Hkv=8, D=128, P=16, bits=8, G=128, length_law="fixed:1", seed=19, max_len=int(lens.max()))
+        print(f"case knobs skew {skew}", flush=True)
+        pg = wl.paging(w, lens)
+        pool = wl.value_pool(w, n_min=int(lens.max()) * w.Hkv * w.D)
+        offs, gain = wl.request_offsets(w), wl.k_channel_gain(w)
+        orc = harness.fill_oracle_cache(oracle, w, pg, pool, offs, gain)
+        dev = harness.fill_device_cache(B, torch, w, pg, pool, offs, gain)
+        q = wl.queries(w)
+        want = oracle.paged_decode_attn(orc, q, pg.block_tables, pg.lens, 1.0 / np.sqrt(w.D), num_threads=8)
+        got = harness.run_device_attn(B, torch, w, dev, q, pg).astype(np.float64)
+        err = float(np.abs(got - want).max())
+        assert np.isfinite(got).all() and not got[lens == 0].any() and err <= ATTN_TOL, f"{err:.3e}"
     finally:
         for k in KNOBS:
             os.environ.pop(k, None)
