@@ -501,6 +501,17 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
             const uint32_t base = next_stage();
             step(std::false_type{}, k, base);
             ++steps_consumed;
+            // A wave lowers its own priority by a step with every 256 tokens it has done, wrapping after four: of the
+            // waves of a SIMD the one that is behind goes first, so they finish together instead of the oldest long
+            // before the youngest (see the vector kernel).
+            if ((steps_consumed & 7) == 0) {        // wave-uniform; no memory operation inside
+                switch ((steps_consumed >> 3) & 3) {
+                case 0: __builtin_amdgcn_s_setprio(3); break;
+                case 1: __builtin_amdgcn_s_setprio(2); break;
+                case 2: __builtin_amdgcn_s_setprio(1); break;
+                default: __builtin_amdgcn_s_setprio(0); break;
+                }
+            }
         }
         {
             const uint32_t base = next_stage();
