@@ -37,7 +37,12 @@ __global__ __launch_bounds__(256) void read_probe_kernel(const u32x4_t *__restri
 #pragma unroll
         for (int u = 0; u < kProbeLoads; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
     };
+    // A wave steps its priority down with every 16 blocks it has read (wrapping after four steps), so that the waves of
+    // a SIMD stay together: left alone the oldest one is served first and finishes long before the youngest, and the
+    // end of the kernel runs with too few waves to keep the memory system busy (the same device as in the attention kernels).
     uint64_t blk = wave;
+    uint32_t pairs = 0;
+    __builtin_amdgcn_s_setprio(3);
     if (blk < n_blocks) {
         issue(a, blk);
         for (;;) {
@@ -49,6 +54,15 @@ __global__ __launch_bounds__(256) void read_probe_kernel(const u32x4_t *__restri
             if (blk >= n_blocks) { fold(b); break; }
             issue(a, blk);
             fold(b);
+            ++pairs;
+            if ((pairs & 7u) == 0u) {
+                switch ((pairs >> 3) & 3u) {
+                case 0: __builtin_amdgcn_s_setprio(3); break;
+                case 1: __builtin_amdgcn_s_setprio(2); break;
+                case 2: __builtin_amdgcn_s_setprio(1); break;
+                default: __builtin_amdgcn_s_setprio(0); break;
+                }
+            }
         }
     }
     for (uint64_t i = n_blocks * kBlock + wave * 64u + lane; i < n16; i += n_waves * 64u) {
