@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published peak HBM3E bandwidth
 
 # HBM bytes per attention launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a
 # copy kernel of known size; see profiles/.  None where not measured.
-MEASURED_TRAFFIC_BYTES = {"int4": 7191341611, "gqa70b": 1103144722, "llama7b": 1996743976, "opt13b": 418244465}
+MEASURED_TRAFFIC_BYTES = {"int4": 7191341611, "gqa70b": 1103144722, "llama7b": 1989225454, "opt13b": 414454493}
 
 
 def parse():
