@@ -455,7 +455,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
-              "(the path shards by request or by KV head without any exchange, see DESIGN.md)", file=sys.stderr)
+              "(the path would shard by request or by KV head, without any exchange between the GPUs)", file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch
