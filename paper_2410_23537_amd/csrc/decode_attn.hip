@@ -165,7 +165,7 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t *context_lens,
         const int my_count = s_hist[tid];
         // cost of this bucket's tiles in units of 64 tokens: their length (the bucket's upper end) plus what starting
         // and ending an item costs a wave (about 128 tokens' worth)
-        const int my_cost = (int)(((int64_t)my_count * (C - (int)(((int64_t)tid * C) / kRemBuckets) + 128)) >> 6);
+        const int my_cost = (int)(((int64_t)my_count * (C - ((tid * C) >> 10) + 128)) >> 6);      // kRemBuckets is 1024, C at most 2^20
         int incl, cost_incl, t0, cost_rem;
         block_scan2_1024(my_count, my_cost, s_wave, incl, cost_incl, t0, cost_rem);
         s_hist[tid] = incl - my_count;
@@ -174,9 +174,9 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t *context_lens,
         // shorter ones, fit that share.
         if (tid == 0) s_first_extra = total;
         __syncthreads();
-        const int64_t cost_all = (((int64_t)total_full * (C + 128)) >> 6) + cost_rem;
-        const int64_t share = cost_all * ws.skew_permille / 1000;
-        const int64_t with_shorter = (int64_t)cost_rem - (cost_incl - my_cost);
+        const float cost_all = (float)total_full * (float)(C + 128) * (1.0f / 64.0f) + (float)cost_rem;
+        const float share = cost_all * (float)ws.skew_permille * 1.0e-3f;
+        const float with_shorter = (float)(cost_rem - (cost_incl - my_cost));
         // only where a wave has enough items for such a shift to be fine-grained: with two or three items per wave it
         // unbalances more than it repairs (measured: +4 % on a 64-request batch)
         const bool many_items = (int64_t)total * items_per_tile >= 3 * (int64_t)ws.min_items;
