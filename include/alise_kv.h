@@ -195,7 +195,9 @@ int alise_kv_dequant_page(const alise_kv_cache *c, int32_t page, void *k_out, vo
  *   q, out        device, fp16 [total_q_tokens][num_q_heads][head_dim], 16-byte aligned: the
  *                 chunks of the B requests back to back.
  *   q_start       device, int32 [B + 1]: request i owns rows q_start[i] .. q_start[i+1] - 1;
- *                 q_start[0] = 0, nondecreasing, q_start[B] = total_q_tokens.  n_i = 0 is legal.
+ *                 q_start[0] = 0, nondecreasing, q_start[B] <= total_q_tokens (rows past q_start[B] are
+ *                 not touched: a caller that captures the call in a graph sizes q, out and the workspace
+ *                 for the largest chunk mix and changes q_start from replay to replay).  n_i = 0 is legal.
  *                 n_i > L_i is a caller error (the chunk is then cut to L_i rows).
  *   block_tables, max_blocks_per_seq, context_lens, max_context_len, softmax_scale, workspace:
  *                 as for alise_paged_decode_attn; the workspace size comes from

@@ -194,3 +194,59 @@ def test_captured_iteration_of_three_layers_with_one_plan(env, w):
         want = eager()
         assert torch.equal(out.view(torch.int16), want.view(torch.int16)), f"replay {r} differs from the eager single calls"
         _ = (q.float() @ q.float().transpose(-1, -2)).sum().item()          # eager work of the program's own between replays
+
+
+@pytest.mark.parametrize("w", [CASES[0], CASES[2]], ids=lambda w: w.name)
+def test_captured_prefill_call_replays_like_eager(env, w):
+    """The chunked-prefill call under graph capture: chunk boundaries and lengths are read from device memory, so
+    one captured call serves other chunk mixes of at most as many query tokens; every replay equals the eager call."""
+    B, torch, oracle = env
+    print(f"case graph prefill {w.name}", flush=True)
+    pg = wl.paging(w)
+    pool = wl.value_pool(w, n_min=int(pg.lens.max()) * w.Hkv * w.D)
+    offs, gain = wl.request_offsets(w), wl.k_channel_gain(w)
+    dev = harness.fill_device_cache(B, torch, w, pg, pool, offs, gain)
+    scale = 1.0 / np.sqrt(w.D)
+    max_len = int(pg.lens.max())
+    bt = torch.from_numpy(pg.block_tables).cuda()
+    total_cap = 64 * w.B
+    q = torch.zeros((total_cap, w.H, w.D), dtype=torch.float16, device="cuda")
+    out = torch.zeros_like(q)
+    q_start = torch.zeros(w.B + 1, dtype=torch.int32, device="cuda")
+    lens = torch.ones(w.B, dtype=torch.int32, device="cuda")
+    ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(dev, w.B, total_cap, w.H), dtype=torch.uint8, device="cuda")
+    e_ws = torch.empty_like(ws)
+
+    def call(o, wsp):
+        B.alise_paged_prefill_attn(dev, q, o, q_start, bt, lens, max_len, scale, wsp)
+
+    def load(r):
+        rng = np.random.default_rng([w.seed, r, 29])
+        L = np.array([rng.integers(1, int(x) + 1) for x in pg.lens], np.int64)
+        n = np.minimum(L, rng.integers(0, 65, w.B))
+        qs = np.concatenate([[0], np.cumsum(n)]).astype(np.int32)
+        q.copy_(torch.from_numpy(rng.standard_normal(tuple(q.shape)).astype(np.float16)))
+        q_start.copy_(torch.from_numpy(qs))
+        lens.copy_(torch.from_numpy(L.astype(np.int32)))
+        return int(qs[-1])
+
+    load(0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call(out, ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call(out, ws)
+    for r in range(1, 5):
+        total = load(r)
+        out.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        e_out = torch.full_like(out, float("nan"))
+        call(e_out, e_ws)
+        torch.cuda.synchronize()
+        assert torch.equal(out[:total].view(torch.int16), e_out[:total].view(torch.int16)), f"replay {r} differs from the eager call"
+        assert torch.isfinite(out[:total].float()).all()
