@@ -151,6 +151,30 @@ int alise_paged_decode_attn(const alise_kv_cache *c, const void *q, void *out,
                             void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * alise_paged_decode_attn without a workspace argument, for callers that cannot allocate
+ * device memory: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  The workspace is a static device array inside the library, of
+ * ALISE_STATIC_SCRATCH_BYTES bytes, which every GPU the library runs on holds until the
+ * process ends.  The call allocates nothing on the host side of HIP or on the device (no
+ * hipMalloc, hipFree or library routine that allocates); its first use on a device asks HIP for
+ * the array's address there (hipGetSymbolAddress) and keeps it.
+ *   - Arguments, results and status codes as for alise_paged_decode_attn (the output is bit for
+ *     bit the same).  If alise_paged_decode_attn_workspace_bytes(c, B, num_q_heads,
+ *     max_context_len) exceeds ALISE_STATIC_SCRATCH_BYTES the call returns
+ *     ALISE_WORKSPACE_TOO_SMALL and launches nothing.
+ *   - All calls on one GPU share that GPU's array: two such calls that may overlap in time (on
+ *     two streams, or from two threads) race.  Nothing in the array has to be cleared between
+ *     calls; what a call leaves there is unspecified.
+ *   - ALISE_DEBUG_VALIDATE is not honoured (its checks copy device arrays to the host).
+ */
+#define ALISE_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+
+int alise_paged_decode_attn_static(const alise_kv_cache *c, const void *q, void *out,
+                                   const int32_t *block_tables, int32_t max_blocks_per_seq,
+                                   const int32_t *context_lens, int32_t B, int32_t num_q_heads,
+                                   int32_t max_context_len, float softmax_scale, void *hip_stream);
+
+/*
  * The same attention in two calls, for a model of many layers              [Sec. 2, Eq. 1-2]
  *
  * How a batch is cut into work items depends on the lengths alone, and the lengths are the same for

@@ -32,7 +32,7 @@ ALISE_HIP_ERROR = 5
 
 EXPORTS = ("alise_kv_codes_bytes", "alise_kv_meta_bytes", "alise_kv_quant_write",
            "alise_paged_decode_attn_workspace_bytes", "alise_paged_decode_attn",
-           "alise_paged_decode_attn_plan", "alise_paged_decode_attn_planned",
+           "alise_paged_decode_attn_plan", "alise_paged_decode_attn_planned", "alise_paged_decode_attn_static",
            "alise_kv_dequant_page", "alise_kv_swap_bytes", "alise_kv_swap_out", "alise_kv_swap_in",
            "alise_paged_prefill_attn_workspace_bytes", "alise_paged_prefill_attn",
            "alise_add_layernorm", "alise_bias_relu", "alise_hbm_read_probe",
@@ -65,6 +65,8 @@ _lib.alise_paged_decode_attn.argtypes = [_P, ctypes.c_void_p, ctypes.c_void_p, c
                                          ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
                                          ctypes.c_int32, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t,
                                          ctypes.c_void_p]
+_lib.alise_paged_decode_attn_static.restype = ctypes.c_int
+_lib.alise_paged_decode_attn_static.argtypes = _lib.alise_paged_decode_attn.argtypes[:10] + [ctypes.c_void_p]
 _lib.alise_paged_decode_attn_planned.restype = ctypes.c_int
 _lib.alise_paged_decode_attn_planned.argtypes = _lib.alise_paged_decode_attn.argtypes
 _lib.alise_paged_decode_attn_plan.restype = ctypes.c_int
@@ -214,6 +216,23 @@ def alise_paged_decode_attn(cache: KVCache, q: torch.Tensor, out: torch.Tensor, 
                                       float(softmax_scale), _dp(workspace),
                                       int(workspace.numel() * workspace.element_size()), _stream())
     _check(st, "alise_paged_decode_attn")
+
+
+ALISE_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def alise_paged_decode_attn_static(cache: KVCache, q: torch.Tensor, out: torch.Tensor, block_tables: torch.Tensor,
+                                   context_lens: torch.Tensor, max_context_len: int, softmax_scale: float) -> None:
+    """alise_paged_decode_attn on the library's own static workspace (nothing is allocated)."""
+    B, H, D = q.shape
+    assert q.dtype == torch.float16 and out.dtype == torch.float16 and tuple(out.shape) == (B, H, D)
+    assert block_tables.dtype == torch.int32 and context_lens.dtype == torch.int32
+    assert q.is_contiguous() and out.is_contiguous() and block_tables.is_contiguous() and context_lens.is_contiguous()
+    assert block_tables.shape[0] == B and context_lens.numel() == B
+    st = _lib.alise_paged_decode_attn_static(ctypes.byref(cache.c_struct()), _dp(q), _dp(out), _dp(block_tables),
+                                             int(block_tables.shape[1]), _dp(context_lens), B, H, int(max_context_len),
+                                             float(softmax_scale), _stream())
+    _check(st, "alise_paged_decode_attn_static")
 
 
 def alise_paged_decode_attn_plan(cache: KVCache, context_lens: torch.Tensor, num_q_heads: int, max_context_len: int,

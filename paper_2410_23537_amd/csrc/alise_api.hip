@@ -6,7 +6,15 @@
 
 #include <algorithm>
 #include <cstdlib>
+#include <mutex>
 #include <vector>
+
+// Workspace of alise_paged_decode_attn_static: a file-scope device array, so that the call needs no allocation
+// by anybody.  Each GPU the library runs on holds its own copy until the process ends.  In host code the array's
+// name is only a handle for hipGetSymbolAddress: the address that kernels, copies and fills may use is the one that
+// call returns for the device that is current, asked once per device and kept in static_scratch_ptr.
+constexpr size_t kStaticScratchBytes = ALISE_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -245,6 +253,25 @@ int num_compute_units()
     return cached[dev];
 }
 
+constexpr int kMaxDevices = 64;
+std::mutex static_scratch_mutex;
+void *static_scratch_ptr[kMaxDevices] = {nullptr};
+
+// Device address of `scratch` on the current device (ALISE_HIP_ERROR if HIP cannot give it).
+int static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return ALISE_HIP_ERROR;
+    std::lock_guard<std::mutex> hold(static_scratch_mutex);
+    if (!static_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return ALISE_HIP_ERROR;
+        static_scratch_ptr[dev] = ptr;
+    }
+    *out = static_scratch_ptr[dev];
+    return ALISE_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -308,7 +335,8 @@ static int decode_attn_call(const alise_kv_cache *c, const void *q, void *out,
                             const int32_t *block_tables, int32_t max_blocks_per_seq,
                             const int32_t *context_lens, int32_t B, int32_t num_q_heads,
                             int32_t max_context_len, float softmax_scale,
-                            void *workspace, size_t workspace_bytes, int32_t phases, void *hip_stream)
+                            void *workspace, size_t workspace_bytes, int32_t phases, void *hip_stream,
+                            bool use_static_scratch = false)
 {
     const bool run = (phases & alise::kPhaseRun) != 0;
     CacheView cv;
@@ -323,7 +351,7 @@ static int decode_attn_call(const alise_kv_cache *c, const void *q, void *out,
         if (!(softmax_scale == softmax_scale) || softmax_scale <= 0.0f) return ALISE_INVALID_ARGUMENT;
         if (!q || !out || !block_tables) return ALISE_INVALID_ARGUMENT;
     }
-    if (!context_lens || !workspace) return ALISE_INVALID_ARGUMENT;
+    if (!context_lens || (!workspace && !use_static_scratch)) return ALISE_INVALID_ARGUMENT;
     if (run) {
         st = check_cache_pointers(c);
         if (st != ALISE_OK) return st;
@@ -331,11 +359,19 @@ static int decode_attn_call(const alise_kv_cache *c, const void *q, void *out,
         if (reinterpret_cast<uintptr_t>(block_tables) & 3u) return ALISE_MISALIGNED;
     }
     if (reinterpret_cast<uintptr_t>(context_lens) & 3u) return ALISE_MISALIGNED;
+    if (use_static_scratch) {
+        // every host check has passed; the size is compared before the first HIP call
+        if (carve_workspace(cv, B, num_q_heads, max_context_len, nullptr, nullptr) > kStaticScratchBytes)
+            return ALISE_WORKSPACE_TOO_SMALL;
+        st = static_scratch(&workspace);
+        if (st != ALISE_OK) return st;
+        workspace_bytes = kStaticScratchBytes;
+    }
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return ALISE_MISALIGNED;
     AttnWorkspace ws;
     const size_t need = carve_workspace(cv, B, num_q_heads, max_context_len, workspace, &ws);
     if (workspace_bytes < need) return ALISE_WORKSPACE_TOO_SMALL;
-    if (debug_validate()) {
+    if (debug_validate() && !use_static_scratch) {      // the checks copy to the host: not for a caller that must not allocate
         hipStream_t hs = static_cast<hipStream_t>(hip_stream);
         if (run) {
             st = validate_lens_and_tables(cv, block_tables, max_blocks_per_seq, context_lens, B, max_context_len, nullptr, hs);
@@ -363,6 +399,15 @@ int alise_paged_decode_attn(const alise_kv_cache *c, const void *q, void *out,
 {
     return decode_attn_call(c, q, out, block_tables, max_blocks_per_seq, context_lens, B, num_q_heads, max_context_len,
                             softmax_scale, workspace, workspace_bytes, alise::kPhasePlan | alise::kPhaseRun, hip_stream);
+}
+
+int alise_paged_decode_attn_static(const alise_kv_cache *c, const void *q, void *out,
+                                   const int32_t *block_tables, int32_t max_blocks_per_seq,
+                                   const int32_t *context_lens, int32_t B, int32_t num_q_heads,
+                                   int32_t max_context_len, float softmax_scale, void *hip_stream)
+{
+    return decode_attn_call(c, q, out, block_tables, max_blocks_per_seq, context_lens, B, num_q_heads, max_context_len,
+                            softmax_scale, nullptr, 0, alise::kPhasePlan | alise::kPhaseRun, hip_stream, true);
 }
 
 int alise_paged_decode_attn_plan(const alise_kv_cache *c, const int32_t *context_lens, int32_t B, int32_t num_q_heads,

@@ -140,6 +140,24 @@ def test_attention_arguments(B, entry):
     assert lib.alise_paged_decode_attn_workspace_bytes(ctypes.byref(c), 2, 8, 1 << 16) > need
 
 
+def test_static_scratch_entry_checks_sizes_before_any_hip_call(B):
+    """The entry point without a workspace argument: same host checks, and a batch whose workspace would not fit the
+    library's static array is refused (no GPU here: a status other than these would mean a HIP call was made)."""
+    lib = B.raw()
+    c = _cache(B)
+    f = lambda c_=ctypes.byref(c), q=0x10000, out=0x20000, bt=0x30000, mb=1 << 12, lens=0x40000, B_=2, H=8, maxlen=256, \
+        scale=0.1: lib.alise_paged_decode_attn_static(c_, q, out, bt, mb, lens, B_, H, maxlen, scale, None)
+    assert f(B_=0) == 0
+    assert f(B_=-1) == 1 and f(H=0) == 1 and f(H=12) == 2 and f(q=0) == 1 and f(lens=0) == 1 and f(q=0x10008) == 4
+    assert f(mb=15) == 1 and f(scale=0.0) == 1
+    limit = B.ALISE_STATIC_SCRATCH_BYTES
+    assert limit == 32 << 20
+    # sizes whose workspace exceeds the array: refused with ALISE_WORKSPACE_TOO_SMALL
+    assert lib.alise_paged_decode_attn_workspace_bytes(ctypes.byref(c), 512, 8, 1 << 14) > limit
+    assert f(B_=512, maxlen=1 << 14) == 3
+    assert lib.alise_paged_decode_attn_workspace_bytes(ctypes.byref(c), 2, 8, 256) <= limit
+
+
 def test_attention_plan_arguments(B):
     lib = B.raw()
     c = _cache(B)
