@@ -1,10 +1,11 @@
 """Parity at the full benchmark sizes, in the launch configuration bench.py times.
 
 The whole step (quantize-and-write of the step's tokens, paged attention, page
-dequantize) runs on the device exactly as in bench.py; the oracle then recomputes
-sampled (request, KV head) pairs one by one from the same seeded inputs: codes and
-meta of every token of the pair bit for bit, the attention rows of its query heads
-within 2e-3.  Whole-output properties (finite, right shape) cover the rest.
+dequantize) runs on the device exactly as in bench.py; the oracle fills a cache of
+its own for the whole batch from the same seeded inputs and attends the whole
+batch: every written code and meta byte is compared bit for bit, every element of
+the attention output within 2e-3.  The prefill leg is compared on sampled query
+tokens (the oracle would need minutes per configuration for all of them).
 """
 import numpy as np
 import pytest
@@ -27,16 +28,37 @@ def env():
     return binding, torch, oracle, DecodeStep
 
 
-def _samples(w, lens, n_random, rng):
-    """(request, kv head) pairs: the longest and the shortest request, one per length quartile, a few random."""
-    order = np.argsort(lens, kind="stable")
-    reqs = {int(order[0]), int(order[-1])} | {int(order[int(f * (len(order) - 1))]) for f in (0.25, 0.5, 0.75)}
-    reqs |= {int(r) for r in rng.integers(0, w.B, n_random)}
-    return [(i, int(rng.integers(0, w.Hkv))) for i in sorted(reqs)]
+def _oracle_cache_of_whole_batch(oracle, st, threads=16):
+    """The oracle's own cache of the whole batch, filled from the same seeded inputs by the oracle's writer
+    (requests own disjoint pages, so they are written side by side)."""
+    from concurrent.futures import ThreadPoolExecutor
+    w, pg = st.w, st.pg
+    cache = oracle.Cache.empty(pg.num_pages, w.P, w.Hkv, w.D, w.bits, w.G)
+
+    def fill(i):
+        L = int(st.lens[i])
+        k, v = wl.request_kv(w, st.pool_host, st.offs, i, 0, L, st.gain)
+        slots = wl.slots_of(w, pg, i, 0, L)
+        for a in range(0, L, 1024):
+            oracle.kv_quant_write(cache, k[a:a + 1024], v[a:a + 1024], slots[a:a + 1024])
+
+    with ThreadPoolExecutor(threads) as ex:
+        list(ex.map(fill, range(w.B)))
+    return cache
+
+
+def _written_slots(w, pg):
+    m = np.zeros((pg.num_pages, w.P), bool)
+    for i, L in enumerate(pg.lens):
+        s = wl.slots_of(w, pg, i, 0, int(L))
+        m[s // w.P, s % w.P] = True
+    return m
 
 
 @pytest.mark.parametrize("name", ["int4", "llama7b", "gqa70b", "opt13b"])
-def test_full_size_step_sampled_against_oracle(env, name):
+def test_full_size_step_whole_output_against_oracle(env, name):
+    """Every written code and meta byte of the whole cache bit for bit, every element of the attention output
+    within 2e-3, the dequantized page bit for bit: nothing is sampled."""
     B, torch, oracle, DecodeStep = env
     w = wl.CONFIGS[name]
     print(f"case full-size {name}: B={w.B} H={w.H} Hkv={w.Hkv} bits={w.bits} G={w.G}", flush=True)
@@ -46,45 +68,43 @@ def test_full_size_step_sampled_against_oracle(env, name):
     st.step()
     torch.cuda.synchronize()
     out = st.out.cpu().numpy().astype(np.float64)
-    assert out.shape == (w.B, w.H, w.D) and np.isfinite(out).all()
+    assert out.shape == (w.B, w.H, w.D)
 
-    qper = w.H // w.Hkv
-    rng = np.random.default_rng(w.seed + 77)
+    orc = _oracle_cache_of_whole_batch(oracle, st)
+    print(f"  oracle cache filled: {int(st.lens.astype(np.int64).sum())} tokens", flush=True)
+    written = _written_slots(w, st.pg)
+    assert int(written.sum()) == int(st.lens.astype(np.int64).sum())
     cache = st.caches[0]
-    worst = 0.0
-    for i, hk in _samples(w, st.lens, 4, rng):
-        L = int(st.lens[i])
-        k, v = wl.request_kv(w, st.pool_host, st.offs, i, 0, L, st.gain)
-        nblk = (L + w.P - 1) // w.P
-        mini = oracle.Cache.empty(nblk, w.P, 1, w.D, w.bits, w.G)
-        oracle.kv_quant_write(mini, k[:, hk:hk + 1], v[:, hk:hk + 1], np.arange(L, dtype=np.int64))
-        pages = torch.from_numpy(st.pg.block_tables[i, :nblk].astype(np.int64)).cuda()
-        valid = (np.arange(nblk * w.P) < L).reshape(nblk, w.P)
-        for name_, arr in (("k_codes", mini.k_codes), ("v_codes", mini.v_codes),
-                           ("k_meta", mini.k_meta), ("v_meta", mini.v_meta)):
-            dev = getattr(cache, name_)[pages, hk].cpu().numpy()
-            ref = arr[:, 0]
-            if name_.endswith("meta"):
-                dev, ref = dev.view(np.uint16), ref.view(np.uint16)
-            assert np.array_equal(dev[valid], ref[valid]), f"{name_} of request {i} head {hk} differ"
-        bt = np.arange(nblk, dtype=np.int32)[None]
-        want = oracle.paged_decode_attn(mini, st.q_host[i:i + 1, hk * qper:(hk + 1) * qper], bt,
-                                        np.array([L], np.int32), st.scale)[0]
-        err = np.abs(out[i, hk * qper:(hk + 1) * qper] - want).max()
-        worst = max(worst, err)
-        assert err <= ATTN_TOL, f"request {i} (L={L}) kv head {hk}: max-abs {err}"
-    print(f"  worst sampled attention error {worst:.3e}", flush=True)
+    step_pages = 4096                   # compare in slabs: the arrays are gigabytes
+    for arr in ("k_codes", "v_codes", "k_meta", "v_meta"):
+        dev_t, ref = getattr(cache, arr), getattr(orc, arr)
+        compared = 0
+        for p0 in range(0, st.pg.num_pages, step_pages):
+            p1 = min(st.pg.num_pages, p0 + step_pages)
+            dev = dev_t[p0:p1].contiguous().cpu().numpy()
+            r = ref[p0:p1]
+            if arr.endswith("meta"):
+                dev, r = dev.view(np.uint16).reshape(p1 - p0, w.Hkv, w.P, -1), r.view(np.uint16).reshape(p1 - p0, w.Hkv, w.P, -1)
+            differ = (dev != r).any(axis=-1) & written[p0:p1, None, :]
+            assert not differ.any(), f"{arr}: {int(differ.sum())} written (page, head, slot) rows differ in pages {p0}..{p1}"
+            compared += int(written[p0:p1].sum()) * w.Hkv
+        assert compared == int(st.lens.astype(np.int64).sum()) * w.Hkv
+    print("  codes and meta of every written slot bit-exact", flush=True)
 
-    # the page dequantized in the step, against the oracle on the oracle's own codes of that page
-    i = int(np.argmax(st.lens))
-    L = int(st.lens[i])
-    n0 = min(L, w.P)
-    k, v = wl.request_kv(w, st.pool_host, st.offs, i, 0, n0, st.gain)
-    mini = oracle.Cache.empty(1, w.P, w.Hkv, w.D, w.bits, w.G)
-    oracle.kv_quant_write(mini, k, v, np.arange(n0, dtype=np.int64))
-    ko, vo = oracle.kv_dequant_page(mini, 0)
-    assert np.array_equal(st.dq_k.cpu().numpy().view(np.uint16)[:n0], ko.view(np.uint16)[:n0])
-    assert np.array_equal(st.dq_v.cpu().numpy().view(np.uint16)[:n0], vo.view(np.uint16)[:n0])
+    want = oracle.paged_decode_attn(orc, st.q_host, st.pg.block_tables, st.lens, st.scale, num_threads=16)
+    assert want.shape == out.shape
+    err = np.abs(out - want)                 # NaN (a row the device never wrote) fails the comparison below
+    worst = float(np.nanmax(err))
+    assert np.isfinite(out).all() and (err <= ATTN_TOL).all(), \
+        f"{int((~(err <= ATTN_TOL)).sum())} of {err.size} outputs beyond {ATTN_TOL}; worst {worst}"
+    print(f"  all {err.size} attention outputs within {ATTN_TOL}: worst {worst:.3e}", flush=True)
+
+    # the page dequantized in the step
+    ko, vo = oracle.kv_dequant_page(orc, st.dq_page)
+    rows = written[st.dq_page]
+    assert rows.any()
+    assert np.array_equal(st.dq_k.cpu().numpy().view(np.uint16)[rows], ko.view(np.uint16)[rows])
+    assert np.array_equal(st.dq_v.cpu().numpy().view(np.uint16)[rows], vo.view(np.uint16)[rows])
 
 
 @pytest.mark.parametrize("name", ["llama7b", "gqa70b", "int4"])
