@@ -544,9 +544,12 @@ def main():
         if prefill is not None:
             result["prefill"] = prefill
             result["prefill_full_batch"] = prefill_leg(w, step, every=1)      # the same with a grid that fills the chip
-            os.environ["ALISE_PREFILL_WEIGHTS"] = "single"                    # read per call by the library
+            from paper_2410_23537_amd import binding as _B
+            os.environ["ALISE_PREFILL_WEIGHTS"] = "single"                    # the library reads its environment on request
+            _B.alise_reload_environment()
             fast = prefill_leg(w, step, every=1)
             del os.environ["ALISE_PREFILL_WEIGHTS"]
+            _B.alise_reload_environment()
             fast["note"] = ("ALISE_PREFILL_WEIGHTS=single: one rounded fp16 number per softmax weight instead of a high and "
                             "a low part; adds up to 2^-12 max|v| to the error, not the default")
             result["prefill_full_batch_single_weight"] = fast

@@ -121,6 +121,17 @@ int alise_kv_quant_write(const alise_kv_cache *c, const void *k, const void *v,
 
 /*
  * Workspace the attention call needs for these sizes (0 on invalid arguments).
+ *
+ * The size is bounded by what the cache can hold, not by B * max_context_len: long requests are cut
+ * into splits of at most 2048 tokens whose partial results ((head_dim + 2) floats per query head)
+ * wait in the workspace for the merge, and a batch has at most
+ *     min(B * ceil(max_context_len / split), B + num_pages * page_size / split)
+ * of them (for batches too small to fill the chip the split is shortened, down to 256 tokens, as far
+ * as a fixed allowance of about 512 + B splits goes).  The second term assumes that the lengths of
+ * one call add up to no more than num_pages * page_size tokens, i.e. that no page is counted for two
+ * requests.  A call whose lengths exceed that (block tables that share pages between requests) and
+ * whose splits do not fit writes nothing at all -- `out` is left untouched, no memory is overrun --
+ * and ALISE_DEBUG_VALIDATE=1 reports lengths beyond the capacity as ALISE_INVALID_ARGUMENT.
  */
 size_t alise_paged_decode_attn_workspace_bytes(const alise_kv_cache *c, int32_t B,
                                                int32_t num_q_heads, int32_t max_context_len);
@@ -143,6 +154,13 @@ size_t alise_paged_decode_attn_workspace_bytes(const alise_kv_cache *c, int32_t 
  *                 that may overlap in time must use distinct workspaces.
  * out[i][h] = sum_t softmax_t(softmax_scale * q[i][h] . k^_t) v^_t over t < L_i, with
  * k^, v^ the dequantized rows; accumulated in fp32, rounded once to fp16.
+ *
+ * Value range.  Layouts with 2 to 16 query heads per KV head (head_dim 128, page_size >= 16, bits = 8
+ * with group_size 64 or 128, or bits = 4 with group_size 32, 64 or 128) run on the matrix cores, where a
+ * softmax weight times the V scale travels as a pair of fp16 numbers: V scales must stay below 256,
+ * i.e. the range max - min of a V group below 65 280 (bits = 8) or 3 840 (bits = 4) -- always true for
+ * fp16 activations of ordinary magnitude; beyond it the output saturates.  All other layouts have no
+ * such limit.  alise_paged_prefill_attn has the same limit for every layout it takes.
  */
 int alise_paged_decode_attn(const alise_kv_cache *c, const void *q, void *out,
                             const int32_t *block_tables, int32_t max_blocks_per_seq,
@@ -274,6 +292,16 @@ int alise_kv_swap_out(const alise_kv_cache *c, const int32_t *block_table, int32
 
 int alise_kv_swap_in(const alise_kv_cache *c, const int32_t *block_table, int32_t num_tokens,
                      const void *packed, size_t packed_bytes, void *hip_stream);
+
+/*
+ * The tuning variables (ALISE_SPLIT_TOKENS, ALISE_SPLIT_TOKENS_GQA, ALISE_WAVES_PER_CU,
+ * ALISE_LOADS_PER_BLOCK, ALISE_MIN_ITEMS_PER_WAVE, ALISE_XCD_SKEW, ALISE_PREFILL_ROW_TILES,
+ * ALISE_PREFILL_WEIGHTS) and ALISE_DEBUG_VALIDATE are read from the environment once per process,
+ * by the first call that needs them.  This call reads them again: for tests and tuning sweeps
+ * that change them inside one process.  It must not run while another thread is inside the
+ * library.  Workspace sizes depend on the split variables: ask for them again afterwards.
+ */
+void alise_reload_environment(void);
 
 /* Static, human-readable name of a status code. */
 const char *alise_status_string(int status);

@@ -38,7 +38,7 @@ EXPORTS = ("alise_kv_codes_bytes", "alise_kv_meta_bytes", "alise_kv_quant_write"
            "alise_add_layernorm", "alise_bias_relu", "alise_hbm_read_probe",
            "alise_sched_create", "alise_sched_destroy", "alise_sched_add_job", "alise_sched_num_jobs",
            "alise_sched_step", "alise_sched_commit",
-           "alise_status_string")
+           "alise_reload_environment", "alise_status_string")
 
 
 class alise_kv_cache(ctypes.Structure):
@@ -95,6 +95,8 @@ _lib.alise_bias_relu.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void
                                  ctypes.c_void_p]
 _lib.alise_hbm_read_probe.restype = ctypes.c_int
 _lib.alise_hbm_read_probe.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+_lib.alise_reload_environment.restype = None
+_lib.alise_reload_environment.argtypes = []
 _lib.alise_status_string.restype = ctypes.c_char_p
 _lib.alise_status_string.argtypes = [ctypes.c_int]
 
@@ -107,6 +109,11 @@ class AliseError(RuntimeError):
 
 def alise_status_string(status: int) -> str:
     return _lib.alise_status_string(int(status)).decode()
+
+
+def alise_reload_environment() -> None:
+    """Read the ALISE_* environment variables again (the library reads them once per process)."""
+    _lib.alise_reload_environment()
 
 
 def _check(status: int, where: str) -> None:

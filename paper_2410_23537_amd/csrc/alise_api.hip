@@ -5,6 +5,7 @@
 #include "alise_kernels.h"
 
 #include <algorithm>
+#include <atomic>
 #include <cstdlib>
 #include <mutex>
 #include <vector>
@@ -80,11 +81,53 @@ int check_cache_pointers(const alise_kv_cache *c)
     return ALISE_OK;
 }
 
+// The tuning environment, read once per process (alise_reload_environment reads it again).
+std::once_flag tuning_once;
+alise::Tuning tuning_values;
+
+long env_long(const char *name, long fallback)
+{
+    const char *e = std::getenv(name);
+    return (e && *e) ? std::strtol(e, nullptr, 10) : fallback;
+}
+
+void read_tuning()
+{
+    alise::Tuning t;
+    long v = env_long("ALISE_SPLIT_TOKENS", 0);
+    t.split_tokens = (v < 64 || v > (1 << 20) || (v % 64) != 0) ? 0 : (int32_t)v;
+    v = env_long("ALISE_SPLIT_TOKENS_GQA", 0);
+    t.split_tokens_gqa = (v < 64 || v > (1 << 20) || (v % 64) != 0) ? 0 : (int32_t)v;
+    v = env_long("ALISE_WAVES_PER_CU", 0);                      // a multiple of 4, at most 32; 0 = as many as fit
+    t.waves_per_cu = (v < 4 || v > 32 || (v % 4) != 0) ? 0 : (int32_t)v;
+    v = env_long("ALISE_LOADS_PER_BLOCK", 0);                   // 2, 3 or 4; 0 = the kernel's default for the bit width
+    t.loads_per_block = (v < 2 || v > 4) ? 0 : (int32_t)v;
+    v = env_long("ALISE_MIN_ITEMS_PER_WAVE", 0);                // 0 = the kernels' own defaults
+    t.min_items_per_wave = (v < 0 || v > 1024) ? 0 : (int32_t)v;
+    // Thousandths of an attention call's work that go to the waves of even workgroups only: 50 measured best on the
+    // large INT4 batch (1145 us without, 1119 us with 34, 1110 us with 50, 1112 us with 70); 0 to 200, 0 = none.
+    v = env_long("ALISE_XCD_SKEW", 50);
+    t.xcd_skew_permille = (v < 0 || v > 200) ? 50 : (int32_t)v;
+    const char *e = std::getenv("ALISE_PREFILL_ROW_TILES");     // row tiles per wave of the prefill kernels: two unless "1"
+    t.prefill_row_tiles = (e && e[0] == '1' && e[1] == 0) ? 1 : 2;
+    e = std::getenv("ALISE_PREFILL_WEIGHTS");                   // "single": one rounded fp16 number per softmax weight
+    t.prefill_split_weights = !(e && e[0] == 's' && e[1] == 'i');
+    // ALISE_DEBUG_VALIDATE=1: the calls also check what they are given in device memory (slots, lengths, block
+    // tables, chunk boundaries).  That takes a copy to the host and a wait for the stream, so it is for debugging
+    // only: without it the contents of device arrays are the caller's responsibility.
+    e = std::getenv("ALISE_DEBUG_VALIDATE");
+    t.debug_validate = e && e[0] == '1' && e[1] == 0;
+    tuning_values = t;
+}
+
 // Tokens per split.  Long requests are cut into splits of this many tokens so that
 // one long and many short requests fill the chip alike; ALISE_SPLIT_TOKENS overrides
 // the default (a multiple of 64) for tuning.
 // A split never spans more than 128 pages (64 on the matrix-core path): the attention
 // kernel keeps a split's block-table entries in two registers (one), one entry per lane.
+// A split longer than a page is therefore also a whole number of pages: the splits of a request
+// start at multiples of the split length, and one that began inside a page would touch one page
+// more than the window holds.
 // Every item costs a wave a few microseconds at its end (the reduction over its token slots,
 // the partial result), so splits are as long as that allows, up to 2048 tokens.
 // The matrix-core path hands a whole group of query heads to one wave; starting and ending
@@ -96,68 +139,22 @@ int check_cache_pointers(const alise_kv_cache *c)
 // the environment fixes the split).
 int32_t split_tokens(int32_t page_size, bool gqa, int32_t *min_split)
 {
-    const char *e = std::getenv(gqa ? "ALISE_SPLIT_TOKENS_GQA" : "ALISE_SPLIT_TOKENS");
-    long v = e ? std::strtol(e, nullptr, 10) : 0;
-    const bool fixed = !(v < 64 || v > (1 << 20) || (v % 64) != 0);
+    const alise::Tuning &t = alise::tuning();
+    long v = gqa ? t.split_tokens_gqa : t.split_tokens;
+    const bool fixed = v != 0;
     if (!fixed) v = 2048;
     const long window = gqa ? 64 : 128;         // pages whose block-table entries a wave keeps at hand
     if (v > window * page_size) v = window * page_size;
+    if (v > page_size) v -= v % page_size;      // page sizes are powers of two up to 256, v a multiple of 64: v stays a multiple of 64
     long lo = fixed ? v : 256;
     if (lo > v) lo = v;
     if (min_split) *min_split = (int32_t)lo;
     return (int32_t)v;
 }
 
-// Waves per compute unit of the persistent attention grid: 0 = as many as fit (the
-// default); ALISE_WAVES_PER_CU fixes it for tuning (a multiple of 4, at most 32).
-int32_t waves_per_cu()
-{
-    const char *e = std::getenv("ALISE_WAVES_PER_CU");
-    long v = e ? std::strtol(e, nullptr, 10) : 0;
-    if (v < 4 || v > 32 || (v % 4) != 0) v = 0;
-    return (int32_t)v;
-}
-
-// Wave-loads per block of the attention kernel (ALISE_LOADS_PER_BLOCK overrides: 2, 3 or 4).
-int32_t loads_per_block()
-{
-    const char *e = std::getenv("ALISE_LOADS_PER_BLOCK");
-    long v = e ? std::strtol(e, nullptr, 10) : 0;
-    if (v < 2 || v > 4) v = 0;      // 0: the kernel's default for the cache's bit width
-    return (int32_t)v;
-}
-
-// Items per wave below which the plan kernel shortens the splits (ALISE_MIN_ITEMS_PER_WAVE
-// overrides; 0 = the kernels' own defaults).
-int32_t min_items_per_wave()
-{
-    const char *e = std::getenv("ALISE_MIN_ITEMS_PER_WAVE");
-    long v = e ? std::strtol(e, nullptr, 10) : 0;
-    if (v < 0 || v > 1024) v = 0;
-    return (int32_t)v;
-}
-
-// Thousandths of an attention call's work that go to the waves of even workgroups only: 50 measured best on the
-// large INT4 batch (1145 us without, 1119 us with 34, 1110 us with 50, 1112 us with 70); ALISE_XCD_SKEW overrides
-// (0 to 200, 0 = none).  See the attention kernel.
-int32_t xcd_skew_permille()
-{
-    const char *e = std::getenv("ALISE_XCD_SKEW");
-    long v = e ? std::strtol(e, nullptr, 10) : 50;
-    if (v < 0 || v > 200) v = 50;
-    return (int32_t)v;
-}
-
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-// ALISE_DEBUG_VALIDATE=1: the calls also check what they are given in device memory (slots, lengths, block
-// tables, chunk boundaries).  That takes a copy to the host and a wait for the stream, so it is for debugging
-// only: without it the contents of device arrays are the caller's responsibility.
-bool debug_validate()
-{
-    const char *e = std::getenv("ALISE_DEBUG_VALIDATE");
-    return e && e[0] == '1' && e[1] == 0;
-}
+bool debug_validate() { return alise::tuning().debug_validate; }
 
 template <class T>
 int fetch_to_host(std::vector<T> &host, const T *dev, size_t n, hipStream_t s)
@@ -177,8 +174,11 @@ int validate_lens_and_tables(const CacheView &cv, const int32_t *block_tables, i
     if (st != ALISE_OK) return st;
     st = fetch_to_host(bt, block_tables, (size_t)B * max_blocks, s);
     if (st != ALISE_OK) return st;
+    int64_t sum = 0;
     for (int32_t i = 0; i < B; ++i) {
         if (lens[i] < 0 || lens[i] > max_len) return ALISE_INVALID_ARGUMENT;
+        sum += lens[i];
+        if (sum > (int64_t)cv.num_pages * cv.P) return ALISE_INVALID_ARGUMENT;     // more tokens than the cache holds: the workspace is not sized for that
         const int64_t nblk = ((int64_t)lens[i] + cv.P - 1) / cv.P;
         if (nblk > max_blocks) return ALISE_INVALID_ARGUMENT;
         for (int64_t b = 0; b < nblk; ++b) {
@@ -190,6 +190,29 @@ int validate_lens_and_tables(const CacheView &cv, const int32_t *block_tables, i
     return ALISE_OK;
 }
 
+// How many tiles (request, token range of one split) a call can produce, which sizes the work order and the
+// split buffers.  With splits of C tokens a batch has at most B * ceil(max_len / C) tiles, and no more than
+// B + capacity / C, capacity = num_pages * page_size being all the tokens the cache can hold (every request adds
+// at most one partial tile to the full ones).  The plan kernel starts from the largest split and halves it only
+// for small batches -- while the tiles of the batch would give a full grid fewer than `min_items` work items --
+// and never beyond what this bound holds (it checks), so the bound is taken at the largest split and widened to
+// the most tiles such a small batch can end with, twice min_items' worth plus one per request; it never exceeds
+// the bound at the smallest split.
+int64_t max_tiles_of(const CacheView &c, int32_t B, int32_t H, int32_t max_len)
+{
+    const bool gqa = alise::gqa_mfma_applies(c, H);
+    int32_t C_min = 0;
+    const int32_t C = split_tokens(c.P, gqa, &C_min);
+    const int64_t capacity = (int64_t)c.num_pages * c.P;
+    auto bound = [&](int64_t split) {
+        const int64_t per_req = ((int64_t)max_len + split - 1) / split;
+        return std::min((int64_t)B * std::max<int64_t>(per_req, 1), (int64_t)B + capacity / split);
+    };
+    const int64_t items_per_tile = gqa ? c.Hkv : H;
+    const int64_t small = (int64_t)B + (2 * alise::plan_min_items(256, gqa) + items_per_tile - 1) / items_per_tile;
+    return std::max<int64_t>(1, std::min(bound(C_min), std::max(bound(C), small)));
+}
+
 // Workspace layout: [n_items, n_merge | tile_base[B+1] | req_full_base[B] | merge_req[B] |
 // order[max_tiles] | part].
 size_t carve_workspace(const CacheView &c, int32_t B, int32_t H, int32_t max_len, void *base,
@@ -197,8 +220,7 @@ size_t carve_workspace(const CacheView &c, int32_t B, int32_t H, int32_t max_len
 {
     int32_t C_min = 0;
     const int32_t C = split_tokens(c.P, alise::gqa_mfma_applies(c, H), &C_min);
-    const int64_t splits = ((int64_t)max_len + C_min - 1) / C_min;
-    const int64_t max_tiles = (int64_t)B * (splits > 0 ? splits : 1);
+    const int64_t max_tiles = max_tiles_of(c, B, H, max_len);
     size_t off = 256;       // header: n_items, n_merge
     const size_t off_base = off;
     off = align_up(off + sizeof(int32_t) * ((size_t)B + 1), 256);
@@ -218,7 +240,7 @@ size_t carve_workspace(const CacheView &c, int32_t B, int32_t H, int32_t max_len
         ws->merge_req = reinterpret_cast<int32_t *>(b + off_rb);
         ws->n_merge = reinterpret_cast<int32_t *>(b + 4);
         ws->n_shared = reinterpret_cast<int32_t *>(b + 8);
-        ws->skew_permille = xcd_skew_permille();
+        ws->skew_permille = alise::tuning().xcd_skew_permille;
         ws->order = reinterpret_cast<int4 *>(b + off_order);
         ws->part = reinterpret_cast<float *>(b + off_part);
         ws->max_tiles = (int32_t)max_tiles;
@@ -233,24 +255,22 @@ int check_attn_sizes(const CacheView &c, int32_t B, int32_t H, int32_t max_len)
 {
     if (B < 0 || H <= 0 || max_len < 0) return ALISE_INVALID_ARGUMENT;
     if (H % c.Hkv != 0) return ALISE_UNSUPPORTED;
-    int32_t C_min = 0;
-    (void)split_tokens(c.P, alise::gqa_mfma_applies(c, H), &C_min);
-    const int64_t splits = ((int64_t)max_len + C_min - 1) / C_min;
-    if ((int64_t)B * (splits > 0 ? splits : 1) * H >= (int64_t)1 << 31) return ALISE_UNSUPPORTED;
+    if (max_tiles_of(c, B, H, max_len) * H >= (int64_t)1 << 31) return ALISE_UNSUPPORTED;
     return ALISE_OK;
 }
 
+// Compute units of the current device, asked once per device (a race between two first calls writes the same value twice).
 int num_compute_units()
 {
-    static int cached[64] = {0};
+    static std::atomic<int> cached[64];
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    if (cached[dev] == 0) {
-        int n = 0;
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-        cached[dev] = n;
+        cached[dev].store(n, std::memory_order_relaxed);
     }
-    return cached[dev];
+    return n;
 }
 
 constexpr int kMaxDevices = 64;
@@ -274,7 +294,23 @@ int static_scratch(void **out)
 
 }  // namespace
 
+namespace alise {
+
+const Tuning &tuning()
+{
+    std::call_once(tuning_once, read_tuning);
+    return tuning_values;
+}
+
+}  // namespace alise
+
 extern "C" {
+
+void alise_reload_environment(void)
+{
+    std::call_once(tuning_once, read_tuning);       // so that a later first use does not overwrite what is read now
+    read_tuning();
+}
 
 size_t alise_kv_codes_bytes(const alise_kv_cache *c)
 {
@@ -380,13 +416,18 @@ static int decode_attn_call(const alise_kv_cache *c, const void *q, void *out,
             std::vector<int32_t> lens;
             st = fetch_to_host(lens, context_lens, (size_t)B, hs);
             if (st != ALISE_OK) return st;
-            for (int32_t L : lens)
+            int64_t sum = 0;
+            for (int32_t L : lens) {
                 if (L < 0 || L > max_context_len) return ALISE_INVALID_ARGUMENT;
+                sum += L;
+            }
+            if (sum > (int64_t)cv.num_pages * cv.P) return ALISE_INVALID_ARGUMENT;
         }
     }
     hipError_t e = alise::launch_decode_attn(cv, q, out, block_tables, max_blocks_per_seq, context_lens, B,
                                              num_q_heads, max_context_len, softmax_scale, ws,
-                                             num_compute_units(), waves_per_cu(), loads_per_block(), min_items_per_wave(),
+                                             num_compute_units(), alise::tuning().waves_per_cu, alise::tuning().loads_per_block,
+                                             alise::tuning().min_items_per_wave,
                                              phases, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? ALISE_OK : ALISE_HIP_ERROR;
 }

@@ -31,6 +31,26 @@ struct AttnWorkspace {
     int32_t skew_permille;  // share of the work (its shortest items) that goes to the favoured waves only
 };
 
+// The tuning environment (ALISE_* variables), read once per process by the C-ABI layer.
+struct Tuning {
+    int32_t split_tokens = 0, split_tokens_gqa = 0;     // 0: chosen from the batch
+    int32_t waves_per_cu = 0, loads_per_block = 0, min_items_per_wave = 0;
+    int32_t xcd_skew_permille = 50;
+    int32_t prefill_row_tiles = 2;
+    bool prefill_split_weights = true;
+    bool debug_validate = false;
+};
+const Tuning &tuning();
+
+// Work items below which the plan kernel shortens the splits: every wave of a full grid (about eight waves per
+// compute unit) should get ALISE_MIN_ITEMS_PER_WAVE items, by default four, or one on the matrix-core path, whose
+// items are heavier to start.
+inline int32_t plan_min_items(int32_t num_cus, bool gqa)
+{
+    const int32_t per_wave = tuning().min_items_per_wave;
+    return num_cus * 8 * (per_wave > 0 ? per_wave : (gqa ? 1 : 4));
+}
+
 // True when the attention call takes the matrix-core path for grouped-query layouts
 // (its tiles are shorter, so the workspace is carved differently).
 bool gqa_mfma_applies(const CacheView &c, int32_t H);

@@ -30,6 +30,8 @@
 // which the mixed-precision FMA multiplies by the fp32 weight exactly.
 #include "attn_common.h"
 
+#include <atomic>
+
 namespace alise {
 namespace {
 
@@ -133,7 +135,11 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t *context_lens,
         int sa, sb, total64, total_req;
         block_scan2_1024((int)((sum + 63) >> 6), nonempty, s_wave, sa, sb, total64, total_req);
         const int64_t tokens = (int64_t)total64 << 6;
-        while (C > ws.min_chunk_tokens && (tokens / C + total_req) * items_per_tile < ws.min_items) C >>= 1;
+        // ... and only while the tiles of the shorter split (at most tokens / split + one per request) fit the work
+        // order and the split buffers, which are sized for the largest split and for small batches
+        while (C > ws.min_chunk_tokens && (tokens / C + total_req) * items_per_tile < ws.min_items &&
+               tokens / (C >> 1) + total_req <= ws.max_tiles)
+            C >>= 1;
     }
     int total = 0, total_full = 0;
     for (int base = 0; base < B; base += 1024) {
@@ -183,7 +189,10 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t *context_lens,
         if (many_items && my_count > 0 && with_shorter <= share) atomicMin(&s_first_extra, total_full + incl - my_count);
         __syncthreads();
     }
-    for (int i = tid; i < B; i += 1024) {
+    // The buffers hold max_tiles tiles: enough for every batch whose lengths add up to no more than the cache's
+    // capacity.  A batch beyond that (requests that share pages) gets no work at all rather than writes past the end.
+    const bool fits = total <= ws.max_tiles;
+    for (int i = tid; fits && i < B; i += 1024) {
         int L = context_lens[i];
         L = L < 0 ? 0 : (L > max_len ? max_len : L);
         const int nfull = L / C;
@@ -200,9 +209,9 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t *context_lens,
     }
     if (tid == 0) {
         ws.tile_base[B] = total;
-        *ws.n_items = total * items_per_tile;
-        *ws.n_shared = s_first_extra * items_per_tile;
-        *ws.n_merge = s_merge;
+        *ws.n_items = fits ? total * items_per_tile : 0;
+        *ws.n_shared = fits ? s_first_extra * items_per_tile : 0;
+        *ws.n_merge = fits ? s_merge : 0;
     }
 }
 
@@ -734,14 +743,16 @@ hipError_t launch_t(const AttnParams &p, int32_t num_cus, int32_t waves_per_cu, 
     const bool uniform_page = p.c.P >= Geo<BITS, D>::TPW;
     // The grid is persistent: as many workgroups as the kernel's registers and LDS let the
     // chip hold at once (asked once per kernel variant), unless the caller fixes the number.
-    static int resident_wgs_per_cu[2] = {0, 0};
-    int &occ = resident_wgs_per_cu[uniform_page ? 1 : 0];
+    // (two threads that ask at the same time store the same number)
+    static std::atomic<int> resident_wgs_per_cu[2];
+    int occ = resident_wgs_per_cu[uniform_page ? 1 : 0].load(std::memory_order_relaxed);
     if (occ == 0) {
         int n = 0;
         hipError_t oe = uniform_page
             ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, decode_attn_kernel<BITS, D, true, NB>, 256, 0)
             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, decode_attn_kernel<BITS, D, false, NB>, 256, 0);
         occ = (oe == hipSuccess && n > 0) ? n : 2;
+        resident_wgs_per_cu[uniform_page ? 1 : 0].store(occ, std::memory_order_relaxed);
     }
     // three workgroups (twelve waves) per compute unit saturate the memory system; a fourth one, where the registers
     // allow it (INT8), only spreads the same work over more lists (llama7b: 307 us with three, 313 us with four)
@@ -794,7 +805,8 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
     // the plan kernel shortens the splits until every wave of a full grid (about eight waves
     // per compute unit) would get this many items; the matrix-core kernel, whose items are
     // heavier to start, asks for one
-    p.ws.min_items = num_cus * 8 * (min_items_per_wave > 0 ? min_items_per_wave : (gqa ? 1 : 4));
+    (void)min_items_per_wave;
+    p.ws.min_items = plan_min_items(num_cus, gqa);
     p.zero_empty = (phases & kPhasePlan) ? 0 : 1;
     hipError_t e = hipSuccess;
     if (phases & kPhasePlan) {

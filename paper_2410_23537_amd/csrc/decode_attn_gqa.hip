@@ -40,6 +40,7 @@
 // Softmax state (running maximum, denominator, weighted zero-points) lives in the lanes of
 // the S^T layout and is brought to the rows of O only at the end of a tile.
 #include "mfma_stream.h"
+#include <atomic>
 #include <type_traits>
 
 namespace alise {
@@ -601,11 +602,14 @@ template <int BITS, int NGRP, int QROWS, int S>
 hipError_t launch_gqa_t(const AttnParams &p, int32_t num_cus, int32_t waves_per_cu, hipStream_t s)
 {
     // one wave per workgroup; as many as the LDS lets a compute unit hold, unless the caller fixes the number
-    static int occ = 0;
+    // (asked once per kernel variant; two threads that ask at the same time store the same number)
+    static std::atomic<int> resident{0};
+    int occ = resident.load(std::memory_order_relaxed);
     if (occ == 0) {
         int n = 0;
         hipError_t oe = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, decode_attn_gqa_kernel<BITS, NGRP, QROWS, S>, 64, 0);
         occ = (oe == hipSuccess && n > 0) ? n : 4;
+        resident.store(occ, std::memory_order_relaxed);
     }
     int waves = num_cus * (waves_per_cu > 0 ? waves_per_cu : occ);
     const int64_t max_items = (int64_t)p.ws.max_tiles * p.c.Hkv;

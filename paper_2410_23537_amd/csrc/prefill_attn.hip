@@ -641,19 +641,11 @@ bool prefill_mfma_applies(const CacheView &c, int32_t H)
 int32_t prefill_tokens_per_workgroup(int32_t qper, int32_t row_tiles) { return 4 * (16 * row_tiles / qper); }
 
 // Row tiles per wave: two, unless ALISE_PREFILL_ROW_TILES=1 (for tuning).
-static int32_t prefill_row_tiles()
-{
-    const char *e = std::getenv("ALISE_PREFILL_ROW_TILES");
-    return (e && e[0] == '1' && e[1] == 0) ? 1 : 2;
-}
+static int32_t prefill_row_tiles() { return tuning().prefill_row_tiles; }
 
 // ALISE_PREFILL_WEIGHTS=single: one rounded fp16 number per weight instead of a high and a low part
 // (faster; adds up to 2^-12 max|v| to the error of a row that a few tokens dominate).
-static bool prefill_split_weights()
-{
-    const char *e = std::getenv("ALISE_PREFILL_WEIGHTS");
-    return !(e && e[0] == 's' && e[1] == 'i');
-}
+static bool prefill_split_weights() { return tuning().prefill_split_weights; }
 
 hipError_t launch_prefill_attn(const CacheView &c, const void *q, void *out, const int32_t *q_start,
                                const int32_t *block_tables, int32_t max_blocks, const int32_t *context_lens,

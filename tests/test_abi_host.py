@@ -135,9 +135,44 @@ def test_attention_arguments(B, entry):
     assert need > 0 and need % 256 == 0
     assert call(wsb=need - 1) == 3
     assert lib.alise_paged_decode_attn_workspace_bytes(ctypes.byref(c), 2, 12, 256) == 0
-    # the workspace grows with the batch and with the longest context
+    # the workspace grows with the batch; with the longest context only as far as the cache's capacity allows
     assert lib.alise_paged_decode_attn_workspace_bytes(ctypes.byref(c), 64, 8, 256) > need
-    assert lib.alise_paged_decode_attn_workspace_bytes(ctypes.byref(c), 2, 8, 1 << 16) > need
+    assert lib.alise_paged_decode_attn_workspace_bytes(ctypes.byref(c), 2, 8, 1 << 16) >= need
+
+
+def _workspace_model(num_pages, P, Hkv, H, D, B_, max_len, gqa):
+    """The documented size of the attention workspace, restated: tiles = min(B ceil(max_len / split),
+    B + capacity / split) at the largest split (2048 tokens, at most 128 pages, 64 on the matrix-core path), at least
+    the small-batch allowance B + 2 * min_items / items_per_tile, never more than the same bound at 256 tokens."""
+    up = lambda v: (v + 255) // 256 * 256
+    C = min(2048, (64 if gqa else 128) * P)
+    C_min = min(256, C)
+    cap = num_pages * P
+    bound = lambda c: min(B_ * max(1, -(-max_len // c)), B_ + cap // c)
+    ipt = Hkv if gqa else H
+    small = B_ + -(-2 * 256 * 8 * (1 if gqa else 4) // ipt)
+    tiles = max(1, min(bound(C_min), max(bound(C), small)))
+    return 256 + up(4 * (B_ + 1)) + 2 * up(4 * B_) + up(16 * tiles) + up(4 * tiles * H * (D + 2))
+
+
+def test_attention_workspace_is_bounded_by_the_cache_capacity(B):
+    lib = B.raw()
+    size = lambda c, B_, H, L: lib.alise_paged_decode_attn_workspace_bytes(ctypes.byref(c), B_, H, L)
+    # the INT4 stress configuration: 512 requests of up to 16384 tokens in a cache of 1.4 M tokens
+    c5 = _cache(B, num_pages=87100, page_size=16, num_kv_heads=32, head_dim=128, bits=4, group_size=32)
+    n5 = size(c5, 512, 32, 16384)
+    assert n5 == _workspace_model(87100, 16, 32, 32, 128, 512, 16384, False)
+    assert n5 < 25 << 20                             # 546 MB when it was sized by B * max_context_len
+    # the grouped-query configuration (matrix-core path: items are KV heads)
+    c4 = _cache(B, num_pages=16100, page_size=32, num_kv_heads=8, head_dim=128, bits=8, group_size=128)
+    assert size(c4, 128, 64, 8192) == _workspace_model(16100, 32, 8, 64, 128, 128, 8192, True)
+    # B = 512 at 128 K context in a cache that holds 2 M tokens: bounded by the capacity, not by 4.4 GB
+    cl = _cache(B, num_pages=1 << 17, page_size=16, num_kv_heads=32, head_dim=128, bits=4, group_size=32)
+    assert size(cl, 512, 32, 1 << 17) == _workspace_model(1 << 17, 16, 32, 32, 128, 512, 1 << 17, False) < 64 << 20
+    # small caches and short contexts: B * ceil(max_len / split) is the smaller term
+    c = _cache(B)
+    assert size(c, 2, 8, 256) == _workspace_model(10, 16, 8, 8, 128, 2, 256, False)
+    assert size(c, 2, 8, 100) == _workspace_model(10, 16, 8, 8, 128, 2, 100, False)
 
 
 def test_static_scratch_entry_checks_sizes_before_any_hip_call(B):
@@ -153,8 +188,9 @@ def test_static_scratch_entry_checks_sizes_before_any_hip_call(B):
     limit = B.ALISE_STATIC_SCRATCH_BYTES
     assert limit == 32 << 20
     # sizes whose workspace exceeds the array: refused with ALISE_WORKSPACE_TOO_SMALL
-    assert lib.alise_paged_decode_attn_workspace_bytes(ctypes.byref(c), 512, 8, 1 << 14) > limit
-    assert f(B_=512, maxlen=1 << 14) == 3
+    big = _cache(B, num_pages=1 << 20, num_kv_heads=8)
+    assert lib.alise_paged_decode_attn_workspace_bytes(ctypes.byref(big), 4096, 64, 1 << 14) > limit
+    assert f(c_=ctypes.byref(big), B_=4096, H=64, maxlen=1 << 14) == 3
     assert lib.alise_paged_decode_attn_workspace_bytes(ctypes.byref(c), 2, 8, 256) <= limit
 
 

@@ -23,7 +23,20 @@ def _refused(B, call):
     assert e.value.status == B.ALISE_INVALID_ARGUMENT
 
 
-def test_device_contents_are_checked_on_request(env, monkeypatch):
+@pytest.fixture
+def validating(env, monkeypatch):
+    """Switches the checks on for one test (the library reads its environment when asked to) and off again."""
+    B, _ = env
+
+    def on():
+        monkeypatch.setenv("ALISE_DEBUG_VALIDATE", "1")
+        B.alise_reload_environment()
+    yield on
+    monkeypatch.delenv("ALISE_DEBUG_VALIDATE", raising=False)
+    B.alise_reload_environment()
+
+
+def test_device_contents_are_checked_on_request(env, validating):
     B, torch = env
     Hkv, H, D, P, num_pages = 2, 2, 128, 16, 12
     cache = B.KVCache.allocate(num_pages, P, Hkv, D, 8, 64, fill=0)
@@ -45,7 +58,16 @@ def test_device_contents_are_checked_on_request(env, monkeypatch):
     B.alise_paged_decode_attn(cache, q, ref, dev(bt), dev(lens), 48, scale, ws)
     torch.cuda.synchronize()
 
-    monkeypatch.setenv("ALISE_DEBUG_VALIDATE", "1")
+    validating()
+    # ---- first show that the checks are on, with inputs that would be harmless if they were launched: a length
+    # beyond the declared maximum (the kernels clamp it) and one slot used twice (the second write wins).  If these
+    # are not refused the test ends here, before any out-of-range index is handed to a kernel.
+    canary = torch.full(q.shape, float("nan"), dtype=torch.float16, device="cuda")
+    _refused(B, lambda: B.alise_paged_decode_attn(cache, q, canary, dev(bt), dev(np.array([20, 49], np.int32)), 48, scale, ws))
+    twice = good_slots.copy(); twice[30] = twice[2]
+    _refused(B, lambda: B.alise_kv_quant_write(cache, k, v, dev(twice)))
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(canary).all())                                 # nothing was launched
     # ---- write
     B.alise_kv_quant_write(cache, k, v, dev(good_slots))                    # valid: passes
     skipped = good_slots.copy(); skipped[3] = -1; skipped[7] = -9           # negative slots are skipped tokens, any number of them
@@ -91,3 +113,42 @@ def test_device_contents_are_checked_on_request(env, monkeypatch):
     _refused(B, lambda: B.alise_kv_swap_out(cache, dev(np.array([0, num_pages], np.int32)), 20, buf))
     _refused(B, lambda: B.alise_kv_swap_in(cache, dev(np.array([8, 8], np.int32)), 20, buf))
     torch.cuda.synchronize()
+
+
+def test_lengths_beyond_the_cache_capacity(env, validating):
+    """The attention workspace is sized by what the cache can hold.  Ten requests that share all 130 pages of a
+    cache (20 800 tokens against a capacity of 2 080) would need more split buffers than that: the call must
+    not overrun anything -- it writes nothing at all -- and with the checks on it is refused.  Two requests that
+    share the pages stay within the bound and are attended to as usual."""
+    B, torch = env
+    Hkv, H, D, P, num_pages = 2, 2, 128, 16, 130
+    cache = B.KVCache.allocate(num_pages, P, Hkv, D, 8, 128, fill=0)
+    rng = np.random.default_rng(11)
+    T = num_pages * P
+    k = torch.from_numpy(rng.standard_normal((T, Hkv, D)).astype(np.float16)).cuda()
+    v = torch.from_numpy(rng.standard_normal((T, Hkv, D)).astype(np.float16)).cuda()
+    B.alise_kv_quant_write(cache, k, v, torch.arange(T, dtype=torch.int64, device="cuda"))
+    scale = 1.0 / np.sqrt(D)
+
+    def run(n_req):
+        q = torch.from_numpy(np.repeat(rng.standard_normal((1, H, D)).astype(np.float16), n_req, axis=0)).cuda()
+        out = torch.full(q.shape, float("nan"), dtype=torch.float16, device="cuda")
+        bt = torch.arange(num_pages, dtype=torch.int32, device="cuda").repeat(n_req, 1).contiguous()
+        lens = torch.full((n_req,), T, dtype=torch.int32, device="cuda")
+        ws = torch.full((B.alise_paged_decode_attn_workspace_bytes(cache, n_req, H, T),), 0xA5, dtype=torch.uint8, device="cuda")
+        guard = torch.full((1 << 20,), 0x5A, dtype=torch.uint8, device="cuda")     # whatever follows the workspace in memory
+        B.alise_paged_decode_attn(cache, q, out, bt, lens, T, scale, ws)
+        torch.cuda.synchronize()
+        assert bool((guard == 0x5A).all())
+        return out
+
+    print("case capacity two requests share the pages", flush=True)
+    out2 = run(2)
+    assert bool(torch.isfinite(out2).all()) and torch.equal(out2[0], out2[1])
+    print("case capacity ten requests share the pages", flush=True)
+    out10 = run(10)
+    assert bool(torch.isnan(out10).all())           # no work was planned, nothing was written
+    validating()
+    with pytest.raises(B.AliseError) as e:
+        run(10)
+    assert e.value.status == B.ALISE_INVALID_ARGUMENT

@@ -1,4 +1,4 @@
-"""Every kernel variant that a tuning knob can select (environment variables read per call) must
+"""Every kernel variant that a tuning knob can select (environment variables, read again on request) must
 compute the same attention (ALISE Sec. 2, Eq. 1-2 over the cache of Sec. 3.2): stage counts and
 wave-loads per block, waves per compute unit, split lengths, the floor of items per wave, and
 the one-row-tile and the single-weight prefill kernels.  Each setting is run on small batches of the four layouts
@@ -64,19 +64,27 @@ def problems(env):
 
 
 @pytest.fixture(autouse=True)
-def clean_environment():
+def clean_environment(env):
     saved = {k: os.environ.pop(k, None) for k in KNOBS}
+    env[0].alise_reload_environment()
     yield
     for k in KNOBS:
         os.environ.pop(k, None)
         if saved[k] is not None:
             os.environ[k] = saved[k]
+    env[0].alise_reload_environment()
+
+
+def _set(B, setting):
+    """The library reads its environment once per process: change it, then have it read again."""
+    os.environ.update(setting)
+    B.alise_reload_environment()
 
 
 @pytest.mark.parametrize("setting", SETTINGS, ids=lambda s: ",".join(f"{k[6:].lower()}={v}" for k, v in s.items()))
 def test_decode_under_every_knob(env, problems, setting):
     B, torch, oracle = env
-    os.environ.update(setting)
+    _set(B, setting)
     for name, (w, pg, orc, dev, q, want) in problems.items():
         print(f"case knobs {setting} {name}", flush=True)
         got = harness.run_device_attn(B, torch, w, dev, q, pg).astype(np.float64)
@@ -88,8 +96,7 @@ def test_decode_under_every_knob(env, problems, setting):
 @pytest.mark.parametrize("tiles", ["1", "2"])
 def test_prefill_with_one_and_two_row_tiles(env, problems, tiles, weights):
     B, torch, oracle = env
-    os.environ["ALISE_PREFILL_ROW_TILES"] = tiles
-    os.environ["ALISE_PREFILL_WEIGHTS"] = weights
+    _set(B, {"ALISE_PREFILL_ROW_TILES": tiles, "ALISE_PREFILL_WEIGHTS": weights})
     for name, (w, pg, orc, dev, q, _) in problems.items():
         print(f"case knobs prefill row tiles {tiles} {name}", flush=True)
         lens = pg.lens.astype(np.int64)
@@ -116,10 +123,8 @@ def test_more_than_64_splits_of_one_request(env, bits, G, Hkv, H):
     """A request of 20 000 tokens in splits of 256: 79 partial results, more than the 64 that the merge
     kernel combines in one pass of a wave, beside short requests that need no merge at all."""
     B, torch, oracle = env
-    saved = {k: os.environ.pop(k, None) for k in KNOBS}
-    os.environ["ALISE_SPLIT_TOKENS"] = "256"
-    os.environ["ALISE_SPLIT_TOKENS_GQA"] = "256"
-    try:
+    _set(B, {"ALISE_SPLIT_TOKENS": "256", "ALISE_SPLIT_TOKENS_GQA": "256"})
+    if True:
         lens = np.array([20000, 3, 700, 0, 257], np.int32)
         w = wl.Workload("many_splits", B=len(lens), H=H, Hkv=Hkv, D=128, P=16, bits=bits, G=G, length_law="fixed:1", seed=9,
                         max_len=int(lens.max()))
@@ -134,11 +139,6 @@ def test_more_than_64_splits_of_one_request(env, bits, G, Hkv, H):
         got = harness.run_device_attn(B, torch, w, dev, q, pg).astype(np.float64)
         err = float(np.abs(got - want).max())
         assert np.isfinite(got).all() and err <= ATTN_TOL, f"{err:.3e}"
-    finally:
-        for k in KNOBS:
-            os.environ.pop(k, None)
-            if saved[k] is not None:
-                os.environ[k] = saved[k]
 
 
 @pytest.mark.parametrize("skew", ["0", "50", "200"])
@@ -148,9 +148,8 @@ def test_short_items_dealt_to_half_of_the_waves(env, skew):
     one (6 700 items and more against a threshold of 6 144).  Every (request, head) must still be attended to
     exactly once: compared with the oracle."""
     B, torch, oracle = env
-    saved = {k: os.environ.pop(k, None) for k in KNOBS}
-    os.environ.update({"ALISE_XCD_SKEW": skew, "ALISE_MIN_ITEMS_PER_WAVE": "1", "ALISE_SPLIT_TOKENS": "256"})
-    try:
+    _set(B, {"ALISE_XCD_SKEW": skew, "ALISE_MIN_ITEMS_PER_WAVE": "1", "ALISE_SPLIT_TOKENS": "256"})
+    if True:
         rng = np.random.default_rng(31)
         lens = rng.integers(0, 600, 420).astype(np.int32)
         lens[:5] = [0, 1, 256, 257, 3000]
@@ -166,8 +165,27 @@ def test_short_items_dealt_to_half_of_the_waves(env, skew):
         got = harness.run_device_attn(B, torch, w, dev, q, pg).astype(np.float64)
         err = float(np.abs(got - want).max())
         assert np.isfinite(got).all() and not got[lens == 0].any() and err <= ATTN_TOL, f"{err:.3e}"
-    finally:
-        for k in KNOBS:
-            os.environ.pop(k, None)
-            if saved[k] is not None:
-                os.environ[k] = saved[k]
+
+
+@pytest.mark.parametrize("Hkv,H,split", [(2, 2, "320"), (2, 2, "32704"), (1, 8, "320"), (1, 8, "16320")])
+def test_fixed_split_that_is_no_multiple_of_the_page(env, Hkv, H, split):
+    """Pages of 256 tokens and a fixed split that is a multiple of 64 but not of the page: the splits of a request
+    start at multiples of the split, so such a split would begin inside a page and reach one page more than the
+    kernels' page window holds.  The library rounds it down to whole pages; requests of several splits must come
+    out right on the vector path and on the matrix-core path."""
+    B, torch, oracle = env
+    _set(B, {"ALISE_SPLIT_TOKENS": split, "ALISE_SPLIT_TOKENS_GQA": split})
+    lens = np.array([70000 if int(split) > 4096 else 1000, 3, 700, 257, 256], np.int32)
+    w = wl.Workload("page256", B=len(lens), H=H, Hkv=Hkv, D=128, P=256, bits=8, G=128, length_law="fixed:1", seed=23,
+                    max_len=int(lens.max()))
+    print(f"case knobs page 256 split {split} H={H}", flush=True)
+    pg = wl.paging(w, lens)
+    pool = wl.value_pool(w, n_min=int(lens.max()) * Hkv * 128)
+    offs, gain = wl.request_offsets(w), wl.k_channel_gain(w)
+    orc = harness.fill_oracle_cache(oracle, w, pg, pool, offs, gain)
+    dev = harness.fill_device_cache(B, torch, w, pg, pool, offs, gain)
+    q = wl.queries(w)
+    want = oracle.paged_decode_attn(orc, q, pg.block_tables, pg.lens, 1.0 / np.sqrt(w.D), num_threads=8)
+    got = harness.run_device_attn(B, torch, w, dev, q, pg).astype(np.float64)
+    err = float(np.abs(got - want).max())
+    assert np.isfinite(got).all() and err <= ATTN_TOL, f"{err:.3e}"

@@ -36,10 +36,19 @@ def test_worked_examples(oracle_mod, row):
     assert sh == scale_hex
     assert zh == int(np.float16(zero).view(np.uint16))
     assert list(c) == codes
+    # the same group through the oracle's writer and its page dequantizer: one KV head whose vector is this group,
+    # written to the second slot of a two-slot page (K carries the group, V its mirror image, so a mix-up shows)
+    n = len(xs)
+    cache = oracle_mod.Cache.empty(1, 2, 1, n, bits, n, fill=0xEE)
+    oracle_mod.kv_quant_write(cache, x.reshape(1, 1, n), x[::-1].reshape(1, 1, n), np.array([1], np.int64))
+    assert cache.k_meta[0, 0, 1, 0].view(np.uint16).tolist() == [scale_hex, int(np.float16(zero).view(np.uint16))]
+    stored = cache.k_codes[0, 0, 1]
+    unpacked = stored if bits == 8 else np.stack([stored & 15, stored >> 4], axis=-1).reshape(-1)
+    assert list(unpacked) == codes
     if dq is not None:
-        lam = float(np.uint16(sh).view(np.float16))
-        xhat = (np.float32(lam) * (c.astype(np.float32) - np.float32(zero))).astype(np.float16)
-        assert [int(v) for v in xhat.view(np.uint16)] == dq
+        kd, vd = oracle_mod.kv_dequant_page(cache, 0)
+        assert [int(v) for v in kd[1, 0].view(np.uint16)] == dq          # the hand-derived column, not a restatement
+        assert [int(v) for v in vd[1, 0].view(np.uint16)] == dq[::-1]
 
 
 # ---------------------------------------------------------------------------

@@ -77,7 +77,7 @@ def test_static_workspace_refuses_what_does_not_fit(env):
     """A batch whose workspace is larger than the static array: a clear status, nothing launched, output untouched."""
     B, torch, _ = env
     print("case no_alloc oversize", flush=True)
-    w = wl.replace(wl.scaled(wl.CONFIGS["int4"], B=512, max_len=16384, name="big"))
+    w = wl.replace(wl.scaled(wl.CONFIGS["gqa70b"], B=4096, max_len=16384, name="big"))
     cache = B.KVCache.allocate(4, w.P, w.Hkv, w.D, w.bits, w.G, fill=0)
     assert B.alise_paged_decode_attn_workspace_bytes(cache, w.B, w.H, 16384) > B.ALISE_STATIC_SCRATCH_BYTES
     q = torch.zeros((w.B, w.H, w.D), dtype=torch.float16, device="cuda")
