@@ -23,9 +23,40 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published peak HBM3E bandwidth
 
-# HBM bytes per attention launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a
-# copy kernel of known size; see profiles/.  None where not measured.
-MEASURED_TRAFFIC_BYTES = {"int4": 7191341611, "gqa70b": 1103144722, "llama7b": 1989225454, "opt13b": 414454493}
+PROFILES = os.path.join(ROOT, "profiles")
+# sources whose change makes a stored traffic figure stale: everything an attention call runs
+ATTENTION_SOURCES = ("alise_api.hip", "alise_kernels.h", "attn_common.h", "decode_attn.hip", "decode_attn_gqa.hip", "mfma_stream.h")
+
+
+def attention_sources_sha256() -> str:
+    import hashlib
+    h = hashlib.sha256()
+    for name in ATTENTION_SOURCES:
+        with open(os.path.join(ROOT, "paper_2410_23537_amd", "csrc", name), "rb") as f:
+            h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload: str):
+    """HBM bytes per launch of the attention kernel from the rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, scaled by a
+    copy kernel of known size) whose summary is profiles/attention_step_<workload>.md.  The summary names the hash of
+    the attention sources it was taken with; if they have changed since, the figure is stale and not reported.
+    Returns (bytes or None, note)."""
+    import re
+    path = os.path.join(PROFILES, f"attention_step_{workload}.md")
+    try:
+        text = open(path).read()
+    except OSError:
+        return None, f"no {os.path.relpath(path, ROOT)}"
+    m_bytes = re.search(r"^traffic_bytes_per_launch:\s*(\d+)", text, re.M)
+    m_sha = re.search(r"^attention_sources_sha256:\s*([0-9a-f]+)", text, re.M)
+    if not m_bytes or not m_sha:
+        return None, f"{os.path.relpath(path, ROOT)} carries no traffic figure"
+    now = attention_sources_sha256()
+    if m_sha.group(1) != now:
+        return None, (f"the counters in {os.path.relpath(path, ROOT)} were taken with attention sources {m_sha.group(1)}, "
+                      f"they are {now} now: profile again")
+    return int(m_bytes.group(1)), f"from {os.path.relpath(path, ROOT)} (same attention sources, {now})"
 
 
 def parse():
@@ -451,6 +482,74 @@ def scheduled_run_leg(w):
     return out
 
 
+def cache_copies(w):
+    """Copies of the cache the steps rotate over: enough distinct addresses that a step's working set (at least 1 GiB
+    in total) cannot be served from the 256 MB last-level cache by the step before it."""
+    import numpy as np
+    from paper_2410_23537_amd import workloads as wl
+    working_set = int(wl.context_lens(w).astype(np.int64).sum()) * w.Hkv * w.row_bytes
+    copies = 1 if working_set >= (1 << 30) else int(math.ceil((1 << 30) / max(working_set, 1))) + 1
+    return min(copies, 64)
+
+
+def time_steps(step, copies, steps, warmup):
+    """`warmup` untimed steps, then exactly `steps` timed ones between two synchronisations; HIP events on the stream
+    of the calls (torch's current stream) around every write and every attention call."""
+    import numpy as np
+    import torch
+    for s in range(warmup):
+        step.step(s % copies)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    evw = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        c = s % copies
+        evw[s][0].record()
+        step.quant_write(c)
+        evw[s][1].record()
+        ev[s][0].record()
+        step.attend(c)
+        ev[s][1].record()
+        step.dequant_page(c)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    attn_all = [a.elapsed_time(b) for a, b in ev]
+    return {"ms_per_step": elapsed / steps * 1e3, "attn_all": attn_all, "attn_ms": float(np.mean(attn_all)),
+            "write_ms": float(np.mean([a.elapsed_time(b) for a, b in evw]))}
+
+
+def other_config_leg(name, steps, warmup):
+    """The same eager step on one of the other benchmark configurations, built, timed and freed: the step time,
+    the attention call's time and roofline, KV tokens per second."""
+    import torch
+    from paper_2410_23537_amd import workloads as wl
+    from paper_2410_23537_amd.decode_step import DecodeStep
+    w = wl.CONFIGS[name]
+    copies = cache_copies(w)
+    step = DecodeStep(w, n_cache_copies=copies)
+    step.populate()
+    t = time_steps(step, copies, steps, warmup)
+    b_attn, b_write, b_dq = step.bytes_attn(), step.bytes_write(), step.bytes_dequant()
+    total = b_attn + b_write + b_dq
+    achieved = b_attn / (t["attn_ms"] * 1e-3) / 1e9
+    traffic, note = measured_traffic(name)
+    out = {"workload": f"{w.name}: B={w.B} H={w.H} Hkv={w.Hkv} D={w.D} page={w.P} INT{w.bits} G={w.G} "
+                       f"lengths={w.length_law} sum(L)={step.kv_tokens()}",
+           "step_tokens_written": int(step.step_slots.numel()), "cache_copies_rotated": copies,
+           "ms_per_step": t["ms_per_step"], "value": total / (t["ms_per_step"] * 1e-3) / 1e9, "unit": "GB/s",
+           "pct_of_hbm_peak": 100.0 * total / (t["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+           "kv_tokens_per_s": step.kv_tokens() / (t["ms_per_step"] * 1e-3),
+           "attention_call_ms": t["attn_ms"], "attention_call_ms_min": float(min(t["attn_all"])), "quant_write_ms": t["write_ms"],
+           "bytes_per_step": {"attn": b_attn, "quant_write": b_write, "dequant_page": b_dq},
+           "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_note": note}}
+    del step
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -465,10 +564,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
     w = wl.CONFIGS[args.workload]
-    probe = wl.context_lens(w)
-    working_set = int(probe.astype(np.int64).sum()) * w.Hkv * w.row_bytes
-    copies = 1 if working_set >= (1 << 30) else int(math.ceil((1 << 30) / max(working_set, 1))) + 1
-    copies = min(copies, 64)
+    copies = cache_copies(w)
     t_setup = time.perf_counter()
     step = DecodeStep(w, n_cache_copies=copies)
     step.populate()
@@ -477,25 +573,8 @@ def main():
           f"sum(L)={step.kv_tokens()} step tokens={int(step.step_slots.numel())} cache copies={copies} "
           f"setup {time.perf_counter() - t_setup:.1f}s", file=sys.stderr, flush=True)
 
-    for s in range(args.warmup):
-        step.step(s % copies)
-    torch.cuda.synchronize()
-
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    evw = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for s in range(args.steps):
-        c = s % copies
-        evw[s][0].record()
-        step.quant_write(c)
-        evw[s][1].record()
-        ev[s][0].record()
-        step.attend(c)
-        ev[s][1].record()
-        step.dequant_page(c)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    timed = time_steps(step, copies, args.steps, args.warmup)
+    ms_per_step, attn_all, attn_ms, write_ms = timed["ms_per_step"], timed["attn_all"], timed["attn_ms"], timed["write_ms"]
 
     if args.traffic_calibration:
         src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
@@ -504,14 +583,11 @@ def main():
             torch.add(src, 1.0, out=dst)
         torch.cuda.synchronize()
 
-    ms_per_step = elapsed / args.steps * 1e3
-    attn_all = [a.elapsed_time(b) for a, b in ev]
-    attn_ms = float(np.mean(attn_all))
-    write_ms = float(np.mean([a.elapsed_time(b) for a, b in evw]))
     b_attn, b_write, b_dq = step.bytes_attn(), step.bytes_write(), step.bytes_dequant()
     total_bytes = b_attn + b_write + b_dq
     value = total_bytes / (ms_per_step * 1e-3) / 1e9
     achieved = b_attn / (attn_ms * 1e-3) / 1e9
+    traffic, traffic_note = measured_traffic(w.name)
     result = {
         "metric": "quantized-KV decode attention HBM GB/s (% of peak) + KV-tokens/s attended",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -530,7 +606,8 @@ def main():
                      "kernel": "alise_paged_decode_attn = plan_kernel + decode_attn(_gqa)_kernel + merge_kernel, "
                                "timed as one call; the attention kernel is >97 % of it",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(w.name)},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_note": traffic_note,
+                     "attention_sources_sha256": attention_sources_sha256()},
     }
     if not args.only_steps:
         ceiling = read_ceiling_leg()
@@ -553,6 +630,9 @@ def main():
             fast["note"] = ("ALISE_PREFILL_WEIGHTS=single: one rounded fp16 number per softmax weight instead of a high and "
                             "a low part; adds up to 2^-12 max|v| to the error, not the default")
             result["prefill_full_batch_single_weight"] = fast
+        if args.workload == "int4":
+            # the other three benchmark configurations, one after another (each built, timed and freed)
+            result["all_configs"] = {n: other_config_leg(n, args.steps, args.warmup) for n in ("opt13b", "llama7b", "gqa70b")}
         result["fused_ops"] = fused_ops_leg(w)
         result["scheduler"] = scheduled_run_leg(w)
     if not args.no_cpu_baseline:
