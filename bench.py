@@ -204,9 +204,8 @@ def prefill_leg(w, step, every=8):
     import torch
     from paper_2410_23537_amd import binding as B
     cache = step.caches[0]
-    ws_bytes = B.alise_paged_prefill_attn_workspace_bytes(cache, w.B, 1, w.H)
-    if ws_bytes == 0:
-        return None                     # a layout the matrix-core prefill kernel does not take (head_dim 64, other group sizes)
+    if w.D != 128 or w.P < 16 or w.H // w.Hkv > 16 or (w.bits == 8 and w.G < 64):
+        return None                     # a layout without a matrix-core prefill kernel: its fallback on the single-query kernels is not benchmarked
     lens = step.lens.astype(np.int64)
     n = np.array([min(512, int(L)) if i % every == 0 else 0 for i, L in enumerate(lens)], np.int64)
     q_start = np.concatenate([[0], np.cumsum(n)]).astype(np.int32)
@@ -217,7 +216,7 @@ def prefill_leg(w, step, every=8):
     bt = torch.from_numpy(step.pg.block_tables).cuda()
     lens_d = torch.from_numpy(step.lens.astype(np.int32)).cuda()
     qs = torch.from_numpy(q_start).cuda()
-    ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(cache, w.B, total, w.H), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(cache, w.B, total, w.H, int(step.lens.max())), dtype=torch.uint8, device="cuda")
     pairs = sum(int((lens[i] - n[i] + np.arange(n[i]) + 1).sum()) for i in range(w.B) if n[i])
     flops = 4.0 * w.D * w.H * pairs     # q.k and p.v, a multiply and an add each, per (query, visible key, head)
 
@@ -421,8 +420,8 @@ def scheduled_run_leg(w):
     out["scheduler_alone"] = {"live_jobs": 1024, "us_per_iteration": dt / reps * 1e6,
                               "note": "alise_sched_step + alise_sched_commit through ctypes, 1024 live jobs, batch 64, M 256"}
     # ---- (2) a scheduled run on the GPU
-    if B.alise_paged_prefill_attn_workspace_bytes(B.KVCache.allocate(1, w.P, w.Hkv, w.D, w.bits, w.G), 1, 1, w.H) == 0:
-        out["scheduled_run"] = None             # no prefill kernel for this layout (head_dim 64, other group sizes)
+    if w.D != 128 or w.P < 16 or w.H // w.Hkv > 16 or (w.bits == 8 and w.G < 64):
+        out["scheduled_run"] = None             # no matrix-core prefill kernel for this layout: not benchmarked
         return out
     n_jobs, M, batch = 192, 48, 32
     arrival, s, n_true, n_pred = (a.tolist() for a in wl.job_trace(n_jobs, 17, mean_gap=120.0, max_prompt=1024, max_output=96))

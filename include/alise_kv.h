@@ -243,15 +243,21 @@ int alise_kv_dequant_page(const alise_kv_cache *c, int32_t page, void *k_out, vo
  *                 n_i > L_i is a caller error (the chunk is then cut to L_i rows).
  *   block_tables, max_blocks_per_seq, context_lens, max_context_len, softmax_scale, workspace:
  *                 as for alise_paged_decode_attn; the workspace size comes from
- *                 alise_paged_prefill_attn_workspace_bytes.
- * Supported shapes: head_dim = 128, page_size >= 16, num_q_heads / num_kv_heads between 1 and
- * 16, and either bits = 8 with group_size 64 or 128, or bits = 4 with group_size 32, 64 or 128; anything
- * else returns ALISE_UNSUPPORTED (and a workspace size of 0).
+ *                 alise_paged_prefill_attn_workspace_bytes with the same B, total_q_tokens,
+ *                 num_q_heads and max_context_len (0 on invalid arguments).
+ * Every layout of the cache is taken.  Those with head_dim = 128, page_size >= 16, num_q_heads /
+ * num_kv_heads between 1 and 16, and either bits = 8 with group_size 64 or 128, or bits = 4 with
+ * group_size 32, 64 or 128, run on the matrix cores and need a workspace of a few bytes per query
+ * token.  The others (head_dim 64, pages of 8 tokens, bits = 8 with groups of 16 or 32 channels, more
+ * than 16 query heads per KV head) run on the single-query kernels, one request per query token whose
+ * context ends at the token's position: correct and far slower (every query token reads its context
+ * by itself), with a workspace of total_q_tokens * ceil(max_context_len / page_size) block-table
+ * entries plus the split buffers of a single-query call over total_q_tokens requests.
  * out[t][h] = sum_u softmax_u(softmax_scale * q[t][h] . k^_u) v^_u over u <= position of t,
  * accumulated in fp32, rounded once to fp16.
  */
 size_t alise_paged_prefill_attn_workspace_bytes(const alise_kv_cache *c, int32_t B, int32_t total_q_tokens,
-                                                int32_t num_q_heads);
+                                                int32_t num_q_heads, int32_t max_context_len);
 
 int alise_paged_prefill_attn(const alise_kv_cache *c, const void *q, void *out, const int32_t *q_start,
                              const int32_t *block_tables, int32_t max_blocks_per_seq,

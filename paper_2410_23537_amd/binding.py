@@ -75,7 +75,7 @@ _lib.alise_paged_decode_attn_plan.argtypes = [_P, ctypes.c_void_p, ctypes.c_int3
 _lib.alise_kv_dequant_page.restype = ctypes.c_int
 _lib.alise_kv_dequant_page.argtypes = [_P, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
 _lib.alise_paged_prefill_attn_workspace_bytes.restype = ctypes.c_size_t
-_lib.alise_paged_prefill_attn_workspace_bytes.argtypes = [_P, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
+_lib.alise_paged_prefill_attn_workspace_bytes.argtypes = [_P, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
 _lib.alise_paged_prefill_attn.restype = ctypes.c_int
 _lib.alise_paged_prefill_attn.argtypes = [_P, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                           ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
@@ -278,9 +278,10 @@ def alise_kv_dequant_page(cache: KVCache, page: int, k_out: torch.Tensor, v_out:
     _check(st, "alise_kv_dequant_page")
 
 
-def alise_paged_prefill_attn_workspace_bytes(cache: KVCache, B: int, total_q_tokens: int, num_q_heads: int) -> int:
+def alise_paged_prefill_attn_workspace_bytes(cache: KVCache, B: int, total_q_tokens: int, num_q_heads: int,
+                                             max_context_len: int) -> int:
     return int(_lib.alise_paged_prefill_attn_workspace_bytes(ctypes.byref(cache.c_struct()), int(B), int(total_q_tokens),
-                                                             int(num_q_heads)))
+                                                             int(num_q_heads), int(max_context_len)))
 
 
 def alise_paged_prefill_attn(cache: KVCache, q: torch.Tensor, out: torch.Tensor, q_start: torch.Tensor,

@@ -198,7 +198,7 @@ int validate_lens_and_tables(const CacheView &cv, const int32_t *block_tables, i
 // and never beyond what this bound holds (it checks), so the bound is taken at the largest split and widened to
 // the most tiles such a small batch can end with, twice min_items' worth plus one per request; it never exceeds
 // the bound at the smallest split.
-int64_t max_tiles_of(const CacheView &c, int32_t B, int32_t H, int32_t max_len)
+int64_t max_tiles_of(const CacheView &c, int32_t B, int32_t H, int32_t max_len, bool bounded_by_capacity = true)
 {
     const bool gqa = alise::gqa_mfma_applies(c, H);
     int32_t C_min = 0;
@@ -206,7 +206,8 @@ int64_t max_tiles_of(const CacheView &c, int32_t B, int32_t H, int32_t max_len)
     const int64_t capacity = (int64_t)c.num_pages * c.P;
     auto bound = [&](int64_t split) {
         const int64_t per_req = ((int64_t)max_len + split - 1) / split;
-        return std::min((int64_t)B * std::max<int64_t>(per_req, 1), (int64_t)B + capacity / split);
+        const int64_t by_length = (int64_t)B * std::max<int64_t>(per_req, 1);
+        return bounded_by_capacity ? std::min(by_length, (int64_t)B + capacity / split) : by_length;
     };
     const int64_t items_per_tile = gqa ? c.Hkv : H;
     const int64_t small = (int64_t)B + (2 * alise::plan_min_items(256, gqa) + items_per_tile - 1) / items_per_tile;
@@ -216,11 +217,11 @@ int64_t max_tiles_of(const CacheView &c, int32_t B, int32_t H, int32_t max_len)
 // Workspace layout: [n_items, n_merge | tile_base[B+1] | req_full_base[B] | merge_req[B] |
 // order[max_tiles] | part].
 size_t carve_workspace(const CacheView &c, int32_t B, int32_t H, int32_t max_len, void *base,
-                       AttnWorkspace *ws)
+                       AttnWorkspace *ws, bool bounded_by_capacity = true)
 {
     int32_t C_min = 0;
     const int32_t C = split_tokens(c.P, alise::gqa_mfma_applies(c, H), &C_min);
-    const int64_t max_tiles = max_tiles_of(c, B, H, max_len);
+    const int64_t max_tiles = max_tiles_of(c, B, H, max_len, bounded_by_capacity);
     size_t off = 256;       // header: n_items, n_merge
     const size_t off_base = off;
     off = align_up(off + sizeof(int32_t) * ((size_t)B + 1), 256);
@@ -251,11 +252,11 @@ size_t carve_workspace(const CacheView &c, int32_t B, int32_t H, int32_t max_len
     return off;
 }
 
-int check_attn_sizes(const CacheView &c, int32_t B, int32_t H, int32_t max_len)
+int check_attn_sizes(const CacheView &c, int32_t B, int32_t H, int32_t max_len, bool bounded_by_capacity = true)
 {
     if (B < 0 || H <= 0 || max_len < 0) return ALISE_INVALID_ARGUMENT;
     if (H % c.Hkv != 0) return ALISE_UNSUPPORTED;
-    if (max_tiles_of(c, B, H, max_len) * H >= (int64_t)1 << 31) return ALISE_UNSUPPORTED;
+    if (max_tiles_of(c, B, H, max_len, bounded_by_capacity) * H >= (int64_t)1 << 31) return ALISE_UNSUPPORTED;
     return ALISE_OK;
 }
 
@@ -497,21 +498,59 @@ static size_t carve_prefill(const CacheView &cv, int32_t B, int32_t total_q, int
     return bytes;
 }
 
+// Layouts without a matrix-core prefill kernel (head_dim 64, pages of 8 tokens, INT8 groups of 16 or 32 channels,
+// more than 16 query heads per KV head) run on the single-query kernel: every query token of a chunk becomes a request
+// of its own whose context ends at its position -- which is what the causal order means.  The workspace then holds
+// the lengths and the block-table rows of these requests (one row of ceil(max_context_len / page_size) entries per
+// query token, copied from its request's row) in front of the single-query call's own workspace.  That call's split
+// buffers cannot be bounded by the cache's capacity here: the requests of one chunk share their pages.
+struct PrefillFallback {
+    int32_t *lens;          // [total_q] context length of every query token, -1 for rows that no chunk owns
+    int32_t *tables;        // [total_q][blocks_per_row]
+    int32_t blocks_per_row;
+    void *attn_workspace;
+    size_t attn_workspace_bytes;
+};
+
+static size_t carve_prefill_fallback(const CacheView &cv, int32_t total_q, int32_t H, int32_t max_len, void *base,
+                                     PrefillFallback *fb)
+{
+    const int64_t blocks_per_row = std::max<int64_t>(1, ((int64_t)max_len + cv.P - 1) / cv.P);
+    const size_t off_tables = align_up(sizeof(int32_t) * (size_t)total_q, 256);
+    const size_t off_attn = align_up(off_tables + sizeof(int32_t) * (size_t)total_q * (size_t)blocks_per_row, 256);
+    const size_t attn_bytes = carve_workspace(cv, total_q, H, max_len, nullptr, nullptr, false);
+    if (fb) {
+        char *b = static_cast<char *>(base);
+        fb->lens = reinterpret_cast<int32_t *>(b);
+        fb->tables = reinterpret_cast<int32_t *>(b + off_tables);
+        fb->blocks_per_row = (int32_t)blocks_per_row;
+        fb->attn_workspace = b + off_attn;
+        fb->attn_workspace_bytes = attn_bytes;
+    }
+    return off_attn + attn_bytes;
+}
+
 static int check_prefill_sizes(const CacheView &cv, int32_t B, int32_t total_q, int32_t H, int32_t max_len)
 {
     if (B < 0 || total_q < 0 || H <= 0 || max_len < 0) return ALISE_INVALID_ARGUMENT;
     if (H % cv.Hkv != 0) return ALISE_UNSUPPORTED;
-    if (!alise::prefill_mfma_applies(cv, H)) return ALISE_UNSUPPORTED;
     if ((int64_t)total_q * H >= (int64_t)1 << 31) return ALISE_UNSUPPORTED;
+    if (!alise::prefill_mfma_applies(cv, H)) {
+        const int64_t blocks_per_row = std::max<int64_t>(1, ((int64_t)max_len + cv.P - 1) / cv.P);
+        if ((int64_t)total_q * blocks_per_row >= (int64_t)1 << 31) return ALISE_UNSUPPORTED;
+        return check_attn_sizes(cv, total_q, H, max_len, false);
+    }
     return ALISE_OK;
 }
 
 size_t alise_paged_prefill_attn_workspace_bytes(const alise_kv_cache *c, int32_t B, int32_t total_q_tokens,
-                                                int32_t num_q_heads)
+                                                int32_t num_q_heads, int32_t max_context_len)
 {
     CacheView cv;
     if (check_cache(c, &cv) != ALISE_OK) return 0;
-    if (check_prefill_sizes(cv, B, total_q_tokens, num_q_heads, 0) != ALISE_OK) return 0;
+    if (check_prefill_sizes(cv, B, total_q_tokens, num_q_heads, max_context_len) != ALISE_OK) return 0;
+    if (!alise::prefill_mfma_applies(cv, num_q_heads))
+        return carve_prefill_fallback(cv, std::max(total_q_tokens, 1), num_q_heads, max_context_len, nullptr, nullptr);
     return carve_prefill(cv, B, total_q_tokens, num_q_heads, nullptr, nullptr);
 }
 
@@ -538,8 +577,11 @@ int alise_paged_prefill_attn(const alise_kv_cache *c, const void *q, void *out, 
         (reinterpret_cast<uintptr_t>(q_start) & 3u))
         return ALISE_MISALIGNED;
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return ALISE_MISALIGNED;
+    const bool matrix_cores = alise::prefill_mfma_applies(cv, num_q_heads);
     alise::PrefillWorkspace ws;
-    const size_t need = carve_prefill(cv, B, total_q_tokens, num_q_heads, workspace, &ws);
+    PrefillFallback fb;
+    const size_t need = matrix_cores ? carve_prefill(cv, B, total_q_tokens, num_q_heads, workspace, &ws)
+                                     : carve_prefill_fallback(cv, total_q_tokens, num_q_heads, max_context_len, workspace, &fb);
     if (workspace_bytes < need) return ALISE_WORKSPACE_TOO_SMALL;
     if (debug_validate()) {
         hipStream_t hs = static_cast<hipStream_t>(hip_stream);
@@ -552,9 +594,21 @@ int alise_paged_prefill_attn(const alise_kv_cache *c, const void *q, void *out, 
         for (int32_t i = 0; i < B; ++i)
             if (qs[i + 1] < qs[i] || qs[i + 1] - qs[i] > lens[i]) return ALISE_INVALID_ARGUMENT;     // a chunk is part of its request
     }
+    hipStream_t hs = static_cast<hipStream_t>(hip_stream);
+    if (!matrix_cores) {
+        hipError_t e = alise::launch_prefill_expand(cv, q_start, block_tables, max_blocks_per_seq, context_lens, B, total_q_tokens,
+                                                    max_context_len, fb.lens, fb.tables, fb.blocks_per_row, hs);
+        if (e != hipSuccess) return ALISE_HIP_ERROR;
+        AttnWorkspace aws;
+        carve_workspace(cv, total_q_tokens, num_q_heads, max_context_len, fb.attn_workspace, &aws, false);
+        e = alise::launch_decode_attn(cv, q, out, fb.tables, fb.blocks_per_row, fb.lens, total_q_tokens, num_q_heads, max_context_len,
+                                      softmax_scale, aws, num_compute_units(), alise::tuning().waves_per_cu,
+                                      alise::tuning().loads_per_block, alise::tuning().min_items_per_wave,
+                                      alise::kPhasePlan | alise::kPhaseRun | alise::kPhaseKeepNegative, hs);
+        return e == hipSuccess ? ALISE_OK : ALISE_HIP_ERROR;
+    }
     hipError_t e = alise::launch_prefill_attn(cv, q, out, q_start, block_tables, max_blocks_per_seq, context_lens, B,
-                                              num_q_heads, max_context_len, softmax_scale, ws,
-                                              static_cast<hipStream_t>(hip_stream));
+                                              num_q_heads, max_context_len, softmax_scale, ws, hs);
     return e == hipSuccess ? ALISE_OK : ALISE_HIP_ERROR;
 }
 

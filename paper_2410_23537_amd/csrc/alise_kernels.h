@@ -92,7 +92,16 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
                               int32_t max_context_len, float softmax_scale,
                               const AttnWorkspace &ws, int32_t num_cus, int32_t waves_per_cu,
                               int32_t loads_per_block, int32_t min_items_per_wave, int32_t phases, hipStream_t s);
-// phases of launch_decode_attn: the plan (needs only the lengths; q, out and block_tables may be null) and the run
-constexpr int32_t kPhasePlan = 1, kPhaseRun = 2;
+// phases of launch_decode_attn: the plan (needs only the lengths; q, out and block_tables may be null) and the run;
+// kPhaseKeepNegative: a request with a negative length is no request at all and its output row is left alone (by default it
+// is an empty request and gets a zero row)
+constexpr int32_t kPhasePlan = 1, kPhaseRun = 2, kPhaseKeepNegative = 4;
+
+// Chunked prefill on the single-query kernel: writes, for every query token t of every chunk (rows q_start[i] .. q_start[i+1]-1
+// belong to request i, whose chunk ends at its last cached token), lens[t] = its position + 1 and copies the entries of its
+// request's block-table row that this length reaches into tables[t][...]; rows that no chunk owns get lens[t] = -1.
+hipError_t launch_prefill_expand(const CacheView &c, const int32_t *q_start, const int32_t *block_tables, int32_t max_blocks,
+                                 const int32_t *context_lens, int32_t B, int32_t total_q, int32_t max_context_len,
+                                 int32_t *lens, int32_t *tables, int32_t blocks_per_row, hipStream_t s);
 
 }  // namespace alise

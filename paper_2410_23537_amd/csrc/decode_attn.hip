@@ -109,7 +109,7 @@ __device__ __forceinline__ int rem_bucket(int r, int C)
 // Also lists the requests whose splits need merging and zeroes the rows of empty requests.
 __global__ __launch_bounds__(1024) void plan_kernel(const int32_t *context_lens, int32_t B, int32_t H,
                                                     int32_t items_per_tile, int32_t max_len, AttnWorkspace ws,
-                                                    _Float16 *out, int32_t D)
+                                                    _Float16 *out, int32_t D, int32_t keep_negative)
 {
     __shared__ int32_t s_wave[2][16];
     __shared__ int32_t s_hist[kRemBuckets];
@@ -145,8 +145,10 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t *context_lens,
     for (int base = 0; base < B; base += 1024) {
         const int i = base + tid;
         int L = 0;
+        bool no_request = false;    // a row that is nobody's: not even a zero row is written
         if (i < B) {
             L = context_lens[i];
+            no_request = keep_negative && L < 0;
             L = L < 0 ? 0 : (L > max_len ? max_len : L);
         }
         const int nfull = L / C;
@@ -159,7 +161,7 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t *context_lens,
             ws.req_full_base[i] = total_full + s_full - nfull;
             if (nrem) atomicAdd(&s_hist[rem_bucket(r, C)], 1);
             if (nfull + nrem > 1) ws.merge_req[atomicAdd(&s_merge, 1)] = i;
-            if (L == 0 && out)           // out == nullptr: a plan made ahead of the calls that use it; they zero these rows
+            if (L == 0 && out && !no_request)           // out == nullptr: a plan made ahead of the calls that use it; they zero these rows
                 for (int e = 0; e < H * D; ++e) out[(int64_t)i * H * D + e] = (_Float16)0.0f;
         }
         total += t_all;
@@ -780,6 +782,51 @@ hipError_t launch_merge(const AttnParams &p, hipStream_t s)
 
 }  // namespace
 
+namespace {
+
+// One wave per query row t: the length and the block-table row of the single-query request that stands for it.  The
+// row's request is found by bisection in q_start, so every row gets a defined entry whatever q_start holds: a length
+// in [1, L] with the entries that length reaches, or -1 (a row that no chunk owns, or one beyond a chunk cut short).
+__global__ __launch_bounds__(256) void prefill_expand_kernel(const int32_t *q_start, const int32_t *block_tables, int32_t max_blocks,
+                                                             const int32_t *context_lens, int32_t B, int32_t total_q, int32_t max_len,
+                                                             int32_t logP, int32_t *lens, int32_t *tables, int32_t blocks_per_row)
+{
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= total_q) return;
+    int len = -1, i = 0;
+    if (t < q_start[B]) {
+        int lo = 0, hi = B;                 // the last request whose first row is at or before t
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (q_start[mid] <= t) lo = mid; else hi = mid;
+        }
+        i = lo;
+        const int L = min(max(context_lens[i], 0), max_len);
+        const int n = min(max(q_start[i + 1] - q_start[i], 0), L);         // a chunk cannot be longer than its request
+        const int j = t - q_start[i];
+        if (j >= 0 && j < n) len = L - n + j + 1;
+    }
+    if (len > 0) {
+        const int nblk = min(min((len + (1 << logP) - 1) >> logP, blocks_per_row), max_blocks);
+        const int32_t *row = block_tables + (int64_t)i * max_blocks;
+        int32_t *dst = tables + (int64_t)t * blocks_per_row;
+        for (int b = lane; b < nblk; b += 64) dst[b] = row[b];
+    }
+    if (lane == 0) lens[t] = len;
+}
+
+}  // namespace
+
+hipError_t launch_prefill_expand(const CacheView &c, const int32_t *q_start, const int32_t *block_tables, int32_t max_blocks,
+                                 const int32_t *context_lens, int32_t B, int32_t total_q, int32_t max_context_len,
+                                 int32_t *lens, int32_t *tables, int32_t blocks_per_row, hipStream_t s)
+{
+    hipLaunchKernelGGL(prefill_expand_kernel, dim3((total_q + 3) / 4), dim3(256), 0, s, q_start, block_tables, max_blocks, context_lens, B,
+                       total_q, max_context_len, c.logP, lens, tables, blocks_per_row);
+    return hipGetLastError();
+}
+
 hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
                               const int32_t *block_tables, int32_t max_blocks,
                               const int32_t *context_lens, int32_t B, int32_t H,
@@ -811,7 +858,7 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
     hipError_t e = hipSuccess;
     if (phases & kPhasePlan) {
         hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, s, context_lens, B, H, gqa ? c.Hkv : H, max_context_len, p.ws,
-                           p.out, c.D);
+                           p.out, c.D, (phases & kPhaseKeepNegative) ? 1 : 0);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -40,8 +40,8 @@ class Replay:
         self.sched = sched
         self.kv_source = kv_source
         self.cache = B.KVCache.allocate(num_pages, shape.P, shape.Hkv, shape.D, shape.bits, shape.G, fill=0)
-        if B.alise_paged_prefill_attn_workspace_bytes(self.cache, 1, 1, shape.H) == 0:
-            raise ValueError("this cache layout has no prefill attention kernel (head_dim 128 with INT8 and G 64 or 128, or INT4 and G 32, 64 or 128)")
+        if B.alise_paged_prefill_attn_workspace_bytes(self.cache, 1, 1, shape.H, max_context) == 0:
+            raise ValueError("unsupported cache layout")
         self.free = list(range(num_pages - 1, -1, -1))
         self.pending_free: list[int] = []
         self.max_context = max_context
@@ -156,7 +156,7 @@ class Replay:
             q_start = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
             q = q_all[:n_pre]
             o = torch.empty_like(q)
-            ws = self._workspace("_ws_pre", B.alise_paged_prefill_attn_workspace_bytes(cache, len(pre), int(q_start[-1]), w.H))
+            ws = self._workspace("_ws_pre", B.alise_paged_prefill_attn_workspace_bytes(cache, len(pre), int(q_start[-1]), w.H, int(lens.max())))
             B.alise_paged_prefill_attn(cache, q, o, torch.from_numpy(q_start).cuda(), self._bt(pre), torch.from_numpy(lens).cuda(),
                                        int(lens.max()), self.scale, ws)
             out["prefill_out"] = o

@@ -248,12 +248,12 @@ def test_prefill_arguments(B):
             a[names.index(k)] = v
         return f(*a)
 
-    need = lib.alise_paged_prefill_attn_workspace_bytes(ctypes.byref(c), 2, 300, 8)
+    need = lib.alise_paged_prefill_attn_workspace_bytes(ctypes.byref(c), 2, 300, 8, 256)
     assert need > 0 and need % 256 == 0
     assert call(B=0) == 0 and call(tq=0) == 0       # nothing to do, nothing launched
     assert call(B=-1) == 1 and call(tq=-1) == 1 and call(H=0) == 1 and call(maxlen=-1) == 1
     assert call(H=12) == 2                          # not a multiple of the 8 KV heads
-    assert call(H=8 * 32) == 2                      # more than 16 query heads per KV head
+    assert call(H=8 * 32, wsb=0) == 3               # more than 16 query heads per KV head: the single-query kernels, a larger workspace
     assert call(mb=0) == 1 and call(mb=15) == 1     # 15 pages of 16 cannot hold 256 tokens
     assert call(scale=0.0) == 1 and call(scale=float("nan")) == 1
     for name in ("q", "out", "qs", "bt", "lens", "ws"):
@@ -262,14 +262,18 @@ def test_prefill_arguments(B):
     assert call(qs=0x60002) == 4 and call(bt=0x30002) == 4 and call(lens=0x40001) == 4
     assert call(ws=0x50010) == 4
     assert call(wsb=need - 1) == 3
-    # layouts the matrix-core kernel does not take
+    # layouts without a matrix-core kernel run on the single-query kernels: one block-table row per query token
+    # (300 rows of 256 / page_size entries) in front of that call's own workspace
     for kw in (dict(head_dim=64), dict(group_size=32), dict(page_size=8)):
-        bad = _cache(B, **kw)
-        assert lib.alise_paged_prefill_attn_workspace_bytes(ctypes.byref(bad), 2, 300, 8) == 0
-        assert call(c=ctypes.byref(bad)) == 2
+        other = _cache(B, **kw)
+        n = lib.alise_paged_prefill_attn_workspace_bytes(ctypes.byref(other), 2, 300, 8, 256)
+        P = kw.get("page_size", 16)
+        inner = lib.alise_paged_decode_attn_workspace_bytes(ctypes.byref(_cache(B, num_pages=1 << 20, **kw)), 300, 8, 256)
+        assert n == 1280 + (300 * (256 // P) * 4 + 255) // 256 * 256 + inner and n % 256 == 0
+        assert call(c=ctypes.byref(other), mb=256 // P, wsb=n - 1) == 3
     for g in (32, 64, 128):                             # INT4 is taken with groups of 32, 64 and 128
         c4 = _cache(B, bits=4, group_size=g)
-        assert lib.alise_paged_prefill_attn_workspace_bytes(ctypes.byref(c4), 2, 300, 8) > 0
+        assert 0 < lib.alise_paged_prefill_attn_workspace_bytes(ctypes.byref(c4), 2, 300, 8, 256) < 8192
 
 
 def test_fused_op_arguments(B):

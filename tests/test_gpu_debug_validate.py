@@ -96,7 +96,7 @@ def test_device_contents_are_checked_on_request(env, validating):
     # ---- prefill attention
     qp = torch.from_numpy(rng.standard_normal((12, H, D)).astype(np.float16)).cuda()
     op = torch.empty_like(qp)
-    wsp = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(cache, 2, 12, H), dtype=torch.uint8, device="cuda")
+    wsp = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(cache, 2, 12, H, 48), dtype=torch.uint8, device="cuda")
     pre = lambda qs, l=lens, t=bt: B.alise_paged_prefill_attn(cache, qp, op, dev(np.array(qs, np.int32)), dev(t), dev(l), 48, scale, wsp)
     pre([0, 5, 12])
     _refused(B, lambda: pre([0, 7, 5]))                                     # boundaries go down

@@ -51,7 +51,7 @@ def test_repeated_calls_return_the_same_bytes(env, w):
     total = int(q_start[-1])
     rng = np.random.default_rng([w.seed, 17])
     qp = torch.from_numpy(rng.standard_normal((total, w.H, w.D)).astype(np.float16)).cuda()
-    ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(dev, w.B, total, w.H), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(dev, w.B, total, w.H, int(lens.max())), dtype=torch.uint8, device="cuda")
     bt, lens_d, qs = torch.from_numpy(pg.block_tables).cuda(), torch.from_numpy(pg.lens.astype(np.int32)).cuda(), torch.from_numpy(q_start).cuda()
     outs = []
     for _ in range(3):

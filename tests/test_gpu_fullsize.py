@@ -128,7 +128,7 @@ def test_full_size_prefill_sampled_against_oracle(env, name):
     bt = torch.from_numpy(st.pg.block_tables).cuda()
     lens_d = torch.from_numpy(st.lens.astype(np.int32)).cuda()
     qs = torch.from_numpy(q_start).cuda()
-    ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(cache, w.B, total, w.H), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(cache, w.B, total, w.H, int(st.lens.max())), dtype=torch.uint8, device="cuda")
     B.alise_paged_prefill_attn(cache, q, out, qs, bt, lens_d, int(st.lens.max()), st.scale, ws)
     torch.cuda.synchronize()
     got = out.cpu().numpy().astype(np.float64)

@@ -214,7 +214,7 @@ def test_captured_prefill_call_replays_like_eager(env, w):
     out = torch.zeros_like(q)
     q_start = torch.zeros(w.B + 1, dtype=torch.int32, device="cuda")
     lens = torch.ones(w.B, dtype=torch.int32, device="cuda")
-    ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(dev, w.B, total_cap, w.H), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(dev, w.B, total_cap, w.H, max_len), dtype=torch.uint8, device="cuda")
     e_ws = torch.empty_like(ws)
 
     def call(o, wsp):

@@ -109,7 +109,7 @@ def test_prefill_with_one_and_two_row_tiles(env, problems, tiles, weights):
         want = oracle.paged_prefill_attn(orc, q_np, q_start, pg.block_tables, pg.lens, scale)
         qd = torch.from_numpy(q_np).cuda()
         out = torch.full(qd.shape, float("nan"), dtype=torch.float16, device="cuda")
-        ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(dev, w.B, total, w.H), dtype=torch.uint8, device="cuda")
+        ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(dev, w.B, total, w.H, int(lens.max())), dtype=torch.uint8, device="cuda")
         B.alise_paged_prefill_attn(dev, qd, out, torch.from_numpy(q_start).cuda(), torch.from_numpy(pg.block_tables).cuda(),
                                    torch.from_numpy(pg.lens.astype(np.int32)).cuda(), int(lens.max()), scale, ws)
         torch.cuda.synchronize()

@@ -327,7 +327,7 @@ def test_more_requests_than_a_plan_pass_holds(env, bits, G, Hkv, H):
     wantp = oracle.paged_prefill_attn(orc, qp_np, q_start, pg.block_tables, pg.lens, 1.0 / np.sqrt(w.D))
     qp = torch.from_numpy(qp_np).cuda()
     op = torch.full(qp.shape, float("nan"), dtype=torch.float16, device="cuda")
-    ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(dev, n, total, H), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(dev, n, total, H, int(lens.max())), dtype=torch.uint8, device="cuda")
     B.alise_paged_prefill_attn(dev, qp, op, torch.from_numpy(q_start).cuda(), torch.from_numpy(pg.block_tables).cuda(),
                                torch.from_numpy(pg.lens.astype(np.int32)).cuda(), int(lens.max()), 1.0 / np.sqrt(w.D), ws)
     torch.cuda.synchronize()

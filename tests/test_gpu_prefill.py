@@ -78,7 +78,7 @@ def test_prefill_against_oracle(env, case, layout):
     lens_d = torch.from_numpy(pg.lens.astype(np.int32)).cuda()
     qs_d = torch.from_numpy(q_start).cuda()
     max_len = int(max(lens))
-    nbytes = B.alise_paged_prefill_attn_workspace_bytes(dev, len(lens), total, w.H)
+    nbytes = B.alise_paged_prefill_attn_workspace_bytes(dev, len(lens), total, w.H, max_len)
     assert nbytes > 0
     ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
     both = torch.cat([out, guard])              # the guard sits right behind the output
@@ -105,7 +105,7 @@ def test_one_token_chunks_equal_the_decode_call(env):
     qs = torch.arange(w.B + 1, dtype=torch.int32, device="cuda")
     bt = torch.from_numpy(pg.block_tables).cuda()
     lens_d = torch.from_numpy(pg.lens.astype(np.int32)).cuda()
-    ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(dev, w.B, w.B, w.H), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(dev, w.B, w.B, w.H, int(pg.lens.max())), dtype=torch.uint8, device="cuda")
     B.alise_paged_prefill_attn(dev, q, out, qs, bt, lens_d, int(pg.lens.max()), 1.0 / np.sqrt(w.D), ws)
     torch.cuda.synchronize()
     pre = out.cpu().numpy().astype(np.float64)
@@ -113,17 +113,54 @@ def test_one_token_chunks_equal_the_decode_call(env):
     assert np.abs(pre - dec).max() <= 2 * ATTN_TOL
 
 
-def test_unsupported_shapes_are_refused(env):
+FALLBACK_LAYOUTS = [
+    # layouts without a matrix-core prefill kernel: they run on the single-query kernel, one request per query token
+    wl.Workload("tiny_d64", B=4, H=8, Hkv=8, D=64, P=16, bits=8, G=64, length_law="fixed:17,64,100,255", seed=1001, max_len=255),
+    wl.Workload("page8", B=5, H=4, Hkv=2, D=128, P=8, bits=8, G=128, length_law="uniform:1,700", seed=41, max_len=700),
+    wl.Workload("int8_g32", B=5, H=2, Hkv=2, D=128, P=16, bits=8, G=32, length_law="uniform:1,3000", seed=42, max_len=3000),
+    wl.Workload("int8_g16_d64", B=4, H=4, Hkv=4, D=64, P=32, bits=8, G=16, length_law="uniform:1,500", seed=43, max_len=500),
+    wl.Workload("int4_d64", B=4, H=4, Hkv=2, D=64, P=16, bits=4, G=32, length_law="uniform:1,900", seed=44, max_len=900),
+    wl.Workload("gqa32", B=3, H=32, Hkv=1, D=128, P=16, bits=8, G=128, length_law="uniform:1,400", seed=45, max_len=400),
+]
+
+
+@pytest.mark.parametrize("w", FALLBACK_LAYOUTS, ids=lambda w: w.name)
+def test_layouts_without_a_matrix_core_kernel(env, w):
+    """Causal prefill over every layout the cache supports: chunks of mixed sizes (none, one token, the whole request,
+    a longer one than the request), rows behind the last chunk that must stay untouched."""
     B, torch, oracle = env
-    c32 = B.KVCache.allocate(4, 16, 2, 128, 8, 32)          # INT8 with groups of 32 (INT4 takes 32, 64 and 128)
-    assert B.alise_paged_prefill_attn_workspace_bytes(c32, 1, 8, 2) == 0
-    for g in (32, 64, 128):
-        assert B.alise_paged_prefill_attn_workspace_bytes(B.KVCache.allocate(4, 16, 2, 128, 4, g), 1, 8, 2) > 0
-    c64 = B.KVCache.allocate(4, 16, 2, 64, 8, 64)           # head_dim 64
-    assert B.alise_paged_prefill_attn_workspace_bytes(c64, 1, 8, 2) == 0
-    ok = B.KVCache.allocate(4, 16, 2, 128, 8, 64)
-    assert B.alise_paged_prefill_attn_workspace_bytes(ok, 1, 8, 2) > 0
-    assert B.alise_paged_prefill_attn_workspace_bytes(ok, 1, 8, 64) == 0      # 32 query heads per KV head
+    print(f"case prefill fallback {w.name}", flush=True)
+    pg = wl.paging(w)
+    lens = pg.lens.astype(np.int64)
+    pool = wl.value_pool(w, n_min=int(lens.max()) * w.Hkv * w.D)
+    offs, gain = wl.request_offsets(w), wl.k_channel_gain(w)
+    orc = harness.fill_oracle_cache(oracle, w, pg, pool, offs, gain)
+    dev = harness.fill_device_cache(B, torch, w, pg, pool, offs, gain)
+    n = np.minimum(lens, [60, 0, 1, 10 ** 6, 33, 7][:w.B])
+    q_start = np.concatenate([[0], np.cumsum(n)]).astype(np.int32)
+    total = int(q_start[-1])
+    rng = np.random.default_rng([w.seed, 3])
+    q_np = rng.standard_normal((total + 5, w.H, w.D)).astype(np.float16)       # five rows that no chunk owns
+    scale = 1.0 / np.sqrt(w.D)
+    want = oracle.paged_prefill_attn(orc, q_np[:total], q_start, pg.block_tables, pg.lens, scale)
+    q = torch.from_numpy(q_np).cuda()
+    out = torch.full(q.shape, 7.0, dtype=torch.float16, device="cuda")
+    max_len = int(lens.max())
+    nbytes = B.alise_paged_prefill_attn_workspace_bytes(dev, w.B, total + 5, w.H, max_len)
+    assert nbytes > 0
+    ws = torch.full((nbytes,), 0xA5, dtype=torch.uint8, device="cuda")
+    B.alise_paged_prefill_attn(dev, q, out, torch.from_numpy(q_start).cuda(), torch.from_numpy(pg.block_tables).cuda(),
+                               torch.from_numpy(pg.lens.astype(np.int32)).cuda(), max_len, scale, ws)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    err = float(np.abs(got[:total] - want).max())
+    print(f"  max-abs error {err:.3e}", flush=True)
+    assert np.isfinite(got).all() and err <= ATTN_TOL
+    assert (got[total:] == 7.0).all(), "rows behind the last chunk were written"
+    with pytest.raises(B.AliseError) as e:
+        B.alise_paged_prefill_attn(dev, q, out, torch.from_numpy(q_start).cuda(), torch.from_numpy(pg.block_tables).cuda(),
+                                   torch.from_numpy(pg.lens.astype(np.int32)).cuda(), max_len, scale, ws[:nbytes - 256])
+    assert e.value.status == B.ALISE_WORKSPACE_TOO_SMALL
 
 
 @pytest.mark.parametrize("vgain", [1.0, 150.0, 20000.0])
@@ -154,7 +191,7 @@ def test_large_value_scales_decode_and_prefill(env, vgain):
     q = torch.from_numpy(q_np).cuda()
     out = torch.full(q.shape, float("nan"), dtype=torch.float16, device="cuda")
     qs_np = np.array([0, n_q], np.int32)
-    ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(dev, 1, n_q, H), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(dev, 1, n_q, H, L), dtype=torch.uint8, device="cuda")
     B.alise_paged_prefill_attn(dev, q, out, torch.from_numpy(qs_np).cuda(), bt, lens_d, L, scale, ws)
     want = oracle.paged_prefill_attn(orc, q_np, qs_np, bt_np, lens_np, scale)
     torch.cuda.synchronize()
@@ -215,7 +252,7 @@ def test_peaked_rows_with_values_up_to_the_fp16_limit_of_the_bar(env, monkeypatc
     assert np.abs(want).max() < 4.0
     q = torch.from_numpy(q_np).cuda()
     out = torch.full(q.shape, float("nan"), dtype=torch.float16, device="cuda")
-    ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(dev, len(lens), total, H), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(dev, len(lens), total, H, max(lens)), dtype=torch.uint8, device="cuda")
     B.alise_paged_prefill_attn(dev, q, out, torch.from_numpy(qs_np).cuda(), torch.from_numpy(bt_np).cuda(),
                                torch.from_numpy(lens_np).cuda(), max(lens), scale, ws)
     torch.cuda.synchronize()
