@@ -19,6 +19,36 @@ HIPCC_FLAGS = [
 ]
 
 
+# The kernels place wait states and load waits by hand inside assembly statements (mfma_stream.h, decode_attn.hip),
+# which the compiler neither sees into nor schedules around.  They were validated -- parity, bit-identical repeats,
+# the peaked-row tests -- with this compiler; another one may place its own instructions differently around them, so
+# a build with another compiler says so and the GPU tests have to be run again before its library is trusted.
+VALIDATED_COMPILER = "AMD clang version 22.0.0git (https://github.com/RadeonOpenCompute/llvm-project roc-7.2.0 26014"
+
+
+def compiler_banner() -> str:
+    try:
+        out = subprocess.run([hipcc(), "--version"], check=True, capture_output=True, text=True).stdout
+    except (OSError, subprocess.CalledProcessError):
+        return ""
+    return next((line.strip() for line in out.splitlines() if "clang version" in line), "")
+
+
+def check_compiler(verbose: bool = False) -> bool:
+    """True if hipcc is the compiler the hand-scheduled kernels were validated with; warns otherwise."""
+    banner = compiler_banner()
+    ok = banner.startswith(VALIDATED_COMPILER)
+    if not ok:
+        import warnings
+        warnings.warn(f"libalise_kv.so is being built with '{banner or 'an unknown compiler'}', not with the compiler its "
+                      f"hand-placed wait states were validated with ('{VALIDATED_COMPILER} ...'): run the GPU tests "
+                      "(pytest -m gpu, in particular test_hand_scheduled_instructions_on_peaked_rows and "
+                      "test_gpu_determinism.py) before trusting this build", RuntimeWarning, stacklevel=2)
+    elif verbose:
+        print(f"compiler: {banner}", flush=True)
+    return ok
+
+
 def hipcc() -> str:
     for cand in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", "hipcc"):
         if cand and (os.path.sep not in cand or os.path.exists(cand)):
@@ -28,6 +58,7 @@ def hipcc() -> str:
 
 def build(verbose: bool = False) -> str:
     """Compile every HIP source for gfx950 into one shared library; always recompiles."""
+    check_compiler(verbose)
     cmd = [hipcc()] + HIPCC_FLAGS + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB_PATH]
     if verbose:
         print(" ".join(cmd), flush=True)

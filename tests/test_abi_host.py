@@ -315,3 +315,16 @@ def test_fused_op_arguments(B):
         assert probe(n=n) == B.ALISE_UNSUPPORTED                  # whole 16-byte units only
     assert probe(src=A + 8) == B.ALISE_MISALIGNED
     assert probe(out=A + 2) == B.ALISE_MISALIGNED
+
+
+def test_build_names_the_compiler_the_kernels_were_validated_with():
+    """The hand-placed wait states of the kernels were validated with one compiler; the build warns about any other."""
+    import warnings
+    from paper_2410_23537_amd import build
+    banner = build.compiler_banner()
+    assert "clang version" in banner
+    with warnings.catch_warnings(record=True) as seen:
+        warnings.simplefilter("always")
+        ok = build.check_compiler()
+    assert ok == banner.startswith(build.VALIDATED_COMPILER)
+    assert ok == (not any("validated" in str(w.message) for w in seen))

@@ -211,17 +211,9 @@ def test_large_value_scales_decode_and_prefill(env, vgain):
     assert np.isfinite(gd).all() and np.abs(gd - wd).max() <= bar, (np.abs(gd - wd).max(), bar)
 
 
-@pytest.mark.parametrize("weights", ["split", "single"])
-@pytest.mark.parametrize("bits,G,Hkv,H", [(8, 64, 4, 4), (8, 128, 2, 16), (4, 32, 4, 4)])
-@pytest.mark.parametrize("qgain", [1.0, 3.0, 8.0])
-def test_peaked_rows_with_values_up_to_the_fp16_limit_of_the_bar(env, monkeypatch, bits, G, Hkv, H, qgain, weights):
-    """Dequantized V values just below 4 are the largest for which an fp16 output can meet 2e-3 at all (half an
-    ulp is 9.8e-4 in [2, 4) and 1.95e-3 in [4, 8)); scaled queries make the rows peaked (a few tokens carry the
-    sum, so errors of single weights do not average out), unscaled ones flat.  The default kernels (a weight
-    as a high and a low fp16 part) must meet the bar there.  With ALISE_PREFILL_WEIGHTS=single a weight
-    is one fp16 number rounded to nearest, which adds at most 2^-12 max|v| to the error: that bound is the bar."""
-    B, torch, oracle = env
-    monkeypatch.setenv("ALISE_PREFILL_WEIGHTS", weights)
+def _peaked_problem(B, torch, oracle, bits, G, Hkv, H, qgain):
+    """Three requests whose dequantized V values come close to 4 and whose queries are scaled by `qgain` (peaked
+    rows for large gains), written by both sides; chunks of 80, 64 and 130 query tokens."""
     D, P = 128, 16
     lens = [333, 64, 1100]
     chunks = [80, 64, 130]
@@ -244,10 +236,45 @@ def test_peaked_rows_with_values_up_to_the_fp16_limit_of_the_bar(env, monkeypatc
         oracle.kv_quant_write(orc, k, v, slots)
         B.alise_kv_quant_write(dev, torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda(), torch.from_numpy(slots).cuda())
     qs_np = np.concatenate([[0], np.cumsum(chunks)]).astype(np.int32)
-    total = int(qs_np[-1])
-    q_np = (rng.standard_normal((total, H, D)) * qgain).astype(np.float16)
-    lens_np = np.array(lens, np.int32)
-    scale = 1.0 / np.sqrt(D)
+    q_np = (rng.standard_normal((int(qs_np[-1]), H, D)) * qgain).astype(np.float16)
+    return dev, orc, bt_np, np.array(lens, np.int32), qs_np, q_np
+
+
+@pytest.fixture
+def knobs(env):
+    """Sets tuning variables for one test: the library reads its environment once and again on request."""
+    import os
+    B = env[0]
+    touched = []
+
+    def set_(**kw):
+        for k, v in kw.items():
+            touched.append((k, os.environ.get(k)))
+            os.environ[k] = v
+        B.alise_reload_environment()
+    yield set_
+    for k, old in reversed(touched):
+        if old is None:
+            os.environ.pop(k, None)
+        else:
+            os.environ[k] = old
+    B.alise_reload_environment()
+
+
+@pytest.mark.parametrize("weights", ["split", "single"])
+@pytest.mark.parametrize("bits,G,Hkv,H", [(8, 64, 4, 4), (8, 128, 2, 16), (4, 32, 4, 4)])
+@pytest.mark.parametrize("qgain", [1.0, 3.0, 8.0])
+def test_peaked_rows_with_values_up_to_the_fp16_limit_of_the_bar(env, knobs, bits, G, Hkv, H, qgain, weights):
+    """Dequantized V values just below 4 are the largest for which an fp16 output can meet 2e-3 at all (half an
+    ulp is 9.8e-4 in [2, 4) and 1.95e-3 in [4, 8)); scaled queries make the rows peaked (a few tokens carry the
+    sum, so errors of single weights do not average out), unscaled ones flat.  The default kernels (a weight
+    as a high and a low fp16 part) must meet the bar there.  With ALISE_PREFILL_WEIGHTS=single a weight
+    is one fp16 number rounded to nearest, which adds at most 2^-12 max|v| to the error: that bound is the bar."""
+    B, torch, oracle = env
+    knobs(ALISE_PREFILL_WEIGHTS=weights)
+    dev, orc, bt_np, lens_np, qs_np, q_np = _peaked_problem(B, torch, oracle, bits, G, Hkv, H, qgain)
+    lens, total = [int(x) for x in lens_np], int(qs_np[-1])
+    scale = 1.0 / np.sqrt(128)
     want = oracle.paged_prefill_attn(orc, q_np, qs_np, bt_np, lens_np, scale)
     assert np.abs(want).max() < 4.0
     q = torch.from_numpy(q_np).cuda()
@@ -261,3 +288,54 @@ def test_peaked_rows_with_values_up_to_the_fp16_limit_of_the_bar(env, monkeypatc
     bar = ATTN_TOL if weights == "split" else ATTN_TOL + 2.0 ** -12 * 4.0
     print(f"  max|want| {np.abs(want).max():.3f} max-abs error {err.max():.3e} (bar {bar:.3e})", flush=True)
     assert np.isfinite(got).all() and err.max() <= bar
+
+
+@pytest.mark.parametrize("bits,G,Hkv,H", [(8, 64, 4, 4), (8, 128, 2, 16), (4, 32, 2, 16), (4, 128, 4, 4)])
+def test_hand_scheduled_instructions_on_peaked_rows(env, knobs, bits, G, Hkv, H):
+    """The matrix-core kernels contain multiply-adds written in assembly that take softmax weights straight from the
+    exponential instruction and bring their own wait states, and waits for loads placed by hand.  Nothing checks
+    those at build time, so this does at run time: on peaked rows (the weights that matter come out of the
+    exponential one instruction before they are used) every variant -- one and two row tiles per wave, split and
+    single weights, and the grouped-query decode kernel -- runs twice with other work on the device in between, and
+    must return the same bytes both times and the oracle's answer.  A missing wait state would show as a difference
+    between the runs or as a row off the bar, not as noise inside it."""
+    B, torch, oracle = env
+    dev, orc, bt_np, lens_np, qs_np, q_np = _peaked_problem(B, torch, oracle, bits, G, Hkv, H, 8.0)
+    lens, total = [int(x) for x in lens_np], int(qs_np[-1])
+    scale = 1.0 / np.sqrt(128)
+    want = oracle.paged_prefill_attn(orc, q_np, qs_np, bt_np, lens_np, scale)
+    q = torch.from_numpy(q_np).cuda()
+    bt, lens_d, qs = torch.from_numpy(bt_np).cuda(), torch.from_numpy(lens_np).cuda(), torch.from_numpy(qs_np).cuda()
+    noise = torch.empty(1 << 26, dtype=torch.float16, device="cuda")
+    for tiles in ("1", "2"):
+        for weights in ("split", "single"):
+            print(f"case hazards prefill bits={bits} G={G} H={H} row tiles {tiles} weights {weights}", flush=True)
+            knobs(ALISE_PREFILL_ROW_TILES=tiles, ALISE_PREFILL_WEIGHTS=weights)
+            ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(dev, len(lens), total, H, max(lens)), dtype=torch.uint8, device="cuda")
+            outs = []
+            for rep in range(2):
+                o = torch.full(q.shape, float("nan"), dtype=torch.float16, device="cuda")
+                B.alise_paged_prefill_attn(dev, q, o, qs, bt, lens_d, max(lens), scale, ws)
+                noise.normal_()                    # other kernels in between: the second run meets another machine state
+                outs.append(o)
+            torch.cuda.synchronize()
+            assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16)), "two runs differ"
+            err = np.abs(outs[0].cpu().numpy().astype(np.float64) - want).max()
+            bar = ATTN_TOL if weights == "split" else ATTN_TOL + 2.0 ** -12 * 4.0
+            assert err <= bar, (tiles, weights, err)
+    if H > Hkv:
+        # the grouped-query decode kernel on the same cache: the last token of every request as its query
+        print(f"case hazards grouped-query decode bits={bits} G={G} H={H}", flush=True)
+        qd_np = np.stack([q_np[qs_np[i + 1] - 1] for i in range(len(lens))])
+        wd = oracle.paged_decode_attn(orc, qd_np, bt_np, lens_np, scale)
+        qd = torch.from_numpy(qd_np).cuda()
+        wsd = torch.empty(B.alise_paged_decode_attn_workspace_bytes(dev, len(lens), H, max(lens)), dtype=torch.uint8, device="cuda")
+        outs = []
+        for rep in range(2):
+            o = torch.full(qd.shape, float("nan"), dtype=torch.float16, device="cuda")
+            B.alise_paged_decode_attn(dev, qd, o, bt, lens_d, max(lens), scale, wsd)
+            noise.normal_()
+            outs.append(o)
+        torch.cuda.synchronize()
+        assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16)), "two runs differ"
+        assert np.abs(outs[0].cpu().numpy().astype(np.float64) - wd).max() <= ATTN_TOL
