@@ -889,6 +889,9 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
 #undef ALISE_DISPATCH
     }
     if (e != hipSuccess) return e;
+    // No request can have more than one split when the longest context fits the shortest split the plan may choose, and
+    // then there is nothing to merge (the zero rows of a run on an earlier plan are the merge kernel's too).
+    if (max_context_len <= p.ws.min_chunk_tokens && !p.zero_empty) return hipSuccess;
     return launch_merge(p, s);
 }
 

@@ -70,6 +70,21 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
     constexpr int LOADS_PER_STEP = BITS == 8 ? 12 : 8;       // direct loads of one step
     constexpr int RD = 4, RG = 2, RQ = 1;       // rings: descriptors, page windows, query rows
     constexpr int QSLOT = QROWS * 256;
+    // PACKED (INT4, at most 8 query heads per KV head).  A 16 x 16 tile of S^T has room for 16 query heads, and with 8
+    // of them half of every step's score, exponential and weight arithmetic -- which is what this kernel's time goes
+    // into: the vector-instruction issue is busy two thirds of the time, the matrix cores an eighth -- would be spent on
+    // columns that hold no head.  So the first product is laid out block-diagonally: its 32 k-slots are 16 channels
+    // of a token of the step's first tile (quarters 0 and 1 of the wave) and the same 16 channels of a token of the
+    // second tile (quarters 2 and 3); column n < 8 of Q^T carries head n in the first half of the k-slots and zeros
+    // in the second, column n >= 8 head n - 8 in the second half.  One product then gives 16 tokens x 8 heads of the
+    // first tile in columns 0..7 and of the second tile in columns 8..15: eight products of 16 channels per step, as
+    // before, but one accumulator tile per scale group instead of two half-empty ones, and four useful scores per
+    // lane instead of eight half-useful ones.  The weights of column n + 8 travel to lane n (a rotation by 8 inside
+    // the row of 16 lanes) to complete the A operand of the second product, whose k-slot order -- four tokens of the
+    // first tile, then four of the second -- is the one it had.  Columns n and n + 8 are the same head: they share one
+    // softmax reference, and their denominators and zero-point sums are added at the end.
+    constexpr bool PACKED = BITS == 4 && QROWS == 8;
+    constexpr int NQ = PACKED ? 8 : 4;          // products (k-chunks) per tile of S^T
     constexpr int OFF_DESC = S * STEPB, OFF_PG = OFF_DESC + RD * 16, OFF_Q = OFF_PG + RG * 256;
     static_assert(S >= 2 && S <= 4, "stage marks occupy four lanes");
     __shared__ __attribute__((aligned(128))) uint8_t lds[OFF_Q + RQ * QSLOT];
@@ -98,7 +113,11 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
     // INT4: rows 4g + r, dword n / 4 of block b at (v_rd ^ 16 b) + 64 r
     const uint32_t v_rd = BITS == 8 ? T_V + (g >> 1) * 1024 + (g & 1) * 512 + (((n >> 2) ^ ((g & 1) * 4)) * 16) + (n & 3) * 4
                                     : T_V + g * 256 + g * 16 + (n >> 2) * 4;
-    const uint32_t m_rd = g * 16 * NGRP;        // meta of this lane's 4 tokens
+    // PACKED: token n of tile g / 2; of piece j (at ^ 16 j) the dwords g % 2 and 2 + g % 2.  (Letting the quarters of the
+    // second tile read the two dwords in the other order, so that the lanes of one read spread over 32 banks instead of 16,
+    // took eight single reads instead of four double ones and measured the same.)
+    const uint32_t k_rd_p = (g >> 1) * TILEB + n * 64 + ((n >> 2) & 3) * 16 + (g & 1) * 4;
+    const uint32_t m_rd = g * 16 * NGRP + (PACKED ? (n >> 3) * TILEB : 0);        // meta of this lane's 4 tokens (PACKED: of the tile its column belongs to)
     const uint32_t v_sel = 0x0c000c00u | ((4u + (n & 3)) << 16) | (uint32_t)(n & 3);     // INT4: byte n % 4 of two dwords into the low bytes of two halves
 
     // ---- this wave's list of items (an item is a tile for one KV head)
@@ -250,27 +269,33 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
         const int nsteps = (t1 - t0 + kStep - 1) / kStep;
 
         // ---- Q^T as the B operand of the four k-chunks: chunk j, slot g*8+e <-> channel (j/2)*64 + g*16 + (j%2)*8 + e
-        h8_t qop[4];
+        h8_t qop[NQ];
         float qs[NGRP];             // sum of this query head's q over the channels of a group
         {
             wait_newer(newer_than(20 + cr % RQ));
             // query row n sits at (n / 4) * 1024 + (n % 4) * 256 of the slot: row c*4+g was written by quarter g of load c
             const uint32_t qa = lds0 + OFF_Q + (cr % RQ) * QSLOT + ((n % QROWS) >> 2) * 1024 + (n & 3) * 256;
-            uint4 raw[4];
-            // INT8: chunk j, slot g*8+e <-> channel (j/2)*64 + g*16 + (j%2)*8 + e;  INT4: channel 32 j + 8 g + {0 4 1 5 2 6 3 7}[e]
-            if constexpr (BITS == 8) lds_read16x4(qa + g * 32, qa + g * 32 + 16, qa + 128 + g * 32, qa + 128 + g * 32 + 16, raw[0], raw[1], raw[2], raw[3]);
+            uint4 raw[NQ];
+            // INT8: chunk j, slot g*8+e <-> channel (j/2)*64 + g*16 + (j%2)*8 + e;  INT4: channel 32 j + 8 g + {0 4 1 5 2 6 3 7}[e];
+            // PACKED: product j, slot g*8+e <-> channel 16 j + 8 (g % 2) + {0 4 1 5 2 6 3 7}[e] of head n % 8, for the quarters of the column's tile
+            if constexpr (PACKED) {
+                const uint32_t qh = qa + (g & 1) * 16;
+                lds_read16x4(qh, qh + 32, qh + 64, qh + 96, raw[0], raw[1], raw[2], raw[3]);
+                lds_read16x4(qh + 128, qh + 160, qh + 192, qh + 224, raw[NQ - 4], raw[NQ - 3], raw[NQ - 2], raw[NQ - 1]);
+            } else if constexpr (BITS == 8) lds_read16x4(qa + g * 32, qa + g * 32 + 16, qa + 128 + g * 32, qa + 128 + g * 32 + 16, raw[0], raw[1], raw[2], raw[3]);
             else lds_read16x4(qa + g * 16, qa + 64 + g * 16, qa + 128 + g * 16, qa + 192 + g * 16, raw[0], raw[1], raw[2], raw[3]);
             float part_sum[NGRP];
 #pragma unroll
             for (int gr = 0; gr < NGRP; ++gr) part_sum[gr] = 0.0f;
+            const bool q_here = PACKED ? ((n & 7) < qper && (g >> 1) == (n >> 3)) : n < qper;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < NQ; ++j) {
                 h8_t v = pack8(raw[j].x, raw[j].y, raw[j].z, raw[j].w);
-                if (n >= qper) v = (h8_t)(_Float16)0.0f;
+                if (!q_here) v = (h8_t)(_Float16)0.0f;
                 float sacc = 0.0f;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) sacc += (float)v[e];
-                part_sum[j * NGRP / 4] += sacc;
+                part_sum[j * NGRP / NQ] += sacc;
                 if constexpr (BITS == 4) {
                     const _Float16 sixteenth = (_Float16)0.0625f;       // the odd nibbles arrive 16 times too large
                     const h8_t w = {v[0], v[4], v[1] * sixteenth, v[5] * sixteenth, v[2], v[6], v[3] * sixteenth, v[7] * sixteenth};
@@ -311,13 +336,19 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
         // tokens past the item's end; the other steps spend no comparison and no select.
         auto step = [&](auto masked_c, int k, uint32_t base) {
             constexpr bool MASKED = decltype(masked_c)::value;
-            // ---- S^T = K Q^T for the two 16-token tiles
-            float s[2][4];
-            uint32_t vmraw[2][4][NGRP];        // V (scale, zero) dwords of this lane's tokens; 0 where the token is masked
+            // ---- S^T = K Q^T for the two 16-token tiles (PACKED: both tiles in one, see above)
+            constexpr int NX = PACKED ? 1 : 2;      // tiles of S^T per step
+            float s[NX][4];
+            uint32_t vmraw[NX][4][NGRP];       // V (scale, zero) dwords of this lane's tokens; 0 where the token is masked
             float mx = kNegInf;
             uint4 kp[2][2];                // INT8: [tile][piece];  INT4: kp[tile][0] holds the dwords of the four chunks
+            uint32_t kd[4][2];             // PACKED: [piece][which of this lane's two dwords of it]
             const uint32_t ka0 = base + k_rd, ma = base + m_rd;
-            if constexpr (BITS == 8) {
+            if constexpr (PACKED) {
+                const uint32_t kb = base + k_rd_p;
+                const uint32_t ka[4] = {kb, kb ^ 16u, kb ^ 32u, kb ^ 48u};
+                lds_read2x4(ka, kd);
+            } else if constexpr (BITS == 8) {
                 const uint32_t ka1 = ka0 ^ 64u;
                 lds_read16x4_at<0, 0, TILEB, TILEB>(ka0, ka1, ka0, ka1, kp[0][0], kp[0][1], kp[1][0], kp[1][1]);
             } else {
@@ -327,8 +358,17 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
                 kp[0][0] = make_uint4(k0[0], k0[1], k0[2], k0[3]);
                 kp[1][0] = make_uint4(k1[0], k1[1], k1[2], k1[3]);
             }
-            uint4 kmeta[2][NGRP], vmeta[2][NGRP];
-            if constexpr (NGRP == 4) {
+            uint4 kmeta[NX][NGRP], vmeta[NX][NGRP];
+            if constexpr (PACKED) {         // the four tokens of this lane's column: one tile's worth
+                if constexpr (NGRP == 4) {
+                    lds_read16x4_at<T_KM, T_KM + 16, T_KM + 32, T_KM + 48>(ma, ma, ma, ma, kmeta[0][0], kmeta[0][1], kmeta[0][2], kmeta[0][3]);
+                    lds_read16x4_at<T_VM, T_VM + 16, T_VM + 32, T_VM + 48>(ma, ma, ma, ma, vmeta[0][0], vmeta[0][1], vmeta[0][2], vmeta[0][3]);
+                } else if constexpr (NGRP == 2) {
+                    lds_read16x4_at<T_KM, T_KM + 16, T_VM, T_VM + 16>(ma, ma, ma, ma, kmeta[0][0], kmeta[0][1], vmeta[0][0], vmeta[0][1]);
+                } else {
+                    lds_read16x2_at<T_KM, T_VM>(ma, ma, kmeta[0][0], vmeta[0][0]);
+                }
+            } else if constexpr (NGRP == 4) {
                 lds_read16x4_at<T_KM, T_KM + 16, T_KM + 32, T_KM + 48>(ma, ma, ma, ma, kmeta[0][0], kmeta[0][1], kmeta[0][2], kmeta[0][3]);
                 lds_read16x4_at<T_VM, T_VM + 16, T_VM + 32, T_VM + 48>(ma, ma, ma, ma, vmeta[0][0], vmeta[0][1], vmeta[0][2], vmeta[0][3]);
                 lds_read16x4_at<TILEB + T_KM, TILEB + T_KM + 16, TILEB + T_KM + 32, TILEB + T_KM + 48>(ma, ma, ma, ma, kmeta[1][0], kmeta[1][1],
@@ -343,14 +383,17 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
                                                                                                   vmeta[1][0], vmeta[1][1]);
             }
 #pragma unroll
-            for (int x = 0; x < 2; ++x) {
+            for (int x = 0; x < NX; ++x) {
                 f4_t acc[NGRP];
 #pragma unroll
                 for (int gr = 0; gr < NGRP; ++gr) acc[gr] = (f4_t)0.0f;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
+                for (int j = 0; j < NQ; ++j) {
                     h8_t a;
-                    if constexpr (BITS == 8) {
+                    if constexpr (PACKED) {
+                        const uint32_t w0 = kd[j >> 1][j & 1], w1 = w0 >> 8;
+                        a = pack8(w0 & 0x000F000Fu, w0 & 0x00F000F0u, w1 & 0x000F000Fu, w1 & 0x00F000F0u);
+                    } else if constexpr (BITS == 8) {
                         const uint4 piece = kp[x][j / 2];
                         const uint32_t w0 = (j % 2) ? piece.z : piece.x, w1 = (j % 2) ? piece.w : piece.y;
                         a = pack8(__builtin_amdgcn_perm(0u, w0, 0x0c010c00u), __builtin_amdgcn_perm(0u, w0, 0x0c030c02u),
@@ -360,10 +403,10 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
                         const uint32_t w0 = j == 0 ? d4.x : j == 1 ? d4.y : j == 2 ? d4.z : d4.w, w1 = w0 >> 8;
                         a = pack8(w0 & 0x000F000Fu, w0 & 0x00F000F0u, w1 & 0x000F000Fu, w1 & 0x00F000F0u);
                     }
-                    f4_t &dst = acc[j * NGRP / 4];
+                    f4_t &dst = acc[j * NGRP / NQ];
                     dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, qop[j], dst, 0, 0, 0);
                 }
-                const int room = t1 - (t0 + k * kStep + x * 16 + g * 4);        // row r of this lane's S^T block is a token of the item iff r < room
+                const int room = t1 - (t0 + k * kStep + (PACKED ? (n >> 3) : x) * 16 + g * 4);        // row r of this lane's S^T block is a token of the item iff r < room
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const bool valid = !MASKED || r < room;
@@ -385,6 +428,7 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
             if (__builtin_amdgcn_ballot_w64(mx > m_ref + lazy_t) != 0) {
                 float mq = fmaxf(mx, __shfl_xor(mx, 16));
                 mq = fmaxf(mq, __shfl_xor(mq, 32));
+                if constexpr (PACKED) mq = fmaxf(mq, __shfl_xor(mq, 8));        // columns n and n + 8 are the same head: one reference
                 m_ref = (mq > m_ref + lazy_t) ? mq : m_ref;
                 const float c_new = __builtin_fmaf(-m_ref, scale24, bias);
                 const float f = __builtin_amdgcn_exp2f(c_new - c_ref);
@@ -401,7 +445,7 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
             }
 
             // ---- a V scale of 2 or more in this step: the biased weights could leave the fp16 range (rare, wave-uniform)
-            if (bias != 0.0f && __builtin_amdgcn_ballot_w64(max_low_half<8 * NGRP>(&vmraw[0][0][0]) >= 0x4000u) != 0) {
+            if (bias != 0.0f && __builtin_amdgcn_ballot_w64(max_low_half<NX * 4 * NGRP>(&vmraw[0][0][0]) >= 0x4000u) != 0) {
                 bias = 0.0f;
                 const float c_new = __builtin_fmaf(-m_ref, scale24, 0.0f);
                 const float fb = __builtin_amdgcn_exp2f(c_new - c_ref);
@@ -416,8 +460,12 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
             // ---- weights p * lambda_v as fp16 high + low parts, in the A-operand order (tile, row).  The high
             // part is the product truncated to fp16, the low part what is left of the exact product.
             h8_t a_hi[NGRP], a_lo[NGRP];
+            if constexpr (PACKED) {
 #pragma unroll
-            for (int x = 0; x < 2; ++x)
+                for (int gr = 0; gr < NGRP; ++gr) a_hi[gr] = a_lo[gr] = (h8_t)(_Float16)0.0f;     // slots 4..7 are filled below
+            }
+#pragma unroll
+            for (int x = 0; x < NX; ++x)
 #pragma unroll
                 for (int rr = 0; rr < 4; rr += 2) {
                     float pj[2];
@@ -443,6 +491,22 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
                         }
                     }
                 }
+
+            if constexpr (PACKED) {
+                // k-slots 4..7 of the A operand are the second tile's tokens: the weights that column n + 8 holds for the
+                // same head (a rotation by 8 inside the row of 16 lanes; rows 8..15 of the product are not used)
+#pragma unroll
+                for (int gr = 0; gr < NGRP; ++gr) {
+                    typedef int32_t i4_t __attribute__((ext_vector_type(4)));
+                    i4_t hi = __builtin_bit_cast(i4_t, a_hi[gr]), lo = __builtin_bit_cast(i4_t, a_lo[gr]);
+                    hi.z = __builtin_amdgcn_update_dpp(0, hi.x, 0x128, 0xf, 0xf, true);
+                    hi.w = __builtin_amdgcn_update_dpp(0, hi.y, 0x128, 0xf, 0xf, true);
+                    lo.z = __builtin_amdgcn_update_dpp(0, lo.x, 0x128, 0xf, 0xf, true);
+                    lo.w = __builtin_amdgcn_update_dpp(0, lo.y, 0x128, 0xf, 0xf, true);
+                    a_hi[gr] = __builtin_bit_cast(h8_t, hi);
+                    a_lo[gr] = __builtin_bit_cast(h8_t, lo);
+                }
+            }
 
             // ---- O += P V
             if constexpr (BITS == 8) {
@@ -524,11 +588,13 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
         fill();                     // the stage just freed: keep loads in flight through the item's end and the next one's start
         float l = l_part + __shfl_xor(l_part, 16);
         l += __shfl_xor(l, 32);
+        if constexpr (PACKED) l += __shfl_xor(l, 8);       // the head's other column (the tokens of the second tiles)
         float zsum[NGRP];
 #pragma unroll
         for (int gr = 0; gr < NGRP; ++gr) {
             float v = z_part[gr] + __shfl_xor(z_part[gr], 16);
             v += __shfl_xor(v, 32);
+            if constexpr (PACKED) v += __shfl_xor(v, 8);
             zsum[gr] = v;
         }
 #pragma unroll

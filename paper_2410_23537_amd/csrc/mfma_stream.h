@@ -87,6 +87,13 @@ __device__ __forceinline__ void lds_read16x4_at(uint32_t a0, uint32_t a1, uint32
                  : "=&v"(r0), "=&v"(r1), "=&v"(r2), "=&v"(r3)
                  : "v"(a0), "v"(a1), "v"(a2), "v"(a3), "n"(O0), "n"(O1), "n"(O2), "n"(O3) : "memory");
 }
+// two 16-byte reads with compile-time byte offsets, one wait
+template <int O0, int O1>
+__device__ __forceinline__ void lds_read16x2_at(uint32_t a0, uint32_t a1, uint4 &r0, uint4 &r1)
+{
+    asm volatile("ds_read_b128 %0, %2 offset:%4\n\tds_read_b128 %1, %3 offset:%5\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(r0), "=&v"(r1) : "v"(a0), "v"(a1), "n"(O0), "n"(O1) : "memory");
+}
 // eight addresses a[set * 4 + r], each read at + r * ROW and at + r * ROW + OFF: r0[i] and r1[i]; one wait
 template <int ROW, int OFF>
 __device__ __forceinline__ void lds_read4x8x2(const uint32_t (&a)[8], uint32_t (&r0)[8], uint32_t (&r1)[8])
@@ -116,6 +123,18 @@ __device__ __forceinline__ void lds_read4x4x2(const uint32_t (&a)[4], uint32_t (
                  : "=&v"(r0[0]), "=&v"(r0[1]), "=&v"(r0[2]), "=&v"(r0[3]), "=&v"(r1[0]), "=&v"(r1[1]), "=&v"(r1[2]), "=&v"(r1[3])
                  : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "n"(OFF)
                  : "memory");
+}
+// four addresses, the dwords at +0 and +8 of each (one two-dword read per address): r[i][0] = [a[i]], r[i][1] = [a[i] + 8]; one wait
+__device__ __forceinline__ void lds_read2x4(const uint32_t (&a)[4], uint32_t (&r)[4][2])
+{
+    typedef uint32_t u2_t __attribute__((ext_vector_type(2)));
+    u2_t r0, r1, r2, r3;
+    asm volatile("ds_read2_b32 %0, %4 offset1:2\n\tds_read2_b32 %1, %5 offset1:2\n\t"
+                 "ds_read2_b32 %2, %6 offset1:2\n\tds_read2_b32 %3, %7 offset1:2\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(r0), "=&v"(r1), "=&v"(r2), "=&v"(r3) : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]) : "memory");
+    r[0][0] = r0.x; r[0][1] = r0.y; r[1][0] = r1.x; r[1][1] = r1.y;
+    r[2][0] = r2.x; r[2][1] = r2.y; r[3][0] = r3.x; r[3][1] = r3.y;
 }
 // two addresses, each read at + r * ROW (r = 0..3) and at + r * ROW + OFF: a0 -> (p0, p1), a1 -> (q0, q1); one wait
 template <int ROW, int OFF>

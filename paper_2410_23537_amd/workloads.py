@@ -77,6 +77,12 @@ CONFIGS: Dict[str, Workload] = {
 }
 
 
+# Variants of the configurations above that the benchmark can also be pointed at (bench.py --workload): not part of
+# the contract's five, used to measure kernels that none of the five selects.
+CONFIGS["gqa70b_int4"] = replace(CONFIGS["gqa70b"], name="gqa70b_int4", bits=4, G=32)      # the grouped-query kernel on INT4 codes
+CONFIGS["gqa70b_int4_g128"] = replace(CONFIGS["gqa70b"], name="gqa70b_int4_g128", bits=4, G=128)
+
+
 def scaled(w: Workload, B: int, max_len: int, name: str | None = None) -> Workload:
     """Same head geometry and length law, fewer requests and a lower length cap."""
     return replace(w, B=B, max_len=max_len, name=name or f"{w.name}_small")
