@@ -535,6 +535,7 @@ static int check_prefill_sizes(const CacheView &cv, int32_t B, int32_t total_q, 
     if (B < 0 || total_q < 0 || H <= 0 || max_len < 0) return ALISE_INVALID_ARGUMENT;
     if (H % cv.Hkv != 0) return ALISE_UNSUPPORTED;
     if ((int64_t)total_q * H >= (int64_t)1 << 31) return ALISE_UNSUPPORTED;
+    if (((int64_t)total_q + B + 8) * cv.Hkv >= (int64_t)1 << 31) return ALISE_UNSUPPORTED;       // workgroups of the matrix-core kernels: (row tile, KV head) pairs
     if (!alise::prefill_mfma_applies(cv, H)) {
         const int64_t blocks_per_row = std::max<int64_t>(1, ((int64_t)max_len + cv.P - 1) / cv.P);
         if ((int64_t)total_q * blocks_per_row >= (int64_t)1 << 31) return ALISE_UNSUPPORTED;

@@ -82,7 +82,11 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
     // lane instead of eight half-useful ones.  The weights of column n + 8 travel to lane n (a rotation by 8 inside
     // the row of 16 lanes) to complete the A operand of the second product, whose k-slot order -- four tokens of the
     // first tile, then four of the second -- is the one it had.  Columns n and n + 8 are the same head: they share one
-    // softmax reference, and their denominators and zero-point sums are added at the end.
+    // softmax reference, and their denominators and zero-point sums are added at the end.  The second product has the
+    // same spare half: rows 8..15 of its A operand belong to no head, so they carry the low parts of the weights and
+    // one product per V operand does what took two (the low sums land in rows 8..15 of O and join rows 0..7 at the
+    // end of the item).  On this chip matrix and vector instructions of a SIMD's waves hardly overlap (a probe with
+    // independent chains of both: 8.4 ms together against 5.5 and 4.8 ms alone), so every instruction saved counts.
     constexpr bool PACKED = BITS == 4 && QROWS == 8;
     constexpr int NQ = PACKED ? 8 : 4;          // products (k-chunks) per tile of S^T
     constexpr int OFF_DESC = S * STEPB, OFF_PG = OFF_DESC + RD * 16, OFF_Q = OFF_PG + RG * 256;
@@ -493,18 +497,22 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
                 }
 
             if constexpr (PACKED) {
-                // k-slots 4..7 of the A operand are the second tile's tokens: the weights that column n + 8 holds for the
-                // same head (a rotation by 8 inside the row of 16 lanes; rows 8..15 of the product are not used)
+                // One A operand instead of two.  Its rows 0..7 are the heads' high parts -- k-slots 0..3 the lane's own
+                // (first tile), k-slots 4..7 the ones that column n + 8 holds for the same head (second tile) -- and its rows
+                // 8..15, which no head uses, are the heads' LOW parts, so that one product per V operand accumulates the high
+                // sums in rows 0..7 and the low sums in rows 8..15 of O; they are added at the end of the item.  Each dword is
+                // one rotation by 8 inside the row of 16 lanes that only half of the lanes take (bank mask), the others keeping
+                // their own part.
 #pragma unroll
                 for (int gr = 0; gr < NGRP; ++gr) {
                     typedef int32_t i4_t __attribute__((ext_vector_type(4)));
-                    i4_t hi = __builtin_bit_cast(i4_t, a_hi[gr]), lo = __builtin_bit_cast(i4_t, a_lo[gr]);
-                    hi.z = __builtin_amdgcn_update_dpp(0, hi.x, 0x128, 0xf, 0xf, true);
-                    hi.w = __builtin_amdgcn_update_dpp(0, hi.y, 0x128, 0xf, 0xf, true);
-                    lo.z = __builtin_amdgcn_update_dpp(0, lo.x, 0x128, 0xf, 0xf, true);
-                    lo.w = __builtin_amdgcn_update_dpp(0, lo.y, 0x128, 0xf, 0xf, true);
-                    a_hi[gr] = __builtin_bit_cast(h8_t, hi);
-                    a_lo[gr] = __builtin_bit_cast(h8_t, lo);
+                    const i4_t hi = __builtin_bit_cast(i4_t, a_hi[gr]), lo = __builtin_bit_cast(i4_t, a_lo[gr]);
+                    i4_t c;
+                    c.x = __builtin_amdgcn_update_dpp(hi.x, lo.x, 0x128, 0xf, 0xc, false);      // lanes 8..15: the low part of lane n - 8
+                    c.y = __builtin_amdgcn_update_dpp(hi.y, lo.y, 0x128, 0xf, 0xc, false);
+                    c.z = __builtin_amdgcn_update_dpp(lo.x, hi.x, 0x128, 0xf, 0x3, false);      // lanes 0..7: the high part of lane n + 8
+                    c.w = __builtin_amdgcn_update_dpp(lo.y, hi.y, 0x128, 0xf, 0x3, false);
+                    a_hi[gr] = __builtin_bit_cast(h8_t, c);
                 }
             }
 
@@ -549,7 +557,7 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
                             const int gr = b * NGRP / 4;
                             f4_t &dst = o[b * 2 + m];
                             dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_hi[gr], bv, dst, 0, 0, 0);
-                            dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_lo[gr], bv, dst, 0, 0, 0);
+                            if constexpr (!PACKED) dst = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_lo[gr], bv, dst, 0, 0, 0);
                         }
                     }
                 }
@@ -586,6 +594,12 @@ __global__ __launch_bounds__(64) void decode_attn_gqa_kernel(AttnParams p)
 
         // ---- per query head: add the four quarters; then fetch the values of this lane's rows
         fill();                     // the stage just freed: keep loads in flight through the item's end and the next one's start
+        if constexpr (PACKED) {        // rows 8..15 of O hold the sums of the low parts: quarter g + 2 has them for the rows of quarter g
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) o[t][r] += __shfl_xor(o[t][r], 32);
+        }
         float l = l_part + __shfl_xor(l_part, 16);
         l += __shfl_xor(l, 32);
         if constexpr (PACKED) l += __shfl_xor(l, 8);       // the head's other column (the tokens of the second tiles)

@@ -138,11 +138,17 @@ __device__ __forceinline__ void prefill_attn_body(const PrefillParams &p)
     // undone at the output) to another.
     __shared__ __attribute__((aligned(128))) uint8_t lds[S * STEPB + 4 * 512];     // stages, then two page-window slots per wave
 
-    const int f = blockIdx.x;
+    // Workgroups start in the order of their number, so the KV head is its fast index: the table is sorted by the
+    // length of the walk, and every head's longest tiles must start before anybody's short ones.  (With the head as
+    // the slow index the last head's longest walk began when the grid was almost through; on chunk mixes with a few
+    // long contexts a fifth to a third of the time went into that tail.  Workgroup w runs on XCD w % 8, so with a
+    // multiple of 8 heads all row tiles of one request and head also share an L2.  Runs of 2 or 8 consecutive table
+    // entries per head before the next head measured within a few per cent of this, either way.)
+    const int f = blockIdx.x / p.c.Hkv;
+    const int hk = blockIdx.x - f * p.c.Hkv;
     if (f >= *p.ws.n_tiles) return;             // workgroup-uniform, before any barrier
     const int2 entry = p.ws.table[f];
     const int i = min(max(entry.x, 0), p.B - 1), rt = max(entry.y, 0);
-    const int hk = blockIdx.y;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -672,7 +678,7 @@ hipError_t launch_prefill_attn(const CacheView &c, const void *q, void *out, con
                        prefill_tokens_per_workgroup(p.qper, rt), max_context_len, ws);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const dim3 grid((unsigned)ws.max_tiles, (unsigned)c.Hkv);         // sized for one row tile per wave: enough for two
+    const dim3 grid((unsigned)ws.max_tiles * (unsigned)c.Hkv);        // sized for one row tile per wave: enough for two
     const bool one_group = c.D / c.G == 1;
     const bool split = prefill_split_weights();
 #define ALISE_PREFILL_LAUNCH(NAME)                                                    \
