@@ -328,3 +328,30 @@ def test_build_names_the_compiler_the_kernels_were_validated_with():
         ok = build.check_compiler()
     assert ok == banner.startswith(build.VALIDATED_COMPILER)
     assert ok == (not any("validated" in str(w.message) for w in seen))
+
+
+def test_bench_reports_traffic_only_for_the_sources_it_was_measured_with(tmp_path, monkeypatch):
+    """bench.py takes roofline.traffic from the rocprofv3 summary of the workload, which names the hash of the attention
+    sources the counters were taken with: a summary of other sources, or none, gives null and a note."""
+    import bench
+    now = bench.attention_sources_sha256()
+    assert len(now) == 16 and int(now, 16) >= 0
+    monkeypatch.setattr(bench, "PROFILES", str(tmp_path))
+    assert bench.measured_traffic("int4")[0] is None                            # no summary at all
+    (tmp_path / "attention_step_int4.md").write_text(f"# x\ntraffic_bytes_per_launch: 7191314368\nattention_sources_sha256: {now}\n")
+    got, note = bench.measured_traffic("int4")
+    assert got == 7191314368 and now in note
+    (tmp_path / "attention_step_int4.md").write_text("# x\ntraffic_bytes_per_launch: 7191314368\nattention_sources_sha256: 0123456789abcdef\n")
+    got, note = bench.measured_traffic("int4")
+    assert got is None and "profile again" in note
+    (tmp_path / "attention_step_int4.md").write_text("# a summary without the two lines\n")
+    assert bench.measured_traffic("int4")[0] is None
+
+
+def test_committed_profiles_match_the_committed_sources():
+    """The summaries under profiles/ were taken with the attention sources as they are committed: bench.py will
+    report their traffic figures."""
+    import bench
+    for name in ("int4", "llama7b", "gqa70b", "opt13b"):
+        got, note = bench.measured_traffic(name)
+        assert got is not None and got > 0, note

@@ -152,3 +152,32 @@ def test_full_size_prefill_sampled_against_oracle(env, name):
             worst = max(worst, err)
             assert err <= ATTN_TOL, f"request {i} (L={L}) query {j}: max-abs {err}"
     print(f"  worst sampled prefill error {worst:.3e}", flush=True)
+
+
+def test_full_size_prefill_whole_output_against_oracle(env):
+    """The prefill leg of the OPT-13B-shaped configuration, every query token of it: the one configuration whose
+    whole prefill output the oracle attends in seconds (2 599 query tokens, 1.3 M (query, key) pairs per head)."""
+    B, torch, oracle, DecodeStep = env
+    w = wl.CONFIGS["opt13b"]
+    st = DecodeStep(w)
+    st.populate(include_step_tokens=True)
+    cache = st.caches[0]
+    lens = st.lens.astype(np.int64)
+    n = np.array([min(512, int(L)) if i % 8 == 0 else 0 for i, L in enumerate(lens)], np.int64)
+    q_start = np.concatenate([[0], np.cumsum(n)]).astype(np.int32)
+    total = int(q_start[-1])
+    print(f"case full-size prefill, whole output, opt13b: {total} query tokens", flush=True)
+    rng = np.random.default_rng(w.seed + 6)
+    q_np = rng.standard_normal((total, w.H, w.D)).astype(np.float16)
+    q = torch.from_numpy(q_np).cuda()
+    out = torch.full(q.shape, float("nan"), dtype=torch.float16, device="cuda")
+    ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(cache, w.B, total, w.H, int(st.lens.max())), dtype=torch.uint8, device="cuda")
+    B.alise_paged_prefill_attn(cache, q, out, torch.from_numpy(q_start).cuda(), torch.from_numpy(st.pg.block_tables).cuda(),
+                               torch.from_numpy(st.lens.astype(np.int32)).cuda(), int(st.lens.max()), st.scale, ws)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    orc = _oracle_cache_of_whole_batch(oracle, st)
+    want = oracle.paged_prefill_attn(orc, q_np, q_start, st.pg.block_tables, st.lens, st.scale, num_threads=16)
+    err = np.abs(got - want)
+    assert np.isfinite(got).all() and (err <= ATTN_TOL).all(), f"worst {np.nanmax(err)}"
+    print(f"  all {err.size} prefill outputs within {ATTN_TOL}: worst {err.max():.3e}", flush=True)
