@@ -69,6 +69,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only-steps", action="store_true",
                     help="skip the legs outside the timed steps (swap, prefill, fused operators, scheduler): for profiler runs")
+    ap.add_argument("--only-prefill", action="store_true",
+                    help="after the timed steps run only the prefill leg with a chunk from every request: for profiler runs")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also launch an elementwise kernel that reads and writes exactly 1 GiB, so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run of this command can be scaled")
@@ -355,6 +357,31 @@ def read_ceiling_leg():
                     "nothing else; median of 10 calls, the call's two launches included"}
 
 
+def issue_overlap_leg():
+    """What bounds the matrix-core kernels: the library's issue probe (alise_issue_overlap_probe) with matrix instructions
+    alone, vector instructions alone, and both in the same waves, two waves per SIMD.  If the two kinds ran side by side
+    `both` would be the longer of the two; on this chip it is close to their sum, so a step of those kernels costs
+    about the sum of its instruction times."""
+    import torch
+    from paper_2410_23537_amd import binding as B
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    iters, out = 20000, {}
+    for name, mode in (("mfma_only_ms", 1), ("valu_only_ms", 2), ("both_ms", 3)):
+        B.alise_issue_overlap_probe(mode, 100, sink)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        B.alise_issue_overlap_probe(mode, iters, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = e0.elapsed_time(e1)
+    hidden = out["mfma_only_ms"] + out["valu_only_ms"] - out["both_ms"]
+    out["overlap_fraction_of_the_shorter"] = hidden / min(out["mfma_only_ms"], out["valu_only_ms"])
+    out["note"] = ("per wave and round: 16 v_mfma_f32_16x16x32_f16 and / or 64 v_fma_f32, independent chains, two waves per SIMD, "
+                   f"{iters} rounds; 1.0 would mean the shorter kind is hidden behind the longer one, 0.0 that their times add up")
+    return out
+
+
 def fused_ops_leg(w):
     """The two other fused operators of the layer (Sec. 3.3 "Implementation"), outside the timed
     steps, on a token batch of this workload's model: 16384 tokens (prefill chunks of an iteration;
@@ -608,7 +635,9 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_note": traffic_note,
                      "attention_sources_sha256": attention_sources_sha256()},
     }
-    if not args.only_steps:
+    if args.only_prefill:
+        result["prefill_full_batch"] = prefill_leg(w, step, every=1)
+    elif not args.only_steps:
         ceiling = read_ceiling_leg()
         result["hbm_read_ceiling"] = ceiling
         result["roofline"]["frac_of_read_ceiling"] = achieved / ceiling["GBs"]
@@ -632,6 +661,7 @@ def main():
         if args.workload == "int4":
             # the other three benchmark configurations, one after another (each built, timed and freed)
             result["all_configs"] = {n: other_config_leg(n, args.steps, args.warmup) for n in ("opt13b", "llama7b", "gqa70b")}
+        result["issue_overlap"] = issue_overlap_leg()
         result["fused_ops"] = fused_ops_leg(w)
         result["scheduler"] = scheduled_run_leg(w)
     if not args.no_cpu_baseline:

@@ -78,6 +78,20 @@ int alise_bias_relu(const void *x, const void *bias, void *y_out, int64_t rows, 
  */
 int alise_hbm_read_probe(const void *src, size_t bytes, void *xor_out, void *hip_stream);
 
+/*
+ * Issue probe: a measurement utility, not an operation of the paper.  The chunked-prefill and the
+ * grouped-query kernels mix matrix instructions with the vector instructions that dequantize and
+ * form the softmax weights; what bounds them depends on whether the two kinds run side by side on
+ * a SIMD.  Every wave of a launch that gives each SIMD two waves runs `iters` rounds of
+ *   mode 1: 16 independent v_mfma_f32_16x16x32_f16,
+ *   mode 2: 64 independent v_fma_f32 (about the same time as mode 1 when run alone),
+ *   mode 3: both.
+ * The caller times the three launches (bench.py: `issue_overlap`).  Nothing of interest is
+ * written; `sink` (device, one float, 4-byte aligned) only keeps the instruction chains alive.
+ * iters in [0, 2^24]; another mode returns ALISE_UNSUPPORTED.
+ */
+int alise_issue_overlap_probe(int32_t mode, int32_t iters, void *sink, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

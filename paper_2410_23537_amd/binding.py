@@ -35,7 +35,7 @@ EXPORTS = ("alise_kv_codes_bytes", "alise_kv_meta_bytes", "alise_kv_quant_write"
            "alise_paged_decode_attn_plan", "alise_paged_decode_attn_planned", "alise_paged_decode_attn_static",
            "alise_kv_dequant_page", "alise_kv_swap_bytes", "alise_kv_swap_out", "alise_kv_swap_in",
            "alise_paged_prefill_attn_workspace_bytes", "alise_paged_prefill_attn",
-           "alise_add_layernorm", "alise_bias_relu", "alise_hbm_read_probe",
+           "alise_add_layernorm", "alise_bias_relu", "alise_hbm_read_probe", "alise_issue_overlap_probe",
            "alise_sched_create", "alise_sched_destroy", "alise_sched_add_job", "alise_sched_num_jobs",
            "alise_sched_step", "alise_sched_commit",
            "alise_reload_environment", "alise_status_string")
@@ -97,6 +97,8 @@ _lib.alise_hbm_read_probe.restype = ctypes.c_int
 _lib.alise_hbm_read_probe.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
 _lib.alise_reload_environment.restype = None
 _lib.alise_reload_environment.argtypes = []
+_lib.alise_issue_overlap_probe.restype = ctypes.c_int
+_lib.alise_issue_overlap_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
 _lib.alise_status_string.restype = ctypes.c_char_p
 _lib.alise_status_string.argtypes = [ctypes.c_int]
 
@@ -353,6 +355,13 @@ def alise_hbm_read_probe(src: torch.Tensor, xor_out: torch.Tensor) -> None:
     assert src.is_cuda and src.is_contiguous() and xor_out.is_cuda and xor_out.numel() == 1 and xor_out.element_size() == 4
     st = _lib.alise_hbm_read_probe(_dp(src), src.numel() * src.element_size(), _dp(xor_out), _stream())
     _check(st, "alise_hbm_read_probe")
+
+
+def alise_issue_overlap_probe(mode: int, iters: int, sink: torch.Tensor) -> None:
+    """mode 1: matrix instructions, 2: vector instructions, 3: both; sink: float32 [1], device."""
+    assert sink.is_cuda and sink.dtype == torch.float32 and sink.numel() == 1
+    st = _lib.alise_issue_overlap_probe(int(mode), int(iters), _dp(sink), _stream())
+    _check(st, "alise_issue_overlap_probe")
 
 
 class alise_sched_config(ctypes.Structure):

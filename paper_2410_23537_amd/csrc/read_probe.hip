@@ -74,8 +74,62 @@ __global__ __launch_bounds__(256) void read_probe_kernel(const u32x4_t *__restri
     if (lane == 0 && acc != 0u) atomicXor(sink, acc);
 }
 
+// Issue probe: do the matrix instructions and the ordinary vector instructions of a SIMD's waves run side by side?
+// Every wave runs `iters` rounds of 16 independent v_mfma_f32_16x16x32_f16 (four accumulator chains; 16 x 16 cycles
+// at the published rate) and/or 64 independent v_fma_f32 (eight chains; 64 x 4 cycles): about equal times when run
+// alone.  The launch gives every SIMD two waves.  If the two kinds overlapped, both together would take as long as
+// the longer one; the matrix-core attention kernels' roofline is derived from what this measures instead.
+typedef _Float16 probe_h8_t __attribute__((ext_vector_type(8)));
+typedef float probe_f4_t __attribute__((ext_vector_type(4)));
+
+template <int MODE>
+__global__ __launch_bounds__(256) void issue_probe_kernel(float *sink, int iters)
+{
+    probe_h8_t a = (probe_h8_t)(_Float16)(threadIdx.x * 0.001f), b = (probe_h8_t)(_Float16)1.0f;
+    probe_f4_t c0 = (probe_f4_t)0.0f, c1 = c0, c2 = c0, c3 = c0;
+    float x0 = threadIdx.x, x1 = 1.0f, x2 = 2.0f, x3 = 3.0f, x4 = 4.0f, x5 = 5.0f, x6 = 6.0f, x7 = 7.0f;
+    const float m = 1.0001f, d = 0.5f;
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (MODE & 1) {
+                c0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c0, 0, 0, 0);
+                c1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c1, 0, 0, 0);
+                c2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c2, 0, 0, 0);
+                c3 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c3, 0, 0, 0);
+            }
+            if (MODE & 2) {
+#pragma unroll
+                for (int v = 0; v < 2; ++v) {
+                    x0 = __builtin_fmaf(x0, m, d); x1 = __builtin_fmaf(x1, m, d); x2 = __builtin_fmaf(x2, m, d); x3 = __builtin_fmaf(x3, m, d);
+                    x4 = __builtin_fmaf(x4, m, d); x5 = __builtin_fmaf(x5, m, d); x6 = __builtin_fmaf(x6, m, d); x7 = __builtin_fmaf(x7, m, d);
+                }
+            }
+        }
+    }
+    const float r = x0 + x1 + x2 + x3 + x4 + x5 + x6 + x7 + c0[0] + c1[1] + c2[2] + c3[3];
+    if (r == 12345.678f) sink[0] = r;           // never true for these inputs; keeps the chains alive
+}
+
 }  // namespace
 }  // namespace alise
+
+extern "C" int alise_issue_overlap_probe(int32_t mode, int32_t iters, void *sink, void *hip_stream)
+{
+    using namespace alise;
+    if (!sink || iters < 0 || iters > (1 << 24)) return ALISE_INVALID_ARGUMENT;
+    if (mode < 1 || mode > 3) return ALISE_UNSUPPORTED;
+    if (reinterpret_cast<uintptr_t>(sink) & 3u) return ALISE_MISALIGNED;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        return ALISE_HIP_ERROR;
+    const dim3 grid((unsigned)cus * 2u), block(256);        // two workgroups of four waves per compute unit: two waves per SIMD
+    if (mode == 1) hipLaunchKernelGGL(issue_probe_kernel<1>, grid, block, 0, s, static_cast<float *>(sink), iters);
+    else if (mode == 2) hipLaunchKernelGGL(issue_probe_kernel<2>, grid, block, 0, s, static_cast<float *>(sink), iters);
+    else hipLaunchKernelGGL(issue_probe_kernel<3>, grid, block, 0, s, static_cast<float *>(sink), iters);
+    return hipGetLastError() == hipSuccess ? ALISE_OK : ALISE_HIP_ERROR;
+}
 
 extern "C" int alise_hbm_read_probe(const void *src, size_t bytes, void *xor_out, void *hip_stream)
 {

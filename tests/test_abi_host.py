@@ -316,6 +316,12 @@ def test_fused_op_arguments(B):
     assert probe(src=A + 8) == B.ALISE_MISALIGNED
     assert probe(out=A + 2) == B.ALISE_MISALIGNED
 
+    issue = lambda mode=3, iters=10, sink=A: lib.alise_issue_overlap_probe(mode, iters, sink, None)
+    assert issue(sink=None) == B.ALISE_INVALID_ARGUMENT
+    assert issue(iters=-1) == B.ALISE_INVALID_ARGUMENT and issue(iters=(1 << 24) + 1) == B.ALISE_INVALID_ARGUMENT
+    assert issue(mode=0) == B.ALISE_UNSUPPORTED and issue(mode=4) == B.ALISE_UNSUPPORTED
+    assert issue(sink=A + 2) == B.ALISE_MISALIGNED
+
 
 def test_build_names_the_compiler_the_kernels_were_validated_with():
     """The hand-placed wait states of the kernels were validated with one compiler; the build warns about any other."""

@@ -165,3 +165,15 @@ def test_read_probe_folds_every_word_once(env, n16):
     torch.cuda.synchronize()
     want = int(np.bitwise_xor.reduce(host)) if n16 else 0
     assert int(out.cpu().numpy().view(np.uint32)[0]) == want
+
+
+def test_issue_probe_runs_in_all_three_modes(env):
+    """The issue probe (matrix instructions, vector instructions, both) is a timing utility: it must run, end, and
+    leave its sink alone."""
+    B, torch, _ = env
+    sink = torch.full((1,), 3.5, dtype=torch.float32, device="cuda")
+    for mode in (1, 2, 3):
+        B.alise_issue_overlap_probe(mode, 50, sink)
+    B.alise_issue_overlap_probe(3, 0, sink)
+    torch.cuda.synchronize()
+    assert float(sink[0]) == 3.5
