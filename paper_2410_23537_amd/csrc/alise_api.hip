@@ -428,7 +428,6 @@ static int decode_attn_call(const alise_kv_cache *c, const void *q, void *out,
     hipError_t e = alise::launch_decode_attn(cv, q, out, block_tables, max_blocks_per_seq, context_lens, B,
                                              num_q_heads, max_context_len, softmax_scale, ws,
                                              num_compute_units(), alise::tuning().waves_per_cu, alise::tuning().loads_per_block,
-                                             alise::tuning().min_items_per_wave,
                                              phases, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? ALISE_OK : ALISE_HIP_ERROR;
 }
@@ -604,7 +603,7 @@ int alise_paged_prefill_attn(const alise_kv_cache *c, const void *q, void *out, 
         carve_workspace(cv, total_q_tokens, num_q_heads, max_context_len, fb.attn_workspace, &aws, false);
         e = alise::launch_decode_attn(cv, q, out, fb.tables, fb.blocks_per_row, fb.lens, total_q_tokens, num_q_heads, max_context_len,
                                       softmax_scale, aws, num_compute_units(), alise::tuning().waves_per_cu,
-                                      alise::tuning().loads_per_block, alise::tuning().min_items_per_wave,
+                                      alise::tuning().loads_per_block,
                                       alise::kPhasePlan | alise::kPhaseRun | alise::kPhaseKeepNegative, hs);
         return e == hipSuccess ? ALISE_OK : ALISE_HIP_ERROR;
     }

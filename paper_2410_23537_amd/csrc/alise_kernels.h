@@ -91,7 +91,7 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
                               const int32_t *context_lens, int32_t B, int32_t H,
                               int32_t max_context_len, float softmax_scale,
                               const AttnWorkspace &ws, int32_t num_cus, int32_t waves_per_cu,
-                              int32_t loads_per_block, int32_t min_items_per_wave, int32_t phases, hipStream_t s);
+                              int32_t loads_per_block, int32_t phases, hipStream_t s);
 // phases of launch_decode_attn: the plan (needs only the lengths; q, out and block_tables may be null) and the run;
 // kPhaseKeepNegative: a request with a negative length is no request at all and its output row is left alone (by default it
 // is an empty request and gets a zero row)

@@ -835,7 +835,7 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
                               const int32_t *context_lens, int32_t B, int32_t H,
                               int32_t max_context_len, float softmax_scale,
                               const AttnWorkspace &ws, int32_t num_cus, int32_t waves_per_cu,
-                              int32_t loads_per_block, int32_t min_items_per_wave, int32_t phases, hipStream_t s)
+                              int32_t loads_per_block, int32_t phases, hipStream_t s)
 {
     if (B == 0) return hipSuccess;
     AttnParams p;
@@ -855,7 +855,6 @@ hipError_t launch_decode_attn(const CacheView &c, const void *q, void *out,
     // the plan kernel shortens the splits until every wave of a full grid (about eight waves
     // per compute unit) would get this many items; the matrix-core kernel, whose items are
     // heavier to start, asks for one
-    (void)min_items_per_wave;
     p.ws.min_items = plan_min_items(num_cus, gqa);
     p.zero_empty = (phases & kPhasePlan) ? 0 : 1;
     hipError_t e = hipSuccess;
