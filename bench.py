@@ -424,7 +424,8 @@ def scheduled_run_leg(w):
     run of 192 synthetic jobs through one attention layer of this workload's shape on the GPU --
     prompts through quantize-and-write + chunked prefill, every later token through
     quantize-and-write + decode attention, preempted jobs offloaded to pinned host memory and
-    uploaded again as Alg. 2 decides -- with the wall clock around it."""
+    uploaded again as Alg. 2 decides -- with the wall clock around it, once through the C++ loop of
+    alise_replay.h and once through the Python loop of replay.py."""
     import numpy as np
     import torch
     from paper_2410_23537_amd import binding as B
@@ -466,8 +467,7 @@ def scheduled_run_leg(w):
         idx = torch.from_numpy(np.concatenate([np.arange((id * 7919) % pool_n + a, (id * 7919) % pool_n + b) for id, a, b in spans])).cuda()
         return pk.index_select(0, idx), pv.index_select(0, idx), pq.index_select(0, idx)
 
-    def run_once():
-        rp = Replay(w, B.Scheduler(**cfg, want_order=False), num_pages=2 * (M + 1) * pages_per_job, max_context=max_ctx, kv_source=source)
+    def drive(add_job, num_jobs, iterate, commit):
         order = sorted(range(n_jobs), key=lambda i: (arrival[i], i))
         k, now, produced = 0, 0, [0] * n_jobs
         torch.cuda.synchronize()
@@ -475,36 +475,54 @@ def scheduled_run_leg(w):
         while True:
             while k < n_jobs and arrival[order[k]] <= now:
                 i = order[k]
-                rp.add_job(i, arrival[i], s[i], n_pred[i])
+                add_job(i)
                 k += 1
-            if rp.sched.num_jobs() == 0:
+            if num_jobs() == 0:
                 if k == n_jobs:
                     break
                 now = arrival[order[k]]
                 continue
-            d = rp.iterate()
+            d = iterate()
             fin = []
             for id in d["batch"]:
                 produced[id] += 1
                 if produced[id] >= n_true[id]:
                     fin.append(id)
-            rp.commit(d["model_time"], fin)
+            commit(d["model_time"], fin)
             now += d["model_time"]
         torch.cuda.synchronize()
-        return rp, time.perf_counter() - t0
+        return time.perf_counter() - t0
 
-    run_once()                      # the first run pays for pinned allocations and one-time queries
-    rp, dt = run_once()
-    st = rp.stats
-    out["scheduled_run"] = {
-        "workload": f"{n_jobs} jobs (Poisson arrivals, log-normal prompts <= 1024 and outputs <= 96, 15 % underpredicted 4x), "
-                    f"batch {batch}, GPU job limit {M}, 4 queues; one attention layer of {w.name}'s shape",
-        "seconds": dt, "iterations": st["iterations"], "iterations_per_s": st["iterations"] / dt,
-        "prefill_tokens": st["prefill_tokens"], "decode_tokens": st["decode_tokens"],
-        "tokens_per_s": (st["prefill_tokens"] + st["decode_tokens"]) / dt,
-        "offloads": st["offloads"], "uploads": st["uploads"], "swapped_bytes": st["offload_bytes"] + st["upload_bytes"],
-        "note": "wall clock of the Python loop around the library calls, second run of the same trace; "
-                "the clock the scheduler sees is its own model time"}
+    def run_python():
+        rp = Replay(w, B.Scheduler(**cfg, want_order=False), num_pages=2 * (M + 1) * pages_per_job, max_context=max_ctx, kv_source=source)
+        dt = drive(lambda i: rp.add_job(i, arrival[i], s[i], n_pred[i]), rp.sched.num_jobs, rp.iterate, rp.commit)
+        return rp.stats, dt
+
+    def run_native():
+        cache = B.KVCache.allocate(2 * (M + 1) * pages_per_job, w.P, w.Hkv, w.D, w.bits, w.G, fill=0)
+        rp = B.NativeReplay(cache, w.H, cfg, max_ctx, batch * max(s), pk, pv, pq, 1.0 / math.sqrt(w.D))
+        dt = drive(lambda i: rp.add_job(i, arrival[i], s[i], n_pred[i], (i * 7919) % pool_n), rp.num_jobs, rp.iterate, rp.commit)
+        st = rp.stats()
+        rp.close()
+        return st, dt
+
+    def report(st, dt, note):
+        return {"seconds": dt, "iterations": st["iterations"], "iterations_per_s": st["iterations"] / dt,
+                "prefill_tokens": st["prefill_tokens"], "decode_tokens": st["decode_tokens"],
+                "tokens_per_s": (st["prefill_tokens"] + st["decode_tokens"]) / dt,
+                "offloads": st["offloads"], "uploads": st["uploads"], "swapped_bytes": st["offload_bytes"] + st["upload_bytes"],
+                "note": note}
+
+    what = (f"{n_jobs} jobs (Poisson arrivals, log-normal prompts <= 1024 and outputs <= 96, 15 % underpredicted 4x), "
+            f"batch {batch}, GPU job limit {M}, 4 queues; one attention layer of {w.name}'s shape")
+    run_native()                    # the first run pays for pinned allocations and one-time queries
+    st, dt = run_native()
+    out["scheduled_run"] = dict(workload=what, **report(
+        st, dt, "the C++ loop of alise_replay.h (one call per iteration from the driver, no host synchronisation inside), "
+                "second run of the same trace; the clock the scheduler sees is its own model time"))
+    run_python()
+    st, dt = run_python()
+    out["scheduled_run_python_loop"] = report(st, dt, "the same trace through replay.py, the Python loop around the same entry points")
     return out
 
 

@@ -38,6 +38,8 @@ EXPORTS = ("alise_kv_codes_bytes", "alise_kv_meta_bytes", "alise_kv_quant_write"
            "alise_add_layernorm", "alise_bias_relu", "alise_hbm_read_probe", "alise_issue_overlap_probe",
            "alise_sched_create", "alise_sched_destroy", "alise_sched_add_job", "alise_sched_num_jobs",
            "alise_sched_step", "alise_sched_commit",
+           "alise_replay_create", "alise_replay_destroy", "alise_replay_add_job", "alise_replay_num_jobs",
+           "alise_replay_iterate", "alise_replay_commit", "alise_replay_synchronize", "alise_replay_get_stats",
            "alise_reload_environment", "alise_status_string")
 
 
@@ -438,6 +440,114 @@ class Scheduler:
     def commit(self, elapsed, finished):
         f = (ctypes.c_int64 * max(1, len(finished)))(*finished)
         _check(_lib.alise_sched_commit(self._h, int(elapsed), f, len(finished)), "alise_sched_commit")
+
+
+class alise_replay_config(ctypes.Structure):
+    _fields_ = [("num_q_heads", ctypes.c_int32), ("max_context", ctypes.c_int32), ("max_iter_tokens", ctypes.c_int32),
+                ("overlap_swaps", ctypes.c_int32), ("softmax_scale", ctypes.c_float), ("reserved", ctypes.c_int32)]
+
+
+class alise_replay_iteration(ctypes.Structure):
+    _fields_ = [("batch_ids", _I64P), ("batch_phase", _I32P), ("batch_out_row", _I64P), ("batch_cap", ctypes.c_int32),
+                ("n_batch", ctypes.c_int32),
+                ("upload_ids", _I64P), ("upload_cap", ctypes.c_int32), ("n_upload", ctypes.c_int32),
+                ("offload_ids", _I64P), ("offload_host", ctypes.POINTER(ctypes.c_void_p)),
+                ("offload_bytes", ctypes.POINTER(ctypes.c_size_t)), ("offload_cap", ctypes.c_int32), ("n_offload", ctypes.c_int32),
+                ("model_time", ctypes.c_int64), ("n_prefill_tokens", ctypes.c_int32), ("n_decode_tokens", ctypes.c_int32)]
+
+
+class alise_replay_stats(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int64) for n in ("iterations", "prefill_tokens", "decode_tokens", "offloads", "uploads",
+                                              "offload_bytes", "upload_bytes")] + \
+               [("free_pages", ctypes.c_int32), ("live_jobs", ctypes.c_int32)]
+
+
+_lib.alise_replay_create.restype = ctypes.c_int
+_lib.alise_replay_create.argtypes = [_P, ctypes.POINTER(alise_sched_config), ctypes.POINTER(alise_replay_config),
+                                     ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p)]
+_lib.alise_replay_destroy.restype = None
+_lib.alise_replay_destroy.argtypes = [ctypes.c_void_p]
+_lib.alise_replay_add_job.restype = ctypes.c_int
+_lib.alise_replay_add_job.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
+                                      ctypes.c_int64]
+_lib.alise_replay_num_jobs.restype = ctypes.c_int32
+_lib.alise_replay_num_jobs.argtypes = [ctypes.c_void_p]
+_lib.alise_replay_iterate.restype = ctypes.c_int
+_lib.alise_replay_iterate.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                      ctypes.POINTER(alise_replay_iteration)]
+_lib.alise_replay_commit.restype = ctypes.c_int
+_lib.alise_replay_commit.argtypes = [ctypes.c_void_p, ctypes.c_int64, _I64P, ctypes.c_int32]
+_lib.alise_replay_synchronize.restype = ctypes.c_int
+_lib.alise_replay_synchronize.argtypes = [ctypes.c_void_p]
+_lib.alise_replay_get_stats.restype = ctypes.c_int
+_lib.alise_replay_get_stats.argtypes = [ctypes.c_void_p, ctypes.POINTER(alise_replay_stats)]
+
+
+class NativeReplay:
+    """The serving loop object of alise_replay.h; argument marshalling only.  Every page of the cache belongs to the object
+    until close(); k_tokens, v_tokens ([rows, Hkv, D]) and q_tokens ([rows, H, D]) are device fp16 tensors in which a job finds its
+    token t at row token_row + t.  ``iterate()`` returns a dict: the decision's lists, 'out' (fp16 [max_iter_tokens, H, D],
+    reused by the next iteration), 'out_row' (first row of each batch job), 'n_prefill_tokens', 'n_decode_tokens', and
+    'offloaded' (id -> (address of the pinned host buffer, bytes))."""
+
+    def __init__(self, cache: "KVCache", num_q_heads: int, sched_cfg: dict, max_context: int, max_iter_tokens: int,
+                 k_tokens: torch.Tensor, v_tokens: torch.Tensor, q_tokens: torch.Tensor, softmax_scale: float,
+                 overlap_swaps: bool = True):
+        for t, h in ((k_tokens, cache.num_kv_heads), (v_tokens, cache.num_kv_heads), (q_tokens, num_q_heads)):
+            assert t.is_cuda and t.dtype == torch.float16 and t.is_contiguous() and t.shape[1:] == (h, cache.head_dim)
+        assert k_tokens.shape[0] == v_tokens.shape[0] == q_tokens.shape[0]
+        self.cache, self.tokens = cache, (k_tokens, v_tokens, q_tokens)
+        self.scfg = alise_sched_config(sched_cfg["num_queues"], sched_cfg["max_batch"], sched_cfg["gpu_job_limit"], 0,
+                                       sched_cfg["limit0"], sched_cfg["age_threshold"], sched_cfg["t0"], sched_cfg["alpha"],
+                                       sched_cfg["beta"])
+        self.rcfg = alise_replay_config(num_q_heads, max_context, max_iter_tokens, int(overlap_swaps), float(softmax_scale), 0)
+        self.out = torch.empty((max_iter_tokens, num_q_heads, cache.head_dim), dtype=torch.float16, device=k_tokens.device)
+        self._rows = k_tokens.shape[0]
+        self._h = ctypes.c_void_p()
+        _check(_lib.alise_replay_create(ctypes.byref(cache.c_struct()), ctypes.byref(self.scfg), ctypes.byref(self.rcfg),
+                                        _stream(), ctypes.byref(self._h)), "alise_replay_create")
+        nb, nm = sched_cfg["max_batch"], sched_cfg["gpu_job_limit"]
+        self._b = ((ctypes.c_int64 * nb)(), (ctypes.c_int32 * nb)(), (ctypes.c_int64 * nb)(), (ctypes.c_int64 * nm)(),
+                   (ctypes.c_int64 * nm)(), (ctypes.c_void_p * nm)(), (ctypes.c_size_t * nm)())
+        bi, bp, br, up, off, oh, ob = self._b
+        self._it = alise_replay_iteration(bi, bp, br, nb, 0, up, nm, 0, off, oh, ob, nm, 0, 0, 0, 0)
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _lib.alise_replay_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def add_job(self, id, arrival, prompt_len, predicted_len, token_row):
+        assert 0 <= token_row and token_row + self.rcfg.max_context <= self._rows, "the job's tokens must lie inside the token arrays"
+        _check(_lib.alise_replay_add_job(self._h, int(id), int(arrival), int(prompt_len), int(predicted_len), int(token_row)),
+               "alise_replay_add_job")
+
+    def num_jobs(self):
+        return int(_lib.alise_replay_num_jobs(self._h))
+
+    def iterate(self):
+        k, v, q = self.tokens
+        it = self._it
+        _check(_lib.alise_replay_iterate(self._h, _dp(k), _dp(v), _dp(q), _dp(self.out), ctypes.byref(it)), "alise_replay_iterate")
+        bi, bp, br, up, off, oh, ob = self._b
+        return {"batch": bi[:it.n_batch], "phase": bp[:it.n_batch], "out_row": br[:it.n_batch], "upload": up[:it.n_upload],
+                "offload": off[:it.n_offload], "offloaded": {off[i]: (oh[i], ob[i]) for i in range(it.n_offload)},
+                "model_time": int(it.model_time), "n_prefill_tokens": it.n_prefill_tokens,
+                "n_decode_tokens": it.n_decode_tokens, "out": self.out}
+
+    def commit(self, elapsed, finished):
+        f = (ctypes.c_int64 * max(1, len(finished)))(*finished)
+        _check(_lib.alise_replay_commit(self._h, int(elapsed), f, len(finished)), "alise_replay_commit")
+
+    def synchronize(self):
+        _check(_lib.alise_replay_synchronize(self._h), "alise_replay_synchronize")
+
+    def stats(self) -> dict:
+        s = alise_replay_stats()
+        _check(_lib.alise_replay_get_stats(self._h, ctypes.byref(s)), "alise_replay_get_stats")
+        return {n: int(getattr(s, n)) for n, _ in s._fields_}
 
 
 def raw():

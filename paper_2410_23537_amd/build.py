@@ -7,7 +7,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libalise_kv.so")
-SOURCES = ["alise_api.hip", "quant_write.hip", "decode_attn.hip", "decode_attn_gqa.hip", "prefill_attn.hip", "swap.hip", "fused_ops.hip", "read_probe.hip", "sched.cpp"]
+SOURCES = ["alise_api.hip", "quant_write.hip", "decode_attn.hip", "decode_attn_gqa.hip", "prefill_attn.hip", "swap.hip", "fused_ops.hip", "read_probe.hip", "sched.cpp", "replay.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -361,3 +361,39 @@ def test_committed_profiles_match_the_committed_sources():
     for name in ("int4", "llama7b", "gqa70b", "opt13b"):
         got, note = bench.measured_traffic(name)
         assert got is not None and got > 0, note
+
+
+def test_replay_arguments(B):
+    """alise_replay.h: everything that can be wrong with the configuration is found before any HIP call."""
+    lib = B.raw()
+    c = _cache(B)
+    sc = B.alise_sched_config(3, 4, 6, 0, 1000, 5000, 2, 1, 20)
+    h = ctypes.c_void_p()
+
+    def create(cache=c, sched=sc, **kw):
+        f = dict(num_q_heads=8, max_context=64, max_iter_tokens=128, overlap_swaps=1, softmax_scale=0.088, reserved=0)
+        f.update(kw)
+        rc = B.alise_replay_config(**f)
+        return lib.alise_replay_create(ctypes.byref(cache) if cache is not None else None,
+                                       ctypes.byref(sched) if sched is not None else None, ctypes.byref(rc), None, ctypes.byref(h))
+
+    assert create(cache=None) == B.ALISE_INVALID_ARGUMENT
+    assert create(sched=None) == B.ALISE_INVALID_ARGUMENT
+    assert create(num_q_heads=0) == B.ALISE_INVALID_ARGUMENT
+    assert create(num_q_heads=12) == B.ALISE_INVALID_ARGUMENT           # not a multiple of the 8 KV heads
+    assert create(max_context=1) == B.ALISE_INVALID_ARGUMENT
+    assert create(max_iter_tokens=0) == B.ALISE_INVALID_ARGUMENT
+    assert create(softmax_scale=0.0) == B.ALISE_INVALID_ARGUMENT
+    assert create(reserved=1) == B.ALISE_INVALID_ARGUMENT
+    assert create(cache=_cache(B, bits=5)) == B.ALISE_UNSUPPORTED
+    assert create(sched=B.alise_sched_config(3, 0, 6, 0, 1000, 5000, 2, 1, 20)) == B.ALISE_INVALID_ARGUMENT
+    assert create(sched=B.alise_sched_config(0, 4, 6, 0, 1000, 5000, 2, 1, 20)) == B.ALISE_INVALID_ARGUMENT   # the scheduler's own check
+    assert h.value is None
+    # NULL objects
+    lib.alise_replay_destroy(None)
+    assert lib.alise_replay_num_jobs(None) == 0
+    assert lib.alise_replay_synchronize(None) == B.ALISE_INVALID_ARGUMENT
+    assert lib.alise_replay_commit(None, 0, None, 0) == B.ALISE_INVALID_ARGUMENT
+    assert lib.alise_replay_add_job(None, 0, 0, 4, 4, 0) == B.ALISE_INVALID_ARGUMENT
+    assert lib.alise_replay_get_stats(None, None) == B.ALISE_INVALID_ARGUMENT
+    assert lib.alise_replay_iterate(None, None, None, None, None, None) == B.ALISE_INVALID_ARGUMENT

@@ -4,7 +4,8 @@ attention of Eq. 1-2): the C++ scheduler plans, the library's kernels run every 
 (quantize-and-write, chunked prefill, decode attention, offload, upload), and a second run of the
 same jobs on the CPU -- the oracle scheduler planning, the oracle's cache and attention
 executing, one private cache per job -- must agree: decisions bit for bit, every offloaded
-request byte for byte, every attention row within 2e-3."""
+request byte for byte, every attention row within 2e-3.  The loop around the calls is either the
+Python one (replay.py) or the C++ one (alise_replay.h); both are held to the same comparison."""
 import numpy as np
 import pytest
 
@@ -44,16 +45,57 @@ SHAPES = {
 }
 
 
+class _NativeLoop:
+    """The C++ loop of alise_replay.h behind the interface of replay.Replay, for the comparison below."""
+
+    def __init__(self, B, torch, w, cfg, num_pages, max_ctx, data, s, overlap):
+        import ctypes
+        self._ctypes, self._torch = ctypes, torch
+        n = len(data)
+        self.base = np.concatenate([[0], np.cumsum([data[i][0].shape[0] for i in range(n)])]).astype(np.int64)
+        pad = [np.zeros((max_ctx,) + data[0][c].shape[1:], np.float16) for c in range(3)]      # rows past the last job's tokens
+        k, v, q = (torch.from_numpy(np.concatenate([data[i][c] for i in range(n)] + [pad[c]])).cuda() for c in range(3))
+        self.cache = B.KVCache.allocate(num_pages, w.P, w.Hkv, w.D, w.bits, w.G, fill=0)
+        self.loop = B.NativeReplay(self.cache, w.H, cfg, max_ctx, cfg["max_batch"] * max(s), k, v, q, 1.0 / np.sqrt(w.D), overlap)
+
+    def add_job(self, id, arrival, prompt_len, predicted_len):
+        self.loop.add_job(id, arrival, prompt_len, predicted_len, int(self.base[id]))
+
+    def iterate(self):
+        d = self.loop.iterate()
+        self.loop.synchronize()
+        n_pre = d["n_prefill_tokens"]
+        pre = [id for id, ph in zip(d["batch"], d["phase"]) if ph == 0]
+        dec = [id for id, ph in zip(d["batch"], d["phase"]) if ph == 1]
+        # rows: the phase-0 jobs back to back in batch order, then one row per phase-1 job
+        assert [d["out_row"][d["batch"].index(id)] for id in dec] == list(range(n_pre, n_pre + len(dec)))
+        d.update(prefill_ids=pre, decode_ids=dec, prefill_out=d["out"][:n_pre].clone(),
+                 decode_out=d["out"][n_pre:n_pre + len(dec)].clone())
+        off = {}
+        for id, (addr, n) in d["offloaded"].items():
+            raw = (self._ctypes.c_ubyte * n).from_address(addr)
+            off[id] = (self._torch.from_numpy(np.frombuffer(raw, np.uint8).copy()), n)
+        d["offloaded"] = off
+        return d
+
+    def commit(self, elapsed, finished):
+        self.loop.commit(elapsed, finished)
+
+    def pages_back(self):
+        return self.loop.stats()["free_pages"] == self.cache.num_pages
+
+
 @pytest.mark.parametrize("shape_name", list(SHAPES))
 @pytest.mark.parametrize("overlap", [True, False], ids=["side_stream", "one_stream"])
-def test_scheduled_run_against_the_oracle(env, shape_name, overlap):
+@pytest.mark.parametrize("loop", ["python_loop", "native_loop"])
+def test_scheduled_run_against_the_oracle(env, shape_name, overlap, loop):
     B, replay, torch, oracle, so = env
     sh = SHAPES[shape_name]
     w = wl.Workload(name=shape_name, B=1, length_law="fixed:1", seed=31, max_len=512, **sh)
     n_jobs = 14
     arrival, s, n_true, n_pred = (a.tolist() for a in wl.job_trace(n_jobs, 11, mean_gap=150.0, max_prompt=90, max_output=24))
     cfg = dict(num_queues=3, limit0=1500, age_threshold=6000, max_batch=3, gpu_job_limit=4, t0=2, alpha=1, beta=20)
-    print(f"case replay {shape_name} overlap={overlap}: prompts {s} outputs {n_true} predicted {n_pred}", flush=True)
+    print(f"case replay {shape_name} {loop} overlap={overlap}: prompts {s} outputs {n_true} predicted {n_pred}", flush=True)
 
     # every job's K, V, Q for all of its tokens, seeded
     rng = np.random.default_rng(5)
@@ -69,8 +111,11 @@ def test_scheduled_run_against_the_oracle(env, shape_name, overlap):
 
     max_ctx = max(s[i] + n_true[i] for i in range(n_jobs)) + 1
     pages_per_job = (max_ctx + w.P - 1) // w.P
-    rp = replay.Replay(w, B.Scheduler(**cfg), num_pages=2 * (cfg["gpu_job_limit"] + 1) * pages_per_job, max_context=max_ctx,
-                       kv_source=source, overlap_swaps=overlap)
+    num_pages = 2 * (cfg["gpu_job_limit"] + 1) * pages_per_job
+    if loop == "native_loop":
+        rp = _NativeLoop(B, torch, w, cfg, num_pages, max_ctx, data, s, overlap)
+    else:
+        rp = replay.Replay(w, B.Scheduler(**cfg), num_pages=num_pages, max_context=max_ctx, kv_source=source, overlap_swaps=overlap)
     osched = so.Scheduler(so.Config(**cfg))
     ocache = {}          # job -> (oracle cache of its own, tokens in it)
     scale = 1.0 / np.sqrt(w.D)
@@ -147,4 +192,72 @@ def test_scheduled_run_against_the_oracle(env, shape_name, overlap):
         assert iters < 5000
     print(f"  {iters} iterations, {n_off} offloads, {n_up} uploads, worst attention error {worst:.2e}", flush=True)
     assert gen == n_true and n_off > 0 and n_up > 0
-    assert len(rp.free) + len(rp.pending_free) == rp.cache.num_pages          # every page came back
+    # every page came back
+    assert rp.pages_back() if loop == "native_loop" else len(rp.free) + len(rp.pending_free) == rp.cache.num_pages
+
+
+@pytest.mark.parametrize("shape_name", ["gqa4_g128_p32", "int4_g32"])
+def test_native_loop_without_host_waits(env, shape_name):
+    """The C++ loop never waits for the GPU in the steady state: metadata goes through a ring of pinned staging buffers, host
+    buffers of uploads are recycled behind events, freed pages are reused behind events.  A run that is left to run free
+    (hundreds of iterations enqueued ahead of the GPU) must give, bit for bit, the outputs and the final cache of a run that
+    waits for the GPU after every iteration -- which the test above checks against the oracle."""
+    B, _, torch, _, _ = env
+    sh = SHAPES[shape_name]
+    w = wl.Workload(name=shape_name, B=1, length_law="fixed:1", seed=31, max_len=512, **sh)
+    n_jobs = 48
+    arrival, s, n_true, n_pred = (a.tolist() for a in wl.job_trace(n_jobs, 23, mean_gap=60.0, max_prompt=120, max_output=40))
+    cfg = dict(num_queues=3, limit0=1500, age_threshold=6000, max_batch=4, gpu_job_limit=5, t0=2, alpha=1, beta=20)
+    max_ctx = max(a + b for a, b in zip(s, n_true)) + 1
+    num_pages = 2 * (cfg["gpu_job_limit"] + cfg["max_batch"] + 1) * ((max_ctx + w.P - 1) // w.P)
+    gen = torch.Generator(device="cuda").manual_seed(9)
+    rows = 4096
+    k = torch.randn((rows + max_ctx, w.Hkv, w.D), dtype=torch.float16, device="cuda", generator=gen) * 1.5
+    v = torch.randn((rows + max_ctx, w.Hkv, w.D), dtype=torch.float16, device="cuda", generator=gen)
+    q = torch.randn((rows + max_ctx, w.H, w.D), dtype=torch.float16, device="cuda", generator=gen)
+
+    def run(wait):
+        cache = B.KVCache.allocate(num_pages, w.P, w.Hkv, w.D, w.bits, w.G, fill=0)
+        rp = B.NativeReplay(cache, w.H, cfg, max_ctx, cfg["max_batch"] * max(s), k, v, q, 1.0 / np.sqrt(w.D), True)
+        order = sorted(range(n_jobs), key=lambda i: (arrival[i], i))
+        nxt, now, produced, log, decisions = 0, 0, [0] * n_jobs, [], []
+        while True:
+            while nxt < n_jobs and arrival[order[nxt]] <= now:
+                i = order[nxt]
+                rp.add_job(i, arrival[i], s[i], n_pred[i], (i * 613) % rows)
+                nxt += 1
+            if rp.num_jobs() == 0:
+                if nxt == n_jobs:
+                    break
+                now = arrival[order[nxt]]
+                continue
+            d = rp.iterate()
+            if wait:
+                rp.synchronize()
+            n = d["n_prefill_tokens"] + d["n_decode_tokens"]
+            log.append(d["out"][:n].clone())                # on the stream the loop runs on: behind this iteration, before the next
+            decisions.append((d["batch"], d["phase"], d["upload"], d["offload"], d["out_row"]))
+            fin = []
+            for id in d["batch"]:
+                produced[id] += 1
+                if produced[id] >= n_true[id]:
+                    fin.append(id)
+            rp.commit(d["model_time"], fin)
+            now += d["model_time"]
+            assert len(log) < 20000
+        rp.synchronize()
+        torch.cuda.synchronize()
+        st = rp.stats()
+        assert st["free_pages"] == num_pages and st["live_jobs"] == 0
+        rp.close()
+        return decisions, torch.cat(log).cpu(), [t.cpu() for t in (cache.k_codes, cache.v_codes, cache.k_meta, cache.v_meta)], st
+
+    print(f"case native loop free-running vs waiting, {shape_name}", flush=True)
+    dec_w, out_w, cache_w, st_w = run(True)
+    dec_f, out_f, cache_f, st_f = run(False)
+    print(f"  {st_f['iterations']} iterations, {st_f['offloads']} offloads, {st_f['uploads']} uploads", flush=True)
+    assert st_f["offloads"] >= 10 and st_f["uploads"] >= 10 and st_f["iterations"] > 100
+    assert dec_w == dec_f and st_w == st_f
+    assert torch.equal(out_w, out_f)
+    for a, b in zip(cache_w, cache_f):
+        assert torch.equal(a, b)
