@@ -33,47 +33,36 @@ struct QuantParams {
 };
 
 __device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
+__device__ __forceinline__ float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
 
 template <int CTRL>
-__device__ __forceinline__ float dpp_f(float v)
+__device__ __forceinline__ uint32_t dpp_u(uint32_t v)
 {
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
 }
 
-// BITS = code width; LPG = lanes per group (G / 8): 2, 4, 8 or 16, so a group never leaves a row of 16 lanes.
-template <int BITS, int LPG, bool BY_HEAD>
-__global__ __launch_bounds__(256) void quant_write_kernel(QuantParams p)
+// The quantizer of one lane's 8 channels (the arithmetic stated in include/alise_kv.h, operation by operation).
+// Returns the packed codes in w0 (and w1 for 8 bits) and the group's meta dword (fp16 scale | fp16 zero << 16).
+//
+// The kernel is bound by vector instructions, not by memory, so every step is written in the cheapest form that
+// still gives the stated result bit for bit:
+//   - range: inside the lane with float min/max (which start from 0, so the results are never NaN and
+//     mn <= 0 <= mx); across the lanes of the group on the bit patterns, where "larger unsigned pattern" is
+//     "larger" for the non-negative mx and "more negative" for the non-positive mn -- one DPP instruction each
+//     per step, no NaN canonicalisation;
+//   - r / qmax, correctly rounded, as q0 = r * c, q1 = fma(fma(-qmax, q0, r), c, q0) with c = RN(1 / qmax): r is
+//     a difference of two fp16 numbers, so 2^-24 <= r <= 131008 or r = 0 and nothing under- or overflows; that
+//     q1 equals the IEEE quotient for qmax = 255 and 15 has been checked for every binary32 r in [0, 131008]
+//     (tests/divcheck/);
+//   - 1 / scale, correctly rounded, as one Newton step on the hardware reciprocal (1 ulp): the scale is an
+//     fp16 number, 11 significant bits, so 1 / scale is at least 2^-36 (relative) away from every rounding
+//     boundary of binary32 while the step's result before rounding is off by less than 2^-45;
+//   - codes: v_cvt_pk_u8_f32 rounds to nearest even and saturates to [0, 255], which is rint + clamp for 8 bits
+//     (for 4 bits the upper clamp is a float minimum first; the lower one cannot be hit by more than -0.5,
+//     which rounds to 0).
+template <int BITS, int LPG>
+__device__ __forceinline__ void quantize8(const h8_t x, uint32_t &w0, uint32_t &w1, uint32_t &meta)
 {
-    const uint32_t gl = blockIdx.x * 256u + threadIdx.x;
-    bool live = gl < p.total_lanes;
-    const uint32_t g = live ? gl : p.total_lanes - 1;
-    const int lane_in_row = (int)(g & ((1u << p.log_lanes_per_row) - 1u));
-    const uint32_t row = g >> p.log_lanes_per_row;
-    int head, which;
-    int64_t t;
-    if constexpr (!BY_HEAD) {
-        // Rows are ordered (token, K|V, head): the lanes of a wave stay inside one
-        // tensor's contiguous [Hkv][D] slab of one token as long as possible.
-        const uint32_t tw = p.c.Hkv == 1 ? row : (__umulhi(row, p.hkv_magic) >> p.hkv_shift);
-        head = (int)(row - tw * (uint32_t)p.c.Hkv);
-        which = (int)(tw & 1u);
-        t = tw >> 1;
-    } else {
-        // Rows are ordered (16 tokens, K|V, head, token of the 16): consecutive rows are the same head of
-        // consecutive tokens, which a prompt's chunk puts side by side in a page.
-        const uint32_t t_lo = row & 15u, r2 = row >> 4;
-        const uint32_t r3 = p.c.Hkv == 1 ? r2 : (__umulhi(r2, p.hkv_magic) >> p.hkv_shift);
-        head = (int)(r2 - r3 * (uint32_t)p.c.Hkv);
-        which = (int)(r3 & 1u);
-        int64_t tt = (int64_t)(r3 >> 1) * 16 + t_lo;
-        live = live && tt < p.T;
-        t = tt < p.T ? tt : p.T - 1;
-    }
-
-    const _Float16 *src = (which ? p.v : p.k) + (t * p.c.Hkv + head) * p.c.D + lane_in_row * 8;
-    const h8_t x = __builtin_nontemporal_load(reinterpret_cast<const h8_t *>(src));    // read once
-    const int64_t slot = p.slots[t];
-
     float xf[8];
     float mn = 0.0f, mx = 0.0f;          // the range always includes 0
 #pragma unroll
@@ -82,57 +71,119 @@ __global__ __launch_bounds__(256) void quant_write_kernel(QuantParams p)
         mn = fminf(mn, xf[i]);
         mx = fmaxf(mx, xf[i]);
     }
-    // minimum and maximum over the lanes of the group, every lane gets both
-    mn = fminf(mn, dpp_f<0xB1>(mn));  mx = fmaxf(mx, dpp_f<0xB1>(mx));                    // quad_perm [1,0,3,2]
-    if constexpr (LPG >= 4) { mn = fminf(mn, dpp_f<0x4E>(mn)); mx = fmaxf(mx, dpp_f<0x4E>(mx)); }     // quad_perm [2,3,0,1]
-    if constexpr (LPG >= 8) { mn = fminf(mn, dpp_f<0x141>(mn)); mx = fmaxf(mx, dpp_f<0x141>(mx)); }   // row_half_mirror
-    if constexpr (LPG >= 16) { mn = fminf(mn, dpp_f<0x140>(mn)); mx = fmaxf(mx, dpp_f<0x140>(mx)); }  // row_mirror
-    const float qmax = (float)((1 << BITS) - 1);
+    uint32_t un = as_u32(mn), ux = as_u32(mx);
+    un = max(un, dpp_u<0xB1>(un));  ux = max(ux, dpp_u<0xB1>(ux));                                  // quad_perm [1,0,3,2]
+    if constexpr (LPG >= 4) { un = max(un, dpp_u<0x4E>(un)); ux = max(ux, dpp_u<0x4E>(ux)); }       // quad_perm [2,3,0,1]
+    if constexpr (LPG >= 8) { un = max(un, dpp_u<0x141>(un)); ux = max(ux, dpp_u<0x141>(ux)); }     // row_half_mirror
+    if constexpr (LPG >= 16) { un = max(un, dpp_u<0x140>(un)); ux = max(ux, dpp_u<0x140>(ux)); }    // row_mirror
+    mn = as_f32(un);
+    mx = as_f32(ux);
+    constexpr float qmax = (float)((1 << BITS) - 1);
+    constexpr float c = 1.0f / qmax;                  // correctly rounded at compile time
     const float r = mx - mn;
-    const float l32 = r / qmax;
+    const float q0 = r * c;
+    const float l32 = __builtin_fmaf(__builtin_fmaf(-qmax, q0, r), c, q0);
     _Float16 h = (_Float16)l32;                       // round to nearest even
-    uint16_t hb = __builtin_bit_cast(uint16_t, h);
-    if ((float)h < l32) hb = (uint16_t)(hb + 1);      // scale is rounded up
+    uint32_t hb = __builtin_bit_cast(uint16_t, h);
+    if ((float)h < l32) hb = hb + 1;                  // scale is rounded up
     if (hb < 0x0400u) hb = 0x0400u;                   // floor at 2^-14
-    const float lam = (float)__builtin_bit_cast(_Float16, hb);
-    const float inv = 1.0f / lam;
-    float zf = __builtin_rintf((-mn) * inv);
-    zf = fminf(fmaxf(zf, 0.0f), qmax);
-    const int zi = (int)zf;
-    zf = (float)zi;
-    uint32_t code[8];
+    const float lam = (float)__builtin_bit_cast(_Float16, (uint16_t)hb);
+    const float y0 = __builtin_amdgcn_rcpf(lam);
+    const float inv = __builtin_fmaf(__builtin_fmaf(-lam, y0, 1.0f), y0, y0);
+    float zs = (-mn) * inv;
+    if constexpr (BITS == 4) zs = fminf(zs, qmax);
+    const uint32_t zi = __builtin_amdgcn_cvt_pk_u8_f32(zs, 0, 0u);       // rint, clamped to [0, qmax]
+    const float zf = (float)zi;
+    float u[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        float u = __builtin_fmaf(xf[i], inv, zf);     // one rounding
-        float qv = __builtin_rintf(u);
-        qv = fminf(fmaxf(qv, 0.0f), qmax);
-        code[i] = (uint32_t)(int)qv;
+        u[i] = __builtin_fmaf(xf[i], inv, zf);        // one rounding
+        if constexpr (BITS == 4) u[i] = fminf(u[i], qmax);
     }
+    uint32_t a = 0, b = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        a = __builtin_amdgcn_cvt_pk_u8_f32(u[i], i, a);
+        b = __builtin_amdgcn_cvt_pk_u8_f32(u[4 + i], i, b);
+    }
+    if constexpr (BITS == 8) {
+        w0 = a;
+        w1 = b;
+    } else {
+        a |= a >> 4;                                  // byte 0: codes 0, 1; byte 2: codes 2, 3
+        b |= b >> 4;
+        w0 = __builtin_amdgcn_perm(b, a, 0x06040200u);
+        w1 = 0;
+    }
+    const uint32_t zb = __builtin_bit_cast(uint16_t, (_Float16)zf);
+    meta = hb | (zb << 16);
+}
+
+// BITS = code width; LPG = lanes per group (G / 8): 2, 4, 8 or 16, so a group never leaves a row of 16 lanes.
+template <int BITS, int LPG, bool BY_HEAD>
+__global__ __launch_bounds__(256) void quant_write_kernel(QuantParams p)
+{
+    const uint32_t gl = blockIdx.x * 256u + threadIdx.x;
+    const int lane_in_row = (int)(gl & ((1u << p.log_lanes_per_row) - 1u));
+    bool live;
+    int head, which;
+    const _Float16 *src;
+    const int64_t *slot_at;
+    if constexpr (!BY_HEAD) {
+        // Rows are ordered (token, K|V, head): the lanes of a wave stay inside one
+        // tensor's contiguous [Hkv][D] slab of one token as long as possible.
+        live = gl < p.total_lanes;
+        const uint32_t g = live ? gl : p.total_lanes - 1;
+        const uint32_t row = g >> p.log_lanes_per_row;
+        const uint32_t tw = p.c.Hkv == 1 ? row : (__umulhi(row, p.hkv_magic) >> p.hkv_shift);
+        head = (int)(row - tw * (uint32_t)p.c.Hkv);
+        which = (int)(tw & 1u);
+        const int64_t t = tw >> 1;
+        src = (which ? p.v : p.k) + (t * p.c.Hkv + head) * p.c.D + (int)(g & ((1u << p.log_lanes_per_row) - 1u)) * 8;
+        slot_at = p.slots + t;
+    } else {
+        // Rows are ordered (16 tokens, K|V, head, token of the 16): consecutive rows are the same head of
+        // consecutive tokens, which a prompt's chunk puts side by side in a page.  The launch covers whole blocks of
+        // 16 tokens, so every lane index is in range, and a wave (4 or 8 rows) lies inside one (block, K|V, head):
+        // those three and every base address are computed once per wave on the scalar unit, the lanes add small
+        // 32-bit offsets.
+        const uint32_t row = gl >> p.log_lanes_per_row;
+        const uint32_t r2 = __builtin_amdgcn_readfirstlane(row >> 4);
+        const uint32_t r3 = p.c.Hkv == 1 ? r2 : (__umulhi(r2, p.hkv_magic) >> p.hkv_shift);
+        head = (int)(r2 - r3 * (uint32_t)p.c.Hkv);
+        which = (int)(r3 & 1u);
+        const int32_t t16 = (int32_t)(r3 >> 1) * 16;              // below T: the block has a token
+        const int32_t t_lo = (int32_t)(row & 15u);
+        live = t16 + t_lo < p.T;
+        const uint32_t dt = (uint32_t)(live ? t_lo : p.T - 1 - t16);
+        const _Float16 *base = (which ? p.v : p.k) + ((int64_t)t16 * p.c.Hkv + head) * p.c.D;
+        src = base + (__umul24(dt, (uint32_t)(p.c.Hkv * p.c.D)) + (uint32_t)lane_in_row * 8u);
+        slot_at = p.slots + t16 + dt;
+    }
+    const h8_t x = __builtin_nontemporal_load(reinterpret_cast<const h8_t *>(src));    // read once
+    const int64_t slot = *slot_at;
+
+    uint32_t w0, w1, m;
+    quantize8<BITS, LPG>(x, w0, w1, m);
     if (!live || slot < 0) return;
 
-    const int64_t page = slot >> p.c.logP;
-    const int off = (int)(slot & (p.c.P - 1));
-    const int64_t blk = page * p.c.Hkv + head;
-    uint8_t *codes = (which ? p.c.v_codes : p.c.k_codes) + blk * p.c.cstride + (int64_t)off * p.c.row_code_bytes;
-    uint32_t *meta = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(which ? p.c.v_meta : p.c.k_meta) +
-                                                  blk * p.c.mstride) + off * p.c.NG;
+    // a valid slot is below num_pages * page_size < 2^31, and num_pages * Hkv < 2^31
+    const uint32_t s32 = (uint32_t)slot;
+    const uint32_t page = s32 >> p.c.logP, off = s32 & (uint32_t)(p.c.P - 1);
+    const uint32_t blk = page * (uint32_t)p.c.Hkv + (uint32_t)head;
+    uint8_t *codes = (which ? p.c.v_codes : p.c.k_codes) + (uint64_t)blk * (uint32_t)p.c.cstride +
+                     (off * (uint32_t)p.c.row_code_bytes + (uint32_t)lane_in_row * BITS);
     if constexpr (BITS == 8) {
-        uint2 w;
-        w.x = code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24);
-        w.y = code[4] | (code[5] << 8) | (code[6] << 16) | (code[7] << 24);
         typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
-        const u32x2_t wv = {w.x, w.y};
-        __builtin_nontemporal_store(wv, reinterpret_cast<u32x2_t *>(codes + lane_in_row * 8));
+        const u32x2_t wv = {w0, w1};
+        __builtin_nontemporal_store(wv, reinterpret_cast<u32x2_t *>(codes));
     } else {
-        uint32_t w = 0;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) w |= code[i] << (4 * i);   // channel 2i low nibble, 2i+1 high
-        __builtin_nontemporal_store(w, reinterpret_cast<uint32_t *>(codes + lane_in_row * 4));
+        __builtin_nontemporal_store(w0, reinterpret_cast<uint32_t *>(codes));     // channel 2i low nibble, 2i+1 high
     }
     if ((lane_in_row % LPG) == 0) {
-        const int grp = lane_in_row / LPG;
-        const uint16_t zb = __builtin_bit_cast(uint16_t, (_Float16)zf);
-        __builtin_nontemporal_store((uint32_t)hb | ((uint32_t)zb << 16), meta + grp);
+        uint8_t *meta = reinterpret_cast<uint8_t *>(which ? p.c.v_meta : p.c.k_meta) + (uint64_t)blk * (uint32_t)p.c.mstride +
+                        (off * (uint32_t)p.c.NG + (uint32_t)(lane_in_row / LPG)) * 4u;
+        __builtin_nontemporal_store(m, reinterpret_cast<uint32_t *>(meta));
     }
 }
 
@@ -209,7 +260,7 @@ hipError_t launch_quant_write(const CacheView &c, const void *k, const void *v,
     // consecutive tokens of one head next to each other a workgroup writes 2 KiB of codes and 128 bytes of
     // scales in one piece instead of sixteen (7 % on a 7 650-token batch).  Small ones are decode steps, one
     // token per request, where the token-major order reads whole tokens and nothing is adjacent anyway.
-    const bool by_head = T >= 1024;
+    const bool by_head = T >= 1024 && (int64_t)c.Hkv * c.D < (1 << 24);     // the kernel multiplies by Hkv * D in 24 bits
     for (int64_t t0 = 0; t0 < T; t0 += tokens_per_launch) {
         const int64_t n = T - t0 < tokens_per_launch ? T - t0 : tokens_per_launch;
         p.k = static_cast<const _Float16 *>(k) + t0 * c.Hkv * c.D;

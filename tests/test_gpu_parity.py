@@ -333,3 +333,59 @@ def test_more_requests_than_a_plan_pass_holds(env, bits, G, Hkv, H):
     torch.cuda.synchronize()
     gotp = op.cpu().numpy().astype(np.float64)
     assert np.isfinite(gotp).all() and np.abs(gotp - wantp).max() <= ATTN_TOL
+
+
+@pytest.mark.parametrize("bits,G", [(8, 64), (8, 16), (4, 32), (4, 128)])
+def test_every_scale_with_values_on_rounding_ties(env, bits, G):
+    """The quantizer's two divisions are not written as divisions in the kernel (a constant reciprocal with one
+    fma correction for (max - min) / qmax, one Newton step on the hardware reciprocal for 1 / scale); both must
+    still be the correctly rounded quotients.  One group for every fp16 scale the format can produce, built so
+    that its range lands just inside the interval that rounds up to that scale, and filled with values
+    (k + 1/2 - zero) * scale: products with 1 / scale that sit on or next to a rounding tie, where a reciprocal
+    off by one ulp flips the code.  Codes, scales and zero-points bit for bit against the oracle, which divides."""
+    B, torch, oracle = env
+    D, P, qmax = 128, 16, (1 << bits) - 1
+    print(f"case every scale bits={bits} G={G}", flush=True)
+    hs = np.arange(0x0400, 0x7C00, dtype=np.uint16)
+    lam = hs.view(np.float16).astype(np.float64)
+    hs, lam = hs[lam * qmax <= 131008.0 * 0.999], lam[lam * qmax <= 131008.0 * 0.999]
+    ulp = lam - (hs - 1).astype(np.uint16).view(np.float16).astype(np.float64)
+    rng = np.random.default_rng(bits * 1000 + G)
+    target = qmax * (lam - ulp * rng.uniform(0.02, 0.98, lam.shape))          # inside (qmax * prev, qmax * lam)
+    share = rng.uniform(0.3, 0.9, lam.shape)                                   # how much of the range is above zero
+    mx16 = np.minimum(target * share, 65504.0).astype(np.float16)
+    mx16 = np.where(mx16.astype(np.float64) > target * share, np.nextafter(mx16, np.float16(0)), mx16)
+    mn16 = (-(np.minimum(target - mx16.astype(np.float64), 65504.0))).astype(np.float16)
+    mx, mn = mx16.astype(np.float64), mn16.astype(np.float64)
+    z = np.clip(np.rint(-mn / lam), 0, qmax)
+    k = rng.integers(0, qmax, size=(len(lam), G))                              # codes 0 .. qmax - 1, then + 1/2
+    x = ((k + 0.5 - z[:, None]) * lam[:, None])
+    x = np.clip(x, mn[:, None], mx[:, None]).astype(np.float16)
+    x = np.clip(x, mn16[:, None], mx16[:, None])                               # rounding to fp16 must not widen the range
+    x[:, 0], x[:, 1] = mx16, mn16
+    n_groups = len(lam) // (D // G) * (D // G)
+    T = n_groups * G // D
+    T -= T % P
+    n_groups = T * D // G
+    rows = x[:n_groups].reshape(T, 1, D)
+    other = rng.standard_normal((T, 1, D)).astype(np.float16)
+    slots = np.arange(T, dtype=np.int64)
+    orc = oracle.Cache.empty(T // P, P, 1, D, bits, G, fill=0)
+    oracle.kv_quant_write(orc, rows, other, slots)
+    got_scales = orc.k_meta.view(np.uint16).reshape(-1, 2)[:, 0]
+    hit = np.isin(hs[:n_groups], got_scales)
+    print(f"  {n_groups} groups, {len(np.unique(got_scales))} distinct scales, {hit.mean() * 100:.1f} % of the targets produced", flush=True)
+    assert hit.mean() > 0.85
+    for T_call in (T, 512):                    # the head-major numbering of large writes and the token-major one
+        dev = B.KVCache.allocate(T // P, P, 1, D, bits, G, fill=0)
+        for t0 in range(0, T, T_call):
+            t1 = min(T, t0 + T_call)
+            B.alise_kv_quant_write(dev, torch.from_numpy(rows[t0:t1]).cuda(), torch.from_numpy(other[t0:t1]).cuda(),
+                                   torch.from_numpy(slots[t0:t1]).cuda())
+        torch.cuda.synchronize()
+        for name in ("k_codes", "v_codes", "k_meta", "v_meta"):
+            d, o = getattr(dev, name).cpu().numpy(), getattr(orc, name)
+            if name.endswith("meta"):
+                d, o = d.view(np.uint16), o.view(np.uint16)
+            bad = np.argwhere(d != o)
+            assert len(bad) == 0, f"{name}, writes of {T_call} tokens: {len(bad)} differ, first at {bad[0]}"
