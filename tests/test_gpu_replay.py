@@ -261,3 +261,66 @@ def test_native_loop_without_host_waits(env, shape_name):
     assert torch.equal(out_w, out_f)
     for a, b in zip(cache_w, cache_f):
         assert torch.equal(a, b)
+
+
+def test_native_loop_error_paths(env):
+    """alise_replay.h: lists that are too short are reported before the scheduler decides (the call can be repeated);
+    a cache with too few free pages, or more new tokens than max_iter_tokens, is reported after it has decided, nothing
+    is enqueued and the object refuses further work."""
+    import ctypes
+    B, _, torch, _, _ = env
+    lib = B.raw()
+    H, Hkv, D, P = 4, 4, 128, 16
+    cfg = dict(num_queues=3, limit0=1500, age_threshold=6000, max_batch=2, gpu_job_limit=3, t0=2, alpha=1, beta=20)
+    rows = 512
+    k = torch.zeros((rows, Hkv, D), dtype=torch.float16, device="cuda")
+    q = torch.zeros((rows, H, D), dtype=torch.float16, device="cuda")
+
+    def loop(num_pages, max_iter_tokens=128):
+        cache = B.KVCache.allocate(num_pages, P, Hkv, D, 8, 64, fill=0)
+        return B.NativeReplay(cache, H, cfg, 100, max_iter_tokens, k, k, q, 0.088)
+
+    print("case native loop error paths", flush=True)
+    # --- add_job
+    rp = loop(16)
+    for bad in [dict(prompt_len=0), dict(prompt_len=100), dict(token_row=-1), dict(prompt_len=129, )]:
+        a = dict(id=1, arrival=0, prompt_len=20, predicted_len=5, token_row=0)
+        a.update(bad)
+        st = lib.alise_replay_add_job(rp._h, a["id"], a["arrival"], a["prompt_len"], a["predicted_len"], a["token_row"])
+        assert st == B.ALISE_INVALID_ARGUMENT, bad
+    rp.add_job(1, 0, 20, 5, 0)
+    assert lib.alise_replay_add_job(rp._h, 1, 0, 20, 5, 0) == B.ALISE_INVALID_ARGUMENT          # the id is live
+    # --- lists too short: nothing has changed, the same call with room succeeds
+    it = rp._it
+    it.batch_cap = 0
+    assert lib.alise_replay_iterate(rp._h, k.data_ptr(), k.data_ptr(), q.data_ptr(), rp.out.data_ptr(), ctypes.byref(it)) \
+        == B.ALISE_WORKSPACE_TOO_SMALL
+    it.batch_cap = cfg["max_batch"]
+    d = rp.iterate()
+    assert d["batch"] == [1] and d["phase"] == [0] and d["n_prefill_tokens"] == 20
+    # commit with an id that was not in the batch: the scheduler's error comes through, nothing changes
+    bad_id = (ctypes.c_int64 * 1)(7)
+    assert lib.alise_replay_commit(rp._h, 1, bad_id, 1) == B.ALISE_INVALID_ARGUMENT
+    rp.commit(d["model_time"], [1])
+    rp.synchronize()
+    assert rp.stats()["free_pages"] == 16 and rp.num_jobs() == 0
+    assert rp.iterate()["batch"] == []              # no live job: nothing to do, no error
+    rp.close()
+    # --- too few pages for the batch: reported, and the object is finished
+    rp = loop(2)
+    rp.add_job(1, 0, 40, 5, 0)                      # needs three pages
+    with pytest.raises(RuntimeError, match="ALISE_WORKSPACE_TOO_SMALL"):
+        rp.iterate()
+    with pytest.raises(RuntimeError, match="ALISE_INVALID_ARGUMENT"):
+        rp.iterate()
+    with pytest.raises(RuntimeError, match="ALISE_INVALID_ARGUMENT"):
+        rp.commit(1, [])
+    rp.close()
+    # --- more new tokens than max_iter_tokens
+    rp = loop(16, max_iter_tokens=50)
+    rp.add_job(1, 0, 30, 5, 0)
+    rp.add_job(2, 0, 30, 5, 100)
+    with pytest.raises(RuntimeError, match="ALISE_WORKSPACE_TOO_SMALL"):
+        rp.iterate()
+    rp.close()
+    torch.cuda.synchronize()
