@@ -29,7 +29,9 @@
  *     the cache or used twice in one write, lengths outside [0, max_context_len],
  *     block-table entries that a length reaches outside [0, num_pages), a request
  *     longer than its block-table row, chunk boundaries that decrease or a chunk
- *     longer than its request, pages named twice in a swap.  This copies the arrays
+ *     longer than its request, pages named twice in a swap, and -- for calls that run on
+ *     the matrix cores -- a V scale of 256 or more among the tokens a length reaches (see
+ *     "Value range" at alise_paged_decode_attn).  This copies the arrays
  *     to the host and waits for the stream: a debugging aid, not for serving.
  *
  * Exact arithmetic of the quantizer (so that codes and meta are reproducible bit

@@ -166,8 +166,10 @@ int fetch_to_host(std::vector<T> &host, const T *dev, size_t n, hipStream_t s)
 }
 
 // Lengths within [0, max_len], and the block-table entries that those lengths reach within [0, num_pages).
+// `v_scale_limit`: the call runs on the matrix cores, where a V scale of 256 or more saturates the fp16 pair that carries
+// weight times scale; every V scale that a length reaches is then read back and checked as well.
 int validate_lens_and_tables(const CacheView &cv, const int32_t *block_tables, int32_t max_blocks, const int32_t *context_lens,
-                             int32_t B, int32_t max_len, std::vector<int32_t> *lens_out, hipStream_t s)
+                             int32_t B, int32_t max_len, std::vector<int32_t> *lens_out, hipStream_t s, bool v_scale_limit = false)
 {
     std::vector<int32_t> lens, bt;
     int st = fetch_to_host(lens, context_lens, (size_t)B, s);
@@ -185,6 +187,21 @@ int validate_lens_and_tables(const CacheView &cv, const int32_t *block_tables, i
             const int32_t page = bt[(size_t)i * max_blocks + b];
             if (page < 0 || page >= cv.num_pages) return ALISE_INVALID_ARGUMENT;
         }
+    }
+    if (v_scale_limit) {
+        std::vector<uint32_t> meta;
+        const size_t span = ((size_t)cv.num_pages * cv.Hkv - 1) * (size_t)cv.mstride + (size_t)cv.P * cv.NG * 4;
+        st = fetch_to_host(meta, cv.v_meta, span / 4, s);
+        if (st != ALISE_OK) return st;
+        for (int32_t i = 0; i < B; ++i)
+            for (int32_t t = 0; t < lens[i]; ++t) {
+                const int64_t page = bt[(size_t)i * max_blocks + t / cv.P];
+                for (int32_t h = 0; h < cv.Hkv; ++h) {
+                    const uint32_t *row = meta.data() + ((size_t)(page * cv.Hkv + h) * cv.mstride) / 4 + (size_t)(t % cv.P) * cv.NG;
+                    for (int32_t g = 0; g < cv.NG; ++g)
+                        if ((row[g] & 0x7fffu) >= 0x5c00u) return ALISE_INVALID_ARGUMENT;       // fp16 256.0, infinities and NaN above it
+                }
+            }
     }
     if (lens_out) lens_out->swap(lens);
     return ALISE_OK;
@@ -214,7 +231,7 @@ int64_t max_tiles_of(const CacheView &c, int32_t B, int32_t H, int32_t max_len, 
     return std::max<int64_t>(1, std::min(bound(C_min), std::max(bound(C), small)));
 }
 
-// Workspace layout: [n_items, n_merge | tile_base[B+1] | req_full_base[B] | merge_req[B] |
+// Workspace layout: [n_items, n_merge | tile_base[B+1] | req_full_base[B] |
 // order[max_tiles] | part].
 size_t carve_workspace(const CacheView &c, int32_t B, int32_t H, int32_t max_len, void *base,
                        AttnWorkspace *ws, bool bounded_by_capacity = true)
@@ -227,8 +244,6 @@ size_t carve_workspace(const CacheView &c, int32_t B, int32_t H, int32_t max_len
     off = align_up(off + sizeof(int32_t) * ((size_t)B + 1), 256);
     const size_t off_fb = off;
     off = align_up(off + sizeof(int32_t) * (size_t)B, 256);
-    const size_t off_rb = off;
-    off = align_up(off + sizeof(int32_t) * (size_t)B, 256);
     const size_t off_order = off;
     off = align_up(off + 16 * (size_t)max_tiles, 256);
     const size_t off_part = off;
@@ -238,7 +253,6 @@ size_t carve_workspace(const CacheView &c, int32_t B, int32_t H, int32_t max_len
         ws->n_items = reinterpret_cast<int32_t *>(b);
         ws->tile_base = reinterpret_cast<int32_t *>(b + off_base);
         ws->req_full_base = reinterpret_cast<int32_t *>(b + off_fb);
-        ws->merge_req = reinterpret_cast<int32_t *>(b + off_rb);
         ws->n_merge = reinterpret_cast<int32_t *>(b + 4);
         ws->n_shared = reinterpret_cast<int32_t *>(b + 8);
         ws->skew_permille = alise::tuning().xcd_skew_permille;
@@ -411,7 +425,8 @@ static int decode_attn_call(const alise_kv_cache *c, const void *q, void *out,
     if (debug_validate() && !use_static_scratch) {      // the checks copy to the host: not for a caller that must not allocate
         hipStream_t hs = static_cast<hipStream_t>(hip_stream);
         if (run) {
-            st = validate_lens_and_tables(cv, block_tables, max_blocks_per_seq, context_lens, B, max_context_len, nullptr, hs);
+            st = validate_lens_and_tables(cv, block_tables, max_blocks_per_seq, context_lens, B, max_context_len, nullptr, hs,
+                                          alise::gqa_mfma_applies(cv, num_q_heads));
             if (st != ALISE_OK) return st;
         } else {
             std::vector<int32_t> lens;
@@ -586,7 +601,7 @@ int alise_paged_prefill_attn(const alise_kv_cache *c, const void *q, void *out, 
     if (debug_validate()) {
         hipStream_t hs = static_cast<hipStream_t>(hip_stream);
         std::vector<int32_t> lens, qs;
-        st = validate_lens_and_tables(cv, block_tables, max_blocks_per_seq, context_lens, B, max_context_len, &lens, hs);
+        st = validate_lens_and_tables(cv, block_tables, max_blocks_per_seq, context_lens, B, max_context_len, &lens, hs, matrix_cores);
         if (st != ALISE_OK) return st;
         st = fetch_to_host(qs, q_start, (size_t)B + 1, hs);
         if (st != ALISE_OK) return st;

@@ -19,8 +19,7 @@ struct AttnWorkspace {
     int32_t *n_items;       // [1]  tiles * H, written by the plan kernel
     int32_t *tile_base;     // [B+1] first tile of each request (exclusive scan of tile counts)
     int32_t *req_full_base; // [B] scratch of the plan kernel: first full tile of each request in the work order
-    int32_t *merge_req;     // [B] requests with more than one split, in no particular order
-    int32_t *n_merge;       // [1] how many of them
+    int32_t *n_merge;       // [1] requests with more than one split (0: the merge has nothing to do)
     int32_t *n_shared;      // [1] items before this one are dealt out among all waves, the rest among the favoured half
     int4 *order;            // [max_tiles] work order: (request, first token, end token, split buffer index or -1)
     float *part;            // [max_tiles * H][D + 2] = (m, l, o[D]) of every split

@@ -101,12 +101,29 @@ __device__ __forceinline__ int rem_bucket(int r, int C)
     return (int)(((uint32_t)(C - r) * (uint32_t)kRemBuckets) / (uint32_t)C);      // in [0, kRemBuckets); C is at most 2^20: no overflow
 }
 
+// Tokens of a request cut into splits of C tokens: full splits and the remainder.  The default splits are powers of two
+// (log2C >= 0: a shift); a split fixed through the environment may be any multiple of 64 (log2C < 0: a division).
+__device__ __forceinline__ void cut(int L, int C, int log2C, int &nfull, int &r)
+{
+    if (log2C >= 0) {
+        nfull = L >> log2C;
+        r = L & (C - 1);
+    } else {
+        nfull = L / C;
+        r = L % C;
+    }
+}
+__device__ __forceinline__ int rem_bucket(int r, int C, int log2C)
+{
+    return log2C >= 0 ? (int)(((uint32_t)(C - r) * (uint32_t)kRemBuckets) >> log2C) : rem_bucket(r, C);
+}
+
 // One workgroup.  Per request: number of full tiles (C tokens) and whether a shorter
 // remainder tile exists.  Tiles of a request are numbered consecutively (tile_base) for
 // the split buffers.  The work order is longest-first: all full tiles, then the remainder
 // tiles by decreasing length (a counting sort over length buckets; the order inside a
 // bucket is arbitrary), so that the waves that finish last finish on the shortest items.
-// Also lists the requests whose splits need merging and zeroes the rows of empty requests.
+// Also counts the requests whose splits need merging and zeroes the rows of empty requests.
 __global__ __launch_bounds__(1024) void plan_kernel(const int32_t *context_lens, int32_t B, int32_t H,
                                                     int32_t items_per_tile, int32_t max_len, AttnWorkspace ws,
                                                     _Float16 *out, int32_t D, int32_t keep_negative)
@@ -144,7 +161,9 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t *context_lens,
             --sh;
         }
     }
+    const int log2C = (C & (C - 1)) == 0 ? 31 - __builtin_clz(C) : -1;
     int total = 0, total_full = 0;
+    int my_L = 0, my_tb = 0, my_fb = 0;     // with B <= 1024 a thread has one request and keeps what it computed for it
     for (int base = 0; base < B; base += 1024) {
         const int i = base + tid;
         int L = 0;
@@ -154,16 +173,19 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t *context_lens,
             no_request = keep_negative && L < 0;
             L = L < 0 ? 0 : (L > max_len ? max_len : L);
         }
-        const int nfull = L / C;
-        const int r = L % C;
+        int nfull, r;
+        cut(L, C, log2C, nfull, r);
         const int nrem = r != 0;
         int s_all, s_full, t_all, t_full;
         block_scan2_1024(nfull + nrem, nfull, s_wave, s_all, s_full, t_all, t_full);
         if (i < B) {
-            ws.tile_base[i] = total + s_all - (nfull + nrem);
-            ws.req_full_base[i] = total_full + s_full - nfull;
-            if (nrem) atomicAdd(&s_hist[rem_bucket(r, C)], 1);
-            if (nfull + nrem > 1) ws.merge_req[atomicAdd(&s_merge, 1)] = i;
+            my_L = L;
+            my_tb = total + s_all - (nfull + nrem);
+            my_fb = total_full + s_full - nfull;
+            ws.tile_base[i] = my_tb;
+            if (B > 1024) ws.req_full_base[i] = my_fb;
+            if (nrem) atomicAdd(&s_hist[rem_bucket(r, C, log2C)], 1);
+            if (nfull + nrem > 1) atomicAdd(&s_merge, 1);
             if (L == 0 && out && !no_request)           // out == nullptr: a plan made ahead of the calls that use it; they zero these rows
                 for (int e = 0; e < H * D; ++e) out[(int64_t)i * H * D + e] = (_Float16)0.0f;
         }
@@ -198,17 +220,20 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t *context_lens,
     // capacity.  A batch beyond that (requests that share pages) gets no work at all rather than writes past the end.
     const bool fits = total <= ws.max_tiles;
     for (int i = tid; fits && i < B; i += 1024) {
-        int L = context_lens[i];
-        L = L < 0 ? 0 : (L > max_len ? max_len : L);
-        const int nfull = L / C;
-        const int r = L % C;
-        const int tb = ws.tile_base[i];
+        int L = my_L, tb = my_tb, fb = my_fb;
+        if (B > 1024) {
+            L = context_lens[i];
+            L = L < 0 ? 0 : (L > max_len ? max_len : L);
+            tb = ws.tile_base[i];
+            fb = ws.req_full_base[i];
+        }
+        int nfull, r;
+        cut(L, C, log2C, nfull, r);
         const bool split = nfull + (r != 0) > 1;
-        const int fb = ws.req_full_base[i];
         for (int s = 0; s < nfull; ++s)
             ws.order[fb + s] = make_int4(i, s * C, (s + 1) * C, split ? tb + s : -1);
         if (r) {
-            const int pos = atomicAdd(&s_hist[rem_bucket(r, C)], 1);
+            const int pos = atomicAdd(&s_hist[rem_bucket(r, C, log2C)], 1);
             ws.order[total_full + pos] = make_int4(i, nfull * C, L, split ? tb + nfull : -1);
         }
     }
@@ -683,7 +708,7 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(AttnParams p)
 // ------------------------------------------------------------------ merge
 
 // Log-sum-exp combination of the splits of every request that has more than one; a
-// fixed grid of waves strides over (listed request, head) pairs.  Lane c reads the (m, l)
+// fixed grid of waves strides over all (request, head) pairs.  Lane c reads the (m, l)
 // header of split c, so the maximum and the denominator are two wave reductions, and the
 // weighted rows are then fetched with independent loads.
 template <int D>
@@ -699,11 +724,15 @@ __global__ __launch_bounds__(256) void merge_kernel(AttnParams p)
                 for (int r = 0; r < D / 64; ++r) dst[r * 64 + lane] = (_Float16)0.0f;
             }
     }
-    const int n_pairs = *p.ws.n_merge * p.H;
-    for (int pair = blockIdx.x * 4 + (threadIdx.x >> 6); pair < n_pairs; pair += n_waves) {
-        const int i = p.ws.merge_req[pair / p.H], h = pair % p.H;
+    // Every (request, head) pair looks up its own splits: the pair's first load does not wait for a list of the requests
+    // that need merging (the count of that list only says whether there is anything to merge at all -- it is 0 too for a
+    // batch that did not fit the workspace and got no work).
+    const int n_merge = *p.ws.n_merge;
+    for (int pair = blockIdx.x * 4 + (threadIdx.x >> 6); pair < p.B * p.H; pair += n_waves) {
+        const int i = pair / p.H, h = pair - i * p.H;
         const int first = p.ws.tile_base[i];
         const int n = p.ws.tile_base[i + 1] - first;
+        if (n_merge == 0 || n < 2) continue;
         const float *part = p.ws.part + ((int64_t)first * p.H + h) * (D + 2);
         const int64_t stride = (int64_t)p.H * (D + 2);
         float m = kNegInf, l = 0.0f, o[D / 64];

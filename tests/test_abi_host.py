@@ -152,7 +152,7 @@ def _workspace_model(num_pages, P, Hkv, H, D, B_, max_len, gqa):
     ipt = Hkv if gqa else H
     small = B_ + -(-2 * 256 * 8 * (1 if gqa else 4) // ipt)
     tiles = max(1, min(bound(C_min), max(bound(C), small)))
-    return 256 + up(4 * (B_ + 1)) + 2 * up(4 * B_) + up(16 * tiles) + up(4 * tiles * H * (D + 2))
+    return 256 + up(4 * (B_ + 1)) + up(4 * B_) + up(16 * tiles) + up(4 * tiles * H * (D + 2))
 
 
 def test_attention_workspace_is_bounded_by_the_cache_capacity(B):

@@ -152,3 +152,46 @@ def test_lengths_beyond_the_cache_capacity(env, validating):
     with pytest.raises(B.AliseError) as e:
         run(10)
     assert e.value.status == B.ALISE_INVALID_ARGUMENT
+
+
+def test_v_scales_beyond_the_matrix_core_range(env, validating):
+    """The matrix-core paths (grouped-query decode, chunked prefill) carry weight x V scale as a pair of fp16 numbers, which
+    holds for V scales below 256; the vector path has no such limit.  With the checks on, a call that would run on the
+    matrix cores over a request whose cached V reaches such a scale is refused; the same cache read by the vector kernel,
+    and a request that does not reach the wide group, pass."""
+    B, torch = env
+    Hkv, D, P, num_pages = 2, 128, 16, 8
+    cache = B.KVCache.allocate(num_pages, P, Hkv, D, 8, 64, fill=0)
+    rng = np.random.default_rng(7)
+    T = 40
+    k = rng.standard_normal((T, Hkv, D)).astype(np.float16)
+    v = rng.standard_normal((T, Hkv, D)).astype(np.float16)
+    v[30, 1, 70], v[30, 1, 71] = 65504.0, -65504.0          # one group of one head of token 30: scale 131008 / 255 = 514
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    B.alise_kv_quant_write(cache, dev(k), dev(v), dev(np.arange(T, dtype=np.int64)))
+    bt = dev(np.array([[0, 1, 2]], np.int32))
+    scale = 1.0 / np.sqrt(D)
+    print("case V scale limit", flush=True)
+
+    def decode(H, L):
+        q = dev(rng.standard_normal((1, H, D)).astype(np.float16))
+        o = torch.empty_like(q)
+        ws = torch.empty(B.alise_paged_decode_attn_workspace_bytes(cache, 1, H, 48), dtype=torch.uint8, device="cuda")
+        B.alise_paged_decode_attn(cache, q, o, bt, dev(np.array([L], np.int32)), 48, scale, ws)
+        torch.cuda.synchronize()
+        return o
+
+    def prefill(H, L, n):
+        q = dev(rng.standard_normal((n, H, D)).astype(np.float16))
+        o = torch.empty_like(q)
+        ws = torch.empty(B.alise_paged_prefill_attn_workspace_bytes(cache, 1, n, H, 48), dtype=torch.uint8, device="cuda")
+        B.alise_paged_prefill_attn(cache, q, o, dev(np.array([0, n], np.int32)), bt, dev(np.array([L], np.int32)), 48, scale, ws)
+        torch.cuda.synchronize()
+        return o
+
+    validating()
+    _refused(B, lambda: decode(8, 40))                      # four query heads per KV head: matrix cores, token 30 in reach
+    _refused(B, lambda: prefill(2, 40, 8))                  # chunked prefill runs on the matrix cores for this layout
+    assert bool(torch.isfinite(decode(8, 30)).all())        # tokens 0 .. 29 only
+    assert bool(torch.isfinite(prefill(2, 30, 8)).all())
+    assert bool(torch.isfinite(decode(2, 40)).all())        # one query head per KV head: the vector kernel, no limit
