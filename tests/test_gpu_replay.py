@@ -324,3 +324,70 @@ def test_native_loop_error_paths(env):
         rp.iterate()
     rp.close()
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("shape_name", ["llama7b", "gqa70b", "int4"])
+def test_both_loops_agree_at_the_benchmark_shapes(env, shape_name):
+    """The two loops call the same entry points with the same arguments, so on the layouts bench.py times (32 or 64 query
+    heads, matrix-core and vector kernels) every decision and every output row of a scheduled run must be the same bit for
+    bit, whichever loop drives it, the C++ one running ahead of the GPU."""
+    B, replay, torch, _, _ = env
+    w = wl.CONFIGS[shape_name]
+    n_jobs = 20
+    arrival, s, n_true, n_pred = (a.tolist() for a in wl.job_trace(n_jobs, 5, mean_gap=80.0, max_prompt=300, max_output=12))
+    cfg = dict(num_queues=3, limit0=3000, age_threshold=20000, max_batch=6, gpu_job_limit=8, t0=2, alpha=1, beta=20)
+    max_ctx = max(a + b for a, b in zip(s, n_true)) + 1
+    num_pages = 2 * (cfg["gpu_job_limit"] + cfg["max_batch"] + 1) * ((max_ctx + w.P - 1) // w.P)
+    gen = torch.Generator(device="cuda").manual_seed(13)
+    rows = 2048
+    k = torch.randn((rows + max_ctx, w.Hkv, w.D), dtype=torch.float16, device="cuda", generator=gen) * 1.5
+    v = torch.randn((rows + max_ctx, w.Hkv, w.D), dtype=torch.float16, device="cuda", generator=gen)
+    q = torch.randn((rows + max_ctx, w.H, w.D), dtype=torch.float16, device="cuda", generator=gen)
+    base = lambda id: (id * 211) % rows
+
+    def source(spans):
+        idx = torch.from_numpy(np.concatenate([np.arange(base(id) + a, base(id) + b) for id, a, b in spans])).cuda()
+        return k.index_select(0, idx), v.index_select(0, idx), q.index_select(0, idx)
+
+    def drive(add_job, num_jobs, iterate, commit, rows_of):
+        order = sorted(range(n_jobs), key=lambda i: (arrival[i], i))
+        nxt, now, produced, log, decisions = 0, 0, [0] * n_jobs, [], []
+        while True:
+            while nxt < n_jobs and arrival[order[nxt]] <= now:
+                add_job(order[nxt])
+                nxt += 1
+            if num_jobs() == 0:
+                if nxt == n_jobs:
+                    return decisions, torch.cat(log).cpu()
+                now = arrival[order[nxt]]
+                continue
+            d = iterate()
+            log.append(rows_of(d))
+            decisions.append((list(d["batch"]), list(d["phase"]), list(d["upload"]), list(d["offload"])))
+            fin = []
+            for id in d["batch"]:
+                produced[id] += 1
+                if produced[id] >= n_true[id]:
+                    fin.append(id)
+            commit(d["model_time"], fin)
+            now += d["model_time"]
+
+    print(f"case both loops, {shape_name}", flush=True)
+    cache = B.KVCache.allocate(num_pages, w.P, w.Hkv, w.D, w.bits, w.G, fill=0)
+    nat = B.NativeReplay(cache, w.H, cfg, max_ctx, cfg["max_batch"] * max(s), k, v, q, 1.0 / np.sqrt(w.D))
+    dec_n, out_n = drive(lambda i: nat.add_job(i, arrival[i], s[i], n_pred[i], base(i)), nat.num_jobs, nat.iterate, nat.commit,
+                         lambda d: d["out"][:d["n_prefill_tokens"] + d["n_decode_tokens"]].clone())
+    nat.synchronize()
+    st = nat.stats()
+    nat.close()
+    py = replay.Replay(w, B.Scheduler(**cfg), num_pages=num_pages, max_context=max_ctx, kv_source=source)
+
+    def rows_py(d):
+        parts = [t for t in (d["prefill_out"], d["decode_out"]) if t is not None]
+        return torch.cat(parts) if parts else torch.empty((0, w.H, w.D), dtype=torch.float16, device="cuda")
+    dec_p, out_p = drive(lambda i: py.add_job(i, arrival[i], s[i], n_pred[i]), py.sched.num_jobs, py.iterate, py.commit, rows_py)
+    torch.cuda.synchronize()
+    print(f"  {st['iterations']} iterations, {st['offloads']} offloads, {st['uploads']} uploads, {out_n.shape[0]} output rows", flush=True)
+    assert dec_n == dec_p
+    assert st["offloads"] > 0 and st["uploads"] > 0
+    assert out_n.shape == out_p.shape and torch.equal(out_n, out_p)
