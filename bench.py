@@ -71,6 +71,8 @@ def parse():
                     help="skip the legs outside the timed steps (swap, prefill, fused operators, scheduler): for profiler runs")
     ap.add_argument("--only-prefill", action="store_true",
                     help="after the timed steps run only the prefill leg with a chunk from every request: for profiler runs")
+    ap.add_argument("--only-scheduler", action="store_true",
+                    help="after the timed steps run only the scheduled run, through the C++ loop alone: for profiler runs")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also launch an elementwise kernel that reads and writes exactly 1 GiB, so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run of this command can be scaled")
@@ -418,7 +420,7 @@ def fused_ops_leg(w):
     return out
 
 
-def scheduled_run_leg(w):
+def scheduled_run_leg(w, python_loop=True):
     """The host-side scheduler (Sec. 3.1 "Preemptive Scheduling", Sec. 3.2 Alg. 2) outside the timed
     steps: (1) decisions per second of the C++ scheduler alone on 1024 live jobs; (2) a scheduled
     run of 192 synthetic jobs through one attention layer of this workload's shape on the GPU --
@@ -520,6 +522,8 @@ def scheduled_run_leg(w):
     out["scheduled_run"] = dict(workload=what, **report(
         st, dt, "the C++ loop of alise_replay.h (one call per iteration from the driver, no host synchronisation inside), "
                 "second run of the same trace; the clock the scheduler sees is its own model time"))
+    if not python_loop:
+        return out
     run_python()
     st, dt = run_python()
     out["scheduled_run_python_loop"] = report(st, dt, "the same trace through replay.py, the Python loop around the same entry points")
@@ -655,6 +659,8 @@ def main():
     }
     if args.only_prefill:
         result["prefill_full_batch"] = prefill_leg(w, step, every=1)
+    elif args.only_scheduler:
+        result["scheduler"] = scheduled_run_leg(w, python_loop=False)
     elif not args.only_steps:
         ceiling = read_ceiling_leg()
         result["hbm_read_ceiling"] = ceiling
