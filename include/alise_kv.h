@@ -117,6 +117,8 @@ size_t alise_kv_meta_bytes(const alise_kv_cache *c);
  *   slot_mapping  device, int64 [T]; token t goes to slot slot_mapping[t];
  *                 a negative slot skips the token.  Slots must be distinct.
  * Writes codes and meta of the addressed slots only.  T = 0 is a no-op.
+ * K and V are finite numbers: a group that holds an infinity or a NaN gets unspecified codes, scale and
+ * zero-point (nothing faults, the other groups are not affected).
  */
 int alise_kv_quant_write(const alise_kv_cache *c, const void *k, const void *v,
                          const int64_t *slot_mapping, int32_t T, void *hip_stream);
