@@ -92,6 +92,7 @@ struct alise_replay {
     std::vector<int32_t> d_phase;
     alise_replay_stats stats{};
     bool broken = false;
+    bool swaps_unseen = false;      // swap_done has been recorded since the compute stream last waited for it
 };
 
 namespace {
@@ -366,13 +367,16 @@ int alise_replay_iterate(alise_replay *r, const void *k_tokens, const void *v_to
 
     // pages given up by the offloads and the finished jobs of the last iteration: every later writer is ordered
     // behind those copies and that iteration
-    if (hipStreamWaitEvent(r->main, r->swap_done, 0) != hipSuccess) return ALISE_HIP_ERROR;
+    if (r->swaps_unseen) {          // nothing to wait for when no swap has been enqueued since the last wait
+        if (hipStreamWaitEvent(r->main, r->swap_done, 0) != hipSuccess) return ALISE_HIP_ERROR;
+        r->swaps_unseen = false;
+    }
     r->free_pages.insert(r->free_pages.end(), r->pending_free.begin(), r->pending_free.end());
     r->pending_free.clear();
-    if (hipStreamWaitEvent(r->side, r->iter_done, 0) != hipSuccess) return ALISE_HIP_ERROR;     // the swaps see what it wrote
 
     // ---- the swaps
     if (d.n_offload + d.n_upload > 0) {
+        if (hipStreamWaitEvent(r->side, r->iter_done, 0) != hipSuccess) return ALISE_HIP_ERROR;     // they see what the last iteration wrote
         int32_t *lists = reinterpret_cast<int32_t *>(sg.side);
         size_t n_ints = 0;
         std::vector<size_t> at(d.n_offload + d.n_upload);
@@ -427,6 +431,7 @@ int alise_replay_iterate(alise_replay *r, const void *k_tokens, const void *v_to
             it->upload_ids[i] = d.upload_ids[i];
         }
         if (hipEventRecord(r->swap_done, r->side) != hipSuccess) return ALISE_HIP_ERROR;
+        r->swaps_unseen = true;
         if (!rel.bufs.empty()) {
             // the uploads read their host buffers until the swap stream has passed this point
             rel.ev = take_event(r);
@@ -436,7 +441,10 @@ int alise_replay_iterate(alise_replay *r, const void *k_tokens, const void *v_to
             bool in_batch = false;
             for (int32_t i = 0; i < d.n_upload && !in_batch; ++i)
                 in_batch = std::find(d.batch_ids, d.batch_ids + d.n_batch, d.upload_ids[i]) != d.batch_ids + d.n_batch;
-            if (in_batch && hipStreamWaitEvent(r->main, r->swap_done, 0) != hipSuccess) return ALISE_HIP_ERROR;
+            if (in_batch) {
+                if (hipStreamWaitEvent(r->main, r->swap_done, 0) != hipSuccess) return ALISE_HIP_ERROR;
+                r->swaps_unseen = false;
+            }
         }
     }
     it->n_offload = d.n_offload;
