@@ -384,6 +384,41 @@ def issue_overlap_leg():
     return out
 
 
+def quant_write_leg(w, tokens=65536):
+    """Quantize-and-write of a prompt-sized batch (Sec. 3.2 "KV Compression"), outside the timed steps: `tokens` new tokens
+    of this workload's shape written into pages of their own, whole prompts side by side in their pages.  The inputs
+    (1-2 GB) do not fit the last-level cache, so every launch reads them from HBM.  Bound: HBM (read fp16, write codes
+    and meta)."""
+    import numpy as np
+    import torch
+    from paper_2410_23537_amd import binding as B
+    from paper_2410_23537_amd import workloads as wl
+    pages = tokens // w.P
+    cache = B.KVCache.allocate(pages, w.P, w.Hkv, w.D, w.bits, w.G, fill=0)
+    gen = torch.Generator(device="cuda").manual_seed(w.seed + 5)
+    k = torch.randn((tokens, w.Hkv, w.D), dtype=torch.float16, device="cuda", generator=gen)
+    v = torch.randn((tokens, w.Hkv, w.D), dtype=torch.float16, device="cuda", generator=gen)
+    perm = torch.randperm(pages, device="cuda", generator=gen)
+    t = torch.arange(tokens, device="cuda")
+    slots = (perm[t // w.P] * w.P + t % w.P).to(torch.int64)
+    for _ in range(2):
+        B.alise_kv_quant_write(cache, k, v, slots)
+    torch.cuda.synchronize()
+    reps = 10
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for a, b in ev:
+        a.record()
+        B.alise_kv_quant_write(cache, k, v, slots)
+        b.record()
+    torch.cuda.synchronize()
+    ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    nbytes = wl.algorithmic_bytes_write(w, tokens)
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    return {"workload": f"{tokens} tokens of {w.name}'s shape into {pages} pages in random order", "ms": ms, "bytes": nbytes,
+            "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                         "traffic": None}}
+
+
 def fused_ops_leg(w):
     """The two other fused operators of the layer (Sec. 3.3 "Implementation"), outside the timed
     steps, on a token batch of this workload's model: 16384 tokens (prefill chunks of an iteration;
@@ -685,6 +720,7 @@ def main():
         if args.workload == "int4":
             # the other three benchmark configurations, one after another (each built, timed and freed)
             result["all_configs"] = {n: other_config_leg(n, args.steps, args.warmup) for n in ("opt13b", "llama7b", "gqa70b")}
+        result["quant_write_large"] = quant_write_leg(w)
         result["issue_overlap"] = issue_overlap_leg()
         result["fused_ops"] = fused_ops_leg(w)
         result["scheduler"] = scheduled_run_leg(w)
