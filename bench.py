@@ -194,6 +194,41 @@ def swap_leg(step):
             out[f"{where}_{name}_GBs"] = moved / (ms * 1e-3) / 1e9
     out["note"] = ("device_staging counts bytes read + written in HBM (plain copy on this box: about 5200 GB/s); "
                    "pinned_host counts bytes over the host link (hipMemcpyAsync of the same buffer: about 56 GB/s)")
+    # Alg. 2 overlaps the movement with computation: the step's attention call alone, and with the offload of this
+    # request running beside it on a second stream (the offload outlasts the call) -- once by the kernel writing pinned
+    # host memory itself, once by the kernel gathering into device memory and the copy engine moving that to the host
+    side = torch.cuda.Stream()
+    host, stage = buf, torch.empty(n, dtype=torch.uint8, device="cuda")
+
+    def attention_ms(beside):
+        ts = []
+        for _ in range(12):
+            torch.cuda.synchronize()
+            with torch.cuda.stream(side):
+                if beside == "kernel":
+                    B.alise_kv_swap_out(cache, bt, L, host)
+                elif beside == "copy_engine":
+                    B.alise_kv_swap_out(cache, bt, L, stage)
+                    host.copy_(stage, non_blocking=True)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            step.attend(0)
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        return float(np.mean(ts[2:]))
+    out["attention_call_ms_alone"] = attention_ms(None)
+    out["attention_call_ms_beside_offload_by_kernel_to_pinned_host"] = attention_ms("kernel")
+    out["attention_call_ms_beside_offload_by_kernel_and_copy_engine"] = attention_ms("copy_engine")
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        B.alise_kv_swap_out(cache, bt, L, stage)
+        host.copy_(stage, non_blocking=True)
+    e1.record()
+    torch.cuda.synchronize()
+    out["copy_engine_offload_GBs"] = n / (e0.elapsed_time(e1) / 5 * 1e-3) / 1e9
     return out
 
 

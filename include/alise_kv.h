@@ -293,7 +293,10 @@ int alise_paged_prefill_attn(const alise_kv_cache *c, const void *q, void *out, 
  *                 in the canonical order.  Whole pages travel, the unused slots of the last
  *                 page included, so an upload reproduces every page bit for bit.
  * Run them on a stream of their own to overlap them with attention; a request must not be
- * attended to or written while it is in transit.  num_tokens = 0 is legal and does nothing.
+ * attended to or written while it is in transit.  Beside an attention call prefer the device
+ * buffer and let hipMemcpyAsync move it: both ways reach the rate of the host link, but a kernel
+ * that reads or writes host memory itself slows an attention call running at the same time by
+ * about a third on an MI355X, and the copy engine does not (measured; bench.py, `swap`).  num_tokens = 0 is legal and does nothing.
  */
 size_t alise_kv_swap_bytes(const alise_kv_cache *c, int32_t num_tokens);
 

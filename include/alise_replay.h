@@ -7,8 +7,9 @@
  * compute, and runs the batch over the compressed paged cache [Sec. 3.2 "KV Compression",
  * Sec. 3.3].  This object is the loop around one attention layer's worth of that: it owns a
  * scheduler (alise_sched.h), the page free list and block tables of a cache (alise_kv.h), pinned
- * host buffers for offloaded requests, a second stream and the events that order it against the
- * caller's, and at every iteration it
+ * host buffers for offloaded requests (filled and read by the copy engine through a device staging
+ * buffer: alise_kv_swap_out / _in gather and scatter in device memory), a second stream and the
+ * events that order it against the caller's, and at every iteration it
  *     offloads the jobs that lost their place (their pages are free one iteration later),
  *     uploads the ones that got one,
  *     quantizes and writes the new K/V of the batch (whole prompts for jobs in their first

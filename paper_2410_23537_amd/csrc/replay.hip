@@ -3,8 +3,8 @@
 // ALISE Sec. 3.1 "Preemptive Scheduling" decides the batch of every iteration, Sec. 3.2 "Dynamic
 // Swapping" with Alg. 2 decides which preempted job's KV cache stays on the GPU; this file is the
 // plumbing that turns those decisions into calls without ever waiting for the GPU in the steady
-// state: a page free list, block tables, pinned host buffers recycled by size class, a second
-// stream for the swaps with two events that order it against the compute stream, and a ring of
+// state: a page free list, block tables, pinned host buffers recycled by size class, a device
+// staging buffer between the swap kernels and the copy engine, a second stream for the swaps with two events that order it against the compute stream, and a ring of
 // pinned staging buffers through which the metadata of an iteration (source rows, slots, chunk
 // boundaries, lengths, block tables, page lists of the swaps) reaches the device in one copy per
 // stream.  The only kernel here gathers the iteration's new token rows into contiguous K, V and Q
@@ -83,6 +83,7 @@ struct alise_replay {
     uint8_t *dev_main = nullptr, *dev_side = nullptr;
     void *kbuf = nullptr, *vbuf = nullptr, *qbuf = nullptr;
     void *ws_dec = nullptr, *ws_pre = nullptr;
+    void *swap_stage = nullptr;     // device staging of one request's offloaded form: the copy engine moves it over the host link
     size_t ws_dec_bytes = 0, ws_pre_bytes = 0;
     std::map<size_t, std::vector<void *>> host_pool;
     std::vector<Release> releases;
@@ -221,6 +222,7 @@ int alise_replay_create(const alise_kv_cache *cache, const alise_sched_config *s
     ok = ok && hipMalloc(&r->qbuf, (size_t)T * r->q_units * 16) == hipSuccess;
     ok = ok && hipMalloc(&r->ws_dec, r->ws_dec_bytes) == hipSuccess;
     ok = ok && hipMalloc(&r->ws_pre, r->ws_pre_bytes) == hipSuccess;
+    ok = ok && hipMalloc(&r->swap_stage, alise_kv_swap_bytes(cache, cfg->max_context)) == hipSuccess;
     if (!ok) {
         (void)hipGetLastError();
         alise_replay_destroy(r);
@@ -258,7 +260,7 @@ void alise_replay_destroy(alise_replay *r)
         if (s.main_done) (void)hipEventDestroy(s.main_done);
         if (s.side_done) (void)hipEventDestroy(s.side_done);
     }
-    for (void *p : {(void *)r->dev_main, (void *)r->dev_side, r->kbuf, r->vbuf, r->qbuf, r->ws_dec, r->ws_pre})
+    for (void *p : {(void *)r->dev_main, (void *)r->dev_side, r->kbuf, r->vbuf, r->qbuf, r->ws_dec, r->ws_pre, r->swap_stage})
         if (p) (void)hipFree(p);
     if (r->iter_done) (void)hipEventDestroy(r->iter_done);
     if (r->swap_done) (void)hipEventDestroy(r->swap_done);
@@ -404,8 +406,11 @@ int alise_replay_iterate(alise_replay *r, const void *k_tokens, const void *v_to
             size_t cls = 0;
             void *buf = host_buffer(r, n, &cls);
             if (!buf) return ALISE_HIP_ERROR;
-            st = alise_kv_swap_out(c, dev_lists + at[i], j.L, buf, n, r->side);
+            // gathered into device memory by the kernel, moved to the host by the copy engine: a kernel that writes host
+            // memory itself slows an attention call running beside it by a third, the copy engine does not
+            st = alise_kv_swap_out(c, dev_lists + at[i], j.L, r->swap_stage, n, r->side);
             if (st != ALISE_OK) return st;
+            if (hipMemcpyAsync(buf, r->swap_stage, n, hipMemcpyDeviceToHost, r->side) != hipSuccess) return ALISE_HIP_ERROR;
             r->pending_free.insert(r->pending_free.end(), j.pages.begin(), j.pages.end());
             j.pages.clear();
             j.host = buf;
@@ -421,7 +426,9 @@ int alise_replay_iterate(alise_replay *r, const void *k_tokens, const void *v_to
         rel.ev = nullptr;
         for (int32_t i = 0; i < d.n_upload; ++i) {
             Job &j = r->jobs[d.upload_ids[i]];
-            st = alise_kv_swap_in(c, dev_lists + at[d.n_offload + i], j.L, j.host, j.host_bytes, r->side);
+            if (hipMemcpyAsync(r->swap_stage, j.host, j.host_bytes, hipMemcpyHostToDevice, r->side) != hipSuccess)
+                return ALISE_HIP_ERROR;
+            st = alise_kv_swap_in(c, dev_lists + at[d.n_offload + i], j.L, r->swap_stage, j.host_bytes, r->side);
             if (st != ALISE_OK) return st;
             rel.bufs.emplace_back(j.host, j.host_class);
             r->stats.uploads += 1;

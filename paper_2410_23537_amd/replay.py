@@ -54,6 +54,9 @@ class Replay:
         self.swap_done = torch.cuda.Event()
         self.iter_done.record(self.main)
         self.swap_done.record(self.side)
+        # offloads and uploads go through device memory: the kernels gather and scatter there, the copy engine moves the
+        # bytes over the host link (a kernel that touches host memory itself slows the attention call beside it)
+        self._swap_stage = torch.empty(B.alise_kv_swap_bytes(self.cache, max_context), dtype=torch.uint8, device="cuda")
         self._ws_dec = torch.empty(0, dtype=torch.uint8, device="cuda")
         self._ws_pre = torch.empty(0, dtype=torch.uint8, device="cuda")
         self._host_pool: dict[int, list] = {}
@@ -112,7 +115,8 @@ class Replay:
                 j = self.jobs[id]
                 n = B.alise_kv_swap_bytes(cache, j.L)
                 buf = self._host_buffer(n)
-                B.alise_kv_swap_out(cache, torch.tensor(j.pages, dtype=torch.int32, device="cuda"), j.L, buf[:n])
+                B.alise_kv_swap_out(cache, torch.tensor(j.pages, dtype=torch.int32, device="cuda"), j.L, self._swap_stage[:n])
+                buf[:n].copy_(self._swap_stage[:n], non_blocking=True)
                 self.pending_free.extend(j.pages)
                 j.pages, j.host, j.host_bytes = [], buf, n
                 offloaded[id] = (buf, n)
@@ -121,7 +125,8 @@ class Replay:
             for id in d["upload"]:
                 j = self.jobs[id]
                 j.pages = self._alloc((j.L + w.P - 1) // w.P)
-                B.alise_kv_swap_in(cache, torch.tensor(j.pages, dtype=torch.int32, device="cuda"), j.L, j.host[:j.host_bytes])
+                self._swap_stage[:j.host_bytes].copy_(j.host[:j.host_bytes], non_blocking=True)
+                B.alise_kv_swap_in(cache, torch.tensor(j.pages, dtype=torch.int32, device="cuda"), j.L, self._swap_stage[:j.host_bytes])
                 self.stats["uploads"] += 1
                 self.stats["upload_bytes"] += j.host_bytes
             self.swap_done.record(self.side)
