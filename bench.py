@@ -71,8 +71,9 @@ def parse():
                     help="skip the legs outside the timed steps (swap, prefill, fused operators, scheduler): for profiler runs")
     ap.add_argument("--only-prefill", action="store_true",
                     help="after the timed steps run only the prefill leg with a chunk from every request: for profiler runs")
-    ap.add_argument("--only-scheduler", action="store_true",
-                    help="after the timed steps run only the scheduled run, through the C++ loop alone: for profiler runs")
+    ap.add_argument("--only-scheduler", nargs="?", const="small", choices=("small", "large"), default=None,
+                    help="after the timed steps run only the scheduled run through the C++ loop, the small trace or the large one: "
+                         "for profiler runs")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also launch an elementwise kernel that reads and writes exactly 1 GiB, so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run of this command can be scaled")
@@ -490,7 +491,76 @@ def fused_ops_leg(w):
     return out
 
 
-def scheduled_run_leg(w, python_loop=True):
+def large_scheduled_run(w):
+    """The scheduled run at a size where the kernels, not the launches, set the pace: 384 jobs with prompts of
+    hundreds to thousands of tokens, batches of 128, 320 caches resident (74 offloads and uploads), through the C++ loop.  Reports the wall
+    clock and what the decode batches streamed from the compressed cache while it ran."""
+    import numpy as np
+    import torch
+    from paper_2410_23537_amd import binding as B
+    from paper_2410_23537_amd import workloads as wl
+    n_jobs, M, batch = 384, 320, 128
+    arrival, s, n_true, n_pred = (a.tolist() for a in wl.job_trace(n_jobs, 29, mean_gap=400.0, max_prompt=4096, max_output=128,
+                                                                    prompt_median=800.0, output_median=48.0))
+    cfg = dict(num_queues=4, limit0=200000, age_threshold=5000000, max_batch=batch, gpu_job_limit=M, t0=2, alpha=1, beta=20)
+    max_ctx = max(a + b for a, b in zip(s, n_true)) + 1
+    pages_per_job = (max_ctx + w.P - 1) // w.P
+    max_iter_tokens = sum(sorted(s)[-batch:])                     # no batch can bring more prompt tokens than its longest prompts
+    pool_n = 1 << 16
+    gen = torch.Generator(device="cuda").manual_seed(w.seed + 3)
+    pk = torch.randn((pool_n + max_ctx, w.Hkv, w.D), dtype=torch.float16, device="cuda", generator=gen)
+    pv = torch.randn((pool_n + max_ctx, w.Hkv, w.D), dtype=torch.float16, device="cuda", generator=gen)
+    pq = torch.randn((pool_n + max_ctx, w.H, w.D), dtype=torch.float16, device="cuda", generator=gen)
+
+    def run_once():
+        cache = B.KVCache.allocate((M + batch + 1) * pages_per_job, w.P, w.Hkv, w.D, w.bits, w.G, fill=0)
+        rp = B.NativeReplay(cache, w.H, cfg, max_ctx, max_iter_tokens, pk, pv, pq, 1.0 / math.sqrt(w.D))
+        order = sorted(range(n_jobs), key=lambda i: (arrival[i], i))
+        k, now, produced, attended = 0, 0, [0] * n_jobs, 0
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        while True:
+            while k < n_jobs and arrival[order[k]] <= now:
+                i = order[k]
+                rp.add_job(i, arrival[i], s[i], n_pred[i], (i * 7919) % pool_n)
+                k += 1
+            if rp.num_jobs() == 0:
+                if k == n_jobs:
+                    break
+                now = arrival[order[k]]
+                continue
+            d = rp.iterate()
+            fin = []
+            for id, ph in zip(d["batch"], d["phase"]):
+                produced[id] += 1
+                if ph == 1:
+                    attended += s[id] + produced[id] - 1          # the tokens this decode step read from the cache
+                if produced[id] >= n_true[id]:
+                    fin.append(id)
+            rp.commit(d["model_time"], fin)
+            now += d["model_time"]
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        st = rp.stats()
+        rp.close()
+        return st, dt, attended
+
+    run_once()
+    st, dt, attended = run_once()
+    streamed = attended * w.Hkv * w.row_bytes
+    return {"workload": f"{n_jobs} jobs (log-normal prompts, median 800, <= 4096; outputs, median 48, <= 128; 15 % underpredicted 4x), "
+                        f"batch {batch}, GPU job limit {M}, 4 queues; one attention layer of {w.name}'s shape, the C++ loop",
+            "seconds": dt, "iterations": st["iterations"], "iterations_per_s": st["iterations"] / dt,
+            "prefill_tokens": st["prefill_tokens"], "decode_tokens": st["decode_tokens"],
+            "tokens_per_s": (st["prefill_tokens"] + st["decode_tokens"]) / dt,
+            "offloads": st["offloads"], "uploads": st["uploads"], "swapped_bytes": st["offload_bytes"] + st["upload_bytes"],
+            "decode_kv_tokens_attended": attended, "decode_cache_GB_streamed": streamed / 1e9,
+            "decode_cache_GBs_over_the_whole_run": streamed / dt / 1e9,
+            "note": "wall clock of the whole run (prefill, writes, swaps and the host included), second run of the trace; "
+                    "the last figure divides the cache bytes the decode batches read by that wall clock"}
+
+
+def scheduled_run_leg(w, python_loop=True, which=None):
     """The host-side scheduler (Sec. 3.1 "Preemptive Scheduling", Sec. 3.2 Alg. 2) outside the timed
     steps: (1) decisions per second of the C++ scheduler alone on 1024 live jobs; (2) a scheduled
     run of 192 synthetic jobs through one attention layer of this workload's shape on the GPU --
@@ -587,11 +657,14 @@ def scheduled_run_leg(w, python_loop=True):
 
     what = (f"{n_jobs} jobs (Poisson arrivals, log-normal prompts <= 1024 and outputs <= 96, 15 % underpredicted 4x), "
             f"batch {batch}, GPU job limit {M}, 4 queues; one attention layer of {w.name}'s shape")
-    run_native()                    # the first run pays for pinned allocations and one-time queries
-    st, dt = run_native()
-    out["scheduled_run"] = dict(workload=what, **report(
-        st, dt, "the C++ loop of alise_replay.h (one call per iteration from the driver, no host synchronisation inside), "
-                "second run of the same trace; the clock the scheduler sees is its own model time"))
+    if which != "large":
+        run_native()                # the first run pays for pinned allocations and one-time queries
+        st, dt = run_native()
+        out["scheduled_run"] = dict(workload=what, **report(
+            st, dt, "the C++ loop of alise_replay.h (one call per iteration from the driver, no host synchronisation inside), "
+                    "second run of the same trace; the clock the scheduler sees is its own model time"))
+    if which != "small":
+        out["scheduled_run_large"] = large_scheduled_run(w)
     if not python_loop:
         return out
     run_python()
@@ -730,7 +803,7 @@ def main():
     if args.only_prefill:
         result["prefill_full_batch"] = prefill_leg(w, step, every=1)
     elif args.only_scheduler:
-        result["scheduler"] = scheduled_run_leg(w, python_loop=False)
+        result["scheduler"] = scheduled_run_leg(w, python_loop=False, which=args.only_scheduler)
     elif not args.only_steps:
         ceiling = read_ceiling_leg()
         result["hbm_read_ceiling"] = ceiling

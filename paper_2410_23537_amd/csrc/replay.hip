@@ -26,17 +26,28 @@ namespace {
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 // Row i of each destination is row rows[i] of its source.  One workgroup per token; rows are whole
-// numbers of 16-byte units.
+// numbers of 16-byte units; a thread has four loads in flight before it stores.
 __global__ __launch_bounds__(256) void gather_tokens_kernel(const int64_t *__restrict__ rows, const u32x4_t *__restrict__ k,
                                                             const u32x4_t *__restrict__ v, const u32x4_t *__restrict__ q,
                                                             u32x4_t *__restrict__ kd, u32x4_t *__restrict__ vd,
                                                             u32x4_t *__restrict__ qd, int32_t kv_units, int32_t q_units)
 {
     const int64_t t = blockIdx.x, r = rows[t];
-    for (int u = threadIdx.x; u < 2 * kv_units + q_units; u += 256) {
-        if (u < kv_units) kd[t * kv_units + u] = k[r * kv_units + u];
-        else if (u < 2 * kv_units) vd[t * kv_units + u - kv_units] = v[r * kv_units + u - kv_units];
-        else qd[t * q_units + u - 2 * kv_units] = q[r * q_units + u - 2 * kv_units];
+    const int n = 2 * kv_units + q_units;
+    auto src_of = [&](int u) {
+        return u < kv_units ? k + r * kv_units + u : u < 2 * kv_units ? v + r * kv_units + (u - kv_units) : q + r * q_units + (u - 2 * kv_units);
+    };
+    auto dst_of = [&](int u) {
+        return u < kv_units ? kd + t * kv_units + u : u < 2 * kv_units ? vd + t * kv_units + (u - kv_units) : qd + t * q_units + (u - 2 * kv_units);
+    };
+    for (int base = threadIdx.x; base < n; base += 1024) {
+        u32x4_t x[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (base + 256 * j < n) x[j] = __builtin_nontemporal_load(src_of(base + 256 * j));
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (base + 256 * j < n) *dst_of(base + 256 * j) = x[j];
     }
 }
 

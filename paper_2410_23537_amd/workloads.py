@@ -264,17 +264,17 @@ def algorithmic_bytes_dequant(w: Workload, n_pages: int = 1) -> int:
 # ---------------------------------------------------------------- job traces for the scheduler
 
 def job_trace(n_jobs: int, seed: int, mean_gap: float = 40.0, max_prompt: int = 512, max_output: int = 256,
-              pred_error: float = 0.1, underestimates: float = 0.15):
+              pred_error: float = 0.1, underestimates: float = 0.15, prompt_median: float = 60.0, output_median: float = 40.0):
     """A seeded stream of serving jobs, stand-in for the chat traces the paper replays: Poisson
-    arrivals (exponential gaps of `mean_gap` ticks), log-normal prompt and output lengths clipped
-    to [1, max], a length prediction that is off by a normal relative error of `pred_error`, and a
+    arrivals (exponential gaps of `mean_gap` ticks), log-normal prompt and output lengths (the given
+    medians, sigma 1) clipped to [1, max], a length prediction that is off by a normal relative error of `pred_error`, and a
     fraction `underestimates` of jobs whose prediction is a quarter of the truth (the short
     mispredictions the demote-and-double rule exists for).  Returns int64 arrays
     (arrival, prompt_len, output_len, predicted_len).  Holds no scheduler arithmetic."""
     rng = np.random.default_rng([seed, n_jobs])
     arrival = np.floor(np.cumsum(rng.exponential(mean_gap, n_jobs))).astype(np.int64)
-    s = np.clip(np.round(np.exp(rng.normal(np.log(60.0), 1.0, n_jobs))), 1, max_prompt).astype(np.int64)
-    n = np.clip(np.round(np.exp(rng.normal(np.log(40.0), 1.0, n_jobs))), 1, max_output).astype(np.int64)
+    s = np.clip(np.round(np.exp(rng.normal(np.log(prompt_median), 1.0, n_jobs))), 1, max_prompt).astype(np.int64)
+    n = np.clip(np.round(np.exp(rng.normal(np.log(output_median), 1.0, n_jobs))), 1, max_output).astype(np.int64)
     pred = np.maximum(1, np.round(n * (1.0 + pred_error * rng.standard_normal(n_jobs)))).astype(np.int64)
     low = rng.random(n_jobs) < underestimates
     pred[low] = np.maximum(1, n[low] // 4)
