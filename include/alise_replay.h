@@ -103,7 +103,9 @@ int32_t alise_replay_num_jobs(const alise_replay *r);
  * Plans one iteration (alise_sched_step) and enqueues all of its work.  offload_host[i] is the
  * pinned host buffer (hipHostMalloc) that holds the offloaded form of offload_ids[i] in the
  * layout of alise_kv_swap_out, offload_bytes[i] bytes of it: complete once the GPU has passed the
- * iteration (alise_replay_synchronize), valid until the job is uploaded again.
+ * iteration (alise_replay_synchronize), valid until the job is uploaded again.  Host buffers come in
+ * power-of-two sizes and are recycled once their upload has passed; an offload that finds none of its
+ * size free allocates one (hipHostMalloc), which is the only allocation after create.
  * Errors: ALISE_WORKSPACE_TOO_SMALL if a list does not fit its capacity (nothing has changed), if
  * the iteration's new tokens exceed max_iter_tokens, or if the cache has too few free pages for
  * the uploads and the batch (size the pool for gpu_job_limit + max_batch jobs of max_context
